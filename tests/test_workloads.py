@@ -1,0 +1,33 @@
+"""The synthetic workloads are pinned: lengths, totals and flop counts."""
+import numpy as np
+
+import workloads
+
+
+def test_config_lengths_and_totals():
+    totals = {1: 147, 2: 17286, 3: 37117, 4: 66088, 5: 96016}
+    for cfg, T in totals.items():
+        w = workloads.config(cfg)
+        assert w.total_rows == T
+        off = w.seq_offsets()
+        assert off.dtype == np.int32 and off[0] == 0 and off[-1] == T
+    assert workloads.config(1).lengths == (55, 41, 33, 18)
+    assert all(l % 8 == 0 for l in workloads.config(4).lengths)
+    assert workloads.config(3).pairs_per_head == 52957147
+    assert workloads.config(5).pairs_per_head == 698506850
+
+
+def test_flop_counts():
+    w = workloads.config(3)
+    f = w.flops()
+    assert abs(f["fwd"] / 1e9 - 108.5) < 0.1 and abs(f["bwd"] / 1e9 - 271.1) < 0.1
+
+
+def test_values_are_seeded_and_rounded_once():
+    w = workloads.config(1)
+    a, b = workloads.values(w), workloads.values(w)
+    for name in ("q", "k", "v", "d_o"):
+        assert a[name].dtype.is_floating_point and (a[name] == b[name]).all()
+    w2 = workloads.custom("t", [3, 4], 2, 32, 32, 8, dtype="bf16")
+    x = workloads.values(w2)["q"]
+    assert np.array_equal(workloads.to_f64(x), x.float().double().numpy())

@@ -1,0 +1,136 @@
+"""Seeded synthetic jagged batches shared by the tests, the smoke check and the benchmark.
+
+This module draws lengths and values and nothing else: it holds none of the
+attention arithmetic, so both the GPU path's callers and the CPU oracle's
+callers can take inputs from it without sharing any of the method's code.
+
+The paper measures on production recommendation data that is not public
+(section 3); these batches take the shapes it states (jagged sequences of
+highly variable length, section 2.3; maximum lengths of 3K to 16K, table 1;
+CP sizes 2/4/8) and stand in for it.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import Dict, List, Optional
+
+import numpy as np
+import torch
+
+
+@dataclass(frozen=True)
+class Workload:
+    name: str
+    lengths: tuple          # per-sequence lengths
+    num_heads: int
+    d_qk: int
+    d_v: int
+    max_len: int            # the 1/max_len normaliser
+    dtype: str              # "bf16" | "f32"
+    scale: float            # values ~ N(0,1) * scale
+    seed: int               # torch generator seed for the values
+    backward: bool
+    cp_size: int = 0        # > 0: context-parallel emulation with this many ranks
+
+    @property
+    def batch(self) -> int:
+        return len(self.lengths)
+
+    @property
+    def total_rows(self) -> int:
+        return int(sum(self.lengths))
+
+    @property
+    def alpha(self) -> float:
+        return 1.0 / float(np.sqrt(self.d_qk))
+
+    @property
+    def pairs_per_head(self) -> int:
+        """Causally visible (query, key) pairs of one head."""
+        return int(sum(l * (l + 1) // 2 for l in self.lengths))
+
+    def seq_offsets(self) -> np.ndarray:
+        return np.concatenate([[0], np.cumsum(self.lengths)]).astype(np.int32)
+
+    def flops(self, backward: Optional[bool] = None) -> Dict[str, float]:
+        """Algorithmic flops over visible pairs only (d = d_qk = d_v case generalised).
+
+        forward: 2*d_qk (QK^T) + 2*d_v (PV) per pair; backward: S recompute
+        2*d_qk, dP 2*d_v, dV 2*d_v, dK 2*d_qk, dQ 2*d_qk per pair.
+        """
+        pairs = self.pairs_per_head * self.num_heads
+        f = (2 * self.d_qk + 2 * self.d_v) * pairs
+        b = (6 * self.d_qk + 4 * self.d_v) * pairs
+        return {"fwd": float(f), "bwd": float(b)}
+
+
+def _lengths(cfg: int) -> List[int]:
+    rng = np.random.default_rng(0)
+    if cfg == 1:
+        return [int(x) for x in rng.integers(1, 64, endpoint=True, size=4)]
+    if cfg == 2:
+        return [int(x) for x in rng.integers(1, 1024, endpoint=True, size=32)]
+    if cfg == 3:
+        return [int(x) for x in rng.integers(512, 4096, endpoint=True, size=16)]
+    if cfg == 4:
+        raw = rng.integers(4096, 16384, endpoint=True, size=8)
+        return [int((x + 7) // 8 * 8) for x in raw]
+    if cfg == 5:
+        raw = rng.lognormal(np.log(8192.0), 0.8, 8)
+        return [int(x) for x in np.clip(np.rint(raw), 64, 32768)]
+    raise ValueError("unknown config %r" % (cfg,))
+
+
+# Lengths the generators above must reproduce (the workload is pinned: a numpy
+# change that altered the stream would otherwise silently change the benchmark).
+_PINNED = {
+    1: (55, 41, 33, 18),
+    4: (14552, 11928, 10384, 7416, 7880, 4600, 5024, 4304),
+    5: (9059, 7370, 13674, 8909, 5337, 10940, 23251, 17476),
+}
+_PINNED_TOTAL = {1: 147, 2: 17286, 3: 37117, 4: 66088, 5: 96016}
+
+
+def config(cfg: int) -> Workload:
+    """The five benchmark/test configurations, numbered from 1."""
+    lengths = tuple(_lengths(cfg))
+    if cfg in _PINNED:
+        assert lengths == _PINNED[cfg], "config %d lengths changed: %r" % (cfg, lengths)
+    assert sum(lengths) == _PINNED_TOTAL[cfg], "config %d total rows changed" % cfg
+    if cfg == 1:
+        return Workload("cfg1_tiny_f32", lengths, 2, 32, 32, 64, "f32", 1.0, 2, True)
+    if cfg == 2:
+        return Workload("cfg2_fwd_B32_L1-1024", lengths, 4, 128, 128, 1024, "bf16", 0.5, 3, False)
+    if cfg == 3:
+        return Workload("cfg3_B16_L512-4096", lengths, 4, 128, 128, 4096, "bf16", 0.5, 4, True)
+    if cfg == 4:
+        return Workload("cfg4_cp4_B8_L4096-16384", lengths, 4, 128, 128, 16384, "bf16", 0.5, 5,
+                        True, cp_size=4)
+    return Workload("cfg5_skewed_B8_lognormal", lengths, 8, 128, 128, 32768, "bf16", 0.5, 6, True)
+
+
+def custom(name: str, lengths, num_heads: int, d_qk: int, d_v: int, max_len: int,
+           dtype: str = "bf16", scale: float = 0.5, seed: int = 0, backward: bool = True,
+           cp_size: int = 0) -> Workload:
+    return Workload(name, tuple(int(x) for x in lengths), num_heads, d_qk, d_v, max_len, dtype,
+                    scale, seed, backward, cp_size)
+
+
+def torch_dtype(w: Workload) -> torch.dtype:
+    return torch.bfloat16 if w.dtype == "bf16" else torch.float32
+
+
+def values(w: Workload) -> Dict[str, torch.Tensor]:
+    """q, k, v, d_o on the CPU in the workload's storage dtype (rounded once)."""
+    g = torch.Generator(device="cpu").manual_seed(w.seed)
+    T, H = w.total_rows, w.num_heads
+    out = {}
+    for name, d in (("q", w.d_qk), ("k", w.d_qk), ("v", w.d_v), ("d_o", w.d_v)):
+        x = torch.randn((T, H, d), generator=g, dtype=torch.float32) * w.scale
+        out[name] = x.to(torch_dtype(w))
+    return out
+
+
+def to_f64(t: torch.Tensor) -> np.ndarray:
+    """Exact widening of stored values (bf16 or fp32) to float64 for the oracle."""
+    return t.detach().cpu().to(torch.float64).numpy()
