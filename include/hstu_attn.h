@@ -1,0 +1,174 @@
+/*
+ * hstu_attn.h -- C ABI of the MI355X (gfx950) jagged HSTU attention library.
+ *
+ * The operation is the HSTU attention of the paper's section 2.1,
+ *
+ *     O = Mask( SiLU( alpha * Q K^T ) ) V / max_len
+ *
+ * with the bias term absent, SiLU(x) = x * sigmoid(x) applied pointwise, the
+ * mask applied outside the SiLU (a masked pair contributes exactly zero), and
+ * a plain 1/max_len normaliser (max_len = 1 gives the equation as printed).
+ * Inputs are jagged tensors in the sense of section 2.2: a `values` buffer of
+ * all sequences' rows back to back plus an int32 `seq_offsets` array; nothing
+ * is padded.  The context-parallel entry point computes one rank's share under
+ * the load-balanced split of section 2.3 (2*CP mini-chunks per sequence, rank r
+ * owns mini-chunks r and 2*CP-1-r).  Because the nonlinearity is pointwise,
+ * partial results over different key sets simply add.
+ *
+ * Conventions common to all entry points
+ *   - Every data pointer is DEVICE memory owned by the caller; `seq_offsets`
+ *     is device memory too and is never read by the host, so no call forces a
+ *     host/device synchronisation (section 3 reports the cost of such syncs).
+ *   - Layouts: q, k, dq, dk: [rows, num_heads, d_qk]; v, o, d_o, dv:
+ *     [rows, num_heads, d_v]; row-major, contiguous.  Row t belongs to sequence
+ *     b iff seq_offsets[b] <= t < seq_offsets[b+1]; seq_offsets[0] == 0,
+ *     non-decreasing, seq_offsets[batch] == total_rows.  Rows at or beyond the
+ *     row counts declared by the caller are never touched, even when the
+ *     offsets on the device say otherwise.
+ *   - All inputs of one call share `dtype`, all outputs share `out_dtype`.
+ *     bf16 inputs are computed with bf16 MFMA operands and fp32 accumulation,
+ *     the SiLU in fp32, and one rounding to bf16 at the output (none when
+ *     out_dtype is fp32); fp32 inputs are computed in fp32 throughout.
+ *   - `workspace` is caller-owned device scratch of at least
+ *     hstu_jagged_attn_workspace_bytes() bytes, 256-byte aligned.  The library
+ *     allocates nothing and keeps no state between calls; calls are
+ *     asynchronous on `hip_stream` (a hipStream_t, NULL = the default stream)
+ *     and calls on different streams with different workspaces may overlap.
+ *   - Return value: HSTU_OK (0) or a negative hstu_status.  Nothing is launched
+ *     when an error is returned.  batch == 0 or total_rows == 0 is HSTU_OK and
+ *     launches nothing.  No exception or abort crosses this boundary.
+ */
+#ifndef HSTU_ATTN_H_
+#define HSTU_ATTN_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  HSTU_OK = 0,
+  HSTU_ERR_NULL_PTR = -1,            /* a required pointer is NULL                         */
+  HSTU_ERR_BAD_SHAPE = -2,           /* batch < 0, num_heads < 1, total_rows < 0 or
+                                        >= 2^31, max_len < 1, alpha not finite              */
+  HSTU_ERR_UNSUPPORTED = -3,         /* head dim not in {32,64,128}, unknown dtype, out_dtype
+                                        neither dtype nor fp32, reserved != 0               */
+  HSTU_ERR_WORKSPACE_TOO_SMALL = -4, /* workspace_bytes below the query function's answer   */
+  HSTU_ERR_BAD_CP = -5,              /* cp_size < 1, a rank out of range, negative rows     */
+  HSTU_ERR_HIP = -6,                 /* a HIP call failed; hipGetLastError() is left intact */
+  HSTU_ERR_MISALIGNED = -7           /* a data pointer is not 16-byte aligned               */
+} hstu_status;
+
+typedef enum { HSTU_BF16 = 0, HSTU_F32 = 1 } hstu_dtype;
+
+typedef enum { HSTU_WS_FWD = 0, HSTU_WS_BWD = 1, HSTU_WS_CP = 2 } hstu_ws_kind;
+
+/* Problem description (section 2.1 for alpha and the mask, section 2.2 for the
+ * jagged batch).  `total_rows` is passed by value so that grids and workspaces
+ * can be sized without reading seq_offsets. */
+typedef struct {
+  int32_t batch;       /* B >= 0: number of sequences                                      */
+  int32_t num_heads;   /* H >= 1: independent heads                                        */
+  int32_t d_qk;        /* 32, 64 or 128                                                    */
+  int32_t d_v;         /* 32, 64 or 128                                                    */
+  int32_t max_len;     /* N >= 1: the normaliser 1/N; lengths above it are still computed  */
+  float alpha;         /* scale inside the SiLU; the paper's 1/sqrt(d_k)                   */
+  int32_t causal;      /* 1: key j visible to query i iff j <= i (in-sequence positions);
+                          0: every key of the same sequence is visible                    */
+  int32_t dtype;       /* hstu_dtype of the input tensors q, k, v, d_o                     */
+  int64_t total_rows;  /* T = seq_offsets[batch], 0 <= T < 2^31                            */
+  int32_t out_dtype;   /* hstu_dtype of the outputs o, dq, dk, dv: equal to dtype, or
+                          HSTU_F32 to receive the fp32 accumulators unrounded (also the
+                          precise choice for accumulate = 1 over several ring steps)      */
+  int32_t reserved;    /* must be 0                                                        */
+} hstu_attn_params;
+
+/* One context-parallel step (section 2.3).  Local layout of rank r: for every
+ * sequence in order, the rows of mini-chunk r followed by the rows of
+ * mini-chunk 2*cp_size-1-r, where mini-chunk m of a sequence of length L holds
+ * in-sequence positions [m*c, min((m+1)*c, L)) with c = ceil(L / (2*cp_size));
+ * tail chunks may be short or empty and no padding row exists anywhere. */
+typedef struct {
+  int32_t cp_size;     /* CP >= 1                                                          */
+  int32_t q_rank;      /* 0..CP-1: the rank whose query rows q_local holds                 */
+  int32_t kv_rank;     /* 0..CP-1: k_part/v_part hold that rank's rows in local layout;
+                          -1: they hold every row in the global (seq_offsets) layout      */
+  int32_t accumulate;  /* 0: outputs are overwritten; 1: results are added to the outputs'
+                          current contents (one ring step on top of the previous ones)    */
+  int64_t q_rows;      /* rows in q_local / d_o_local / o_local / dq_local                 */
+  int64_t kv_rows;     /* rows in k_part / v_part / dk_part / dv_part                      */
+} hstu_cp_desc;
+
+/* Forward over the whole jagged batch (section 2.1 equation, section 2.2 layout).
+ *   q, k : [T, H, d_qk]   v : [T, H, d_v]   seq_offsets : int32 [B+1]   (inputs)
+ *   o    : [T, H, d_v]    (output; every row of every sequence is written once, nothing else)
+ */
+int hstu_jagged_attn_fwd(const hstu_attn_params* params, const void* q, const void* k,
+                         const void* v, const int32_t* seq_offsets, void* o, void* workspace,
+                         size_t workspace_bytes, void* hip_stream);
+
+/* Backward: exact gradients of sum(O * d_o) with respect to q, k, v.  S is
+ * recomputed from q and k; no forward output or statistic is needed because the
+ * SiLU is pointwise.  dk and dv are accumulated per key tile without atomics;
+ * dq is produced by a second pass over key tiles, so results are deterministic.
+ *   d_o : [T, H, d_v] (input)    dq, dk : [T, H, d_qk]   dv : [T, H, d_v] (outputs)
+ */
+int hstu_jagged_attn_bwd(const hstu_attn_params* params, const void* q, const void* k,
+                         const void* v, const void* d_o, const int32_t* seq_offsets, void* dq,
+                         void* dk, void* dv, void* workspace, size_t workspace_bytes,
+                         void* hip_stream);
+
+/* One context-parallel rank's partial (section 2.3): the query rows of
+ * `q_rank` against the keys of `kv_rank` (or all keys), masked on positions
+ * inside the whole sequence, every visible (query chunk, key chunk) pair in one
+ * launch.  `params->total_rows` and `seq_offsets_global` describe the full,
+ * unsplit batch.
+ *   q_local [q_rows,H,d_qk], k_part [kv_rows,H,d_qk], v_part [kv_rows,H,d_v]   (inputs)
+ *   d_o_local [q_rows,H,d_v] or NULL for forward only
+ *   o_local [q_rows,H,d_v] (output, may be NULL when d_o_local is given)
+ *   dq_local [q_rows,H,d_qk], dk_part [kv_rows,H,d_qk], dv_part [kv_rows,H,d_v]
+ *       (outputs, required iff d_o_local != NULL)
+ * Summing o_local (dq_local) over kv_rank = 0..CP-1 gives q_rank's rows of the
+ * full result; summing dk_part (dv_part) over q_rank gives kv_rank's rows.
+ */
+int hstu_jagged_attn_cp_partial(const hstu_attn_params* params, const hstu_cp_desc* cp,
+                                const void* q_local, const void* k_part, const void* v_part,
+                                const void* d_o_local, const int32_t* seq_offsets_global,
+                                void* o_local, void* dq_local, void* dk_part, void* dv_part,
+                                void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Bytes of workspace the given entry point needs for `params` (an upper bound
+ * that depends on batch, total_rows and num_heads only; 0 on invalid params).
+ * `which` is a hstu_ws_kind. */
+size_t hstu_jagged_attn_workspace_bytes(const hstu_attn_params* params, int which);
+
+/* Host-side check of an offsets array the caller still has on the host:
+ * HSTU_OK iff host_offsets[0] == 0, non-decreasing, host_offsets[batch] == total_rows. */
+int hstu_validate_offsets_host(const int32_t* host_offsets, int32_t batch, int64_t total_rows);
+
+/* Static, NUL-terminated description of a status code. */
+const char* hstu_attn_status_string(int status);
+
+/* ---- schedule inspection (for tests of the tile table, section 2.2 / 2.3) -------------------
+ * Builds on the device, exactly as the attention entry points do, the table of work items for
+ * one side of a problem and copies it to host memory (this call synchronises the stream).
+ *   side: 0 = items are query tiles streaming over key segments (forward, dq pass)
+ *         1 = items are key tiles streaming over query segments (dk/dv pass)
+ *   cp == NULL: whole-batch attention; else the context-parallel problem it describes
+ *   items_host: room for max_items * 12 int32; per item
+ *       {row0, nrows, pos0, nseg, seg_row0[2], seg_len[2], seg_pos0[2], cost, 0}
+ *   returns the number of items (>= 0) in schedule order (non-increasing cost), or a status < 0.
+ */
+int hstu_debug_dump_schedule(const hstu_attn_params* params, const hstu_cp_desc* cp, int side,
+                             const int32_t* seq_offsets, int32_t* items_host, int32_t max_items,
+                             void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Rows per work item on the given side for `params` (tile height used by the schedule). */
+int hstu_schedule_tile_rows(const hstu_attn_params* params, int side);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HSTU_ATTN_H_ */

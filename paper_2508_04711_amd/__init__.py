@@ -1,0 +1,17 @@
+"""MI355X (gfx950) jagged HSTU attention: thin Python binding over the C-ABI HIP library.
+
+Everything is computed by the HIP kernels in csrc/; this package only marshals arguments.
+"""
+from .binding import (  # noqa: F401
+    HstuError,
+    hstu_attn_status_string,
+    hstu_debug_dump_schedule,
+    hstu_jagged_attn_bwd,
+    hstu_jagged_attn_cp_partial,
+    hstu_jagged_attn_fwd,
+    hstu_jagged_attn_workspace_bytes,
+    hstu_schedule_tile_rows,
+    hstu_validate_offsets_host,
+    library_path,
+    load_library,
+)

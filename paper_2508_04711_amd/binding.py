@@ -1,0 +1,295 @@
+"""ctypes binding of libhstu_attn.so: same names as the C entry points, marshalling only.
+
+PyTorch appears here for device memory and streams alone: tensors are allocated by the
+caller (or here, for outputs and workspace) and handed to the library as raw pointers.
+There is no fallback path: if the HIP library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libhstu_attn.so")
+_lib = None
+
+HSTU_BF16, HSTU_F32 = 0, 1
+HSTU_WS_FWD, HSTU_WS_BWD, HSTU_WS_CP = 0, 1, 2
+
+
+class HstuError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s: %s (status %d)" % (where, hstu_attn_status_string(status), status))
+
+
+class _Params(ctypes.Structure):
+    _fields_ = [
+        ("batch", ctypes.c_int32), ("num_heads", ctypes.c_int32), ("d_qk", ctypes.c_int32),
+        ("d_v", ctypes.c_int32), ("max_len", ctypes.c_int32), ("alpha", ctypes.c_float),
+        ("causal", ctypes.c_int32), ("dtype", ctypes.c_int32), ("total_rows", ctypes.c_int64),
+        ("out_dtype", ctypes.c_int32), ("reserved", ctypes.c_int32),
+    ]
+
+
+class _CpDesc(ctypes.Structure):
+    _fields_ = [
+        ("cp_size", ctypes.c_int32), ("q_rank", ctypes.c_int32), ("kv_rank", ctypes.c_int32),
+        ("accumulate", ctypes.c_int32), ("q_rows", ctypes.c_int64), ("kv_rows", ctypes.c_int64),
+    ]
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Loads the built HIP library; raises if it has not been built (no CPU fallback exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError(
+            "libhstu_attn.so is not built: run `python -c 'import __graft_entry__ as g; g.build()'`"
+            " (or paper_2508_04711_amd/build.py) first; there is no fallback implementation")
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, i32p = ctypes.c_void_p, ctypes.c_void_p
+    pp = ctypes.POINTER(_Params)
+    lib.hstu_jagged_attn_fwd.restype = ctypes.c_int
+    lib.hstu_jagged_attn_fwd.argtypes = [pp, vp, vp, vp, i32p, vp, vp, ctypes.c_size_t, vp]
+    lib.hstu_jagged_attn_bwd.restype = ctypes.c_int
+    lib.hstu_jagged_attn_bwd.argtypes = [pp, vp, vp, vp, vp, i32p, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.hstu_jagged_attn_cp_partial.restype = ctypes.c_int
+    lib.hstu_jagged_attn_cp_partial.argtypes = [pp, ctypes.POINTER(_CpDesc), vp, vp, vp, vp, i32p,
+                                                vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.hstu_jagged_attn_workspace_bytes.restype = ctypes.c_size_t
+    lib.hstu_jagged_attn_workspace_bytes.argtypes = [pp, ctypes.c_int]
+    lib.hstu_validate_offsets_host.restype = ctypes.c_int
+    lib.hstu_validate_offsets_host.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64]
+    lib.hstu_attn_status_string.restype = ctypes.c_char_p
+    lib.hstu_attn_status_string.argtypes = [ctypes.c_int]
+    lib.hstu_debug_dump_schedule.restype = ctypes.c_int
+    lib.hstu_debug_dump_schedule.argtypes = [pp, ctypes.POINTER(_CpDesc), ctypes.c_int, i32p,
+                                             ctypes.c_void_p, ctypes.c_int32, vp, ctypes.c_size_t, vp]
+    lib.hstu_schedule_tile_rows.restype = ctypes.c_int
+    lib.hstu_schedule_tile_rows.argtypes = [pp, ctypes.c_int]
+    _lib = lib
+    return lib
+
+
+def hstu_attn_status_string(status: int) -> str:
+    return load_library().hstu_attn_status_string(int(status)).decode()
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.bfloat16:
+        return HSTU_BF16
+    if t.dtype == torch.float32:
+        return HSTU_F32
+    raise TypeError("unsupported dtype %s" % t.dtype)
+
+
+def _params(batch, num_heads, d_qk, d_v, max_len, alpha, causal, dtype_code, total_rows,
+            out_dtype_code=None) -> _Params:
+    return _Params(int(batch), int(num_heads), int(d_qk), int(d_v), int(max_len), float(alpha),
+                   int(bool(causal)), int(dtype_code), int(total_rows),
+                   int(dtype_code if out_dtype_code is None else out_dtype_code), 0)
+
+
+def _out_dtype(in_dtype: torch.dtype, out_dtype: Optional[torch.dtype]) -> torch.dtype:
+    return in_dtype if out_dtype is None else out_dtype
+
+
+def _code(dt: torch.dtype) -> int:
+    if dt == torch.bfloat16:
+        return HSTU_BF16
+    if dt == torch.float32:
+        return HSTU_F32
+    raise TypeError("unsupported dtype %s" % dt)
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return ctypes.c_void_p(t.data_ptr()) if t is not None else None
+
+
+def _stream(stream) -> ctypes.c_void_p:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _check_tensor(t: torch.Tensor, name: str, rows: int, heads: int, dim: int, dtype) -> None:
+    if not t.is_cuda:
+        raise ValueError("%s must be a device tensor" % name)
+    if not t.is_contiguous():
+        raise ValueError("%s must be contiguous" % name)
+    if tuple(t.shape) != (rows, heads, dim) or t.dtype != dtype:
+        raise ValueError("%s: expected %s %s, got %s %s" % (name, (rows, heads, dim), dtype,
+                                                          tuple(t.shape), t.dtype))
+
+
+def _workspace(params: _Params, which: int, workspace: Optional[torch.Tensor], device) -> torch.Tensor:
+    need = hstu_jagged_attn_workspace_bytes(params, which)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=device)
+    return workspace
+
+
+def hstu_jagged_attn_workspace_bytes(params_or_tuple, which: int) -> int:
+    """Bytes of device workspace the entry point `which` (0 fwd, 1 bwd, 2 cp) needs."""
+    p = params_or_tuple if isinstance(params_or_tuple, _Params) else _params(*params_or_tuple)
+    return int(load_library().hstu_jagged_attn_workspace_bytes(ctypes.byref(p), int(which)))
+
+
+def hstu_validate_offsets_host(host_offsets, total_rows: int) -> int:
+    off = np.ascontiguousarray(host_offsets, dtype=np.int32)
+    return int(load_library().hstu_validate_offsets_host(
+        off.ctypes.data_as(ctypes.c_void_p), len(off) - 1, int(total_rows)))
+
+
+def hstu_jagged_attn_fwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor,
+                         seq_offsets: torch.Tensor, max_len: int, alpha: float, causal: bool = True,
+                         out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                         stream=None, out_dtype: Optional[torch.dtype] = None) -> torch.Tensor:
+    """O = Mask(SiLU(alpha Q K^T)) V / max_len over a jagged batch; q,k: [T,H,d_qk], v: [T,H,d_v].
+
+    out_dtype: dtype of the result (default: the inputs'; torch.float32 keeps the accumulators).
+    """
+    T, H, dqk = q.shape
+    dv = v.shape[2]
+    _check_tensor(q, "q", T, H, dqk, q.dtype); _check_tensor(k, "k", T, H, dqk, q.dtype)
+    _check_tensor(v, "v", T, H, dv, q.dtype)
+    if seq_offsets.dtype != torch.int32 or not seq_offsets.is_cuda or not seq_offsets.is_contiguous():
+        raise ValueError("seq_offsets must be a contiguous int32 device tensor")
+    B = seq_offsets.numel() - 1
+    odt = out.dtype if out is not None else _out_dtype(q.dtype, out_dtype)
+    if out is None:
+        out = torch.empty((T, H, dv), dtype=odt, device=q.device)
+    else:
+        _check_tensor(out, "out", T, H, dv, odt)
+    p = _params(B, H, dqk, dv, max_len, alpha, causal, _dtype_code(q), T, _code(odt))
+    ws = _workspace(p, HSTU_WS_FWD, workspace, q.device)
+    rc = load_library().hstu_jagged_attn_fwd(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v),
+                                             _ptr(seq_offsets), _ptr(out), _ptr(ws), ws.numel(),
+                                             _stream(stream))
+    if rc != 0:
+        raise HstuError(rc, "hstu_jagged_attn_fwd")
+    return out
+
+
+def hstu_jagged_attn_bwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, d_o: torch.Tensor,
+                         seq_offsets: torch.Tensor, max_len: int, alpha: float, causal: bool = True,
+                         out: Optional[Tuple[torch.Tensor, torch.Tensor, torch.Tensor]] = None,
+                         workspace: Optional[torch.Tensor] = None, stream=None,
+                         out_dtype: Optional[torch.dtype] = None
+                         ) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:
+    """(dQ, dK, dV) of sum(O * d_o) for the forward above."""
+    T, H, dqk = q.shape
+    dv = v.shape[2]
+    _check_tensor(q, "q", T, H, dqk, q.dtype); _check_tensor(k, "k", T, H, dqk, q.dtype)
+    _check_tensor(v, "v", T, H, dv, q.dtype); _check_tensor(d_o, "d_o", T, H, dv, q.dtype)
+    if seq_offsets.dtype != torch.int32 or not seq_offsets.is_cuda or not seq_offsets.is_contiguous():
+        raise ValueError("seq_offsets must be a contiguous int32 device tensor")
+    B = seq_offsets.numel() - 1
+    odt = out[0].dtype if out is not None else _out_dtype(q.dtype, out_dtype)
+    if out is None:
+        dq = torch.empty_like(q, dtype=odt); dk = torch.empty_like(k, dtype=odt)
+        dvv = torch.empty_like(v, dtype=odt)
+    else:
+        dq, dk, dvv = out
+        _check_tensor(dq, "dq", T, H, dqk, odt); _check_tensor(dk, "dk", T, H, dqk, odt)
+        _check_tensor(dvv, "dv", T, H, dv, odt)
+    p = _params(B, H, dqk, dv, max_len, alpha, causal, _dtype_code(q), T, _code(odt))
+    ws = _workspace(p, HSTU_WS_BWD, workspace, q.device)
+    rc = load_library().hstu_jagged_attn_bwd(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(d_o),
+                                             _ptr(seq_offsets), _ptr(dq), _ptr(dk), _ptr(dvv),
+                                             _ptr(ws), ws.numel(), _stream(stream))
+    if rc != 0:
+        raise HstuError(rc, "hstu_jagged_attn_bwd")
+    return dq, dk, dvv
+
+
+def hstu_jagged_attn_cp_partial(q_local: torch.Tensor, k_part: torch.Tensor, v_part: torch.Tensor,
+                                d_o_local: Optional[torch.Tensor], seq_offsets_global: torch.Tensor,
+                                total_rows: int, max_len: int, alpha: float, causal: bool,
+                                cp_size: int, q_rank: int, kv_rank: int, accumulate: bool = False,
+                                out: Optional[tuple] = None, want_o: bool = True,
+                                workspace: Optional[torch.Tensor] = None, stream=None,
+                                out_dtype: Optional[torch.dtype] = None):
+    """One context-parallel rank's partial: returns (o_local, dq_local, dk_part, dv_part).
+
+    The gradients are None when d_o_local is None; o_local is None when want_o is False.
+    `out` may pass the four output tensors (required when accumulate is set).
+    """
+    nq, H, dqk = q_local.shape
+    nk, _, dv = v_part.shape
+    dt = q_local.dtype
+    _check_tensor(q_local, "q_local", nq, H, dqk, dt); _check_tensor(k_part, "k_part", nk, H, dqk, dt)
+    _check_tensor(v_part, "v_part", nk, H, dv, dt)
+    if d_o_local is not None:
+        _check_tensor(d_o_local, "d_o_local", nq, H, dv, dt)
+    so = seq_offsets_global
+    if so.dtype != torch.int32 or not so.is_cuda or not so.is_contiguous():
+        raise ValueError("seq_offsets_global must be a contiguous int32 device tensor")
+    B = so.numel() - 1
+    odt = _out_dtype(dt, out_dtype)
+    if out is not None:
+        o, dq, dk, dvv = out
+        first = next(t for t in out if t is not None)
+        odt = first.dtype
+        for t, name, rows, dim in ((o, "o_local", nq, dv), (dq, "dq_local", nq, dqk),
+                                   (dk, "dk_part", nk, dqk), (dvv, "dv_part", nk, dv)):
+            if t is not None:
+                _check_tensor(t, name, rows, H, dim, odt)
+    else:
+        if accumulate:
+            raise ValueError("accumulate needs the outputs to add to")
+        o = torch.empty((nq, H, dv), dtype=odt, device=q_local.device) if want_o else None
+        if d_o_local is not None:
+            dq = torch.empty_like(q_local, dtype=odt); dk = torch.empty_like(k_part, dtype=odt)
+            dvv = torch.empty_like(v_part, dtype=odt)
+        else:
+            dq = dk = dvv = None
+    p = _params(B, H, dqk, dv, max_len, alpha, causal, _dtype_code(q_local), total_rows, _code(odt))
+    desc = _CpDesc(int(cp_size), int(q_rank), int(kv_rank), int(bool(accumulate)), int(nq), int(nk))
+    ws = _workspace(p, HSTU_WS_CP, workspace, q_local.device)
+    rc = load_library().hstu_jagged_attn_cp_partial(
+        ctypes.byref(p), ctypes.byref(desc), _ptr(q_local), _ptr(k_part), _ptr(v_part),
+        _ptr(d_o_local), _ptr(so), _ptr(o), _ptr(dq), _ptr(dk), _ptr(dvv), _ptr(ws), ws.numel(),
+        _stream(stream))
+    if rc != 0:
+        raise HstuError(rc, "hstu_jagged_attn_cp_partial")
+    return o, dq, dk, dvv
+
+
+def hstu_schedule_tile_rows(dtype_code: int, d_qk: int, d_v: int, side: int) -> int:
+    p = _params(1, 1, d_qk, d_v, 1, 1.0, True, dtype_code, 1)
+    return int(load_library().hstu_schedule_tile_rows(ctypes.byref(p), int(side)))
+
+
+def hstu_debug_dump_schedule(seq_offsets: torch.Tensor, total_rows: int, num_heads: int, d_qk: int,
+                             d_v: int, causal: bool, dtype_code: int, side: int,
+                             cp: Optional[Tuple[int, int, int, int, int]] = None) -> np.ndarray:
+    """The device-built schedule as an int32 array [n_items, 12] in schedule order.
+
+    cp = (cp_size, q_rank, kv_rank, q_rows, kv_rows) for a context-parallel problem.
+    """
+    B = seq_offsets.numel() - 1
+    p = _params(B, num_heads, d_qk, d_v, 1, 1.0, causal, dtype_code, total_rows)
+    desc = None
+    if cp is not None:
+        desc = _CpDesc(int(cp[0]), int(cp[1]), int(cp[2]), 0, int(cp[3]), int(cp[4]))
+    ws = _workspace(p, HSTU_WS_CP if cp is not None else HSTU_WS_FWD, None, seq_offsets.device)
+    max_items = int(total_rows) // 32 + 2 * B + 8
+    buf = np.zeros((max_items, 12), dtype=np.int32)
+    n = load_library().hstu_debug_dump_schedule(
+        ctypes.byref(p), ctypes.byref(desc) if desc is not None else None, int(side),
+        _ptr(seq_offsets), buf.ctypes.data_as(ctypes.c_void_p), max_items, _ptr(ws), ws.numel(),
+        _stream(None))
+    if n < 0:
+        raise HstuError(n, "hstu_debug_dump_schedule")
+    return buf[:n].copy()

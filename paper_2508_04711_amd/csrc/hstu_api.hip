@@ -1,0 +1,358 @@
+// C ABI of the jagged HSTU attention library: argument checks, workspace carving, launches.
+// See include/hstu_attn.h for the contract of every entry point.
+#include <cmath>
+#include <vector>
+
+#include "../../include/hstu_attn.h"
+#include "hstu_common.h"
+
+namespace {
+
+using namespace hstu;
+
+bool dim_ok(int d) { return d == 32 || d == 64 || d == 128; }
+
+int check_params(const hstu_attn_params* p) {
+  if (!p) return HSTU_ERR_NULL_PTR;
+  if (p->batch < 0 || p->num_heads < 1 || p->total_rows < 0 || p->total_rows >= (1ll << 31) ||
+      p->max_len < 1 || !std::isfinite(p->alpha))
+    return HSTU_ERR_BAD_SHAPE;
+  if (!dim_ok(p->d_qk) || !dim_ok(p->d_v)) return HSTU_ERR_UNSUPPORTED;
+  if (p->dtype != HSTU_BF16 && p->dtype != HSTU_F32) return HSTU_ERR_UNSUPPORTED;
+  if (p->out_dtype != p->dtype && p->out_dtype != HSTU_F32) return HSTU_ERR_UNSUPPORTED;
+  if (p->reserved != 0) return HSTU_ERR_UNSUPPORTED;
+  return HSTU_OK;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int tile_rows(int dtype, int pass) {
+  return dtype == HSTU_BF16 ? tile_rows_bf16(pass) : tile_rows_f32(pass);
+}
+
+// One schedule: who owns, who is streamed, how many rows each side's buffers hold.
+struct SideSpec {
+  int side;           // 0: owners are queries, 1: owners are keys
+  int pass;           // which kernel family consumes it (tile height)
+  int owner_rank, streamed_rank;
+  int64_t owner_rows, streamed_rows;
+  int segs;           // segments per sequence on the owner side (1 global, 2 rank-local)
+};
+
+struct BuiltPlan {
+  Plan plan;
+  int64_t max_items;
+  size_t end;
+};
+
+int64_t items_bound(const hstu_attn_params* p, const SideSpec& s) {
+  return max_items_bound(s.owner_rows, p->batch, s.segs, tile_rows(p->dtype, s.pass));
+}
+
+size_t plan_bytes(const hstu_attn_params* p, const SideSpec& s, size_t base) {
+  return plan_layout(base, p->batch, items_bound(p, s)).end;
+}
+
+// Carves one schedule out of the workspace at byte offset `base` and launches its build.
+int build_plan(const hstu_attn_params* p, int cp_size, const SideSpec& s, const int32_t* off,
+               char* ws, size_t ws_bytes, size_t base, hipStream_t stream, BuiltPlan* out) {
+  const int64_t max_items = items_bound(p, s);
+  if (max_items * p->num_heads >= (1ll << 31)) return HSTU_ERR_BAD_SHAPE;
+  const PlanLayout l = plan_layout(base, p->batch, max_items);
+  if (l.end > ws_bytes) return HSTU_ERR_WORKSPACE_TOO_SMALL;
+  PlanArgs a;
+  a.off = off;
+  a.batch = p->batch;
+  a.total_rows = (int32_t)p->total_rows;
+  a.cp = cp_size;
+  a.owner_rank = s.owner_rank;
+  a.streamed_rank = s.streamed_rank;
+  a.side = s.side;
+  a.tile = tile_rows(p->dtype, s.pass);
+  a.causal = p->causal ? 1 : 0;
+  a.owner_rows = (int32_t)s.owner_rows;
+  a.streamed_rows = (int32_t)s.streamed_rows;
+  a.max_items = (int32_t)max_items;
+  int shift = 0;
+  while (((s.streamed_rows / 32 + 4) >> shift) >= 2048) ++shift;
+  a.cost_shift = shift;
+  a.header = reinterpret_cast<int32_t*>(ws + l.header);
+  a.owner_base = reinterpret_cast<int32_t*>(ws + l.owner_base);
+  a.streamed_base = reinterpret_cast<int32_t*>(ws + l.streamed_base);
+  a.tile_base = reinterpret_cast<int32_t*>(ws + l.tile_base);
+  a.order = reinterpret_cast<int32_t*>(ws + l.order);
+  a.items = reinterpret_cast<Item*>(ws + l.items);
+  if (launch_plan(a, stream) != hipSuccess) return HSTU_ERR_HIP;
+  out->plan.header = a.header;
+  out->plan.order = a.order;
+  out->plan.items = a.items;
+  out->max_items = max_items;
+  out->end = l.end;
+  return HSTU_OK;
+}
+
+AttnArgs base_args(const hstu_attn_params* p, const BuiltPlan& bp, int accumulate) {
+  AttnArgs a = {};
+  a.plan = bp.plan;
+  a.num_heads = p->num_heads;
+  a.causal = p->causal ? 1 : 0;
+  a.accumulate = accumulate;
+  a.max_items = (int32_t)bp.max_items;
+  a.out_f32 = p->out_dtype == HSTU_F32 ? 1 : 0;
+  a.alpha = p->alpha;
+  a.inv_n = 1.0f / (float)p->max_len;
+  return a;
+}
+
+int run_pass(const hstu_attn_params* p, int pass, const AttnArgs& a, hipStream_t stream) {
+  hipError_t e;
+  if (p->dtype == HSTU_BF16) {
+    e = pass == PASS_FWD ? launch_fwd_bf16(a, p->d_qk, p->d_v, stream)
+        : pass == PASS_DKDV ? launch_dkdv_bf16(a, p->d_qk, p->d_v, stream)
+                            : launch_dq_bf16(a, p->d_qk, p->d_v, stream);
+  } else {
+    e = pass == PASS_FWD ? launch_fwd_f32(a, p->d_qk, p->d_v, stream)
+        : pass == PASS_DKDV ? launch_dkdv_f32(a, p->d_qk, p->d_v, stream)
+                            : launch_dq_f32(a, p->d_qk, p->d_v, stream);
+  }
+  return e == hipSuccess ? HSTU_OK : HSTU_ERR_HIP;
+}
+
+SideSpec full_side(const hstu_attn_params* p, int side, int pass) {
+  return SideSpec{side, pass, -1, -1, p->total_rows, p->total_rows, 1};
+}
+
+int64_t clamp_rows(int64_t rows, int64_t total) { return rows < total ? rows : total; }
+
+SideSpec cp_side(const hstu_attn_params* p, const hstu_cp_desc* cp, int side, int pass) {
+  const int64_t qr = clamp_rows(cp->q_rows, p->total_rows), kr = clamp_rows(cp->kv_rows, p->total_rows);
+  if (side == 0) return SideSpec{0, pass, cp->q_rank, cp->kv_rank, qr, kr, 2};
+  return SideSpec{1, pass, cp->kv_rank, cp->q_rank, kr, qr, cp->kv_rank < 0 ? 1 : 2};
+}
+
+int check_cp(const hstu_attn_params* p, const hstu_cp_desc* cp) {
+  if (!cp) return HSTU_ERR_NULL_PTR;
+  if (cp->cp_size < 1 || cp->q_rank < 0 || cp->q_rank >= cp->cp_size || cp->kv_rank < -1 ||
+      cp->kv_rank >= cp->cp_size || cp->q_rows < 0 || cp->kv_rows < 0 ||
+      (int64_t)cp->cp_size * 2 >= (1ll << 31))
+    return HSTU_ERR_BAD_CP;
+  (void)p;
+  return HSTU_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* hstu_attn_status_string(int status) {
+  switch (status) {
+    case HSTU_OK: return "ok";
+    case HSTU_ERR_NULL_PTR: return "a required pointer is NULL";
+    case HSTU_ERR_BAD_SHAPE: return "bad shape: batch, num_heads, total_rows, max_len or alpha out of range";
+    case HSTU_ERR_UNSUPPORTED: return "unsupported head dimension or dtype";
+    case HSTU_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
+    case HSTU_ERR_BAD_CP: return "bad context-parallel descriptor";
+    case HSTU_ERR_HIP: return "a HIP call failed";
+    case HSTU_ERR_MISALIGNED: return "a data pointer is not 16-byte aligned";
+    default: return "unknown status";
+  }
+}
+
+int hstu_validate_offsets_host(const int32_t* host_offsets, int32_t batch, int64_t total_rows) {
+  if (!host_offsets) return HSTU_ERR_NULL_PTR;
+  if (batch < 0 || total_rows < 0) return HSTU_ERR_BAD_SHAPE;
+  if (host_offsets[0] != 0) return HSTU_ERR_BAD_SHAPE;
+  for (int32_t b = 0; b < batch; ++b)
+    if (host_offsets[b + 1] < host_offsets[b]) return HSTU_ERR_BAD_SHAPE;
+  if ((int64_t)host_offsets[batch] != total_rows) return HSTU_ERR_BAD_SHAPE;
+  return HSTU_OK;
+}
+
+int hstu_schedule_tile_rows(const hstu_attn_params* params, int side) {
+  const int rc = check_params(params);
+  if (rc != HSTU_OK) return rc;
+  return tile_rows(params->dtype, side == 0 ? PASS_FWD : PASS_DKDV);
+}
+
+size_t hstu_jagged_attn_workspace_bytes(const hstu_attn_params* params, int which) {
+  if (check_params(params) != HSTU_OK) return 0;
+  size_t end = 0;
+  if (which == HSTU_WS_FWD) {
+    end = plan_bytes(params, full_side(params, 0, PASS_FWD), 0);
+  } else if (which == HSTU_WS_BWD) {
+    end = plan_bytes(params, full_side(params, 1, PASS_DKDV), 0);
+    end = plan_bytes(params, full_side(params, 0, PASS_DQ), end);
+  } else if (which == HSTU_WS_CP) {
+    // rank-local sides never hold more rows than the whole batch
+    SideSpec s{0, PASS_FWD, 0, 0, params->total_rows, params->total_rows, 2};
+    end = plan_bytes(params, s, 0);
+    s.pass = PASS_DKDV; s.side = 1;
+    end = plan_bytes(params, s, end);
+    s.pass = PASS_DQ; s.side = 0;
+    end = plan_bytes(params, s, end);
+  } else {
+    return 0;
+  }
+  return end + 256;
+}
+
+int hstu_jagged_attn_fwd(const hstu_attn_params* params, const void* q, const void* k,
+                         const void* v, const int32_t* seq_offsets, void* o, void* workspace,
+                         size_t workspace_bytes, void* hip_stream) {
+  int rc = check_params(params);
+  if (rc != HSTU_OK) return rc;
+  if (params->batch == 0 || params->total_rows == 0) return HSTU_OK;
+  if (!q || !k || !v || !o || !seq_offsets || !workspace) return HSTU_ERR_NULL_PTR;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(workspace))
+    return HSTU_ERR_MISALIGNED;
+  if (workspace_bytes < hstu_jagged_attn_workspace_bytes(params, HSTU_WS_FWD))
+    return HSTU_ERR_WORKSPACE_TOO_SMALL;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  BuiltPlan bp;
+  rc = build_plan(params, 1, full_side(params, 0, PASS_FWD), seq_offsets, (char*)workspace,
+                  workspace_bytes, 0, stream, &bp);
+  if (rc != HSTU_OK) return rc;
+  AttnArgs a = base_args(params, bp, 0);
+  a.q = q; a.k = k; a.v = v; a.o = o;
+  return run_pass(params, PASS_FWD, a, stream);
+}
+
+int hstu_jagged_attn_bwd(const hstu_attn_params* params, const void* q, const void* k,
+                         const void* v, const void* d_o, const int32_t* seq_offsets, void* dq,
+                         void* dk, void* dv, void* workspace, size_t workspace_bytes,
+                         void* hip_stream) {
+  int rc = check_params(params);
+  if (rc != HSTU_OK) return rc;
+  if (params->batch == 0 || params->total_rows == 0) return HSTU_OK;
+  if (!q || !k || !v || !d_o || !dq || !dk || !dv || !seq_offsets || !workspace)
+    return HSTU_ERR_NULL_PTR;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(d_o) || !aligned16(dq) ||
+      !aligned16(dk) || !aligned16(dv) || !aligned16(workspace))
+    return HSTU_ERR_MISALIGNED;
+  if (workspace_bytes < hstu_jagged_attn_workspace_bytes(params, HSTU_WS_BWD))
+    return HSTU_ERR_WORKSPACE_TOO_SMALL;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  BuiltPlan pk, pq;
+  rc = build_plan(params, 1, full_side(params, 1, PASS_DKDV), seq_offsets, (char*)workspace,
+                  workspace_bytes, 0, stream, &pk);
+  if (rc != HSTU_OK) return rc;
+  rc = build_plan(params, 1, full_side(params, 0, PASS_DQ), seq_offsets, (char*)workspace,
+                  workspace_bytes, pk.end, stream, &pq);
+  if (rc != HSTU_OK) return rc;
+  AttnArgs a = base_args(params, pk, 0);
+  a.q = q; a.k = k; a.v = v; a.d_o = d_o; a.dk = dk; a.dv = dv;
+  rc = run_pass(params, PASS_DKDV, a, stream);
+  if (rc != HSTU_OK) return rc;
+  AttnArgs b = base_args(params, pq, 0);
+  b.q = q; b.k = k; b.v = v; b.d_o = d_o; b.dq = dq;
+  return run_pass(params, PASS_DQ, b, stream);
+}
+
+int hstu_jagged_attn_cp_partial(const hstu_attn_params* params, const hstu_cp_desc* cp,
+                                const void* q_local, const void* k_part, const void* v_part,
+                                const void* d_o_local, const int32_t* seq_offsets_global,
+                                void* o_local, void* dq_local, void* dk_part, void* dv_part,
+                                void* workspace, size_t workspace_bytes, void* hip_stream) {
+  int rc = check_params(params);
+  if (rc != HSTU_OK) return rc;
+  rc = check_cp(params, cp);
+  if (rc != HSTU_OK) return rc;
+  if (params->batch == 0 || params->total_rows == 0) return HSTU_OK;
+  const bool backward = d_o_local != nullptr;
+  if (!q_local || !k_part || !v_part || !seq_offsets_global || !workspace) return HSTU_ERR_NULL_PTR;
+  if (!backward && !o_local) return HSTU_ERR_NULL_PTR;
+  if (backward && (!dq_local || !dk_part || !dv_part)) return HSTU_ERR_NULL_PTR;
+  const void* ptrs[] = {q_local, k_part, v_part, d_o_local, o_local, dq_local, dk_part, dv_part, workspace};
+  for (const void* ptr : ptrs)
+    if (ptr && !aligned16(ptr)) return HSTU_ERR_MISALIGNED;
+  if (workspace_bytes < hstu_jagged_attn_workspace_bytes(params, HSTU_WS_CP))
+    return HSTU_ERR_WORKSPACE_TOO_SMALL;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  char* ws = (char*)workspace;
+  const int acc = cp->accumulate ? 1 : 0;
+  size_t base = 0;
+  if (o_local && cp->q_rows > 0) {
+    BuiltPlan pf;
+    rc = build_plan(params, cp->cp_size, cp_side(params, cp, 0, PASS_FWD), seq_offsets_global, ws,
+                    workspace_bytes, base, stream, &pf);
+    if (rc != HSTU_OK) return rc;
+    base = pf.end;
+    AttnArgs a = base_args(params, pf, acc);
+    a.q = q_local; a.k = k_part; a.v = v_part; a.o = o_local;
+    rc = run_pass(params, PASS_FWD, a, stream);
+    if (rc != HSTU_OK) return rc;
+  }
+  if (backward) {
+    if (cp->kv_rows > 0) {
+      BuiltPlan pk;
+      rc = build_plan(params, cp->cp_size, cp_side(params, cp, 1, PASS_DKDV), seq_offsets_global,
+                      ws, workspace_bytes, base, stream, &pk);
+      if (rc != HSTU_OK) return rc;
+      base = pk.end;
+      AttnArgs a = base_args(params, pk, acc);
+      a.q = q_local; a.k = k_part; a.v = v_part; a.d_o = d_o_local; a.dk = dk_part; a.dv = dv_part;
+      rc = run_pass(params, PASS_DKDV, a, stream);
+      if (rc != HSTU_OK) return rc;
+    }
+    if (cp->q_rows > 0) {
+      BuiltPlan pq;
+      rc = build_plan(params, cp->cp_size, cp_side(params, cp, 0, PASS_DQ), seq_offsets_global, ws,
+                      workspace_bytes, base, stream, &pq);
+      if (rc != HSTU_OK) return rc;
+      AttnArgs b = base_args(params, pq, acc);
+      b.q = q_local; b.k = k_part; b.v = v_part; b.d_o = d_o_local; b.dq = dq_local;
+      rc = run_pass(params, PASS_DQ, b, stream);
+      if (rc != HSTU_OK) return rc;
+    }
+  }
+  return HSTU_OK;
+}
+
+int hstu_debug_dump_schedule(const hstu_attn_params* params, const hstu_cp_desc* cp, int side,
+                             const int32_t* seq_offsets, int32_t* items_host, int32_t max_items,
+                             void* workspace, size_t workspace_bytes, void* hip_stream) {
+  int rc = check_params(params);
+  if (rc != HSTU_OK) return rc;
+  if (cp) {
+    rc = check_cp(params, cp);
+    if (rc != HSTU_OK) return rc;
+  }
+  if (side != 0 && side != 1) return HSTU_ERR_BAD_SHAPE;
+  if (params->batch == 0 || params->total_rows == 0) return 0;
+  if (!seq_offsets || !items_host || !workspace) return HSTU_ERR_NULL_PTR;
+  if (workspace_bytes < hstu_jagged_attn_workspace_bytes(params, cp ? HSTU_WS_CP : HSTU_WS_FWD))
+    return HSTU_ERR_WORKSPACE_TOO_SMALL;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const int pass = side == 0 ? PASS_FWD : PASS_DKDV;
+  const SideSpec s = cp ? cp_side(params, cp, side, pass) : full_side(params, side, pass);
+  BuiltPlan bp;
+  rc = build_plan(params, cp ? cp->cp_size : 1, s, seq_offsets, (char*)workspace, workspace_bytes,
+                  0, stream, &bp);
+  if (rc != HSTU_OK) return rc;
+  int32_t n = 0;
+  if (hipMemcpyAsync(&n, bp.plan.header, sizeof(int32_t), hipMemcpyDeviceToHost, stream) != hipSuccess)
+    return HSTU_ERR_HIP;
+  if (hipStreamSynchronize(stream) != hipSuccess) return HSTU_ERR_HIP;
+  if (n > max_items) return HSTU_ERR_WORKSPACE_TOO_SMALL;
+  if (n == 0) return 0;
+  std::vector<int32_t> order(n);
+  std::vector<Item> items(n);
+  if (hipMemcpyAsync(order.data(), bp.plan.order, sizeof(int32_t) * n, hipMemcpyDeviceToHost, stream) != hipSuccess ||
+      hipMemcpyAsync(items.data(), bp.plan.items, sizeof(Item) * n, hipMemcpyDeviceToHost, stream) != hipSuccess ||
+      hipStreamSynchronize(stream) != hipSuccess)
+    return HSTU_ERR_HIP;
+  for (int32_t i = 0; i < n; ++i) {
+    const int32_t idx = order[i];
+    if (idx < 0 || idx >= n) return HSTU_ERR_HIP;
+    const Item& it = items[idx];
+    int32_t* dst = items_host + (size_t)i * 12;
+    dst[0] = it.row0; dst[1] = it.nrows; dst[2] = it.pos0; dst[3] = it.nseg;
+    dst[4] = it.seg_row0[0]; dst[5] = it.seg_row0[1];
+    dst[6] = it.seg_len[0]; dst[7] = it.seg_len[1];
+    dst[8] = it.seg_pos0[0]; dst[9] = it.seg_pos0[1];
+    dst[10] = it.cost; dst[11] = 0;
+  }
+  return n;
+}
+
+}  // extern "C"

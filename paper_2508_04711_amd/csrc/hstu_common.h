@@ -1,0 +1,117 @@
+// Internal declarations shared by the library's translation units (not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace hstu {
+
+// One unit of scheduled work: a tile of "owner" rows (query rows for the forward and dq
+// passes, key rows for the dk/dv pass) plus up to two segments of "streamed" rows of the
+// same sequence that the tile is computed against.  Rows index the caller's buffers;
+// positions are in-sequence positions and drive the causal mask, so the same kernels serve
+// whole-batch attention (one segment, row == offset + position) and a context-parallel
+// rank's share (two mini-chunks per side, section 2.3 of the paper).
+struct Item {
+  int32_t row0;         // first owner row of the tile
+  int32_t nrows;        // valid owner rows (0..tile)
+  int32_t pos0;         // in-sequence position of row0
+  int32_t nseg;         // streamed segments in use (0..2)
+  int32_t seg_row0[2];  // first streamed row of each segment
+  int32_t seg_len[2];   // rows in each segment
+  int32_t seg_pos0[2];  // in-sequence position of each segment's first row
+  int32_t cost;         // visible 32-row streamed blocks (the sort key)
+  int32_t pad;
+};
+static_assert(sizeof(Item) == 48, "Item layout is part of the schedule dump format");
+
+// Device view of a built schedule.
+struct Plan {
+  const int32_t* header;  // [0] = number of items
+  const int32_t* order;   // order[slot] = item index, non-increasing cost
+  const Item* items;
+};
+
+// Byte offsets of one schedule's arrays inside the workspace.
+struct PlanLayout {
+  size_t header, owner_base, streamed_base, tile_base, order, items, end;
+};
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+inline PlanLayout plan_layout(size_t base, int64_t batch, int64_t max_items) {
+  PlanLayout l;
+  size_t p = align_up(base, 256);
+  l.header = p;        p += 64;
+  l.owner_base = p;    p = align_up(p + (size_t)(batch + 1) * 4, 64);
+  l.streamed_base = p; p = align_up(p + (size_t)(batch + 1) * 4, 64);
+  l.tile_base = p;     p = align_up(p + (size_t)(batch + 1) * 4, 64);
+  l.order = p;         p = align_up(p + (size_t)max_items * 4, 64);
+  l.items = p;         p = align_up(p + (size_t)max_items * sizeof(Item), 64);
+  l.end = p;
+  return l;
+}
+
+// Upper bound on the number of items when `rows` owner rows of `batch` sequences, each cut
+// into at most `segs` segments, are tiled by `tile` rows.
+inline int64_t max_items_bound(int64_t rows, int64_t batch, int segs, int tile) {
+  return rows / tile + (int64_t)segs * batch + 1;
+}
+
+struct PlanArgs {
+  const int32_t* off;     // device, batch + 1
+  int32_t batch;
+  int32_t total_rows;     // rows of the global layout
+  int32_t cp;             // context-parallel size (1 for whole-batch attention)
+  int32_t owner_rank;     // -1: owner side is in the global layout
+  int32_t streamed_rank;  // -1: streamed side is in the global layout
+  int32_t side;           // 0: owners are queries, 1: owners are keys
+  int32_t tile;           // owner rows per item
+  int32_t causal;
+  int32_t owner_rows;     // rows the caller declared for the owner-side buffers
+  int32_t streamed_rows;  // rows the caller declared for the streamed-side buffers
+  int32_t max_items;
+  int32_t cost_shift;     // cost >> cost_shift selects the sort bin
+  int32_t* header;
+  int32_t* owner_base;
+  int32_t* streamed_base;
+  int32_t* tile_base;
+  int32_t* order;
+  Item* items;
+};
+
+hipError_t launch_plan(const PlanArgs& a, hipStream_t stream);
+
+// Arguments of the attention kernels.
+struct AttnArgs {
+  const void* q;
+  const void* k;
+  const void* v;
+  const void* d_o;
+  void* o;
+  void* dq;
+  void* dk;
+  void* dv;
+  Plan plan;
+  int32_t num_heads;
+  int32_t causal;
+  int32_t accumulate;
+  int32_t max_items;
+  int32_t out_f32;  // outputs are fp32 (bf16 kernels only; the fp32 kernels always write fp32)
+  float alpha;
+  float inv_n;
+};
+
+// Owner rows per item each kernel family expects (pass: 0 forward, 1 dk/dv, 2 dq); the
+// schedule must be built with the same value.
+enum { PASS_FWD = 0, PASS_DKDV = 1, PASS_DQ = 2 };
+int tile_rows_bf16(int pass);
+int tile_rows_f32(int pass);
+
+hipError_t launch_fwd_bf16(const AttnArgs& a, int d_qk, int d_v, hipStream_t stream);
+hipError_t launch_dkdv_bf16(const AttnArgs& a, int d_qk, int d_v, hipStream_t stream);
+hipError_t launch_dq_bf16(const AttnArgs& a, int d_qk, int d_v, hipStream_t stream);
+hipError_t launch_fwd_f32(const AttnArgs& a, int d_qk, int d_v, hipStream_t stream);
+hipError_t launch_dkdv_f32(const AttnArgs& a, int d_qk, int d_v, hipStream_t stream);
+hipError_t launch_dq_f32(const AttnArgs& a, int d_qk, int d_v, hipStream_t stream);
+
+}  // namespace hstu

@@ -1,0 +1,644 @@
+// bf16 jagged HSTU attention on the gfx950 matrix cores: forward, dk/dv pass, dq pass.
+//
+// Paper, section 2.1: O = Mask(SiLU(alpha * Q K^T)) V (bias absent), here divided by max_len.
+// All three kernels share one shape.  A workgroup takes one schedule item for one head: a
+// tile of "owner" rows, 32 per wavefront, whose data a wave keeps in registers as MFMA B
+// operands, and streams the other side's rows through LDS in tiles of 64, double buffered,
+// as MFMA A operands.  Scores are produced transposed with respect to the owner rows so that
+// the accumulator registers of the first product are, lane for lane, the B (or A) operand of
+// the second one; nothing but the streamed tiles ever goes through LDS.
+//
+//   v_mfma_f32_32x32x16_bf16  D[32x32] += A[32x16] * B[16x32]   (lane l: n = l%32, hh = l/32)
+//     A: lane holds row n,    k = 8*hh .. 8*hh+7          B: lane holds column n, same k
+//     D: lane holds column n, rows 8*(r/4) + 4*hh + r%4   for r = 0..15
+//
+// Products whose contraction runs over streamed rows (P V, P^T dO, dS^T Q, dS K) need the
+// streamed tile transposed; ds_read_b64_tr_b16 delivers that straight from the row-major
+// tile: within each group of 16 lanes, lane i receives the four 16-bit elements that lanes
+// i/4, i/4+4, i/4+8, i/4+12 address at element index i%4, i.e. a 4x16 block comes back as
+// one column per lane.
+//
+// LDS tiles are dense [64 rows][D] bf16 with the 16-byte chunk index XOR-swizzled by the row
+// so that both the row-wise 16-byte operand reads and the transposing 8-byte reads are free
+// of bank conflicts without padding.
+//
+// SiLU, its derivative and the mask are evaluated in fp32 on the accumulator registers; P and
+// dS are rounded to bf16 only as operands of the second product; alpha and 1/max_len are
+// folded into one fp32 scale at the output, which is rounded to bf16 once.
+#include "hstu_common.h"
+
+namespace hstu {
+
+namespace {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
+typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
+typedef __attribute__((__vector_size__(2 * sizeof(uint32_t)))) uint32_t u32x2;
+
+#define HSTU_LDS(T, p) ((__attribute__((address_space(3))) T*)(p))
+
+constexpr int ST = 64;  // streamed rows per LDS tile
+
+// Swizzle of the 16-byte chunk index by the row: rows r..r+7 at one chunk land in eight
+// different bank groups (row-wise reads) and the 4 rows x 2 chunks a 16-lane transposing read
+// touches do too.
+template <int D>
+__device__ __forceinline__ int swz(int row) {
+  if (D >= 64) return (row & 7) ^ ((row & 1) << 2);
+  return (row >> 1) & 3;
+}
+
+// Byte offset inside a [rows][D] bf16 LDS tile of 16-byte chunk `chunk` of row `row`.
+template <int D>
+__device__ __forceinline__ int lds_off(int row, int chunk) {
+  return row * (D * 2) + ((chunk ^ swz<D>(row)) << 4);
+}
+
+// Row-wise A operand: 8 consecutive elements [col8*8, col8*8+8) of row `row`.
+template <int D>
+__device__ __forceinline__ bf16x8 lds_read_rows(const char* tile, int row, int col8) {
+  return *HSTU_LDS(bf16x8, tile + lds_off<D>(row, col8));
+}
+
+// Transposed operand for one 32x32x16 product: lane (n, hh) receives, for column
+// col0 + n, the rows row0 + 4*hh + {0,1,2,3} and row0 + 8 + 4*hh + {0,1,2,3}: exactly the
+// streamed rows a lane's accumulator registers 8c..8c+7 belong to when row0 = 32*blk + 16*c.
+template <int D>
+__device__ __forceinline__ bf16x8 lds_read_cols(const char* tile, int row0, int col0, int lane) {
+  const int i = lane & 15, g = lane >> 4;
+  const int row = row0 + ((g >> 1) << 2) + (i >> 2);
+  const int col = col0 + ((g & 1) << 4) + ((i & 3) << 2);  // element column of this lane's 8 bytes
+  const int within = (col & 7) << 1;
+  const char* p0 = tile + lds_off<D>(row, col >> 3) + within;
+  const char* p1 = tile + lds_off<D>(row + 8, col >> 3) + within;
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(HSTU_LDS(s16x4, p0));
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(HSTU_LDS(s16x4, p1));
+  typedef __attribute__((__vector_size__(8 * sizeof(short)))) short s16x8;
+  const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, both);
+}
+
+// A streamed tile on its way from global memory to LDS, held in registers meanwhile.
+template <int D, int NT>
+struct TileRegs {
+  static constexpr int CPR = D / 8;                        // 16-byte chunks per row
+  static constexpr int CHUNKS = ST * CPR;
+  static constexpr int ITERS = (CHUNKS + NT - 1) / NT;
+  u32x4 r[ITERS];
+
+  // base: element pointer to (row 0 of the tile, this head); rows >= valid read as zero.
+  __device__ __forceinline__ void load(const __bf16* base, int64_t row_stride, int valid, int tid) {
+#pragma unroll
+    for (int i = 0; i < ITERS; ++i) {
+      const int c = tid + i * NT;
+      const int row = c / CPR, chunk = c % CPR;
+      u32x4 z = {0u, 0u, 0u, 0u};
+      if (c < CHUNKS && row < valid) z = *(const u32x4*)(base + row * row_stride + chunk * 8);
+      r[i] = z;
+    }
+  }
+  __device__ __forceinline__ void store(char* tile, int tid) const {
+#pragma unroll
+    for (int i = 0; i < ITERS; ++i) {
+      const int c = tid + i * NT;
+      const int row = c / CPR, chunk = c % CPR;
+      if (c < CHUNKS) *HSTU_LDS(u32x4, tile + lds_off<D>(row, chunk)) = r[i];
+    }
+  }
+};
+
+// 32 owner rows of one head as B operands: lane (n, hh) holds row n, elements 16*s + 8*hh + e.
+template <int D>
+__device__ __forceinline__ void load_owner(bf16x8 (&reg)[D / 16], const __bf16* base,
+                                           int64_t row_stride, int row, bool valid, int hh) {
+#pragma unroll
+  for (int s = 0; s < D / 16; ++s) {
+    u32x4 z = {0u, 0u, 0u, 0u};
+    if (valid) z = *(const u32x4*)(base + row * row_stride + s * 16 + hh * 8);
+    reg[s] = __builtin_bit_cast(bf16x8, z);
+  }
+}
+
+__device__ __forceinline__ f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+// sigmoid(alpha * s) with c1 = -alpha * log2(e).  exp2 overflow gives rcp(inf) = 0.
+__device__ __forceinline__ float sigmoid_scaled(float s, float c1) {
+  return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(s * c1));
+}
+
+__device__ __forceinline__ bf16x8 pack8(const float* x) {
+  bf16x8 r;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) r[e] = (__bf16)x[e];
+  return r;
+}
+
+// Streamed rows of a segment that matter to an owner tile, as [beg, end) in segment rows.
+// side 0 (owners are queries): keys at positions <= the tile's last position.
+// side 1 (owners are keys): queries at positions >= the tile's first position.
+template <int SIDE>
+__device__ __forceinline__ void visible_range(const Item& it, int g, int causal, int& beg, int& end) {
+  beg = 0;
+  end = it.seg_len[g];
+  if (causal) {
+    if (SIDE == 0) {
+      const int e = it.pos0 + it.nrows - it.seg_pos0[g];
+      end = e < 0 ? 0 : (e < end ? e : end);
+    } else {
+      const int b = it.pos0 - it.seg_pos0[g];
+      beg = b < 0 ? 0 : (b < end ? b : end);
+      beg &= ~31;
+    }
+  }
+}
+
+// The streamed tiles of an item, flattened over its segments.
+struct Stream {
+  int n[2];    // tiles per segment
+  int beg[2];  // first streamed row (segment-relative) of tile 0
+  int end[2];  // end of the visible range (segment-relative)
+  int total;
+};
+
+template <int SIDE>
+__device__ __forceinline__ Stream make_stream(const Item& it, int causal) {
+  Stream s;
+#pragma unroll
+  for (int g = 0; g < 2; ++g) {
+    s.n[g] = 0; s.beg[g] = 0; s.end[g] = 0;
+    if (g < it.nseg) {
+      visible_range<SIDE>(it, g, causal, s.beg[g], s.end[g]);
+      s.n[g] = (s.end[g] - s.beg[g] + ST - 1) / ST;
+    }
+  }
+  s.total = s.n[0] + s.n[1];
+  return s;
+}
+
+// Tile j of the stream: segment, first segment-relative row, valid rows, first position.
+struct TileRef { int row; int valid; int pos; };
+
+__device__ __forceinline__ TileRef tile_ref(const Item& it, const Stream& s, int j) {
+  const int g = j < s.n[0] ? 0 : 1;
+  const int t = g ? j - s.n[0] : j;
+  const int rel = s.beg[g] + t * ST;
+  TileRef r;
+  r.row = it.seg_row0[g] + rel;
+  r.valid = s.end[g] - rel;  // may exceed ST; callers clamp by ST through the loader
+  r.pos = it.seg_pos0[g] + rel;
+  return r;
+}
+
+// Epilogue for accumulators held "owner row per lane": blk[c][r] is element
+// c*32 + 8*(r/4) + 4*hh + r%4 of the lane's row.  `elem` is the element offset of the row start.
+template <int D>
+__device__ __forceinline__ void store_owner_major(void* out, int64_t elem, const f32x16 (&acc)[D / 32],
+                                                  float scale, int hh, int accumulate, int out_f32) {
+#pragma unroll
+  for (int c = 0; c < D / 32; ++c)
+#pragma unroll
+    for (int q4 = 0; q4 < 4; ++q4) {
+      const int64_t e0 = elem + c * 32 + 8 * q4 + 4 * hh;
+      float x[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) x[e] = acc[c][4 * q4 + e] * scale;
+      if (out_f32) {
+        float4* dst = (float4*)((float*)out + e0);
+        if (accumulate) {
+          const float4 old = *dst;
+          x[0] += old.x; x[1] += old.y; x[2] += old.z; x[3] += old.w;
+        }
+        *dst = make_float4(x[0], x[1], x[2], x[3]);
+      } else {
+        bf16x4* dst = (bf16x4*)((__bf16*)out + e0);
+        if (accumulate) {
+          const bf16x4 old = *dst;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) x[e] += (float)old[e];
+        }
+        bf16x4 o4;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o4[e] = (__bf16)x[e];
+        *dst = o4;
+      }
+    }
+}
+
+// One element of an output tensor, either dtype, optionally added to what is there.
+__device__ __forceinline__ void store_one(void* out, int64_t elem, float x, int accumulate, int out_f32) {
+  if (out_f32) {
+    float* d = (float*)out + elem;
+    *d = accumulate ? *d + x : x;
+  } else {
+    __bf16* d = (__bf16*)out + elem;
+    *d = (__bf16)(accumulate ? (float)*d + x : x);
+  }
+}
+
+__device__ __forceinline__ bool fetch_item(const Plan& plan, int slot, Item& it) {
+  if (slot >= plan.header[0]) return false;
+  it = plan.items[plan.order[slot]];
+  return it.nrows > 0;
+}
+
+// =============================================================================================
+// Forward: owners are query rows, keys and values are streamed.
+//   S^T = K Q^T (A = K tile rows, B = Q registers)  ->  P^T in accumulator layout
+//   O^T += V^T P^T (A = V tile transposed read, B = P^T registers)
+// =============================================================================================
+template <int DQK, int DV, int NW>
+__global__ void __launch_bounds__(NW * 64) hstu_fwd_bf16(AttnArgs a) {
+  constexpr int NT = NW * 64;
+  constexpr int KB = ST * DQK * 2, VB = ST * DV * 2;
+  __shared__ __attribute__((aligned(16))) char smem[2 * (KB + VB)];
+  auto kbuf = [&](int b) { return smem + b * (KB + VB); };
+  auto vbuf = [&](int b) { return smem + b * (KB + VB) + KB; };
+
+  const int H = a.num_heads;
+  const int slot = blockIdx.x / H, h = blockIdx.x % H;
+  Item it;
+  if (!fetch_item(a.plan, slot, it)) return;
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 31, hh = lane >> 5;
+  const int64_t sq = (int64_t)H * DQK, sv = (int64_t)H * DV;
+  const __bf16* qg = (const __bf16*)a.q + (int64_t)it.row0 * sq + h * DQK;
+  const __bf16* kg = (const __bf16*)a.k + h * DQK;
+  const __bf16* vg = (const __bf16*)a.v + h * DV;
+
+  const int orow = wave * 32 + n;  // this lane's owner row inside the tile
+  const bool wave_on = wave * 32 < it.nrows;
+  bf16x8 qreg[DQK / 16];
+  load_owner<DQK>(qreg, qg, sq, orow, orow < it.nrows, hh);
+
+  f32x16 oacc[DV / 32];
+#pragma unroll
+  for (int i = 0; i < DV / 32; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) oacc[i][r] = 0.f;
+
+  const Stream st = make_stream<0>(it, a.causal);
+  const float c1 = -a.alpha * 1.4426950408889634f;
+  const int q_lo = it.pos0 + wave * 32, q_hi = q_lo + 31;
+
+  TileRegs<DQK, NT> kr;
+  TileRegs<DV, NT> vr;
+  if (st.total > 0) {
+    const TileRef t0 = tile_ref(it, st, 0);
+    kr.load(kg + (int64_t)t0.row * sq, sq, t0.valid, tid);
+    vr.load(vg + (int64_t)t0.row * sv, sv, t0.valid, tid);
+    kr.store(kbuf(0), tid);
+    vr.store(vbuf(0), tid);
+  }
+  __syncthreads();
+
+  for (int j = 0; j < st.total; ++j) {
+    const TileRef tj = tile_ref(it, st, j);
+    const bool more = j + 1 < st.total;
+    if (more) {
+      const TileRef tn = tile_ref(it, st, j + 1);
+      kr.load(kg + (int64_t)tn.row * sq, sq, tn.valid, tid);
+      vr.load(vg + (int64_t)tn.row * sv, sv, tn.valid, tid);
+    }
+    const char* kt = kbuf(j & 1);
+    const char* vt = vbuf(j & 1);
+    if (wave_on) {
+#pragma unroll
+      for (int blk = 0; blk < ST / 32; ++blk) {
+        const int k_lo = tj.pos + blk * 32;
+        if (blk * 32 >= tj.valid) continue;           // nothing visible in this block
+        if (a.causal && k_lo > q_hi) continue;        // wholly above this wave's diagonal
+        f32x16 s;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[r] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < DQK / 16; ++ks)
+          s = mfma(lds_read_rows<DQK>(kt, blk * 32 + n, ks * 2 + hh), qreg[ks], s);
+        float p[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) p[r] = s[r] * sigmoid_scaled(s[r], c1);
+        if (a.causal && k_lo + 31 > q_lo) {           // the diagonal crosses this block
+          const int qpos = q_lo + n;
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int kpos = k_lo + 8 * (r >> 2) + 4 * hh + (r & 3);
+            p[r] = kpos <= qpos ? p[r] : 0.f;
+          }
+        }
+        const bf16x8 pb0 = pack8(p), pb1 = pack8(p + 8);
+#pragma unroll
+        for (int dvb = 0; dvb < DV / 32; ++dvb) {
+          oacc[dvb] = mfma(lds_read_cols<DV>(vt, blk * 32, dvb * 32, lane), pb0, oacc[dvb]);
+          oacc[dvb] = mfma(lds_read_cols<DV>(vt, blk * 32 + 16, dvb * 32, lane), pb1, oacc[dvb]);
+        }
+      }
+    }
+    if (more) {
+      kr.store(kbuf((j + 1) & 1), tid);
+      vr.store(vbuf((j + 1) & 1), tid);
+    }
+    __syncthreads();
+  }
+
+  // O^T accumulators: lane holds query row n, elements dvb*32 + 8*(r/4) + 4*hh + r%4.
+  if (orow < it.nrows)
+    store_owner_major<DV>(a.o, ((int64_t)it.row0 + orow) * sv + h * DV, oacc, a.alpha * a.inv_n, hh,
+                          a.accumulate, a.out_f32);
+}
+
+// =============================================================================================
+// dk/dv pass: owners are key rows (K and V rows in registers), Q and dO are streamed.
+//   S  = Q K^T   (A = Q tile rows,  B = K registers)   lane: key n, query rows in registers
+//   dP = dO V^T  (A = dO tile rows, B = V registers)
+//   dV += P^T dO   (A = P registers,  B = dO tile transposed read)
+//   dK += dS^T Q   (A = dS registers, B = Q tile transposed read)
+// Each key tile belongs to exactly one workgroup, so dk and dv need no atomics.
+// =============================================================================================
+template <int DQK, int DV, int NW>
+__global__ void __launch_bounds__(NW * 64) hstu_dkdv_bf16(AttnArgs a) {
+  constexpr int NT = NW * 64;
+  constexpr int QB = ST * DQK * 2, GB = ST * DV * 2;
+  __shared__ __attribute__((aligned(16))) char smem[2 * (QB + GB)];
+  auto qbuf = [&](int b) { return smem + b * (QB + GB); };
+  auto gbuf = [&](int b) { return smem + b * (QB + GB) + QB; };
+
+  const int H = a.num_heads;
+  const int slot = blockIdx.x / H, h = blockIdx.x % H;
+  Item it;
+  if (!fetch_item(a.plan, slot, it)) return;
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 31, hh = lane >> 5;
+  const int64_t sq = (int64_t)H * DQK, sv = (int64_t)H * DV;
+  const __bf16* qg = (const __bf16*)a.q + h * DQK;
+  const __bf16* gg = (const __bf16*)a.d_o + h * DV;
+  const __bf16* kg = (const __bf16*)a.k + (int64_t)it.row0 * sq + h * DQK;
+  const __bf16* vg = (const __bf16*)a.v + (int64_t)it.row0 * sv + h * DV;
+
+  const int orow = wave * 32 + n;
+  const bool wave_on = wave * 32 < it.nrows;
+  bf16x8 kreg[DQK / 16], vreg[DV / 16];
+  load_owner<DQK>(kreg, kg, sq, orow, orow < it.nrows, hh);
+  load_owner<DV>(vreg, vg, sv, orow, orow < it.nrows, hh);
+
+  f32x16 dkacc[DQK / 32], dvacc[DV / 32];
+#pragma unroll
+  for (int i = 0; i < DQK / 32; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) dkacc[i][r] = 0.f;
+#pragma unroll
+  for (int i = 0; i < DV / 32; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) dvacc[i][r] = 0.f;
+
+  const Stream st = make_stream<1>(it, a.causal);
+  const float c1 = -a.alpha * 1.4426950408889634f;
+  const int k_lo = it.pos0 + wave * 32, k_hi = k_lo + 31;
+
+  TileRegs<DQK, NT> qr;
+  TileRegs<DV, NT> gr;
+  if (st.total > 0) {
+    const TileRef t0 = tile_ref(it, st, 0);
+    qr.load(qg + (int64_t)t0.row * sq, sq, t0.valid, tid);
+    gr.load(gg + (int64_t)t0.row * sv, sv, t0.valid, tid);
+    qr.store(qbuf(0), tid);
+    gr.store(gbuf(0), tid);
+  }
+  __syncthreads();
+
+  for (int j = 0; j < st.total; ++j) {
+    const TileRef tj = tile_ref(it, st, j);
+    const bool more = j + 1 < st.total;
+    if (more) {
+      const TileRef tn = tile_ref(it, st, j + 1);
+      qr.load(qg + (int64_t)tn.row * sq, sq, tn.valid, tid);
+      gr.load(gg + (int64_t)tn.row * sv, sv, tn.valid, tid);
+    }
+    const char* qt = qbuf(j & 1);
+    const char* gt = gbuf(j & 1);
+    if (wave_on) {
+#pragma unroll
+      for (int blk = 0; blk < ST / 32; ++blk) {
+        const int q_lo = tj.pos + blk * 32;
+        if (blk * 32 >= tj.valid) continue;
+        if (a.causal && q_lo + 31 < k_lo) continue;   // every query here precedes every key
+        f32x16 s, dp;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
+#pragma unroll
+        for (int ks = 0; ks < DQK / 16; ++ks)
+          s = mfma(lds_read_rows<DQK>(qt, blk * 32 + n, ks * 2 + hh), kreg[ks], s);
+#pragma unroll
+        for (int ks = 0; ks < DV / 16; ++ks)
+          dp = mfma(lds_read_rows<DV>(gt, blk * 32 + n, ks * 2 + hh), vreg[ks], dp);
+        // p' = s*sg (p = alpha*p'/N);  silu'(alpha*s) = sg + alpha*p'*(1-sg);  ds' = dp*silu'
+        float p[16], ds[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const float sg = sigmoid_scaled(s[r], c1);
+          p[r] = s[r] * sg;
+          ds[r] = dp[r] * (sg + a.alpha * p[r] * (1.0f - sg));
+        }
+        if (a.causal && q_lo < k_hi) {
+          const int kpos = k_lo + n;
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int qpos = q_lo + 8 * (r >> 2) + 4 * hh + (r & 3);
+            const bool vis = kpos <= qpos;
+            p[r] = vis ? p[r] : 0.f;
+            ds[r] = vis ? ds[r] : 0.f;
+          }
+        }
+        const bf16x8 pb0 = pack8(p), pb1 = pack8(p + 8);
+        const bf16x8 db0 = pack8(ds), db1 = pack8(ds + 8);
+#pragma unroll
+        for (int c = 0; c < DV / 32; ++c) {
+          dvacc[c] = mfma(pb0, lds_read_cols<DV>(gt, blk * 32, c * 32, lane), dvacc[c]);
+          dvacc[c] = mfma(pb1, lds_read_cols<DV>(gt, blk * 32 + 16, c * 32, lane), dvacc[c]);
+        }
+#pragma unroll
+        for (int c = 0; c < DQK / 32; ++c) {
+          dkacc[c] = mfma(db0, lds_read_cols<DQK>(qt, blk * 32, c * 32, lane), dkacc[c]);
+          dkacc[c] = mfma(db1, lds_read_cols<DQK>(qt, blk * 32 + 16, c * 32, lane), dkacc[c]);
+        }
+      }
+    }
+    if (more) {
+      qr.store(qbuf((j + 1) & 1), tid);
+      gr.store(gbuf((j + 1) & 1), tid);
+    }
+    __syncthreads();
+  }
+
+  // Accumulators: lane holds column c*32 + n of key rows 8*(r/4) + 4*hh + r%4 of its wave.
+  if (wave_on) {
+    const float scale = a.alpha * a.inv_n;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int row = wave * 32 + 8 * (r >> 2) + 4 * hh + (r & 3);
+      if (row >= it.nrows) continue;
+      const int64_t ek = ((int64_t)it.row0 + row) * sq + h * DQK + n;
+      const int64_t ev = ((int64_t)it.row0 + row) * sv + h * DV + n;
+#pragma unroll
+      for (int c = 0; c < DQK / 32; ++c)
+        store_one(a.dk, ek + c * 32, dkacc[c][r] * scale, a.accumulate, a.out_f32);
+#pragma unroll
+      for (int c = 0; c < DV / 32; ++c)
+        store_one(a.dv, ev + c * 32, dvacc[c][r] * scale, a.accumulate, a.out_f32);
+    }
+  }
+}
+
+// =============================================================================================
+// dq pass: owners are query rows (Q and dO rows in registers), K and V are streamed.
+//   S^T  = K Q^T   (A = K tile rows, B = Q registers)
+//   dP^T = V dO^T  (A = V tile rows, B = dO registers)
+//   dQ^T += K^T dS^T (A = K tile transposed read, B = dS^T registers)
+// A second recomputation of S instead of atomics: dq is deterministic.
+// =============================================================================================
+template <int DQK, int DV, int NW>
+__global__ void __launch_bounds__(NW * 64) hstu_dq_bf16(AttnArgs a) {
+  constexpr int NT = NW * 64;
+  constexpr int KB = ST * DQK * 2, VB = ST * DV * 2;
+  __shared__ __attribute__((aligned(16))) char smem[2 * (KB + VB)];
+  auto kbuf = [&](int b) { return smem + b * (KB + VB); };
+  auto vbuf = [&](int b) { return smem + b * (KB + VB) + KB; };
+
+  const int H = a.num_heads;
+  const int slot = blockIdx.x / H, h = blockIdx.x % H;
+  Item it;
+  if (!fetch_item(a.plan, slot, it)) return;
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 31, hh = lane >> 5;
+  const int64_t sq = (int64_t)H * DQK, sv = (int64_t)H * DV;
+  const __bf16* qg = (const __bf16*)a.q + (int64_t)it.row0 * sq + h * DQK;
+  const __bf16* gg = (const __bf16*)a.d_o + (int64_t)it.row0 * sv + h * DV;
+  const __bf16* kg = (const __bf16*)a.k + h * DQK;
+  const __bf16* vg = (const __bf16*)a.v + h * DV;
+
+  const int orow = wave * 32 + n;
+  const bool wave_on = wave * 32 < it.nrows;
+  bf16x8 qreg[DQK / 16], greg[DV / 16];
+  load_owner<DQK>(qreg, qg, sq, orow, orow < it.nrows, hh);
+  load_owner<DV>(greg, gg, sv, orow, orow < it.nrows, hh);
+
+  f32x16 dqacc[DQK / 32];
+#pragma unroll
+  for (int i = 0; i < DQK / 32; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) dqacc[i][r] = 0.f;
+
+  const Stream st = make_stream<0>(it, a.causal);
+  const float c1 = -a.alpha * 1.4426950408889634f;
+  const int q_lo = it.pos0 + wave * 32, q_hi = q_lo + 31;
+
+  TileRegs<DQK, NT> kr;
+  TileRegs<DV, NT> vr;
+  if (st.total > 0) {
+    const TileRef t0 = tile_ref(it, st, 0);
+    kr.load(kg + (int64_t)t0.row * sq, sq, t0.valid, tid);
+    vr.load(vg + (int64_t)t0.row * sv, sv, t0.valid, tid);
+    kr.store(kbuf(0), tid);
+    vr.store(vbuf(0), tid);
+  }
+  __syncthreads();
+
+  for (int j = 0; j < st.total; ++j) {
+    const TileRef tj = tile_ref(it, st, j);
+    const bool more = j + 1 < st.total;
+    if (more) {
+      const TileRef tn = tile_ref(it, st, j + 1);
+      kr.load(kg + (int64_t)tn.row * sq, sq, tn.valid, tid);
+      vr.load(vg + (int64_t)tn.row * sv, sv, tn.valid, tid);
+    }
+    const char* kt = kbuf(j & 1);
+    const char* vt = vbuf(j & 1);
+    if (wave_on) {
+#pragma unroll
+      for (int blk = 0; blk < ST / 32; ++blk) {
+        const int k_lo = tj.pos + blk * 32;
+        if (blk * 32 >= tj.valid) continue;
+        if (a.causal && k_lo > q_hi) continue;
+        f32x16 s, dp;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
+#pragma unroll
+        for (int ks = 0; ks < DQK / 16; ++ks)
+          s = mfma(lds_read_rows<DQK>(kt, blk * 32 + n, ks * 2 + hh), qreg[ks], s);
+#pragma unroll
+        for (int ks = 0; ks < DV / 16; ++ks)
+          dp = mfma(lds_read_rows<DV>(vt, blk * 32 + n, ks * 2 + hh), greg[ks], dp);
+        float ds[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const float sg = sigmoid_scaled(s[r], c1);
+          const float p = s[r] * sg;
+          ds[r] = dp[r] * (sg + a.alpha * p * (1.0f - sg));
+        }
+        if (a.causal && k_lo + 31 > q_lo) {
+          const int qpos = q_lo + n;
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int kpos = k_lo + 8 * (r >> 2) + 4 * hh + (r & 3);
+            ds[r] = kpos <= qpos ? ds[r] : 0.f;
+          }
+        }
+        const bf16x8 db0 = pack8(ds), db1 = pack8(ds + 8);
+#pragma unroll
+        for (int c = 0; c < DQK / 32; ++c) {
+          dqacc[c] = mfma(lds_read_cols<DQK>(kt, blk * 32, c * 32, lane), db0, dqacc[c]);
+          dqacc[c] = mfma(lds_read_cols<DQK>(kt, blk * 32 + 16, c * 32, lane), db1, dqacc[c]);
+        }
+      }
+    }
+    if (more) {
+      kr.store(kbuf((j + 1) & 1), tid);
+      vr.store(vbuf((j + 1) & 1), tid);
+    }
+    __syncthreads();
+  }
+
+  // dQ^T accumulators: lane holds query row n, elements c*32 + 8*(r/4) + 4*hh + r%4.
+  if (orow < it.nrows)
+    store_owner_major<DQK>(a.dq, ((int64_t)it.row0 + orow) * sq + h * DQK, dqacc, a.alpha * a.inv_n,
+                           hh, a.accumulate, a.out_f32);
+}
+
+constexpr int FWD_NW = 4, DQ_NW = 4, DKDV_NW = 4;
+
+}  // namespace
+
+int tile_rows_bf16(int pass) {
+  return 32 * (pass == PASS_FWD ? FWD_NW : (pass == PASS_DKDV ? DKDV_NW : DQ_NW));
+}
+
+#define HSTU_DISPATCH_D(KERNEL, NW)                                                     \
+  do {                                                                                  \
+    const dim3 grid((unsigned)((int64_t)a.max_items * a.num_heads)), block(NW * 64);    \
+    if (d_qk == 128 && d_v == 128) hipLaunchKernelGGL((KERNEL<128, 128, NW>), grid, block, 0, stream, a); \
+    else if (d_qk == 64 && d_v == 64) hipLaunchKernelGGL((KERNEL<64, 64, NW>), grid, block, 0, stream, a); \
+    else if (d_qk == 32 && d_v == 32) hipLaunchKernelGGL((KERNEL<32, 32, NW>), grid, block, 0, stream, a); \
+    else if (d_qk == 128 && d_v == 64) hipLaunchKernelGGL((KERNEL<128, 64, NW>), grid, block, 0, stream, a); \
+    else if (d_qk == 64 && d_v == 128) hipLaunchKernelGGL((KERNEL<64, 128, NW>), grid, block, 0, stream, a); \
+    else if (d_qk == 128 && d_v == 32) hipLaunchKernelGGL((KERNEL<128, 32, NW>), grid, block, 0, stream, a); \
+    else if (d_qk == 32 && d_v == 128) hipLaunchKernelGGL((KERNEL<32, 128, NW>), grid, block, 0, stream, a); \
+    else if (d_qk == 64 && d_v == 32) hipLaunchKernelGGL((KERNEL<64, 32, NW>), grid, block, 0, stream, a); \
+    else if (d_qk == 32 && d_v == 64) hipLaunchKernelGGL((KERNEL<32, 64, NW>), grid, block, 0, stream, a); \
+    else return hipErrorInvalidValue;                                                   \
+    return hipGetLastError();                                                           \
+  } while (0)
+
+hipError_t launch_fwd_bf16(const AttnArgs& a, int d_qk, int d_v, hipStream_t stream) {
+  HSTU_DISPATCH_D(hstu_fwd_bf16, FWD_NW);
+}
+hipError_t launch_dkdv_bf16(const AttnArgs& a, int d_qk, int d_v, hipStream_t stream) {
+  HSTU_DISPATCH_D(hstu_dkdv_bf16, DKDV_NW);
+}
+hipError_t launch_dq_bf16(const AttnArgs& a, int d_qk, int d_v, hipStream_t stream) {
+  HSTU_DISPATCH_D(hstu_dq_bf16, DQ_NW);
+}
+
+}  // namespace hstu

@@ -1,0 +1,204 @@
+// Schedule ("tile table") construction on the device.
+//
+// From the int32 seq_offsets of a jagged batch (paper, section 2.2) this kernel lists every
+// owner tile of every sequence together with the streamed segments it has to be computed
+// against, and orders the list by non-increasing cost so that the hardware dispatcher, which
+// hands out workgroups in index order, sees the heavy tiles first (longest-processing-time
+// order; the cost of a causal tile grows with its position in the sequence).  Tiles that lie
+// wholly above the diagonal never appear.  For a context-parallel rank (section 2.3) each
+// side of a sequence consists of the two mini-chunks the rank owns.
+//
+// Nothing here needs the host to know the offsets: the grid of the attention kernels is
+// sized from an upper bound on the item count and surplus workgroups exit at once, so no
+// device-to-host copy or synchronisation is involved (section 3 measures what such
+// synchronisations cost).
+#include "hstu_common.h"
+
+namespace hstu {
+
+namespace {
+
+constexpr int PLAN_THREADS = 1024;
+constexpr int NBINS = 2048;
+
+// The (up to two) segments one side of one sequence consists of.
+struct Side {
+  int nseg;
+  int len[2];
+  int pos[2];
+  int rows;  // len[0] + len[1]
+};
+
+__device__ inline Side make_side(int L, int cp, int rank) {
+  Side s;
+  if (rank < 0) {
+    s.nseg = 1; s.len[0] = L; s.pos[0] = 0; s.len[1] = 0; s.pos[1] = 0;
+  } else {
+    // mini-chunk m covers positions [m*c, min((m+1)*c, L)), c = ceil(L / (2*cp))
+    const long long c = ((long long)L + 2 * cp - 1) / (2 * cp);
+    const int m0 = rank, m1 = 2 * cp - 1 - rank;
+    long long b0 = m0 * c, e0 = (m0 + 1) * c, b1 = m1 * c, e1 = (m1 + 1) * c;
+    b0 = b0 < L ? b0 : L; e0 = e0 < L ? e0 : L; b1 = b1 < L ? b1 : L; e1 = e1 < L ? e1 : L;
+    s.nseg = 2;
+    s.len[0] = (int)(e0 - b0); s.pos[0] = (int)b0;
+    s.len[1] = (int)(e1 - b1); s.pos[1] = (int)b1;
+    if (s.len[1] > 0 && s.pos[1] == s.pos[0] + s.len[0]) {  // adjacent chunks: one segment
+      s.len[0] += s.len[1]; s.len[1] = 0; s.nseg = 1;
+    }
+    if (s.len[1] == 0) s.nseg = 1;
+  }
+  s.rows = s.len[0] + s.len[1];
+  return s;
+}
+
+__device__ inline int clampi(long long x, int lo, int hi) {
+  return x < lo ? lo : (x > hi ? hi : (int)x);
+}
+
+// Sanitised [start, end) of sequence b in the global layout: whatever the device array
+// holds, 0 <= start <= end <= total_rows.
+__device__ inline void seq_range(const int32_t* off, int b, int total_rows, int& s, int& e) {
+  s = clampi(off[b], 0, total_rows);
+  e = clampi(off[b + 1], s, total_rows);
+}
+
+__device__ inline int tiles_of(const Side& s, int tile) {
+  return (s.len[0] + tile - 1) / tile + (s.len[1] + tile - 1) / tile;
+}
+
+// Inclusive scan of one value per thread across the block; returns the inclusive prefix and
+// leaves the block total in *total.  `buf` has PLAN_THREADS ints.
+__device__ inline int block_scan(int v, int* buf, int* total) {
+  const int tid = threadIdx.x;
+  buf[tid] = v;
+  __syncthreads();
+  for (int d = 1; d < PLAN_THREADS; d <<= 1) {
+    int t = tid >= d ? buf[tid - d] : 0;
+    __syncthreads();
+    buf[tid] += t;
+    __syncthreads();
+  }
+  int r = buf[tid];
+  *total = buf[PLAN_THREADS - 1];
+  __syncthreads();
+  return r;
+}
+
+__global__ void __launch_bounds__(PLAN_THREADS) plan_kernel(PlanArgs a) {
+  __shared__ int scan_buf[PLAN_THREADS];
+  __shared__ int hist[NBINS];
+  __shared__ int num_items_s;
+  const int tid = threadIdx.x;
+
+  // ---- pass 1: per-sequence bases (prefix sums over the batch) --------------------------
+  int carry_owner = 0, carry_streamed = 0, carry_tiles = 0;
+  for (int b0 = 0; b0 < a.batch; b0 += PLAN_THREADS) {
+    const int b = b0 + tid;
+    int orows = 0, srows = 0, ntile = 0, s = 0, e = 0;
+    if (b < a.batch) {
+      seq_range(a.off, b, a.total_rows, s, e);
+      const Side so = make_side(e - s, a.cp, a.owner_rank);
+      const Side ss = make_side(e - s, a.cp, a.streamed_rank);
+      orows = so.rows; srows = ss.rows; ntile = tiles_of(so, a.tile);
+    }
+    int tot;
+    const int io = block_scan(orows, scan_buf, &tot);   const int tot_o = tot;
+    const int is = block_scan(srows, scan_buf, &tot);   const int tot_s = tot;
+    const int it = block_scan(ntile, scan_buf, &tot);   const int tot_t = tot;
+    if (b < a.batch) {
+      // global layouts keep the caller's offsets; local layouts are packed rank rows
+      a.owner_base[b] = a.owner_rank < 0 ? s : carry_owner + io - orows;
+      a.streamed_base[b] = a.streamed_rank < 0 ? s : carry_streamed + is - srows;
+      a.tile_base[b] = carry_tiles + it - ntile;
+    }
+    carry_owner += tot_o; carry_streamed += tot_s; carry_tiles += tot_t;
+  }
+  if (tid == 0) {
+    a.tile_base[a.batch] = carry_tiles;
+    num_items_s = carry_tiles < a.max_items ? carry_tiles : a.max_items;
+  }
+  for (int i = tid; i < NBINS; i += PLAN_THREADS) hist[i] = 0;
+  __syncthreads();
+  const int num_items = num_items_s;
+
+  // ---- pass 2: describe every item, histogram its cost -----------------------------------
+  for (int i = tid; i < num_items; i += PLAN_THREADS) {
+    int lo = 0, hi = a.batch;  // largest b with tile_base[b] <= i
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (a.tile_base[mid] <= i) lo = mid; else hi = mid;
+    }
+    const int b = lo;
+    int s, e;
+    seq_range(a.off, b, a.total_rows, s, e);
+    const Side so = make_side(e - s, a.cp, a.owner_rank);
+    const Side ss = make_side(e - s, a.cp, a.streamed_rank);
+    int t = i - a.tile_base[b];
+    const int nt0 = (so.len[0] + a.tile - 1) / a.tile;
+    const int u = t < nt0 ? 0 : 1;
+    if (u) t -= nt0;
+    Item it;
+    it.row0 = a.owner_base[b] + (u ? so.len[0] : 0) + t * a.tile;
+    it.nrows = so.len[u] - t * a.tile;
+    if (it.nrows > a.tile) it.nrows = a.tile;
+    it.pos0 = so.pos[u] + t * a.tile;
+    // never beyond the rows the caller declared for its buffers
+    it.nrows = clampi((long long)a.owner_rows - it.row0, 0, it.nrows);
+    it.nseg = 0;
+    it.cost = 0;
+    for (int g = 0; g < 2; ++g) { it.seg_row0[g] = 0; it.seg_len[g] = 0; it.seg_pos0[g] = 0; }
+    int srow = a.streamed_base[b];
+    for (int g = 0; g < ss.nseg; ++g) {
+      int len = clampi((long long)a.streamed_rows - srow, 0, ss.len[g]);
+      int vis;  // streamed rows that at least one owner row sees
+      if (!a.causal) {
+        vis = len;
+      } else if (a.side == 0) {  // keys at positions <= last query position
+        vis = clampi((long long)it.pos0 + it.nrows - ss.pos[g], 0, len);
+      } else {                   // queries at positions >= first key position
+        vis = len - clampi((long long)it.pos0 - ss.pos[g], 0, len);
+      }
+      if (it.nrows > 0 && vis > 0) {
+        const int n = it.nseg++;
+        it.seg_row0[n] = srow; it.seg_len[n] = len; it.seg_pos0[n] = ss.pos[g];
+        it.cost += (vis + 31) >> 5;
+      }
+      srow += ss.len[g];
+    }
+    it.pad = 0;
+    a.items[i] = it;
+    int bin = it.cost >> a.cost_shift;
+    if (bin > NBINS - 1) bin = NBINS - 1;
+    atomicAdd(&hist[NBINS - 1 - bin], 1);  // reversed: heavy items get the low indices
+  }
+  __syncthreads();
+
+  // ---- pass 3: bin start positions (exclusive scan over the reversed histogram) ----------
+  {
+    const int h0 = hist[2 * tid], h1 = hist[2 * tid + 1];
+    int tot;
+    const int inc = block_scan(h0 + h1, scan_buf, &tot);
+    hist[2 * tid] = inc - h0 - h1;
+    hist[2 * tid + 1] = inc - h1;
+  }
+  __syncthreads();
+
+  // ---- pass 4: scatter item indices into schedule order ----------------------------------
+  for (int i = tid; i < num_items; i += PLAN_THREADS) {
+    int bin = a.items[i].cost >> a.cost_shift;
+    if (bin > NBINS - 1) bin = NBINS - 1;
+    const int pos = atomicAdd(&hist[NBINS - 1 - bin], 1);
+    a.order[pos] = i;
+  }
+  if (tid == 0) a.header[0] = num_items;
+}
+
+}  // namespace
+
+hipError_t launch_plan(const PlanArgs& a, hipStream_t stream) {
+  static_assert(NBINS == 2 * PLAN_THREADS, "pass 3 handles two bins per thread");
+  hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(PLAN_THREADS), 0, stream, a);
+  return hipGetLastError();
+}
+
+}  // namespace hstu
