@@ -1,0 +1,218 @@
+#!/usr/bin/env python3
+"""Benchmark of the jagged HSTU attention hot path on one MI355X.
+
+One step = one pass of the whole hot path over one synthetic jagged batch: schedule build,
+forward, dk/dv pass, dq pass (forward only for the forward-only workload; for the
+context-parallel workload every rank's partial, ranks one after the other on the one GPU).
+Inputs are resident in HBM before the timed region starts.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg5|cfg3|cfg2|cfg4]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import workloads  # noqa: E402
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E peak
+
+
+def _traffic_from_profiles(kernel: str, workload: str):
+    """HBM bytes per launch measured with rocprofv3 --pmc, if a summary for it is committed."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_%s_%s.txt" % (kernel, workload))
+    try:
+        for line in open(path):
+            if line.startswith("hbm_bytes_per_launch:"):
+                return float(line.split(":")[1].split()[0])
+    except OSError:
+        pass
+    return None
+
+
+def _cpu_baseline(w: workloads.Workload, prefix_rows: int):
+    """The oracle as it stands, timed on this machine's host cores on a bounded sample."""
+    import oracle  # CPU-baseline leg only
+    lengths = [min(l, prefix_rows) for l in w.lengths]
+    sub = workloads.custom("sample", lengths, w.num_heads, w.d_qk, w.d_v, w.max_len, w.dtype,
+                           w.scale, w.seed, w.backward)
+    vals = workloads.values(sub)
+    f64 = {k: workloads.to_f64(v) for k, v in vals.items()}
+    off = sub.seq_offsets()
+    t0 = time.perf_counter()
+    oracle.fwd(f64["q"], f64["k"], f64["v"], off, sub.max_len, sub.alpha, True)
+    fl = sub.flops()["fwd"]
+    if w.backward:
+        oracle.bwd(f64["q"], f64["k"], f64["v"], f64["d_o"], off, sub.max_len, sub.alpha, True)
+        fl += sub.flops()["bwd"]
+    dt = time.perf_counter() - t0
+    return {
+        "value": fl / dt / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
+        "sample": "first %d rows of each of the %d sequences, all %d heads, %s, %.1f s of oracle time"
+                  % (prefix_rows, sub.batch, sub.num_heads, "fwd+bwd" if w.backward else "fwd", dt),
+    }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg5", choices=["cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-prefix-rows", type=int, default=0, help="rows per sequence in the CPU sample")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU only: this build has no multi-GPU path (run with --gpus 1)",
+              file=sys.stderr)
+        return 2
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        return 2
+
+    import paper_2508_04711_amd as lib
+    lib.load_library()  # fail loudly if the HIP library is not built
+
+    cfg = int(args.workload[3:])
+    w = workloads.config(cfg)
+    dev = torch.device("cuda:0")
+    vals = {k: v.to(dev) for k, v in workloads.values(w).items()}
+    off_np = w.seq_offsets()
+    off = torch.from_numpy(off_np).to(dev)
+    T, H = w.total_rows, w.num_heads
+    dt = workloads.torch_dtype(w)
+    fl = w.flops()
+    step_flops = fl["fwd"] + (fl["bwd"] if w.backward else 0.0)
+
+    if w.cp_size:
+        # Emulate every rank on the one GPU: rank r's query rows (mini-chunks r and 2CP-1-r of
+        # every sequence, gathered beforehand) against all causally visible keys.
+        cp = w.cp_size
+        ranks = []
+        for r in range(cp):
+            rows = []
+            for b, L in enumerate(w.lengths):
+                c = -(-L // (2 * cp))
+                for m in (r, 2 * cp - 1 - r):
+                    lo, hi = min(m * c, L), min((m + 1) * c, L)
+                    rows.append(torch.arange(off_np[b] + lo, off_np[b] + hi))
+            idx = torch.cat(rows).to(dev)
+            ranks.append({
+                "q": vals["q"][idx].contiguous(), "d_o": vals["d_o"][idx].contiguous(),
+                "o": torch.empty((len(idx), H, w.d_v), dtype=dt, device=dev),
+                "dq": torch.empty((len(idx), H, w.d_qk), dtype=dt, device=dev),
+                "dk": torch.empty((T, H, w.d_qk), dtype=dt, device=dev),
+                "dv": torch.empty((T, H, w.d_v), dtype=dt, device=dev),
+            })
+        ws = torch.empty(lib.hstu_jagged_attn_workspace_bytes(
+            (w.batch, H, w.d_qk, w.d_v, w.max_len, w.alpha, True, 0, T), 2), dtype=torch.uint8, device=dev)
+
+        def step():
+            for r, rk in enumerate(ranks):
+                lib.hstu_jagged_attn_cp_partial(rk["q"], vals["k"], vals["v"], rk["d_o"], off, T,
+                                                w.max_len, w.alpha, True, cp, r, -1,
+                                                out=(rk["o"], rk["dq"], rk["dk"], rk["dv"]), workspace=ws)
+    else:
+        o = torch.empty((T, H, w.d_v), dtype=dt, device=dev)
+        dq = torch.empty((T, H, w.d_qk), dtype=dt, device=dev)
+        dk = torch.empty_like(dq)
+        dv = torch.empty_like(o)
+        p = (w.batch, H, w.d_qk, w.d_v, w.max_len, w.alpha, True, 0, T)
+        ws = torch.empty(max(lib.hstu_jagged_attn_workspace_bytes(p, 0),
+                             lib.hstu_jagged_attn_workspace_bytes(p, 1)), dtype=torch.uint8, device=dev)
+
+        def step():
+            lib.hstu_jagged_attn_fwd(vals["q"], vals["k"], vals["v"], off, w.max_len, w.alpha, True,
+                                     out=o, workspace=ws)
+            if w.backward:
+                lib.hstu_jagged_attn_bwd(vals["q"], vals["k"], vals["v"], vals["d_o"], off, w.max_len,
+                                         w.alpha, True, out=(dq, dk, dv), workspace=ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed / args.steps * 1e3
+    tflops = step_flops / (ms_per_step * 1e-3) / 1e12
+
+    # Per-kernel durations over the same steps: HIP events recorded by the library on the
+    # stream it launches on, one pair per kernel launch.
+    prof_steps = max(1, min(args.steps, 10))
+    lib.hstu_debug_timing_begin(64 * prof_steps * max(1, w.cp_size))
+    for _ in range(prof_steps):
+        step()
+    recs = lib.hstu_debug_timing_end(64 * prof_steps * max(1, w.cp_size))
+    per_kind = {}
+    for kind, ms in recs:
+        per_kind.setdefault(kind, []).append(ms)
+    launches_per_step = {k: len(v) // prof_steps for k, v in per_kind.items()}
+    avg_ms = {k: float(np.mean(v)) for k, v in per_kind.items()}
+    ms_by_kind_per_step = {k: avg_ms[k] * launches_per_step[k] for k in avg_ms}
+
+    # Dominant kernel and its roofline.  Algorithmic flops per visible pair and head:
+    # forward 2*d_qk + 2*d_v; dk/dv pass 4*d_qk + 4*d_v (S recompute, dP, dV, dK);
+    # dq pass 2*d_qk (dS K; its own recomputation of S and dP is not counted).
+    pairs = w.pairs_per_head * H
+    alg = {"fwd": (2 * w.d_qk + 2 * w.d_v) * pairs, "dkdv": (4 * w.d_qk + 4 * w.d_v) * pairs,
+           "dq": 2 * w.d_qk * pairs}
+    hw = {"fwd": alg["fwd"], "dkdv": alg["dkdv"], "dq": (4 * w.d_qk + 2 * w.d_v) * pairs}
+    dom = max((k for k in ms_by_kind_per_step if k in alg), key=lambda k: ms_by_kind_per_step[k])
+    n_launch = launches_per_step[dom]
+    dom_ms = avg_ms[dom]
+    achieved = alg[dom] / n_launch / (dom_ms * 1e-3) / 1e12
+    kernel_name = {"fwd": "hstu_fwd_bf16", "dkdv": "hstu_dkdv_bf16", "dq": "hstu_dq_bf16"}[dom]
+    roofline = {
+        "bound": "mfma", "kernel": kernel_name, "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
+        "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
+        "traffic": _traffic_from_profiles(kernel_name, w.name),
+        "avg_launch_ms": dom_ms, "launches_per_step": n_launch,
+        "kernels": {k: {"avg_ms": avg_ms[k], "launches_per_step": launches_per_step[k],
+                        "algorithmic_tflops": (alg[k] / launches_per_step[k] / (avg_ms[k] * 1e-3) / 1e12)
+                        if k in alg else None,
+                        "executed_tflops": (hw[k] / launches_per_step[k] / (avg_ms[k] * 1e-3) / 1e12)
+                        if k in hw else None}
+                    for k in avg_ms},
+    }
+    if cfg == 2:
+        # below the ridge: report the forward against HBM bandwidth over algorithmic bytes
+        bytes_alg = 2.0 * T * H * (2 * w.d_qk + 2 * w.d_v)
+        gbs = bytes_alg / (avg_ms["fwd"] * 1e-3) / 1e9
+        roofline.update({"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                         "frac": gbs / PEAK_HBM_GBS})
+
+    out = {
+        "metric": "jagged HSTU attn fwd+bwd TFLOP/s (causal-visible, bf16)" if w.backward
+                  else "jagged HSTU attn fwd TFLOP/s (causal-visible, bf16)",
+        "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": w.name, "batch": w.batch, "total_rows": T, "num_heads": H,
+                   "d_qk": w.d_qk, "d_v": w.d_v, "max_len": w.max_len, "causal": True,
+                   "cp_size": w.cp_size, "pairs_per_head": w.pairs_per_head,
+                   "flops_per_step": step_flops},
+        "frac_of_bf16_mfma_peak": tflops / PEAK_BF16_TFLOPS,
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        prefix = args.cpu_prefix_rows or {2: 1024, 3: 1536, 4: 2048, 5: 2048}[cfg]
+        out["cpu_baseline"] = _cpu_baseline(w, prefix)
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -165,6 +165,18 @@ int hstu_debug_dump_schedule(const hstu_attn_params* params, const hstu_cp_desc*
                              const int32_t* seq_offsets, int32_t* items_host, int32_t max_items,
                              void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* ---- per-launch timing (for benchmarks; the roofline figures of the measurement section) -----
+ * Between hstu_debug_timing_begin() and hstu_debug_timing_end() every kernel the library
+ * launches from the calling thread is bracketed by HIP events recorded on the stream it is
+ * launched on.  This is the one piece of (thread-local) state the library ever keeps.
+ *   begin: max_records in [1, 65536]; launches beyond it are not recorded.
+ *   end:   waits for the recorded launches, writes per launch, in launch order, its kind
+ *          (0 forward, 1 dk/dv pass, 2 dq pass, 3 schedule build) and its duration in
+ *          milliseconds; returns the number written (<= capacity) or a status < 0.
+ */
+int hstu_debug_timing_begin(int max_records);
+int hstu_debug_timing_end(int32_t* kinds, float* milliseconds, int capacity);
+
 /* Rows per work item on the given side for `params` (tile height used by the schedule). */
 int hstu_schedule_tile_rows(const hstu_attn_params* params, int side);
 

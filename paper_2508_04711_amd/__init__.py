@@ -6,6 +6,8 @@ from .binding import (  # noqa: F401
     HstuError,
     hstu_attn_status_string,
     hstu_debug_dump_schedule,
+    hstu_debug_timing_begin,
+    hstu_debug_timing_end,
     hstu_jagged_attn_bwd,
     hstu_jagged_attn_cp_partial,
     hstu_jagged_attn_fwd,

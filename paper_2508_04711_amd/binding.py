@@ -75,6 +75,10 @@ def load_library():
     lib.hstu_debug_dump_schedule.restype = ctypes.c_int
     lib.hstu_debug_dump_schedule.argtypes = [pp, ctypes.POINTER(_CpDesc), ctypes.c_int, i32p,
                                              ctypes.c_void_p, ctypes.c_int32, vp, ctypes.c_size_t, vp]
+    lib.hstu_debug_timing_begin.restype = ctypes.c_int
+    lib.hstu_debug_timing_begin.argtypes = [ctypes.c_int]
+    lib.hstu_debug_timing_end.restype = ctypes.c_int
+    lib.hstu_debug_timing_end.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int]
     lib.hstu_schedule_tile_rows.restype = ctypes.c_int
     lib.hstu_schedule_tile_rows.argtypes = [pp, ctypes.c_int]
     _lib = lib
@@ -293,3 +297,23 @@ def hstu_debug_dump_schedule(seq_offsets: torch.Tensor, total_rows: int, num_hea
     if n < 0:
         raise HstuError(n, "hstu_debug_dump_schedule")
     return buf[:n].copy()
+
+
+KERNEL_KINDS = {0: "fwd", 1: "dkdv", 2: "dq", 3: "plan"}
+
+
+def hstu_debug_timing_begin(max_records: int = 4096) -> None:
+    rc = load_library().hstu_debug_timing_begin(int(max_records))
+    if rc != 0:
+        raise HstuError(rc, "hstu_debug_timing_begin")
+
+
+def hstu_debug_timing_end(capacity: int = 4096):
+    """List of (kind name, milliseconds), one per kernel launched since timing began."""
+    kinds = np.zeros(capacity, dtype=np.int32)
+    ms = np.zeros(capacity, dtype=np.float32)
+    n = load_library().hstu_debug_timing_end(kinds.ctypes.data_as(ctypes.c_void_p),
+                                             ms.ctypes.data_as(ctypes.c_void_p), int(capacity))
+    if n < 0:
+        raise HstuError(n, "hstu_debug_timing_end")
+    return [(KERNEL_KINDS.get(int(kinds[i]), "?"), float(ms[i])) for i in range(n)]

@@ -12,6 +12,35 @@ using namespace hstu;
 
 bool dim_ok(int d) { return d == 32 || d == 64 || d == 128; }
 
+// Optional per-launch timing (hstu_debug_timing_begin/end): thread-local, off by default.
+struct Timing {
+  bool on = false;
+  std::vector<hipEvent_t> start, stop;
+  std::vector<int> kind;
+  size_t used = 0;
+};
+thread_local Timing g_timing;
+
+struct TimedLaunch {
+  hipStream_t stream;
+  bool active;
+  TimedLaunch(int kind, hipStream_t s) : stream(s), active(false) {
+    Timing& t = g_timing;
+    if (t.on && t.used < t.start.size()) {
+      active = true;
+      t.kind[t.used] = kind;
+      (void)hipEventRecord(t.start[t.used], stream);
+    }
+  }
+  ~TimedLaunch() {
+    if (active) {
+      Timing& t = g_timing;
+      (void)hipEventRecord(t.stop[t.used], stream);
+      ++t.used;
+    }
+  }
+};
+
 int check_params(const hstu_attn_params* p) {
   if (!p) return HSTU_ERR_NULL_PTR;
   if (p->batch < 0 || p->num_heads < 1 || p->total_rows < 0 || p->total_rows >= (1ll << 31) ||
@@ -82,7 +111,10 @@ int build_plan(const hstu_attn_params* p, int cp_size, const SideSpec& s, const 
   a.tile_base = reinterpret_cast<int32_t*>(ws + l.tile_base);
   a.order = reinterpret_cast<int32_t*>(ws + l.order);
   a.items = reinterpret_cast<Item*>(ws + l.items);
-  if (launch_plan(a, stream) != hipSuccess) return HSTU_ERR_HIP;
+  {
+    TimedLaunch timed(3, stream);
+    if (launch_plan(a, stream) != hipSuccess) return HSTU_ERR_HIP;
+  }
   out->plan.header = a.header;
   out->plan.order = a.order;
   out->plan.items = a.items;
@@ -106,6 +138,7 @@ AttnArgs base_args(const hstu_attn_params* p, const BuiltPlan& bp, int accumulat
 
 int run_pass(const hstu_attn_params* p, int pass, const AttnArgs& a, hipStream_t stream) {
   hipError_t e;
+  TimedLaunch timed(pass, stream);
   if (p->dtype == HSTU_BF16) {
     e = pass == PASS_FWD ? launch_fwd_bf16(a, p->d_qk, p->d_v, stream)
         : pass == PASS_DKDV ? launch_dkdv_bf16(a, p->d_qk, p->d_v, stream)
@@ -306,6 +339,44 @@ int hstu_jagged_attn_cp_partial(const hstu_attn_params* params, const hstu_cp_de
     }
   }
   return HSTU_OK;
+}
+
+int hstu_debug_timing_begin(int max_records) {
+  Timing& t = g_timing;
+  if (t.on || max_records < 1 || max_records > (1 << 16)) return HSTU_ERR_BAD_SHAPE;
+  t.start.assign(max_records, nullptr);
+  t.stop.assign(max_records, nullptr);
+  t.kind.assign(max_records, -1);
+  t.used = 0;
+  for (int i = 0; i < max_records; ++i)
+    if (hipEventCreate(&t.start[i]) != hipSuccess || hipEventCreate(&t.stop[i]) != hipSuccess)
+      return HSTU_ERR_HIP;
+  t.on = true;
+  return HSTU_OK;
+}
+
+int hstu_debug_timing_end(int32_t* kinds, float* milliseconds, int capacity) {
+  Timing& t = g_timing;
+  if (!t.on) return HSTU_ERR_BAD_SHAPE;
+  t.on = false;
+  int n = 0, rc = HSTU_OK;
+  for (size_t i = 0; i < t.used; ++i) {
+    float ms = 0.f;
+    if (hipEventSynchronize(t.stop[i]) != hipSuccess ||
+        hipEventElapsedTime(&ms, t.start[i], t.stop[i]) != hipSuccess)
+      rc = HSTU_ERR_HIP;
+    if (n < capacity && kinds && milliseconds) {
+      kinds[n] = t.kind[i];
+      milliseconds[n] = ms;
+      ++n;
+    }
+  }
+  for (size_t i = 0; i < t.start.size(); ++i) {
+    if (t.start[i]) (void)hipEventDestroy(t.start[i]);
+    if (t.stop[i]) (void)hipEventDestroy(t.stop[i]);
+  }
+  t.start.clear(); t.stop.clear(); t.kind.clear(); t.used = 0;
+  return rc == HSTU_OK ? n : rc;
 }
 
 int hstu_debug_dump_schedule(const hstu_attn_params* params, const hstu_cp_desc* cp, int side,

@@ -1,0 +1,120 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, and rejects bad arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "hstu_attn.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2508_04711_amd import binding
+    if not os.path.exists(binding.library_path()):
+        from paper_2508_04711_amd import build
+        build.build()
+    return binding.load_library()
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(hstu_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = _declared_functions()
+    assert {"hstu_jagged_attn_fwd", "hstu_jagged_attn_bwd", "hstu_jagged_attn_cp_partial",
+            "hstu_jagged_attn_workspace_bytes", "hstu_attn_status_string"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def _params(binding, **kw):
+    base = dict(batch=2, num_heads=2, d_qk=64, d_v=64, max_len=16, alpha=0.125, causal=1, dtype=0,
+                total_rows=10, out_dtype=0, reserved=0)
+    base.update(kw)
+    return binding._Params(base["batch"], base["num_heads"], base["d_qk"], base["d_v"],
+                           base["max_len"], base["alpha"], base["causal"], base["dtype"],
+                           base["total_rows"], base["out_dtype"], base["reserved"])
+
+
+def test_status_strings(lib):
+    from paper_2508_04711_amd import binding
+    assert binding.hstu_attn_status_string(0) == "ok"
+    seen = {binding.hstu_attn_status_string(s) for s in range(-7, 1)}
+    assert len(seen) == 8 and "unknown status" not in seen
+    assert binding.hstu_attn_status_string(-99) == "unknown status"
+
+
+def test_bad_arguments_are_rejected_on_the_host(lib):
+    from paper_2508_04711_amd import binding
+    fake = ctypes.c_void_p(0x1000)      # never dereferenced: every call below fails validation first
+    def fwd(p, q=fake, ws=fake, ws_bytes=1 << 20):
+        return lib.hstu_jagged_attn_fwd(ctypes.byref(p), q, fake, fake, fake, fake, ws, ws_bytes, None)
+    assert fwd(_params(binding, d_qk=48)) == -3
+    assert fwd(_params(binding, dtype=7)) == -3
+    assert fwd(_params(binding, out_dtype=0, dtype=1)) == -3       # fp32 in, bf16 out
+    assert fwd(_params(binding, reserved=1)) == -3
+    assert fwd(_params(binding, num_heads=0)) == -2
+    assert fwd(_params(binding, max_len=0)) == -2
+    assert fwd(_params(binding, total_rows=-1)) == -2
+    assert fwd(_params(binding, total_rows=1 << 31)) == -2
+    assert fwd(_params(binding, alpha=float("nan"))) == -2
+    assert fwd(_params(binding), q=None) == -1
+    assert fwd(_params(binding), q=ctypes.c_void_p(0x1004)) == -7
+    assert fwd(_params(binding), ws_bytes=16) == -4
+    assert lib.hstu_jagged_attn_fwd(None, fake, fake, fake, fake, fake, fake, 1 << 20, None) == -1
+    # empty problems succeed without a launch, whatever the pointers
+    assert fwd(_params(binding, batch=0, total_rows=0), q=None) == 0
+    assert fwd(_params(binding, total_rows=0), q=None) == 0
+    bwd = lib.hstu_jagged_attn_bwd(ctypes.byref(_params(binding)), fake, fake, fake, None, fake,
+                                   fake, fake, fake, fake, 1 << 20, None)
+    assert bwd == -1
+    cp = binding._CpDesc(2, 2, 0, 0, 5, 5)       # q_rank out of range
+    rc = lib.hstu_jagged_attn_cp_partial(ctypes.byref(_params(binding)), ctypes.byref(cp), fake, fake,
+                                         fake, None, fake, fake, None, None, None, fake, 1 << 20, None)
+    assert rc == -5
+    cp = binding._CpDesc(0, 0, 0, 0, 5, 5)
+    rc = lib.hstu_jagged_attn_cp_partial(ctypes.byref(_params(binding)), ctypes.byref(cp), fake, fake,
+                                         fake, None, fake, fake, None, None, None, fake, 1 << 20, None)
+    assert rc == -5
+
+
+def test_workspace_query(lib):
+    from paper_2508_04711_amd import binding
+    p = _params(binding, batch=16, total_rows=37117, d_qk=128, d_v=128)
+    sizes = [lib.hstu_jagged_attn_workspace_bytes(ctypes.byref(p), k) for k in (0, 1, 2)]
+    assert 0 < sizes[0] < sizes[1] < sizes[2] < (1 << 20)
+    assert lib.hstu_jagged_attn_workspace_bytes(ctypes.byref(p), 9) == 0
+    assert lib.hstu_jagged_attn_workspace_bytes(ctypes.byref(_params(binding, d_v=5)), 0) == 0
+    # grows with the batch and with the rows, not with the heads
+    big = _params(binding, batch=1000, total_rows=10 ** 6, d_qk=128, d_v=128)
+    assert lib.hstu_jagged_attn_workspace_bytes(ctypes.byref(big), 0) > sizes[0]
+
+
+def test_validate_offsets_host(lib):
+    from paper_2508_04711_amd import binding
+    assert binding.hstu_validate_offsets_host([0, 3, 3, 10], 10) == 0
+    assert binding.hstu_validate_offsets_host([1, 3, 10], 10) == -2
+    assert binding.hstu_validate_offsets_host([0, 5, 4, 10], 10) == -2
+    assert binding.hstu_validate_offsets_host([0, 5, 9], 10) == -2
+
+
+def test_tile_rows(lib):
+    from paper_2508_04711_amd import binding
+    for side in (0, 1):
+        assert binding.hstu_schedule_tile_rows(0, 128, 128, side) % 32 == 0
+        assert binding.hstu_schedule_tile_rows(1, 32, 32, side) > 0
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    from paper_2508_04711_amd import binding
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "_LIB_PATH", "/nonexistent/libhstu_attn.so")
+    with pytest.raises(RuntimeError):
+        binding.load_library()

@@ -1,0 +1,121 @@
+"""The device-built schedule (tile table) against a re-derivation in Python: integer work, exact.
+
+Jagged addressing must be bit-exact: every tile's rows, positions and streamed segments must be
+exactly those the offsets imply, every owner row must belong to exactly one tile, tiles wholly
+above the diagonal must be absent, and heavy tiles must come first.
+"""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+
+def _side(L, cp, rank):
+    """Segments [(pos, len)] of one side of a sequence (rank < 0: the whole sequence)."""
+    if rank < 0:
+        return [(0, L)]
+    c = -(-L // (2 * cp))
+    segs = []
+    for m in (rank, 2 * cp - 1 - rank):
+        lo, hi = min(m * c, L), min((m + 1) * c, L)
+        segs.append((lo, hi - lo))
+    if segs[1][1] > 0 and segs[1][0] == segs[0][0] + segs[0][1]:
+        segs = [(segs[0][0], segs[0][1] + segs[1][1])]
+    return [s for i, s in enumerate(segs) if s[1] > 0 or i == 0]
+
+
+def _expected_items(lengths, tile, causal, side, cp=1, owner_rank=-1, streamed_rank=-1):
+    items = []
+    obase = sbase = 0
+    off = 0
+    for L in lengths:
+        osegs, ssegs = _side(L, cp, owner_rank), _side(L, cp, streamed_rank)
+        ob = off if owner_rank < 0 else obase
+        sb = off if streamed_rank < 0 else sbase
+        orow = ob
+        for (opos, olen) in osegs:
+            for t in range(0, olen, tile):
+                nrows = min(tile, olen - t)
+                pos0 = opos + t
+                segs, cost, srow = [], 0, sb
+                for (spos, slen) in ssegs:
+                    if not causal:
+                        vis = slen
+                    elif side == 0:
+                        vis = min(max(pos0 + nrows - spos, 0), slen)
+                    else:
+                        vis = slen - min(max(pos0 - spos, 0), slen)
+                    if vis > 0:
+                        segs.append((srow, slen, spos))
+                        cost += (vis + 31) // 32
+                    srow += slen
+                segs += [(0, 0, 0)] * (2 - len(segs))
+                nseg = sum(1 for s in segs if s[1] > 0)
+                items.append((orow + t, nrows, pos0, nseg, segs[0][0], segs[1][0], segs[0][1],
+                              segs[1][1], segs[0][2], segs[1][2], cost, 0))
+            orow += olen
+        obase += sum(s[1] for s in osegs)
+        sbase += sum(s[1] for s in ssegs)
+        off += L
+    return items
+
+
+CASES = [
+    ([55, 41, 33, 18], True),
+    ([1, 0, 129, 128, 127, 0, 700, 3], True),
+    ([300, 5, 260], False),
+    (list(np.random.default_rng(5).integers(0, 600, size=70)), True),
+]
+
+
+@pytest.mark.parametrize("side", [0, 1])
+@pytest.mark.parametrize("lengths,causal", CASES)
+def test_full_attention_schedule(lengths, causal, side):
+    import paper_2508_04711_amd as lib
+    lengths = [int(x) for x in lengths]
+    T = sum(lengths)
+    off = torch.tensor(np.concatenate([[0], np.cumsum(lengths)]), dtype=torch.int32, device="cuda")
+    tile = lib.hstu_schedule_tile_rows(0, 128, 128, side)
+    got = lib.hstu_debug_dump_schedule(off, T, 2, 128, 128, causal, 0, side)
+    want = _expected_items(lengths, tile, causal, side)
+    assert sorted(map(tuple, got.tolist())) == sorted(want)
+    costs = got[:, 10]
+    assert np.all(costs[:-1] >= costs[1:]), "heavy tiles first"
+    covered = np.zeros(T, dtype=np.int64)
+    for it in got:
+        covered[it[0]:it[0] + it[1]] += 1
+    assert np.all(covered == 1), "every row in exactly one tile"
+
+
+@pytest.mark.parametrize("side", [0, 1])
+@pytest.mark.parametrize("cp,q_rank,kv_rank", [(2, 0, 1), (2, 1, 0), (4, 3, -1), (4, 0, 0), (3, 1, 2), (1, 0, 0)])
+def test_context_parallel_schedule(cp, q_rank, kv_rank, side):
+    import oracle
+    import paper_2508_04711_amd as lib
+    lengths = [16, 5, 0, 233, 1, 400, 64, 777]
+    T = sum(lengths)
+    off_np = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int32)
+    off = torch.from_numpy(off_np).cuda()
+    nq = len(oracle.cp_global_rows(off_np, cp, q_rank))
+    nk = len(oracle.cp_global_rows(off_np, cp, kv_rank))
+    tile = lib.hstu_schedule_tile_rows(0, 64, 64, side)
+    got = lib.hstu_debug_dump_schedule(off, T, 2, 64, 64, True, 0, side, cp=(cp, q_rank, kv_rank, nq, nk))
+    owner, streamed = (q_rank, kv_rank) if side == 0 else (kv_rank, q_rank)
+    want = _expected_items(lengths, tile, True, side, cp, owner, streamed)
+    assert sorted(map(tuple, got.tolist())) == sorted(want)
+    covered = np.zeros(nq if side == 0 else nk, dtype=np.int64)
+    for it in got:
+        covered[it[0]:it[0] + it[1]] += 1
+    assert np.all(covered == 1)
+
+
+def test_inconsistent_offsets_never_leave_the_declared_rows():
+    # offsets that overshoot the declared total: tiles are clipped to the declared rows
+    import paper_2508_04711_amd as lib
+    off = torch.tensor([0, 100, 5000], dtype=torch.int32, device="cuda")
+    got = lib.hstu_debug_dump_schedule(off, 300, 1, 64, 64, True, 0, 0)
+    for it in got:
+        assert 0 <= it[0] and it[0] + it[1] <= 300
+        for g in range(it[3]):
+            assert 0 <= it[4 + g] and it[4 + g] + it[6 + g] <= 300
