@@ -42,13 +42,16 @@ typedef __attribute__((__vector_size__(2 * sizeof(uint32_t)))) uint32_t u32x2;
 
 constexpr int ST = 64;  // streamed rows per LDS tile
 
-// Swizzle of the 16-byte chunk index by the row: rows r..r+7 at one chunk land in eight
-// different bank groups (row-wise reads) and the 4 rows x 2 chunks a 16-lane transposing read
-// touches do too.
+// Swizzle of the 16-byte chunk index by the row.  LDS has 64 banks of 4 bytes, i.e. 16 chunk
+// positions per 256 bytes.  The position of (row, chunk) is its byte offset / 16 mod 16; the
+// swizzle makes (a) 16 consecutive rows at one logical chunk (a row-wise operand read) and
+// (b) 4 consecutive rows x 4 consecutive chunks (what 32 lanes of a transposing read touch)
+// each land on 16 different positions, with no padding.
 template <int D>
 __device__ __forceinline__ int swz(int row) {
-  if (D >= 64) return (row & 7) ^ ((row & 1) << 2);
-  return (row >> 1) & 3;
+  if (D == 128) return ((row & 3) << 2) | ((row >> 2) & 3);       // 1 row per 256 bytes
+  if (D == 64) return (((row >> 1) & 1) << 2) | ((row >> 2) & 3);  // 2 rows per 256 bytes
+  return (row >> 2) & 3;                                           // 4 rows per 256 bytes
 }
 
 // Byte offset inside a [rows][D] bf16 LDS tile of 16-byte chunk `chunk` of row `row`.
@@ -89,15 +92,20 @@ struct TileRegs {
   static constexpr int ITERS = (CHUNKS + NT - 1) / NT;
   u32x4 r[ITERS];
 
-  // base: element pointer to (row 0 of the tile, this head); rows >= valid read as zero.
+  // base: element pointer to (row 0 of the tile, this head); rows >= valid read as zero.  The
+  // loads go through a buffer resource that covers exactly the valid rows, so the hardware's
+  // range check supplies the zeros and no lane needs a branch.
   __device__ __forceinline__ void load(const __bf16* base, int64_t row_stride, int valid, int tid) {
+    const int rs = (int)row_stride * 2;  // bytes
+    const int rows = valid < 0 ? 0 : (valid < ST ? valid : ST);
+    const __amdgpu_buffer_rsrc_t rsrc =
+        __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, rows * rs, 0x00020000);
 #pragma unroll
     for (int i = 0; i < ITERS; ++i) {
       const int c = tid + i * NT;
       const int row = c / CPR, chunk = c % CPR;
-      u32x4 z = {0u, 0u, 0u, 0u};
-      if (c < CHUNKS && row < valid) z = *(const u32x4*)(base + row * row_stride + chunk * 8);
-      r[i] = z;
+      const int off = c < CHUNKS ? row * rs + chunk * 16 : 0x7fffffff;
+      r[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, off, 0, 0);
     }
   }
   __device__ __forceinline__ void store(char* tile, int tid) const {
@@ -111,13 +119,16 @@ struct TileRegs {
 };
 
 // 32 owner rows of one head as B operands: lane (n, hh) holds row n, elements 16*s + 8*hh + e.
+// base points at (row 0 of the owner tile, this head); rows >= nrows read as zero.
 template <int D>
 __device__ __forceinline__ void load_owner(bf16x8 (&reg)[D / 16], const __bf16* base,
-                                           int64_t row_stride, int row, bool valid, int hh) {
+                                           int64_t row_stride, int row, int nrows, int hh) {
+  const int rs = (int)row_stride * 2;
+  const __amdgpu_buffer_rsrc_t rsrc =
+      __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, nrows * rs, 0x00020000);
 #pragma unroll
   for (int s = 0; s < D / 16; ++s) {
-    u32x4 z = {0u, 0u, 0u, 0u};
-    if (valid) z = *(const u32x4*)(base + row * row_stride + s * 16 + hh * 8);
+    const u32x4 z = __builtin_amdgcn_raw_buffer_load_b128(rsrc, row * rs + s * 32 + hh * 16, 0, 0);
     reg[s] = __builtin_bit_cast(bf16x8, z);
   }
 }
@@ -273,7 +284,7 @@ __global__ void __launch_bounds__(NW * 64) hstu_fwd_bf16(AttnArgs a) {
   const int orow = wave * 32 + n;  // this lane's owner row inside the tile
   const bool wave_on = wave * 32 < it.nrows;
   bf16x8 qreg[DQK / 16];
-  load_owner<DQK>(qreg, qg, sq, orow, orow < it.nrows, hh);
+  load_owner<DQK>(qreg, qg, sq, orow, it.nrows, hh);
 
   f32x16 oacc[DV / 32];
 #pragma unroll
@@ -381,8 +392,8 @@ __global__ void __launch_bounds__(NW * 64) hstu_dkdv_bf16(AttnArgs a) {
   const int orow = wave * 32 + n;
   const bool wave_on = wave * 32 < it.nrows;
   bf16x8 kreg[DQK / 16], vreg[DV / 16];
-  load_owner<DQK>(kreg, kg, sq, orow, orow < it.nrows, hh);
-  load_owner<DV>(vreg, vg, sv, orow, orow < it.nrows, hh);
+  load_owner<DQK>(kreg, kg, sq, orow, it.nrows, hh);
+  load_owner<DV>(vreg, vg, sv, orow, it.nrows, hh);
 
   f32x16 dkacc[DQK / 32], dvacc[DV / 32];
 #pragma unroll
@@ -522,8 +533,8 @@ __global__ void __launch_bounds__(NW * 64) hstu_dq_bf16(AttnArgs a) {
   const int orow = wave * 32 + n;
   const bool wave_on = wave * 32 < it.nrows;
   bf16x8 qreg[DQK / 16], greg[DV / 16];
-  load_owner<DQK>(qreg, qg, sq, orow, orow < it.nrows, hh);
-  load_owner<DV>(greg, gg, sv, orow, orow < it.nrows, hh);
+  load_owner<DQK>(qreg, qg, sq, orow, it.nrows, hh);
+  load_owner<DV>(greg, gg, sv, orow, it.nrows, hh);
 
   f32x16 dqacc[DQK / 32];
 #pragma unroll
