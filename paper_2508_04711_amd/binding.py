@@ -14,7 +14,8 @@ import numpy as np
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libhstu_attn.so")
+# HSTU_ATTN_LIB selects another build of the same library (A/B comparisons of kernels).
+_LIB_PATH = os.environ.get("HSTU_ATTN_LIB") or os.path.join(_HERE, "libhstu_attn.so")
 _lib = None
 
 HSTU_BF16, HSTU_F32 = 0, 1

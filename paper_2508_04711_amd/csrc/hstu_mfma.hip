@@ -25,6 +25,8 @@
 // SiLU, its derivative and the mask are evaluated in fp32 on the accumulator registers; P and
 // dS are rounded to bf16 only as operands of the second product; alpha and 1/max_len are
 // folded into one fp32 scale at the output, which is rounded to bf16 once.
+#include <type_traits>
+
 #include "hstu_common.h"
 
 namespace hstu {
@@ -40,6 +42,9 @@ typedef __attribute__((__vector_size__(2 * sizeof(uint32_t)))) uint32_t u32x2;
 
 #define HSTU_LDS(T, p) ((__attribute__((address_space(3))) T*)(p))
 
+#ifndef HSTU_ABLATE
+#define HSTU_ABLATE 0
+#endif
 constexpr int ST = 64;  // streamed rows per LDS tile
 
 // Swizzle of the 16-byte chunk index by the row.  LDS has 64 banks of 4 bytes, i.e. 16 chunk
@@ -84,6 +89,45 @@ __device__ __forceinline__ bf16x8 lds_read_cols(const char* tile, int row0, int 
   return __builtin_bit_cast(bf16x8, both);
 }
 
+// Per-lane byte offsets of operand reads inside a tile, computed once per kernel.  The swizzle
+// depends on row mod 16 only, so a read of block blk (rows 32*blk + ...) is the same offset plus
+// a constant, which the compiler folds into the instruction's immediate offset.
+template <int D>
+struct RowAddr {  // row-wise operand reads of row n (+32*blk): one address per 16-element step
+  int a[D / 16];
+  __device__ __forceinline__ void init(int n, int hh) {
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ++ks) a[ks] = lds_off<D>(n, ks * 2 + hh);
+  }
+  __device__ __forceinline__ bf16x8 read(const char* tile, int blk, int ks) const {
+    return *HSTU_LDS(bf16x8, tile + blk * 32 * D * 2 + a[ks]);
+  }
+};
+
+template <int D>
+struct ColAddr {  // transposing reads: per 32-column block, the lane's address in rows 0..7 and 8..15
+  int a[D / 32][2];
+  __device__ __forceinline__ void init(int lane) {
+    const int i = lane & 15, g = lane >> 4;
+    const int row = ((g >> 1) << 2) + (i >> 2);
+#pragma unroll
+    for (int c = 0; c < D / 32; ++c) {
+      const int col = c * 32 + ((g & 1) << 4) + ((i & 3) << 2);
+      a[c][0] = lds_off<D>(row, col >> 3) + ((col & 7) << 1);
+      a[c][1] = lds_off<D>(row + 8, col >> 3) + ((col & 7) << 1);
+    }
+  }
+  // operand for streamed rows 16*half16 .. 16*half16+15 of the tile (half16 = 2*blk + c), columns 32*cb ..
+  __device__ __forceinline__ bf16x8 read(const char* tile, int half16, int cb) const {
+    const char* base = tile + half16 * 16 * D * 2;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(HSTU_LDS(s16x4, base + a[cb][0]));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(HSTU_LDS(s16x4, base + a[cb][1]));
+    typedef __attribute__((__vector_size__(8 * sizeof(short)))) short s16x8;
+    const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, both);
+  }
+};
+
 // A streamed tile on its way from global memory to LDS, held in registers meanwhile.
 template <int D, int NT>
 struct TileRegs {
@@ -118,14 +162,43 @@ struct TileRegs {
   }
 };
 
+// Asynchronous copy of one streamed tile (ST rows of one head) from global memory straight into
+// its swizzled LDS layout: each wave-wide load moves 64 x 16 bytes into 1 KB of consecutive LDS
+// (lane l lands at byte 16*l), so the lane that fills physical chunk pc of a row fetches the
+// logical chunk pc ^ swz(row).  Rows >= valid are outside the buffer resource and arrive as
+// zeros.  `tile` must be 1 KB aligned and uniform across the wave.
+template <int D, int NW>
+__device__ __forceinline__ void tile_copy_async(char* tile, const __bf16* base, int64_t row_stride,
+                                                int valid, int wave, int lane) {
+  constexpr int CPR = D / 8;            // 16-byte chunks per row
+  constexpr int RPL = 64 / CPR;         // rows per wave-wide load
+  constexpr int LOADS = ST / RPL;       // wave-wide loads per tile
+  const int rs = (int)row_stride * 2;   // bytes
+  const int rows = valid < 0 ? 0 : (valid < ST ? valid : ST);
+  const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      (void*)base, 0, __builtin_amdgcn_readfirstlane(rows * rs), 0x00020000);
+#pragma unroll
+  for (int i = 0; i < (LOADS + NW - 1) / NW; ++i) {
+    const int idx = i * NW + wave;
+    if (LOADS % NW != 0 && idx >= LOADS) break;
+    const int row = idx * RPL + lane / CPR;
+    const int chunk = (lane % CPR) ^ swz<D>(row);
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, HSTU_LDS(void, tile + idx * 1024), 16,
+                                             row * rs + chunk * 16, 0, 0, 0);
+  }
+}
+
+// Completion of this wave's outstanding tile copies (they count as vector memory loads).
+__device__ __forceinline__ void tile_copy_wait() { __builtin_amdgcn_s_waitcnt(0x0f70); }
+
 // 32 owner rows of one head as B operands: lane (n, hh) holds row n, elements 16*s + 8*hh + e.
 // base points at (row 0 of the owner tile, this head); rows >= nrows read as zero.
 template <int D>
 __device__ __forceinline__ void load_owner(bf16x8 (&reg)[D / 16], const __bf16* base,
                                            int64_t row_stride, int row, int nrows, int hh) {
   const int rs = (int)row_stride * 2;
-  const __amdgpu_buffer_rsrc_t rsrc =
-      __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, nrows * rs, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      (void*)base, 0, __builtin_amdgcn_readfirstlane(nrows * rs), 0x00020000);
 #pragma unroll
   for (int s = 0; s < D / 16; ++s) {
     const u32x4 z = __builtin_amdgcn_raw_buffer_load_b128(rsrc, row * rs + s * 32 + hh * 16, 0, 0);
@@ -139,7 +212,11 @@ __device__ __forceinline__ f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c) {
 
 // sigmoid(alpha * s) with c1 = -alpha * log2(e).  exp2 overflow gives rcp(inf) = 0.
 __device__ __forceinline__ float sigmoid_scaled(float s, float c1) {
+#if HSTU_ABLATE == 1
+  return c1;
+#else
   return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(s * c1));
+#endif
 }
 
 __device__ __forceinline__ bf16x8 pack8(const float* x) {
@@ -253,7 +330,21 @@ __device__ __forceinline__ void store_one(void* out, int64_t elem, float x, int 
 
 __device__ __forceinline__ bool fetch_item(const Plan& plan, int slot, Item& it) {
   if (slot >= plan.header[0]) return false;
-  it = plan.items[plan.order[slot]];
+  const Item* src = plan.items + plan.order[slot];
+  // The item is the same for every lane: keep it in scalar registers so that everything derived
+  // from it (addresses, buffer resources, loop bounds) is uniform.
+  it.row0 = __builtin_amdgcn_readfirstlane(src->row0);
+  it.nrows = __builtin_amdgcn_readfirstlane(src->nrows);
+  it.pos0 = __builtin_amdgcn_readfirstlane(src->pos0);
+  it.nseg = __builtin_amdgcn_readfirstlane(src->nseg);
+#pragma unroll
+  for (int g = 0; g < 2; ++g) {
+    it.seg_row0[g] = __builtin_amdgcn_readfirstlane(src->seg_row0[g]);
+    it.seg_len[g] = __builtin_amdgcn_readfirstlane(src->seg_len[g]);
+    it.seg_pos0[g] = __builtin_amdgcn_readfirstlane(src->seg_pos0[g]);
+  }
+  it.cost = 0;
+  it.pad = 0;
   return it.nrows > 0;
 }
 
@@ -262,20 +353,109 @@ __device__ __forceinline__ bool fetch_item(const Plan& plan, int slot, Item& it)
 //   S^T = K Q^T (A = K tile rows, B = Q registers)  ->  P^T in accumulator layout
 //   O^T += V^T P^T (A = V tile transposed read, B = P^T registers)
 // =============================================================================================
+
+// One 32-key block of a tile on the diagonal: blocks wholly above the wave's rows are skipped,
+// the block the diagonal crosses is masked element by element.
+template <int DQK, int DV>
+__device__ __forceinline__ void fwd_block_masked(const char* kt, const char* vt, int blk,
+                                                 const RowAddr<DQK>& ra, const ColAddr<DV>& ca,
+                                                 const bf16x8 (&qreg)[DQK / 16],
+                                                 f32x16 (&oacc)[DV / 32], float c1, int k_lo,
+                                                 int q_lo, bool mask, int n, int hh) {
+  f32x16 s;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) s[r] = 0.f;
+#pragma unroll
+  for (int ks = 0; ks < DQK / 16; ++ks) s = mfma(ra.read(kt, blk, ks), qreg[ks], s);
+  float p[16];
+#pragma unroll
+  for (int r = 0; r < 16; ++r) p[r] = s[r] * sigmoid_scaled(s[r], c1);
+  if (mask) {
+    const int qpos = q_lo + n;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int kpos = k_lo + 8 * (r >> 2) + 4 * hh + (r & 3);
+      p[r] = kpos <= qpos ? p[r] : 0.f;
+    }
+  }
+  const bf16x8 pb0 = pack8(p), pb1 = pack8(p + 8);
+#pragma unroll
+  for (int dvb = 0; dvb < DV / 32; ++dvb) {
+    oacc[dvb] = mfma(ca.read(vt, blk * 2, dvb), pb0, oacc[dvb]);
+    oacc[dvb] = mfma(ca.read(vt, blk * 2 + 1, dvb), pb1, oacc[dvb]);
+  }
+}
+
+// A whole 64-key tile with nothing to mask (every key precedes every query row of the wave, or
+// the problem is not causal; rows beyond the segment are zero in LDS and contribute nothing).
+// Operands are fetched from LDS a whole product ahead, and the SiLU of one block is interleaved
+// with the matrix instructions of its neighbours: S(1) runs while P(0) is formed, P(0) V runs
+// while P(1) is formed.
+template <int DQK, int DV>
+__device__ __forceinline__ void fwd_tile_full(const char* kt, const char* vt,
+                                              const RowAddr<DQK>& ra, const ColAddr<DV>& ca,
+                                              const bf16x8 (&qreg)[DQK / 16],
+                                              f32x16 (&oacc)[DV / 32], float c1) {
+  constexpr int KS = DQK / 16, NPV = DV / 16;
+  constexpr int EQK = 16 / KS, EPV = 16 / NPV;  // SiLU elements per interleaved matrix instruction
+  bf16x8 ka[KS], va[NPV];
+  f32x16 s0, s1;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) { s0[r] = 0.f; s1[r] = 0.f; }
+
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) ka[ks] = ra.read(kt, 0, ks);
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) s0 = mfma(ka[ks], qreg[ks], s0);
+
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) ka[ks] = ra.read(kt, 1, ks);
+#pragma unroll
+  for (int i = 0; i < NPV; ++i) va[i] = ca.read(vt, i & 1, i >> 1);
+
+  float p[16];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) {
+    s1 = mfma(ka[ks], qreg[ks], s1);
+#pragma unroll
+    for (int e = ks * EQK; e < (ks + 1) * EQK; ++e) p[e] = s0[e] * sigmoid_scaled(s0[e], c1);
+  }
+  bf16x8 pb0 = pack8(p), pb1 = pack8(p + 8);
+
+  bf16x8 vb[NPV];
+#pragma unroll
+  for (int i = 0; i < NPV; ++i) vb[i] = ca.read(vt, 2 + (i & 1), i >> 1);
+
+  float p1[16];
+#pragma unroll
+  for (int i = 0; i < NPV; ++i) {
+    oacc[i >> 1] = mfma(va[i], (i & 1) ? pb1 : pb0, oacc[i >> 1]);
+#pragma unroll
+    for (int e = i * EPV; e < (i + 1) * EPV; ++e) p1[e] = s1[e] * sigmoid_scaled(s1[e], c1);
+  }
+  pb0 = pack8(p1);
+  pb1 = pack8(p1 + 8);
+#pragma unroll
+  for (int i = 0; i < NPV; ++i) oacc[i >> 1] = mfma(vb[i], (i & 1) ? pb1 : pb0, oacc[i >> 1]);
+}
+
 template <int DQK, int DV, int NW>
-__global__ void __launch_bounds__(NW * 64) hstu_fwd_bf16(AttnArgs a) {
-  constexpr int NT = NW * 64;
+__global__ void __launch_bounds__(NW * 64, 2) hstu_fwd_bf16(AttnArgs a) {
   constexpr int KB = ST * DQK * 2, VB = ST * DV * 2;
-  __shared__ __attribute__((aligned(16))) char smem[2 * (KB + VB)];
-  auto kbuf = [&](int b) { return smem + b * (KB + VB); };
-  auto vbuf = [&](int b) { return smem + b * (KB + VB) + KB; };
+  // Two separate arrays, one per buffer: the compiler can then see that the asynchronous copy
+  // into one buffer cannot alias the operand reads from the other.
+  __shared__ __attribute__((aligned(1024))) char smem0[KB + VB];
+  __shared__ __attribute__((aligned(1024))) char smem1[KB + VB];
+  auto kbuf = [&](int b) { return b ? smem1 : smem0; };
+  auto vbuf = [&](int b) { return (b ? smem1 : smem0) + KB; };
 
   const int H = a.num_heads;
   const int slot = blockIdx.x / H, h = blockIdx.x % H;
   Item it;
   if (!fetch_item(a.plan, slot, it)) return;
 
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 31, hh = lane >> 5;
+  const int tid = threadIdx.x, lane = tid & 63, n = lane & 31, hh = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int64_t sq = (int64_t)H * DQK, sv = (int64_t)H * DV;
   const __bf16* qg = (const __bf16*)a.q + (int64_t)it.row0 * sq + h * DQK;
   const __bf16* kg = (const __bf16*)a.k + h * DQK;
@@ -296,63 +476,52 @@ __global__ void __launch_bounds__(NW * 64) hstu_fwd_bf16(AttnArgs a) {
   const float c1 = -a.alpha * 1.4426950408889634f;
   const int q_lo = it.pos0 + wave * 32, q_hi = q_lo + 31;
 
-  TileRegs<DQK, NT> kr;
-  TileRegs<DV, NT> vr;
   if (st.total > 0) {
     const TileRef t0 = tile_ref(it, st, 0);
-    kr.load(kg + (int64_t)t0.row * sq, sq, t0.valid, tid);
-    vr.load(vg + (int64_t)t0.row * sv, sv, t0.valid, tid);
-    kr.store(kbuf(0), tid);
-    vr.store(vbuf(0), tid);
+    tile_copy_async<DQK, NW>(kbuf(0), kg + (int64_t)t0.row * sq, sq, t0.valid, wave, lane);
+    tile_copy_async<DV, NW>(vbuf(0), vg + (int64_t)t0.row * sv, sv, t0.valid, wave, lane);
   }
+  tile_copy_wait();
   __syncthreads();
 
-  for (int j = 0; j < st.total; ++j) {
+  RowAddr<DQK> ra;
+  ColAddr<DV> ca;
+  ra.init(n, hh);
+  ca.init(lane);
+
+  // One tile of the stream; BUF is a compile-time buffer index so that every LDS address is a
+  // per-lane register plus an immediate.
+  auto step = [&](int j, auto buf_tag) {
+    constexpr int BUF = decltype(buf_tag)::value;
     const TileRef tj = tile_ref(it, st, j);
-    const bool more = j + 1 < st.total;
-    if (more) {
+    if (HSTU_ABLATE != 3 && j + 1 < st.total) {  // the other buffer was last read before the barrier that ended j-1
       const TileRef tn = tile_ref(it, st, j + 1);
-      kr.load(kg + (int64_t)tn.row * sq, sq, tn.valid, tid);
-      vr.load(vg + (int64_t)tn.row * sv, sv, tn.valid, tid);
+      tile_copy_async<DQK, NW>(kbuf(BUF ^ 1), kg + (int64_t)tn.row * sq, sq, tn.valid, wave, lane);
+      tile_copy_async<DV, NW>(vbuf(BUF ^ 1), vg + (int64_t)tn.row * sv, sv, tn.valid, wave, lane);
     }
-    const char* kt = kbuf(j & 1);
-    const char* vt = vbuf(j & 1);
+    const char* kt = kbuf(BUF);
+    const char* vt = vbuf(BUF);
     if (wave_on) {
+      if (!a.causal || tj.pos + ST - 1 <= q_lo) {
+        fwd_tile_full<DQK, DV>(kt, vt, ra, ca, qreg, oacc, c1);
+      } else {
 #pragma unroll
-      for (int blk = 0; blk < ST / 32; ++blk) {
-        const int k_lo = tj.pos + blk * 32;
-        if (blk * 32 >= tj.valid) continue;           // nothing visible in this block
-        if (a.causal && k_lo > q_hi) continue;        // wholly above this wave's diagonal
-        f32x16 s;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) s[r] = 0.f;
-#pragma unroll
-        for (int ks = 0; ks < DQK / 16; ++ks)
-          s = mfma(lds_read_rows<DQK>(kt, blk * 32 + n, ks * 2 + hh), qreg[ks], s);
-        float p[16];
-#pragma unroll
-        for (int r = 0; r < 16; ++r) p[r] = s[r] * sigmoid_scaled(s[r], c1);
-        if (a.causal && k_lo + 31 > q_lo) {           // the diagonal crosses this block
-          const int qpos = q_lo + n;
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int kpos = k_lo + 8 * (r >> 2) + 4 * hh + (r & 3);
-            p[r] = kpos <= qpos ? p[r] : 0.f;
-          }
-        }
-        const bf16x8 pb0 = pack8(p), pb1 = pack8(p + 8);
-#pragma unroll
-        for (int dvb = 0; dvb < DV / 32; ++dvb) {
-          oacc[dvb] = mfma(lds_read_cols<DV>(vt, blk * 32, dvb * 32, lane), pb0, oacc[dvb]);
-          oacc[dvb] = mfma(lds_read_cols<DV>(vt, blk * 32 + 16, dvb * 32, lane), pb1, oacc[dvb]);
+        for (int blk = 0; blk < ST / 32; ++blk) {
+          const int k_lo = tj.pos + blk * 32;
+          if (blk * 32 >= tj.valid || k_lo > q_hi) continue;
+          fwd_block_masked<DQK, DV>(kt, vt, blk, ra, ca, qreg, oacc, c1, k_lo, q_lo,
+                                    k_lo + 31 > q_lo, n, hh);
         }
       }
     }
-    if (more) {
-      kr.store(kbuf((j + 1) & 1), tid);
-      vr.store(vbuf((j + 1) & 1), tid);
-    }
+#if HSTU_ABLATE != 4
+    tile_copy_wait();
     __syncthreads();
+#endif
+  };
+  for (int j = 0; j < st.total; j += 2) {
+    step(j, std::integral_constant<int, 0>{});
+    if (j + 1 < st.total) step(j + 1, std::integral_constant<int, 1>{});
   }
 
   // O^T accumulators: lane holds query row n, elements dvb*32 + 8*(r/4) + 4*hh + r%4.
@@ -369,20 +538,160 @@ __global__ void __launch_bounds__(NW * 64) hstu_fwd_bf16(AttnArgs a) {
 //   dK += dS^T Q   (A = dS registers, B = Q tile transposed read)
 // Each key tile belongs to exactly one workgroup, so dk and dv need no atomics.
 // =============================================================================================
+
+// p' = s*sg (p = alpha*p'/N);  silu'(alpha*s) = sg + alpha*p'*(1-sg);  ds' = dp*silu' (ds = ds'/N)
+__device__ __forceinline__ void bwd_elem(float s, float dp, float c1, float alpha, float& p, float& ds) {
+  const float sg = sigmoid_scaled(s, c1);
+  p = s * sg;
+  ds = dp * (sg + alpha * p * (1.0f - sg));
+}
+
+// One 32-query block of a tile the diagonal touches.
+template <int DQK, int DV>
+__device__ __forceinline__ void dkdv_block_masked(const char* qt, const char* gt, int blk,
+                                                  const RowAddr<DQK>& raq, const RowAddr<DV>& rag,
+                                                  const ColAddr<DQK>& caq, const ColAddr<DV>& cag,
+                                                  const bf16x8 (&kreg)[DQK / 16],
+                                                  const bf16x8 (&vreg)[DV / 16],
+                                                  f32x16 (&dkacc)[DQK / 32], f32x16 (&dvacc)[DV / 32],
+                                                  float c1, float alpha, int q_lo, int k_lo, bool mask,
+                                                  int n, int hh) {
+  f32x16 s, dp;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
+#pragma unroll
+  for (int ks = 0; ks < DQK / 16; ++ks) s = mfma(raq.read(qt, blk, ks), kreg[ks], s);
+#pragma unroll
+  for (int ks = 0; ks < DV / 16; ++ks) dp = mfma(rag.read(gt, blk, ks), vreg[ks], dp);
+  float p[16], ds[16];
+#pragma unroll
+  for (int r = 0; r < 16; ++r) bwd_elem(s[r], dp[r], c1, alpha, p[r], ds[r]);
+  if (mask) {
+    const int kpos = k_lo + n;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int qpos = q_lo + 8 * (r >> 2) + 4 * hh + (r & 3);
+      const bool vis = kpos <= qpos;
+      p[r] = vis ? p[r] : 0.f;
+      ds[r] = vis ? ds[r] : 0.f;
+    }
+  }
+  const bf16x8 pb0 = pack8(p), pb1 = pack8(p + 8);
+  const bf16x8 db0 = pack8(ds), db1 = pack8(ds + 8);
+#pragma unroll
+  for (int c = 0; c < DV / 32; ++c) {
+    dvacc[c] = mfma(pb0, cag.read(gt, blk * 2, c), dvacc[c]);
+    dvacc[c] = mfma(pb1, cag.read(gt, blk * 2 + 1, c), dvacc[c]);
+  }
+#pragma unroll
+  for (int c = 0; c < DQK / 32; ++c) {
+    dkacc[c] = mfma(db0, caq.read(qt, blk * 2, c), dkacc[c]);
+    dkacc[c] = mfma(db1, caq.read(qt, blk * 2 + 1, c), dkacc[c]);
+  }
+}
+
+// A whole 64-query tile in which every query sees every key of the wave.  Four stages of
+// KS + VS matrix instructions each: scores of block 0, scores of block 1, dV/dK of block 0,
+// dV/dK of block 1.  The elementwise work of block 0 is issued between the matrix instructions
+// of the second stage and that of block 1 between those of the third; LDS operand reads run a
+// few instructions ahead of their use and are spread over all stages instead of arriving in
+// bursts (with one wave per SIMD nothing else would hide them).  A scheduling fence after every
+// slot keeps the compiler from regrouping the three instruction streams.
+template <int DQK, int DV>
+__device__ __forceinline__ void dkdv_tile_full(const char* qt, const char* gt,
+                                               const RowAddr<DQK>& raq, const RowAddr<DV>& rag,
+                                               const ColAddr<DQK>& caq, const ColAddr<DV>& cag,
+                                               const bf16x8 (&kreg)[DQK / 16],
+                                               const bf16x8 (&vreg)[DV / 16],
+                                               f32x16 (&dkacc)[DQK / 32], f32x16 (&dvacc)[DV / 32],
+                                               float c1, float alpha) {
+  constexpr int KS = DQK / 16, VS = DV / 16, NS = KS + VS;
+  constexpr int AHEAD = NS < 4 ? NS : 4;  // operand reads in flight ahead of the first use
+  bf16x8 op[NS];   // row-wise operands: Q rows then dO rows of the block being scored
+  bf16x8 tp[NS];   // transposed operands: dO^T then Q^T of the block being contracted
+  f32x16 s0, d0, s1, d1;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) { s0[r] = 0.f; d0[r] = 0.f; s1[r] = 0.f; d1[r] = 0.f; }
+
+  auto read_rows = [&](int blk, int m) {
+    return m < KS ? raq.read(qt, blk, m) : rag.read(gt, blk, m - KS);
+  };
+  auto read_cols = [&](int blk, int m) {  // m < VS: dO^T operand m; else Q^T operand m - VS
+    return m < VS ? cag.read(gt, blk * 2 + (m & 1), m >> 1)
+                  : caq.read(qt, blk * 2 + ((m - VS) & 1), (m - VS) >> 1);
+  };
+  auto fence = [] { __builtin_amdgcn_sched_barrier(0); };
+
+  // ---- stage 1: scores of block 0; operands of block 1 follow each use
+#pragma unroll
+  for (int m = 0; m < AHEAD; ++m) op[m] = read_rows(0, m);
+  fence();
+#pragma unroll
+  for (int m = 0; m < NS; ++m) {
+    if (m < KS) s0 = mfma(op[m], kreg[m], s0);
+    else d0 = mfma(op[m], vreg[m - KS], d0);
+    if (m + AHEAD < NS) op[m + AHEAD] = read_rows(0, m + AHEAD);
+    if (m >= AHEAD) op[m - AHEAD] = read_rows(1, m - AHEAD);
+    fence();
+  }
+#pragma unroll
+  for (int m = NS - AHEAD; m < NS; ++m) op[m] = read_rows(1, m);
+  fence();
+
+  // ---- stage 2: scores of block 1 | elementwise of block 0 | transposed operands of block 0
+  // (fences every GRP slots: inside a group the scheduler interleaves the independent
+  // elementwise chains, which hides the latency of the transcendental instructions)
+  constexpr int GRP = 4;
+  float p[16], ds[16];
+#pragma unroll
+  for (int m = 0; m < NS; ++m) {
+    if (m < KS) s1 = mfma(op[m], kreg[m], s1);
+    else d1 = mfma(op[m], vreg[m - KS], d1);
+    tp[m] = read_cols(0, m);
+#pragma unroll
+    for (int e = m * 16 / NS; e < (m + 1) * 16 / NS; ++e) bwd_elem(s0[e], d0[e], c1, alpha, p[e], ds[e]);
+    if (m % GRP == GRP - 1) fence();
+  }
+  bf16x8 pb0 = pack8(p), pb1 = pack8(p + 8), db0 = pack8(ds), db1 = pack8(ds + 8);
+  fence();
+
+  // ---- stage 3: dV/dK of block 0 | elementwise of block 1 | transposed operands of block 1
+  float p1[16], ds1[16];
+#pragma unroll
+  for (int m = 0; m < NS; ++m) {
+    if (m < VS) dvacc[m >> 1] = mfma((m & 1) ? pb1 : pb0, tp[m], dvacc[m >> 1]);
+    else dkacc[(m - VS) >> 1] = mfma(((m - VS) & 1) ? db1 : db0, tp[m], dkacc[(m - VS) >> 1]);
+    tp[m] = read_cols(1, m);
+#pragma unroll
+    for (int e = m * 16 / NS; e < (m + 1) * 16 / NS; ++e) bwd_elem(s1[e], d1[e], c1, alpha, p1[e], ds1[e]);
+    if (m % GRP == GRP - 1) fence();
+  }
+  pb0 = pack8(p1); pb1 = pack8(p1 + 8); db0 = pack8(ds1); db1 = pack8(ds1 + 8);
+  fence();
+
+  // ---- stage 4: dV/dK of block 1
+#pragma unroll
+  for (int m = 0; m < NS; ++m) {
+    if (m < VS) dvacc[m >> 1] = mfma((m & 1) ? pb1 : pb0, tp[m], dvacc[m >> 1]);
+    else dkacc[(m - VS) >> 1] = mfma(((m - VS) & 1) ? db1 : db0, tp[m], dkacc[(m - VS) >> 1]);
+  }
+}
+
 template <int DQK, int DV, int NW>
 __global__ void __launch_bounds__(NW * 64) hstu_dkdv_bf16(AttnArgs a) {
-  constexpr int NT = NW * 64;
   constexpr int QB = ST * DQK * 2, GB = ST * DV * 2;
-  __shared__ __attribute__((aligned(16))) char smem[2 * (QB + GB)];
-  auto qbuf = [&](int b) { return smem + b * (QB + GB); };
-  auto gbuf = [&](int b) { return smem + b * (QB + GB) + QB; };
+  __shared__ __attribute__((aligned(1024))) char smem0[QB + GB];
+  __shared__ __attribute__((aligned(1024))) char smem1[QB + GB];
+  auto qbuf = [&](int b) { return b ? smem1 : smem0; };
+  auto gbuf = [&](int b) { return (b ? smem1 : smem0) + QB; };
 
   const int H = a.num_heads;
   const int slot = blockIdx.x / H, h = blockIdx.x % H;
   Item it;
   if (!fetch_item(a.plan, slot, it)) return;
 
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 31, hh = lane >> 5;
+  const int tid = threadIdx.x, lane = tid & 63, n = lane & 31, hh = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int64_t sq = (int64_t)H * DQK, sv = (int64_t)H * DV;
   const __bf16* qg = (const __bf16*)a.q + h * DQK;
   const __bf16* gg = (const __bf16*)a.d_o + h * DV;
@@ -409,79 +718,46 @@ __global__ void __launch_bounds__(NW * 64) hstu_dkdv_bf16(AttnArgs a) {
   const float c1 = -a.alpha * 1.4426950408889634f;
   const int k_lo = it.pos0 + wave * 32, k_hi = k_lo + 31;
 
-  TileRegs<DQK, NT> qr;
-  TileRegs<DV, NT> gr;
+  RowAddr<DQK> raq; RowAddr<DV> rag; ColAddr<DQK> caq; ColAddr<DV> cag;
+  raq.init(n, hh); rag.init(n, hh); caq.init(lane); cag.init(lane);
+
   if (st.total > 0) {
     const TileRef t0 = tile_ref(it, st, 0);
-    qr.load(qg + (int64_t)t0.row * sq, sq, t0.valid, tid);
-    gr.load(gg + (int64_t)t0.row * sv, sv, t0.valid, tid);
-    qr.store(qbuf(0), tid);
-    gr.store(gbuf(0), tid);
+    tile_copy_async<DQK, NW>(qbuf(0), qg + (int64_t)t0.row * sq, sq, t0.valid, wave, lane);
+    tile_copy_async<DV, NW>(gbuf(0), gg + (int64_t)t0.row * sv, sv, t0.valid, wave, lane);
   }
+  tile_copy_wait();
   __syncthreads();
 
-  for (int j = 0; j < st.total; ++j) {
+  auto step = [&](int j, auto buf_tag) {
+    constexpr int BUF = decltype(buf_tag)::value;
     const TileRef tj = tile_ref(it, st, j);
-    const bool more = j + 1 < st.total;
-    if (more) {
+    if (j + 1 < st.total) {
       const TileRef tn = tile_ref(it, st, j + 1);
-      qr.load(qg + (int64_t)tn.row * sq, sq, tn.valid, tid);
-      gr.load(gg + (int64_t)tn.row * sv, sv, tn.valid, tid);
+      tile_copy_async<DQK, NW>(qbuf(BUF ^ 1), qg + (int64_t)tn.row * sq, sq, tn.valid, wave, lane);
+      tile_copy_async<DV, NW>(gbuf(BUF ^ 1), gg + (int64_t)tn.row * sv, sv, tn.valid, wave, lane);
     }
-    const char* qt = qbuf(j & 1);
-    const char* gt = gbuf(j & 1);
+    const char* qt = qbuf(BUF);
+    const char* gt = gbuf(BUF);
     if (wave_on) {
+      if (!a.causal || tj.pos >= k_hi) {
+        dkdv_tile_full<DQK, DV>(qt, gt, raq, rag, caq, cag, kreg, vreg, dkacc, dvacc, c1, a.alpha);
+      } else {
 #pragma unroll
-      for (int blk = 0; blk < ST / 32; ++blk) {
-        const int q_lo = tj.pos + blk * 32;
-        if (blk * 32 >= tj.valid) continue;
-        if (a.causal && q_lo + 31 < k_lo) continue;   // every query here precedes every key
-        f32x16 s, dp;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
-#pragma unroll
-        for (int ks = 0; ks < DQK / 16; ++ks)
-          s = mfma(lds_read_rows<DQK>(qt, blk * 32 + n, ks * 2 + hh), kreg[ks], s);
-#pragma unroll
-        for (int ks = 0; ks < DV / 16; ++ks)
-          dp = mfma(lds_read_rows<DV>(gt, blk * 32 + n, ks * 2 + hh), vreg[ks], dp);
-        // p' = s*sg (p = alpha*p'/N);  silu'(alpha*s) = sg + alpha*p'*(1-sg);  ds' = dp*silu'
-        float p[16], ds[16];
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const float sg = sigmoid_scaled(s[r], c1);
-          p[r] = s[r] * sg;
-          ds[r] = dp[r] * (sg + a.alpha * p[r] * (1.0f - sg));
-        }
-        if (a.causal && q_lo < k_hi) {
-          const int kpos = k_lo + n;
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int qpos = q_lo + 8 * (r >> 2) + 4 * hh + (r & 3);
-            const bool vis = kpos <= qpos;
-            p[r] = vis ? p[r] : 0.f;
-            ds[r] = vis ? ds[r] : 0.f;
-          }
-        }
-        const bf16x8 pb0 = pack8(p), pb1 = pack8(p + 8);
-        const bf16x8 db0 = pack8(ds), db1 = pack8(ds + 8);
-#pragma unroll
-        for (int c = 0; c < DV / 32; ++c) {
-          dvacc[c] = mfma(pb0, lds_read_cols<DV>(gt, blk * 32, c * 32, lane), dvacc[c]);
-          dvacc[c] = mfma(pb1, lds_read_cols<DV>(gt, blk * 32 + 16, c * 32, lane), dvacc[c]);
-        }
-#pragma unroll
-        for (int c = 0; c < DQK / 32; ++c) {
-          dkacc[c] = mfma(db0, lds_read_cols<DQK>(qt, blk * 32, c * 32, lane), dkacc[c]);
-          dkacc[c] = mfma(db1, lds_read_cols<DQK>(qt, blk * 32 + 16, c * 32, lane), dkacc[c]);
+        for (int blk = 0; blk < ST / 32; ++blk) {
+          const int q_lo = tj.pos + blk * 32;
+          if (blk * 32 >= tj.valid || q_lo + 31 < k_lo) continue;  // every query precedes every key
+          dkdv_block_masked<DQK, DV>(qt, gt, blk, raq, rag, caq, cag, kreg, vreg, dkacc, dvacc, c1,
+                                     a.alpha, q_lo, k_lo, q_lo < k_hi, n, hh);
         }
       }
     }
-    if (more) {
-      qr.store(qbuf((j + 1) & 1), tid);
-      gr.store(gbuf((j + 1) & 1), tid);
-    }
+    tile_copy_wait();
     __syncthreads();
+  };
+  for (int j = 0; j < st.total; j += 2) {
+    step(j, std::integral_constant<int, 0>{});
+    if (j + 1 < st.total) step(j + 1, std::integral_constant<int, 1>{});
   }
 
   // Accumulators: lane holds column c*32 + n of key rows 8*(r/4) + 4*hh + r%4 of its wave.
@@ -510,20 +786,118 @@ __global__ void __launch_bounds__(NW * 64) hstu_dkdv_bf16(AttnArgs a) {
 //   dQ^T += K^T dS^T (A = K tile transposed read, B = dS^T registers)
 // A second recomputation of S instead of atomics: dq is deterministic.
 // =============================================================================================
+template <int DQK, int DV>
+__device__ __forceinline__ void dq_block_masked(const char* kt, const char* vt, int blk,
+                                                const RowAddr<DQK>& rak, const RowAddr<DV>& rav,
+                                                const ColAddr<DQK>& cak,
+                                                const bf16x8 (&qreg)[DQK / 16],
+                                                const bf16x8 (&greg)[DV / 16],
+                                                f32x16 (&dqacc)[DQK / 32], float c1, float alpha,
+                                                int k_lo, int q_lo, bool mask, int n, int hh) {
+  f32x16 s, dp;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
+#pragma unroll
+  for (int ks = 0; ks < DQK / 16; ++ks) s = mfma(rak.read(kt, blk, ks), qreg[ks], s);
+#pragma unroll
+  for (int ks = 0; ks < DV / 16; ++ks) dp = mfma(rav.read(vt, blk, ks), greg[ks], dp);
+  float ds[16];
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    float p;
+    bwd_elem(s[r], dp[r], c1, alpha, p, ds[r]);
+  }
+  if (mask) {
+    const int qpos = q_lo + n;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int kpos = k_lo + 8 * (r >> 2) + 4 * hh + (r & 3);
+      ds[r] = kpos <= qpos ? ds[r] : 0.f;
+    }
+  }
+  const bf16x8 db0 = pack8(ds), db1 = pack8(ds + 8);
+#pragma unroll
+  for (int c = 0; c < DQK / 32; ++c) {
+    dqacc[c] = mfma(cak.read(kt, blk * 2, c), db0, dqacc[c]);
+    dqacc[c] = mfma(cak.read(kt, blk * 2 + 1, c), db1, dqacc[c]);
+  }
+}
+
+template <int DQK, int DV>
+__device__ __forceinline__ void dq_tile_full(const char* kt, const char* vt,
+                                             const RowAddr<DQK>& rak, const RowAddr<DV>& rav,
+                                             const ColAddr<DQK>& cak,
+                                             const bf16x8 (&qreg)[DQK / 16],
+                                             const bf16x8 (&greg)[DV / 16],
+                                             f32x16 (&dqacc)[DQK / 32], float c1, float alpha) {
+  constexpr int KS = DQK / 16, VS = DV / 16, NS = KS + VS;
+  bf16x8 ka[KS], va[VS], kT[KS];
+  f32x16 s0, d0, s1, d1;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) { s0[r] = 0.f; d0[r] = 0.f; s1[r] = 0.f; d1[r] = 0.f; }
+
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) ka[ks] = rak.read(kt, 0, ks);
+#pragma unroll
+  for (int ks = 0; ks < VS; ++ks) va[ks] = rav.read(vt, 0, ks);
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) s0 = mfma(ka[ks], qreg[ks], s0);
+#pragma unroll
+  for (int ks = 0; ks < VS; ++ks) d0 = mfma(va[ks], greg[ks], d0);
+
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) ka[ks] = rak.read(kt, 1, ks);
+#pragma unroll
+  for (int ks = 0; ks < VS; ++ks) va[ks] = rav.read(vt, 1, ks);
+#pragma unroll
+  for (int i = 0; i < KS; ++i) kT[i] = cak.read(kt, i & 1, i >> 1);
+
+  float ds[16];
+#pragma unroll
+  for (int m = 0; m < NS; ++m) {
+    if (m < KS) s1 = mfma(ka[m], qreg[m], s1);
+    else d1 = mfma(va[m - KS], greg[m - KS], d1);
+#pragma unroll
+    for (int e = m * 16 / NS; e < (m + 1) * 16 / NS; ++e) {
+      float p;
+      bwd_elem(s0[e], d0[e], c1, alpha, p, ds[e]);
+    }
+  }
+  bf16x8 db0 = pack8(ds), db1 = pack8(ds + 8);
+
+  float ds1[16];
+#pragma unroll
+  for (int i = 0; i < KS; ++i) {
+    dqacc[i >> 1] = mfma(kT[i], (i & 1) ? db1 : db0, dqacc[i >> 1]);
+#pragma unroll
+    for (int e = i * 16 / KS; e < (i + 1) * 16 / KS; ++e) {
+      float p;
+      bwd_elem(s1[e], d1[e], c1, alpha, p, ds1[e]);
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < KS; ++i) kT[i] = cak.read(kt, 2 + (i & 1), i >> 1);
+  db0 = pack8(ds1);
+  db1 = pack8(ds1 + 8);
+#pragma unroll
+  for (int i = 0; i < KS; ++i) dqacc[i >> 1] = mfma(kT[i], (i & 1) ? db1 : db0, dqacc[i >> 1]);
+}
+
 template <int DQK, int DV, int NW>
-__global__ void __launch_bounds__(NW * 64) hstu_dq_bf16(AttnArgs a) {
-  constexpr int NT = NW * 64;
+__global__ void __launch_bounds__(NW * 64, 2) hstu_dq_bf16(AttnArgs a) {
   constexpr int KB = ST * DQK * 2, VB = ST * DV * 2;
-  __shared__ __attribute__((aligned(16))) char smem[2 * (KB + VB)];
-  auto kbuf = [&](int b) { return smem + b * (KB + VB); };
-  auto vbuf = [&](int b) { return smem + b * (KB + VB) + KB; };
+  __shared__ __attribute__((aligned(1024))) char smem0[KB + VB];
+  __shared__ __attribute__((aligned(1024))) char smem1[KB + VB];
+  auto kbuf = [&](int b) { return b ? smem1 : smem0; };
+  auto vbuf = [&](int b) { return (b ? smem1 : smem0) + KB; };
 
   const int H = a.num_heads;
   const int slot = blockIdx.x / H, h = blockIdx.x % H;
   Item it;
   if (!fetch_item(a.plan, slot, it)) return;
 
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 31, hh = lane >> 5;
+  const int tid = threadIdx.x, lane = tid & 63, n = lane & 31, hh = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int64_t sq = (int64_t)H * DQK, sv = (int64_t)H * DV;
   const __bf16* qg = (const __bf16*)a.q + (int64_t)it.row0 * sq + h * DQK;
   const __bf16* gg = (const __bf16*)a.d_o + (int64_t)it.row0 * sv + h * DV;
@@ -546,70 +920,46 @@ __global__ void __launch_bounds__(NW * 64) hstu_dq_bf16(AttnArgs a) {
   const float c1 = -a.alpha * 1.4426950408889634f;
   const int q_lo = it.pos0 + wave * 32, q_hi = q_lo + 31;
 
-  TileRegs<DQK, NT> kr;
-  TileRegs<DV, NT> vr;
+  RowAddr<DQK> rak; RowAddr<DV> rav; ColAddr<DQK> cak;
+  rak.init(n, hh); rav.init(n, hh); cak.init(lane);
+
   if (st.total > 0) {
     const TileRef t0 = tile_ref(it, st, 0);
-    kr.load(kg + (int64_t)t0.row * sq, sq, t0.valid, tid);
-    vr.load(vg + (int64_t)t0.row * sv, sv, t0.valid, tid);
-    kr.store(kbuf(0), tid);
-    vr.store(vbuf(0), tid);
+    tile_copy_async<DQK, NW>(kbuf(0), kg + (int64_t)t0.row * sq, sq, t0.valid, wave, lane);
+    tile_copy_async<DV, NW>(vbuf(0), vg + (int64_t)t0.row * sv, sv, t0.valid, wave, lane);
   }
+  tile_copy_wait();
   __syncthreads();
 
-  for (int j = 0; j < st.total; ++j) {
+  auto step = [&](int j, auto buf_tag) {
+    constexpr int BUF = decltype(buf_tag)::value;
     const TileRef tj = tile_ref(it, st, j);
-    const bool more = j + 1 < st.total;
-    if (more) {
+    if (j + 1 < st.total) {
       const TileRef tn = tile_ref(it, st, j + 1);
-      kr.load(kg + (int64_t)tn.row * sq, sq, tn.valid, tid);
-      vr.load(vg + (int64_t)tn.row * sv, sv, tn.valid, tid);
+      tile_copy_async<DQK, NW>(kbuf(BUF ^ 1), kg + (int64_t)tn.row * sq, sq, tn.valid, wave, lane);
+      tile_copy_async<DV, NW>(vbuf(BUF ^ 1), vg + (int64_t)tn.row * sv, sv, tn.valid, wave, lane);
     }
-    const char* kt = kbuf(j & 1);
-    const char* vt = vbuf(j & 1);
+    const char* kt = kbuf(BUF);
+    const char* vt = vbuf(BUF);
     if (wave_on) {
+      if (!a.causal || tj.pos + ST - 1 <= q_lo) {
+        dq_tile_full<DQK, DV>(kt, vt, rak, rav, cak, qreg, greg, dqacc, c1, a.alpha);
+      } else {
 #pragma unroll
-      for (int blk = 0; blk < ST / 32; ++blk) {
-        const int k_lo = tj.pos + blk * 32;
-        if (blk * 32 >= tj.valid) continue;
-        if (a.causal && k_lo > q_hi) continue;
-        f32x16 s, dp;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
-#pragma unroll
-        for (int ks = 0; ks < DQK / 16; ++ks)
-          s = mfma(lds_read_rows<DQK>(kt, blk * 32 + n, ks * 2 + hh), qreg[ks], s);
-#pragma unroll
-        for (int ks = 0; ks < DV / 16; ++ks)
-          dp = mfma(lds_read_rows<DV>(vt, blk * 32 + n, ks * 2 + hh), greg[ks], dp);
-        float ds[16];
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const float sg = sigmoid_scaled(s[r], c1);
-          const float p = s[r] * sg;
-          ds[r] = dp[r] * (sg + a.alpha * p * (1.0f - sg));
-        }
-        if (a.causal && k_lo + 31 > q_lo) {
-          const int qpos = q_lo + n;
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int kpos = k_lo + 8 * (r >> 2) + 4 * hh + (r & 3);
-            ds[r] = kpos <= qpos ? ds[r] : 0.f;
-          }
-        }
-        const bf16x8 db0 = pack8(ds), db1 = pack8(ds + 8);
-#pragma unroll
-        for (int c = 0; c < DQK / 32; ++c) {
-          dqacc[c] = mfma(lds_read_cols<DQK>(kt, blk * 32, c * 32, lane), db0, dqacc[c]);
-          dqacc[c] = mfma(lds_read_cols<DQK>(kt, blk * 32 + 16, c * 32, lane), db1, dqacc[c]);
+        for (int blk = 0; blk < ST / 32; ++blk) {
+          const int k_lo = tj.pos + blk * 32;
+          if (blk * 32 >= tj.valid || k_lo > q_hi) continue;
+          dq_block_masked<DQK, DV>(kt, vt, blk, rak, rav, cak, qreg, greg, dqacc, c1, a.alpha, k_lo,
+                                   q_lo, k_lo + 31 > q_lo, n, hh);
         }
       }
     }
-    if (more) {
-      kr.store(kbuf((j + 1) & 1), tid);
-      vr.store(vbuf((j + 1) & 1), tid);
-    }
+    tile_copy_wait();
     __syncthreads();
+  };
+  for (int j = 0; j < st.total; j += 2) {
+    step(j, std::integral_constant<int, 0>{});
+    if (j + 1 < st.total) step(j + 1, std::integral_constant<int, 1>{});
   }
 
   // dQ^T accumulators: lane holds query row n, elements c*32 + 8*(r/4) + 4*hh + r%4.
