@@ -171,13 +171,14 @@ int hstu_debug_dump_schedule(const hstu_attn_params* params, const hstu_cp_desc*
  * launched on.  This is the one piece of (thread-local) state the library ever keeps.
  *   begin: max_records in [1, 65536]; launches beyond it are not recorded.
  *   end:   waits for the recorded launches, writes per launch, in launch order, its kind
- *          (0 forward, 1 dk/dv pass, 2 dq pass, 3 schedule build) and its duration in
+ *          (0 forward, 1 dk/dv pass, 2 dq pass, 3 schedule build, 4 transposed copy) and its duration in
  *          milliseconds; returns the number written (<= capacity) or a status < 0.
  */
 int hstu_debug_timing_begin(int max_records);
 int hstu_debug_timing_end(int32_t* kinds, float* milliseconds, int capacity);
 
-/* Rows per work item on the given side for `params` (tile height used by the schedule). */
+/* Rows per work item on the given side for a whole-batch problem described by `params` (the
+ * tile height depends on the problem size: large problems use taller query tiles). */
 int hstu_schedule_tile_rows(const hstu_attn_params* params, int side);
 
 #ifdef __cplusplus

@@ -271,8 +271,10 @@ def hstu_jagged_attn_cp_partial(q_local: torch.Tensor, k_part: torch.Tensor, v_p
     return o, dq, dk, dvv
 
 
-def hstu_schedule_tile_rows(dtype_code: int, d_qk: int, d_v: int, side: int) -> int:
-    p = _params(1, 1, d_qk, d_v, 1, 1.0, True, dtype_code, 1)
+def hstu_schedule_tile_rows(dtype_code: int, d_qk: int, d_v: int, side: int, total_rows: int = 1,
+                            num_heads: int = 1) -> int:
+    """Owner rows per schedule item on `side` for a whole-batch problem of the given size."""
+    p = _params(1, num_heads, d_qk, d_v, 1, 1.0, True, dtype_code, total_rows)
     return int(load_library().hstu_schedule_tile_rows(ctypes.byref(p), int(side)))
 
 
@@ -300,7 +302,7 @@ def hstu_debug_dump_schedule(seq_offsets: torch.Tensor, total_rows: int, num_hea
     return buf[:n].copy()
 
 
-KERNEL_KINDS = {0: "fwd", 1: "dkdv", 2: "dq", 3: "plan"}
+KERNEL_KINDS = {0: "fwd", 1: "dkdv", 2: "dq", 3: "plan", 4: "transpose"}
 
 
 def hstu_debug_timing_begin(max_records: int = 4096) -> None:

@@ -55,8 +55,12 @@ int check_params(const hstu_attn_params* p) {
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-int tile_rows(int dtype, int pass) {
-  return dtype == HSTU_BF16 ? tile_rows_bf16(pass) : tile_rows_f32(pass);
+// Wavefronts per workgroup and owner rows per item of a pass on a problem of the given size.
+int pass_waves(const hstu_attn_params* p, int pass, int64_t owner_rows) {
+  return p->dtype == HSTU_BF16 ? waves_bf16(pass, owner_rows, p->num_heads) : 4;
+}
+int tile_rows(const hstu_attn_params* p, int pass, int64_t owner_rows) {
+  return p->dtype == HSTU_BF16 ? 32 * pass_waves(p, pass, owner_rows) : tile_rows_f32(pass);
 }
 
 // One schedule: who owns, who is streamed, how many rows each side's buffers hold.
@@ -66,28 +70,47 @@ struct SideSpec {
   int owner_rank, streamed_rank;
   int64_t owner_rows, streamed_rows;
   int segs;           // segments per sequence on the owner side (1 global, 2 rank-local)
+  int ssegs;          // segments per sequence on the streamed side
 };
 
 struct BuiltPlan {
   Plan plan;
   int64_t max_items;
   size_t end;
+  int waves;
 };
 
+// Bound on the items of a schedule, taken with the smallest tile any kernel variant uses so that
+// it holds whichever variant the problem size selects (surplus workgroups exit at once).
 int64_t items_bound(const hstu_attn_params* p, const SideSpec& s) {
-  return max_items_bound(s.owner_rows, p->batch, s.segs, tile_rows(p->dtype, s.pass));
+  return max_items_bound(s.owner_rows, p->batch, s.segs,
+                         p->dtype == HSTU_BF16 ? 128 : tile_rows_f32(s.pass));
+}
+
+// Bound on the 64-row tiles of the streamed side (the transposed copies have 64 columns each).
+int64_t stiles_bound(const hstu_attn_params* p, const SideSpec& s) {
+  return max_items_bound(s.streamed_rows, p->batch, s.ssegs, 64);
 }
 
 size_t plan_bytes(const hstu_attn_params* p, const SideSpec& s, size_t base) {
-  return plan_layout(base, p->batch, items_bound(p, s)).end;
+  return plan_layout(base, p->batch, items_bound(p, s), stiles_bound(p, s)).end;
 }
 
-// Carves one schedule out of the workspace at byte offset `base` and launches its build.
-int build_plan(const hstu_attn_params* p, int cp_size, const SideSpec& s, const int32_t* off,
-               char* ws, size_t ws_bytes, size_t base, hipStream_t stream, BuiltPlan* out) {
-  const int64_t max_items = items_bound(p, s);
-  if (max_items * p->num_heads >= (1ll << 31)) return HSTU_ERR_BAD_SHAPE;
-  const PlanLayout l = plan_layout(base, p->batch, max_items);
+// Bytes of one transposed copy of a streamed tensor with head dimension d (bf16 only).
+size_t tcopy_bytes(const hstu_attn_params* p, const SideSpec& s, int d) {
+  if (p->dtype != HSTU_BF16) return 0;
+  return align_up((size_t)p->num_heads * d * 64 * stiles_bound(p, s) * 2, 256);
+}
+
+// Carves one schedule out of the workspace at byte offset `base` and fills the arguments of
+// its build (launched by launch_built).
+int prepare_plan(const hstu_attn_params* p, int cp_size, const SideSpec& s, const int32_t* off,
+                 char* ws, size_t ws_bytes, size_t base, PlanArgs* args, BuiltPlan* out) {
+  const int64_t max_items = items_bound(p, s), max_stiles = stiles_bound(p, s);
+  if (max_items * p->num_heads >= (1ll << 31) || max_stiles * p->num_heads >= (1ll << 31) ||
+      max_stiles * 64 * 2 * 128 >= (1ll << 31))  // transposed rows are addressed with 32-bit byte offsets
+    return HSTU_ERR_BAD_SHAPE;
+  const PlanLayout l = plan_layout(base, p->batch, max_items, max_stiles);
   if (l.end > ws_bytes) return HSTU_ERR_WORKSPACE_TOO_SMALL;
   PlanArgs a;
   a.off = off;
@@ -97,11 +120,12 @@ int build_plan(const hstu_attn_params* p, int cp_size, const SideSpec& s, const 
   a.owner_rank = s.owner_rank;
   a.streamed_rank = s.streamed_rank;
   a.side = s.side;
-  a.tile = tile_rows(p->dtype, s.pass);
+  a.tile = tile_rows(p, s.pass, s.owner_rows);
   a.causal = p->causal ? 1 : 0;
   a.owner_rows = (int32_t)s.owner_rows;
   a.streamed_rows = (int32_t)s.streamed_rows;
   a.max_items = (int32_t)max_items;
+  a.max_stiles = (int32_t)max_stiles;
   int shift = 0;
   while (((s.streamed_rows / 32 + 4) >> shift) >= 2048) ++shift;
   a.cost_shift = shift;
@@ -109,18 +133,51 @@ int build_plan(const hstu_attn_params* p, int cp_size, const SideSpec& s, const 
   a.owner_base = reinterpret_cast<int32_t*>(ws + l.owner_base);
   a.streamed_base = reinterpret_cast<int32_t*>(ws + l.streamed_base);
   a.tile_base = reinterpret_cast<int32_t*>(ws + l.tile_base);
+  a.stile_base = reinterpret_cast<int32_t*>(ws + l.stile_base);
+  a.ttile = reinterpret_cast<int32_t*>(ws + l.ttile);
   a.order = reinterpret_cast<int32_t*>(ws + l.order);
   a.items = reinterpret_cast<Item*>(ws + l.items);
-  {
-    TimedLaunch timed(3, stream);
-    if (launch_plan(a, stream) != hipSuccess) return HSTU_ERR_HIP;
-  }
+  *args = a;
   out->plan.header = a.header;
   out->plan.order = a.order;
   out->plan.items = a.items;
+  out->plan.ttile = a.ttile;
+  out->plan.max_stiles = a.max_stiles;
   out->max_items = max_items;
+  out->waves = pass_waves(p, s.pass, s.owner_rows);
   out->end = l.end;
   return HSTU_OK;
+}
+
+// Carves a transposed copy out of the workspace at *base and launches its construction.
+int make_tcopy(const hstu_attn_params* p, const SideSpec& s, const BuiltPlan& bp, const void* src,
+               int d, char* ws, size_t ws_bytes, size_t* base, hipStream_t stream, const void** out) {
+  *out = nullptr;
+  if (p->dtype != HSTU_BF16) return HSTU_OK;
+  const size_t at = align_up(*base, 256), bytes = tcopy_bytes(p, s, d);
+  if (at + bytes > ws_bytes) return HSTU_ERR_WORKSPACE_TOO_SMALL;
+  {
+    TimedLaunch timed(4, stream);
+    if (launch_transpose_bf16(src, ws + at, bp.plan, p->num_heads, d, stream) != hipSuccess)
+      return HSTU_ERR_HIP;
+  }
+  *out = ws + at;
+  *base = at + bytes;
+  return HSTU_OK;
+}
+
+int launch_built(const PlanArgs* args, int count, hipStream_t stream) {
+  TimedLaunch timed(3, stream);
+  return launch_plans(args, count, stream) == hipSuccess ? HSTU_OK : HSTU_ERR_HIP;
+}
+
+// One schedule: prepare and launch.
+int build_plan(const hstu_attn_params* p, int cp_size, const SideSpec& s, const int32_t* off,
+               char* ws, size_t ws_bytes, size_t base, hipStream_t stream, BuiltPlan* out) {
+  PlanArgs args;
+  const int rc = prepare_plan(p, cp_size, s, off, ws, ws_bytes, base, &args, out);
+  if (rc != HSTU_OK) return rc;
+  return launch_built(&args, 1, stream);
 }
 
 AttnArgs base_args(const hstu_attn_params* p, const BuiltPlan& bp, int accumulate) {
@@ -130,6 +187,7 @@ AttnArgs base_args(const hstu_attn_params* p, const BuiltPlan& bp, int accumulat
   a.causal = p->causal ? 1 : 0;
   a.accumulate = accumulate;
   a.max_items = (int32_t)bp.max_items;
+  a.waves = bp.waves;
   a.out_f32 = p->out_dtype == HSTU_F32 ? 1 : 0;
   a.alpha = p->alpha;
   a.inv_n = 1.0f / (float)p->max_len;
@@ -152,15 +210,15 @@ int run_pass(const hstu_attn_params* p, int pass, const AttnArgs& a, hipStream_t
 }
 
 SideSpec full_side(const hstu_attn_params* p, int side, int pass) {
-  return SideSpec{side, pass, -1, -1, p->total_rows, p->total_rows, 1};
+  return SideSpec{side, pass, -1, -1, p->total_rows, p->total_rows, 1, 1};
 }
 
 int64_t clamp_rows(int64_t rows, int64_t total) { return rows < total ? rows : total; }
 
 SideSpec cp_side(const hstu_attn_params* p, const hstu_cp_desc* cp, int side, int pass) {
   const int64_t qr = clamp_rows(cp->q_rows, p->total_rows), kr = clamp_rows(cp->kv_rows, p->total_rows);
-  if (side == 0) return SideSpec{0, pass, cp->q_rank, cp->kv_rank, qr, kr, 2};
-  return SideSpec{1, pass, cp->kv_rank, cp->q_rank, kr, qr, cp->kv_rank < 0 ? 1 : 2};
+  if (side == 0) return SideSpec{0, pass, cp->q_rank, cp->kv_rank, qr, kr, 2, cp->kv_rank < 0 ? 1 : 2};
+  return SideSpec{1, pass, cp->kv_rank, cp->q_rank, kr, qr, cp->kv_rank < 0 ? 1 : 2, 2};
 }
 
 int check_cp(const hstu_attn_params* p, const hstu_cp_desc* cp) {
@@ -204,29 +262,36 @@ int hstu_validate_offsets_host(const int32_t* host_offsets, int32_t batch, int64
 int hstu_schedule_tile_rows(const hstu_attn_params* params, int side) {
   const int rc = check_params(params);
   if (rc != HSTU_OK) return rc;
-  return tile_rows(params->dtype, side == 0 ? PASS_FWD : PASS_DKDV);
+  return tile_rows(params, side == 0 ? PASS_FWD : PASS_DKDV, params->total_rows);
 }
 
 size_t hstu_jagged_attn_workspace_bytes(const hstu_attn_params* params, int which) {
   if (check_params(params) != HSTU_OK) return 0;
+  const hstu_attn_params* p = params;
   size_t end = 0;
+  // Each pass: its schedule, then the transposed copies of the tensors it streams (bf16 only).
+  auto pass_bytes = [&](const SideSpec& s, int d_a, int d_b) {
+    end = plan_bytes(p, s, end);
+    if (d_a) end = align_up(end, 256) + tcopy_bytes(p, s, d_a);
+    if (d_b) end = align_up(end, 256) + tcopy_bytes(p, s, d_b);
+  };
   if (which == HSTU_WS_FWD) {
-    end = plan_bytes(params, full_side(params, 0, PASS_FWD), 0);
+    pass_bytes(full_side(p, 0, PASS_FWD), p->d_v, 0);
   } else if (which == HSTU_WS_BWD) {
-    end = plan_bytes(params, full_side(params, 1, PASS_DKDV), 0);
-    end = plan_bytes(params, full_side(params, 0, PASS_DQ), end);
+    pass_bytes(full_side(p, 1, PASS_DKDV), 0, 0);
+    pass_bytes(full_side(p, 0, PASS_DQ), 0, 0);
   } else if (which == HSTU_WS_CP) {
     // rank-local sides never hold more rows than the whole batch
-    SideSpec s{0, PASS_FWD, 0, 0, params->total_rows, params->total_rows, 2};
-    end = plan_bytes(params, s, 0);
+    SideSpec s{0, PASS_FWD, 0, 0, p->total_rows, p->total_rows, 2, 2};
+    pass_bytes(s, p->d_v, 0);
     s.pass = PASS_DKDV; s.side = 1;
-    end = plan_bytes(params, s, end);
+    pass_bytes(s, 0, 0);
     s.pass = PASS_DQ; s.side = 0;
-    end = plan_bytes(params, s, end);
+    pass_bytes(s, 0, 0);
   } else {
     return 0;
   }
-  return end + 256;
+  return end + 4096;  // slack for the 256-byte alignment of each piece
 }
 
 int hstu_jagged_attn_fwd(const hstu_attn_params* params, const void* q, const void* k,
@@ -245,8 +310,12 @@ int hstu_jagged_attn_fwd(const hstu_attn_params* params, const void* q, const vo
   rc = build_plan(params, 1, full_side(params, 0, PASS_FWD), seq_offsets, (char*)workspace,
                   workspace_bytes, 0, stream, &bp);
   if (rc != HSTU_OK) return rc;
+  size_t base = bp.end;
   AttnArgs a = base_args(params, bp, 0);
   a.q = q; a.k = k; a.v = v; a.o = o;
+  rc = make_tcopy(params, full_side(params, 0, PASS_FWD), bp, v, params->d_v, (char*)workspace,
+                  workspace_bytes, &base, stream, &a.vt);
+  if (rc != HSTU_OK) return rc;
   return run_pass(params, PASS_FWD, a, stream);
 }
 
@@ -266,11 +335,14 @@ int hstu_jagged_attn_bwd(const hstu_attn_params* params, const void* q, const vo
     return HSTU_ERR_WORKSPACE_TOO_SMALL;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   BuiltPlan pk, pq;
-  rc = build_plan(params, 1, full_side(params, 1, PASS_DKDV), seq_offsets, (char*)workspace,
-                  workspace_bytes, 0, stream, &pk);
+  PlanArgs pa[2];
+  rc = prepare_plan(params, 1, full_side(params, 1, PASS_DKDV), seq_offsets, (char*)workspace,
+                    workspace_bytes, 0, &pa[0], &pk);
   if (rc != HSTU_OK) return rc;
-  rc = build_plan(params, 1, full_side(params, 0, PASS_DQ), seq_offsets, (char*)workspace,
-                  workspace_bytes, pk.end, stream, &pq);
+  rc = prepare_plan(params, 1, full_side(params, 0, PASS_DQ), seq_offsets, (char*)workspace,
+                    workspace_bytes, pk.end, &pa[1], &pq);
+  if (rc != HSTU_OK) return rc;
+  rc = launch_built(pa, 2, stream);
   if (rc != HSTU_OK) return rc;
   AttnArgs a = base_args(params, pk, 0);
   a.q = q; a.k = k; a.v = v; a.d_o = d_o; a.dk = dk; a.dv = dv;
@@ -312,6 +384,9 @@ int hstu_jagged_attn_cp_partial(const hstu_attn_params* params, const hstu_cp_de
     base = pf.end;
     AttnArgs a = base_args(params, pf, acc);
     a.q = q_local; a.k = k_part; a.v = v_part; a.o = o_local;
+    rc = make_tcopy(params, cp_side(params, cp, 0, PASS_FWD), pf, v_part, params->d_v, ws,
+                    workspace_bytes, &base, stream, &a.vt);
+    if (rc != HSTU_OK) return rc;
     rc = run_pass(params, PASS_FWD, a, stream);
     if (rc != HSTU_OK) return rc;
   }

@@ -19,32 +19,37 @@ struct Item {
   int32_t seg_row0[2];  // first streamed row of each segment
   int32_t seg_len[2];   // rows in each segment
   int32_t seg_pos0[2];  // in-sequence position of each segment's first row
+  int32_t seg_tcol0[2]; // column of each segment's first row in the transposed streamed copies
   int32_t cost;         // visible 32-row streamed blocks (the sort key)
-  int32_t pad;
+  int32_t pad[3];
 };
-static_assert(sizeof(Item) == 48, "Item layout is part of the schedule dump format");
+static_assert(sizeof(Item) == 64, "Item is one 64-byte record");
 
 // Device view of a built schedule.
 struct Plan {
-  const int32_t* header;  // [0] = number of items
+  const int32_t* header;  // [0] = number of items, [1] = number of 64-row streamed tiles
   const int32_t* order;   // order[slot] = item index, non-increasing cost
   const Item* items;
+  const int32_t* ttile;   // per 64-row streamed tile: first row, valid rows
+  int32_t max_stiles;     // host bound on the streamed tiles; transposed copies have 64x this many columns
 };
 
 // Byte offsets of one schedule's arrays inside the workspace.
 struct PlanLayout {
-  size_t header, owner_base, streamed_base, tile_base, order, items, end;
+  size_t header, owner_base, streamed_base, tile_base, stile_base, ttile, order, items, end;
 };
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-inline PlanLayout plan_layout(size_t base, int64_t batch, int64_t max_items) {
+inline PlanLayout plan_layout(size_t base, int64_t batch, int64_t max_items, int64_t max_stiles) {
   PlanLayout l;
   size_t p = align_up(base, 256);
   l.header = p;        p += 64;
   l.owner_base = p;    p = align_up(p + (size_t)(batch + 1) * 4, 64);
   l.streamed_base = p; p = align_up(p + (size_t)(batch + 1) * 4, 64);
   l.tile_base = p;     p = align_up(p + (size_t)(batch + 1) * 4, 64);
+  l.stile_base = p;    p = align_up(p + (size_t)(batch + 1) * 4, 64);
+  l.ttile = p;         p = align_up(p + (size_t)max_stiles * 8, 64);
   l.order = p;         p = align_up(p + (size_t)max_items * 4, 64);
   l.items = p;         p = align_up(p + (size_t)max_items * sizeof(Item), 64);
   l.end = p;
@@ -70,16 +75,20 @@ struct PlanArgs {
   int32_t owner_rows;     // rows the caller declared for the owner-side buffers
   int32_t streamed_rows;  // rows the caller declared for the streamed-side buffers
   int32_t max_items;
+  int32_t max_stiles;     // bound on the 64-row tiles of the streamed side
   int32_t cost_shift;     // cost >> cost_shift selects the sort bin
   int32_t* header;
   int32_t* owner_base;
   int32_t* streamed_base;
   int32_t* tile_base;
+  int32_t* stile_base;
+  int32_t* ttile;
   int32_t* order;
   Item* items;
 };
 
-hipError_t launch_plan(const PlanArgs& a, hipStream_t stream);
+// Builds one or two schedules in one launch (one workgroup each).
+hipError_t launch_plans(const PlanArgs* a, int count, hipStream_t stream);
 
 // Arguments of the attention kernels.
 struct AttnArgs {
@@ -87,6 +96,7 @@ struct AttnArgs {
   const void* k;
   const void* v;
   const void* d_o;
+  const void* vt;   // transposed copy of v (bf16 forward; see launch_transpose_bf16)
   void* o;
   void* dq;
   void* dk;
@@ -96,6 +106,7 @@ struct AttnArgs {
   int32_t causal;
   int32_t accumulate;
   int32_t max_items;
+  int32_t waves;    // wavefronts per workgroup (bf16 kernels): owner tile = 32 * waves rows
   int32_t out_f32;  // outputs are fp32 (bf16 kernels only; the fp32 kernels always write fp32)
   float alpha;
   float inv_n;
@@ -104,8 +115,17 @@ struct AttnArgs {
 // Owner rows per item each kernel family expects (pass: 0 forward, 1 dk/dv, 2 dq); the
 // schedule must be built with the same value.
 enum { PASS_FWD = 0, PASS_DKDV = 1, PASS_DQ = 2 };
-int tile_rows_bf16(int pass);
+// Wavefronts per workgroup (32 owner rows each) the bf16 kernels of a pass use for a problem
+// with `owner_rows` owner rows and `heads` heads: large problems take the wider workgroup, which
+// halves the traffic of streamed tiles; small ones keep enough workgroups to fill the chip.
+int waves_bf16(int pass, int64_t owner_rows, int heads);
 int tile_rows_f32(int pass);
+
+// Transposed copy of a streamed bf16 tensor: src [rows, H, D] -> dst [H, D, 64 * max_stiles], one
+// 64-column group per streamed tile, columns permuted inside each group of 16 into the order
+// the matrix instructions consume them, zero beyond the valid rows.
+hipError_t launch_transpose_bf16(const void* src, void* dst, const Plan& plan, int num_heads, int d,
+                                 hipStream_t stream);
 
 hipError_t launch_fwd_bf16(const AttnArgs& a, int d_qk, int d_v, hipStream_t stream);
 hipError_t launch_dkdv_bf16(const AttnArgs& a, int d_qk, int d_v, hipStream_t stream);

@@ -51,19 +51,23 @@ constexpr int ST = 64;  // streamed rows per LDS tile
 // positions per 256 bytes.  The position of (row, chunk) is its byte offset / 16 mod 16; the
 // swizzle makes (a) 16 consecutive rows at one logical chunk (a row-wise operand read) and
 // (b) 4 consecutive rows x 4 consecutive chunks (what 32 lanes of a transposing read touch)
-// each land on 16 different positions, with no padding.
-template <int D>
-__device__ __forceinline__ int swz(int row) {
-  if (D == 128) return ((row & 3) << 2) | ((row >> 2) & 3);       // 1 row per 256 bytes
-  if (D == 64) return (((row >> 1) & 1) << 2) | ((row >> 2) & 3);  // 2 rows per 256 bytes
+// each land on 16 different positions, with no padding.  RB is the row length in bytes.
+template <int RB>
+__device__ __forceinline__ int swz_rb(int row) {
+  if (RB == 256) return ((row & 3) << 2) | ((row >> 2) & 3);       // 1 row per 256 bytes
+  if (RB == 128) return (((row >> 1) & 1) << 2) | ((row >> 2) & 3);  // 2 rows per 256 bytes
   return (row >> 2) & 3;                                           // 4 rows per 256 bytes
 }
-
-// Byte offset inside a [rows][D] bf16 LDS tile of 16-byte chunk `chunk` of row `row`.
 template <int D>
-__device__ __forceinline__ int lds_off(int row, int chunk) {
-  return row * (D * 2) + ((chunk ^ swz<D>(row)) << 4);
+__device__ __forceinline__ int swz(int row) { return swz_rb<D * 2>(row); }
+
+// Byte offset inside a tile with RB-byte rows of 16-byte chunk `chunk` of row `row`.
+template <int RB>
+__device__ __forceinline__ int lds_off_rb(int row, int chunk) {
+  return row * RB + ((chunk ^ swz_rb<RB>(row)) << 4);
 }
+template <int D>
+__device__ __forceinline__ int lds_off(int row, int chunk) { return lds_off_rb<D * 2>(row, chunk); }
 
 // Row-wise A operand: 8 consecutive elements [col8*8, col8*8+8) of row `row`.
 template <int D>
@@ -100,7 +104,11 @@ struct RowAddr {  // row-wise operand reads of row n (+32*blk): one address per 
     for (int ks = 0; ks < D / 16; ++ks) a[ks] = lds_off<D>(n, ks * 2 + hh);
   }
   __device__ __forceinline__ bf16x8 read(const char* tile, int blk, int ks) const {
+#if HSTU_ABLATE == 5 || HSTU_ABLATE == 6
+    bf16x8 r; for (int e = 0; e < 8; ++e) r[e] = (__bf16)(float)(a[ks] + blk); return r;
+#else
     return *HSTU_LDS(bf16x8, tile + blk * 32 * D * 2 + a[ks]);
+#endif
   }
 };
 
@@ -127,6 +135,50 @@ struct ColAddr {  // transposing reads: per 32-column block, the lane's address 
     return __builtin_bit_cast(bf16x8, both);
   }
 };
+
+// Transposed streamed tiles.  A transposed copy of a streamed tensor lives in the workspace as
+// [H][D][columns], 64 columns (= 64 streamed rows) per tile, and inside every group of 16
+// columns the rows are stored in the order 0-3, 8-11, 4-7, 12-15: exactly the order in which the
+// accumulator registers of a 32x32 score block hold them, so that a plain 16-byte row read of
+// the transposed tile is the operand of the second product (no transposing LDS reads needed).
+// In LDS such a tile is [D rows][128 bytes], swizzled like any tile with 128-byte rows.
+constexpr int TRB = ST * 2;  // bytes per row of a transposed tile
+
+template <int D>
+struct TrAddr {  // lane (n, hh): row n (+32*cb), chunk 2*half16 + hh for half16 = 0..3
+  int a[4];
+  __device__ __forceinline__ void init(int n, int hh) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) a[q] = lds_off_rb<TRB>(n, q * 2 + hh);
+  }
+  // operand for streamed rows 16*half16 .. +15 of the tile and output columns 32*cb .. +31
+  __device__ __forceinline__ bf16x8 read(const char* tile, int half16, int cb) const {
+#if HSTU_ABLATE == 5 || HSTU_ABLATE == 6
+    bf16x8 r; for (int e = 0; e < 8; ++e) r[e] = (__bf16)(float)(a[half16] + cb); return r;
+#else
+    return *HSTU_LDS(bf16x8, tile + cb * 32 * TRB + a[half16]);
+#endif
+  }
+};
+
+// Asynchronous copy of one transposed tile: D rows of 128 bytes, row r at src + r * col_stride.
+template <int D, int NW>
+__device__ __forceinline__ void ttile_copy_async(char* tile, const __bf16* src, int64_t col_stride,
+                                                 int wave, int lane) {
+  constexpr int LOADS = D / 8;  // 8 rows of 128 bytes per wave-wide load
+  const int rs = (int)col_stride * 2;
+  const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      (void*)src, 0, __builtin_amdgcn_readfirstlane((D - 1) * rs + TRB), 0x00020000);
+#pragma unroll
+  for (int i = 0; i < (LOADS + NW - 1) / NW; ++i) {
+    const int idx = i * NW + wave;
+    if (LOADS % NW != 0 && idx >= LOADS) break;
+    const int row = idx * 8 + (lane >> 3);
+    const int chunk = (lane & 7) ^ swz_rb<TRB>(row);
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, HSTU_LDS(void, tile + idx * 1024), 16,
+                                             row * rs + chunk * 16, 0, 0, 0);
+  }
+}
 
 // A streamed tile on its way from global memory to LDS, held in registers meanwhile.
 template <int D, int NT>
@@ -188,8 +240,47 @@ __device__ __forceinline__ void tile_copy_async(char* tile, const __bf16* base, 
   }
 }
 
-// Completion of this wave's outstanding tile copies (they count as vector memory loads).
-__device__ __forceinline__ void tile_copy_wait() { __builtin_amdgcn_s_waitcnt(0x0f70); }
+// Wave-wide loads that make up one row-major tile copy.
+template <int D>
+constexpr int tile_loads() { return ST / (64 / (D / 8)); }
+
+// Waits until at most N of this wave's vector memory loads (tile copies included) are still in
+// flight; loads complete in order, so the N newest may remain outstanding.
+template <int N = 0>
+__device__ __forceinline__ void tile_copy_wait() {
+  static_assert(N >= 0 && N < 16, "vmcnt immediate");
+  __builtin_amdgcn_s_waitcnt(0x0f70 | N);
+}
+
+// The owner rows are fetched with ordinary loads before the first tile copy is issued; waiting
+// for them first keeps the in-flight counts of the tile copies exact.
+__device__ __forceinline__ void load_owner_wait() { __builtin_amdgcn_s_waitcnt(0x0f70); }
+
+// Register-staged tile copy (alternative to the asynchronous LDS copy): R rows of RB bytes.
+template <int R, int RB, int NT>
+struct StagedTile {
+  static constexpr int CPR = RB / 16, CHUNKS = R * CPR, ITERS = (CHUNKS + NT - 1) / NT;
+  u32x4 r[ITERS];
+  __device__ __forceinline__ void load(const void* base, int rs_bytes, int valid_rows, int tid) {
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)base, 0, __builtin_amdgcn_readfirstlane((valid_rows - 1) * rs_bytes + RB), 0x00020000);
+#pragma unroll
+    for (int i = 0; i < ITERS; ++i) {
+      const int c = tid + i * NT;
+      const int row = c / CPR, chunk = c % CPR;
+      const int off = (c < CHUNKS && row < valid_rows) ? row * rs_bytes + chunk * 16 : 0x7fffffff;
+      r[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, off, 0, 0);
+    }
+  }
+  __device__ __forceinline__ void store(char* tile, int tid) const {
+#pragma unroll
+    for (int i = 0; i < ITERS; ++i) {
+      const int c = tid + i * NT;
+      const int row = c / CPR, chunk = c % CPR;
+      if (c < CHUNKS) *HSTU_LDS(u32x4, tile + lds_off_rb<RB>(row, chunk)) = r[i];
+    }
+  }
+};
 
 // 32 owner rows of one head as B operands: lane (n, hh) holds row n, elements 16*s + 8*hh + e.
 // base points at (row 0 of the owner tile, this head); rows >= nrows read as zero.
@@ -212,7 +303,7 @@ __device__ __forceinline__ f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c) {
 
 // sigmoid(alpha * s) with c1 = -alpha * log2(e).  exp2 overflow gives rcp(inf) = 0.
 __device__ __forceinline__ float sigmoid_scaled(float s, float c1) {
-#if HSTU_ABLATE == 1
+#if HSTU_ABLATE == 1 || HSTU_ABLATE == 6
   return c1;
 #else
   return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(s * c1));
@@ -240,7 +331,7 @@ __device__ __forceinline__ void visible_range(const Item& it, int g, int causal,
     } else {
       const int b = it.pos0 - it.seg_pos0[g];
       beg = b < 0 ? 0 : (b < end ? b : end);
-      beg &= ~31;
+      beg &= ~(ST - 1);
     }
   }
 }
@@ -269,7 +360,7 @@ __device__ __forceinline__ Stream make_stream(const Item& it, int causal) {
 }
 
 // Tile j of the stream: segment, first segment-relative row, valid rows, first position.
-struct TileRef { int row; int valid; int pos; };
+struct TileRef { int row; int valid; int pos; int tcol; };
 
 __device__ __forceinline__ TileRef tile_ref(const Item& it, const Stream& s, int j) {
   const int g = j < s.n[0] ? 0 : 1;
@@ -279,6 +370,7 @@ __device__ __forceinline__ TileRef tile_ref(const Item& it, const Stream& s, int
   r.row = it.seg_row0[g] + rel;
   r.valid = s.end[g] - rel;  // may exceed ST; callers clamp by ST through the loader
   r.pos = it.seg_pos0[g] + rel;
+  r.tcol = it.seg_tcol0[g] + rel;  // a multiple of 64: streams start on tile boundaries
   return r;
 }
 
@@ -342,9 +434,9 @@ __device__ __forceinline__ bool fetch_item(const Plan& plan, int slot, Item& it)
     it.seg_row0[g] = __builtin_amdgcn_readfirstlane(src->seg_row0[g]);
     it.seg_len[g] = __builtin_amdgcn_readfirstlane(src->seg_len[g]);
     it.seg_pos0[g] = __builtin_amdgcn_readfirstlane(src->seg_pos0[g]);
+    it.seg_tcol0[g] = __builtin_amdgcn_readfirstlane(src->seg_tcol0[g]);
   }
   it.cost = 0;
-  it.pad = 0;
   return it.nrows > 0;
 }
 
@@ -358,7 +450,7 @@ __device__ __forceinline__ bool fetch_item(const Plan& plan, int slot, Item& it)
 // the block the diagonal crosses is masked element by element.
 template <int DQK, int DV>
 __device__ __forceinline__ void fwd_block_masked(const char* kt, const char* vt, int blk,
-                                                 const RowAddr<DQK>& ra, const ColAddr<DV>& ca,
+                                                 const RowAddr<DQK>& ra, const TrAddr<DV>& ca,
                                                  const bf16x8 (&qreg)[DQK / 16],
                                                  f32x16 (&oacc)[DV / 32], float c1, int k_lo,
                                                  int q_lo, bool mask, int n, int hh) {
@@ -393,7 +485,7 @@ __device__ __forceinline__ void fwd_block_masked(const char* kt, const char* vt,
 // while P(1) is formed.
 template <int DQK, int DV>
 __device__ __forceinline__ void fwd_tile_full(const char* kt, const char* vt,
-                                              const RowAddr<DQK>& ra, const ColAddr<DV>& ca,
+                                              const RowAddr<DQK>& ra, const TrAddr<DV>& ca,
                                               const bf16x8 (&qreg)[DQK / 16],
                                               f32x16 (&oacc)[DV / 32], float c1) {
   constexpr int KS = DQK / 16, NPV = DV / 16;
@@ -442,12 +534,16 @@ __device__ __forceinline__ void fwd_tile_full(const char* kt, const char* vt,
 template <int DQK, int DV, int NW>
 __global__ void __launch_bounds__(NW * 64, 2) hstu_fwd_bf16(AttnArgs a) {
   constexpr int KB = ST * DQK * 2, VB = ST * DV * 2;
-  // Two separate arrays, one per buffer: the compiler can then see that the asynchronous copy
-  // into one buffer cannot alias the operand reads from the other.
+  // NBUF tile buffers: the copy of tile j+NBUF-1 is in flight while tile j is computed.  Eight
+  // waves share three buffers (one workgroup per CU), four waves two (two workgroups per CU).
+  // One array per buffer: the compiler can then see that a copy into one buffer cannot alias
+  // the operand reads from another.
+  constexpr int NBUF = NW >= 8 ? 3 : 2, PD = NBUF - 1;
   __shared__ __attribute__((aligned(1024))) char smem0[KB + VB];
   __shared__ __attribute__((aligned(1024))) char smem1[KB + VB];
-  auto kbuf = [&](int b) { return b ? smem1 : smem0; };
-  auto vbuf = [&](int b) { return (b ? smem1 : smem0) + KB; };
+  __shared__ __attribute__((aligned(1024))) char smem2[NBUF > 2 ? KB + VB : 1024];
+  auto kbuf = [&](int b) { return b == 0 ? smem0 : (b == 1 ? smem1 : smem2); };
+  auto vbuf = [&](int b) { return kbuf(b) + KB; };
 
   const int H = a.num_heads;
   const int slot = blockIdx.x / H, h = blockIdx.x % H;
@@ -459,7 +555,8 @@ __global__ void __launch_bounds__(NW * 64, 2) hstu_fwd_bf16(AttnArgs a) {
   const int64_t sq = (int64_t)H * DQK, sv = (int64_t)H * DV;
   const __bf16* qg = (const __bf16*)a.q + (int64_t)it.row0 * sq + h * DQK;
   const __bf16* kg = (const __bf16*)a.k + h * DQK;
-  const __bf16* vg = (const __bf16*)a.v + h * DV;
+  const int64_t tcols = (int64_t)ST * a.plan.max_stiles;           // columns of the transposed copy
+  const __bf16* vtg = (const __bf16*)a.vt + (int64_t)h * DV * tcols;  // V^T of this head: [DV][tcols]
 
   const int orow = wave * 32 + n;  // this lane's owner row inside the tile
   const bool wave_on = wave * 32 < it.nrows;
@@ -476,29 +573,44 @@ __global__ void __launch_bounds__(NW * 64, 2) hstu_fwd_bf16(AttnArgs a) {
   const float c1 = -a.alpha * 1.4426950408889634f;
   const int q_lo = it.pos0 + wave * 32, q_hi = q_lo + 31;
 
-  if (st.total > 0) {
-    const TileRef t0 = tile_ref(it, st, 0);
-    tile_copy_async<DQK, NW>(kbuf(0), kg + (int64_t)t0.row * sq, sq, t0.valid, wave, lane);
-    tile_copy_async<DV, NW>(vbuf(0), vg + (int64_t)t0.row * sv, sv, t0.valid, wave, lane);
-  }
-  tile_copy_wait();
+  auto copy_tile = [&](int j, int buf) {
+    const TileRef t = tile_ref(it, st, j);
+    tile_copy_async<DQK, NW>(kbuf(buf), kg + (int64_t)t.row * sq, sq, t.valid, wave, lane);
+    ttile_copy_async<DV, NW>(vbuf(buf), vtg + t.tcol, tcols, wave, lane);
+  };
+  // wave-wide loads one wave issues per tile copy (the in-flight count the waits below allow)
+  constexpr int LPT = (tile_loads<DQK>() + NW - 1) / NW + (DV / 8 + NW - 1) / NW;
+
+  load_owner_wait();
+  if (st.total > 0) copy_tile(0, 0);
+  if (PD > 1 && st.total > 1) copy_tile(1, 1);
+  if (PD > 1 && st.total > 1) tile_copy_wait<LPT>(); else tile_copy_wait<0>();
   __syncthreads();
 
   RowAddr<DQK> ra;
-  ColAddr<DV> ca;
+  TrAddr<DV> ca;
   ra.init(n, hh);
-  ca.init(lane);
+  ca.init(n, hh);
 
   // One tile of the stream; BUF is a compile-time buffer index so that every LDS address is a
   // per-lane register plus an immediate.
   auto step = [&](int j, auto buf_tag) {
     constexpr int BUF = decltype(buf_tag)::value;
     const TileRef tj = tile_ref(it, st, j);
-    if (HSTU_ABLATE != 3 && j + 1 < st.total) {  // the other buffer was last read before the barrier that ended j-1
-      const TileRef tn = tile_ref(it, st, j + 1);
-      tile_copy_async<DQK, NW>(kbuf(BUF ^ 1), kg + (int64_t)tn.row * sq, sq, tn.valid, wave, lane);
-      tile_copy_async<DV, NW>(vbuf(BUF ^ 1), vg + (int64_t)tn.row * sv, sv, tn.valid, wave, lane);
+    // buffer (BUF + PD) % NBUF held tile j-1: every wave finished it before the barrier that ended j-1
+    const bool more = HSTU_ABLATE != 3 && j + PD < st.total;
+#if HSTU_ABLATE == 7
+    StagedTile<ST, DQK * 2, NW * 64> ks_;
+    StagedTile<DV, TRB, NW * 64> vs_;
+    if (more) {
+      const TileRef t = tile_ref(it, st, j + PD);
+      const int vr = t.valid < 0 ? 0 : (t.valid < ST ? t.valid : ST);
+      ks_.load(kg + (int64_t)t.row * sq, (int)sq * 2, vr, tid);
+      vs_.load(vtg + t.tcol, (int)tcols * 2, DV, tid);
     }
+#else
+    if (more) copy_tile(j + PD, (BUF + PD) % NBUF);
+#endif
     const char* kt = kbuf(BUF);
     const char* vt = vbuf(BUF);
     if (wave_on) {
@@ -514,14 +626,18 @@ __global__ void __launch_bounds__(NW * 64, 2) hstu_fwd_bf16(AttnArgs a) {
         }
       }
     }
-#if HSTU_ABLATE != 4
-    tile_copy_wait();
-    __syncthreads();
+    // tile j+1 must have landed; with three buffers the copy just issued may stay in flight
+#if HSTU_ABLATE == 7
+    if (more) { ks_.store(kbuf((BUF + PD) % NBUF), tid); vs_.store(vbuf((BUF + PD) % NBUF), tid); }
+#else
+    if (PD > 1 && more) tile_copy_wait<LPT>(); else tile_copy_wait<0>();
 #endif
+    __syncthreads();
   };
-  for (int j = 0; j < st.total; j += 2) {
+  for (int j = 0; j < st.total; j += NBUF) {
     step(j, std::integral_constant<int, 0>{});
     if (j + 1 < st.total) step(j + 1, std::integral_constant<int, 1>{});
+    if (NBUF > 2 && j + 2 < st.total) step(j + 2, std::integral_constant<int, (NBUF > 2 ? 2 : 0)>{});
   }
 
   // O^T accumulators: lane holds query row n, elements dvb*32 + 8*(r/4) + 4*hh + r%4.
@@ -928,7 +1044,7 @@ __global__ void __launch_bounds__(NW * 64, 2) hstu_dq_bf16(AttnArgs a) {
     tile_copy_async<DQK, NW>(kbuf(0), kg + (int64_t)t0.row * sq, sq, t0.valid, wave, lane);
     tile_copy_async<DV, NW>(vbuf(0), vg + (int64_t)t0.row * sv, sv, t0.valid, wave, lane);
   }
-  tile_copy_wait();
+  tile_copy_wait<0>();
   __syncthreads();
 
   auto step = [&](int j, auto buf_tag) {
@@ -954,7 +1070,7 @@ __global__ void __launch_bounds__(NW * 64, 2) hstu_dq_bf16(AttnArgs a) {
         }
       }
     }
-    tile_copy_wait();
+    tile_copy_wait<0>();
     __syncthreads();
   };
   for (int j = 0; j < st.total; j += 2) {
@@ -968,12 +1084,47 @@ __global__ void __launch_bounds__(NW * 64, 2) hstu_dq_bf16(AttnArgs a) {
                            hh, a.accumulate, a.out_f32);
 }
 
-constexpr int FWD_NW = 4, DQ_NW = 4, DKDV_NW = 4;
+// =============================================================================================
+// Transposed copies of streamed tensors (see TrAddr): src [rows][H][D] -> dst [H][D][columns].
+// One workgroup per (64-row streamed tile, head); memory bound, a few percent of a pass.
+// =============================================================================================
+template <int D>
+__global__ void __launch_bounds__(256) hstu_transpose_bf16(const uint16_t* __restrict__ src,
+                                                           uint16_t* __restrict__ dst, Plan plan,
+                                                           int H) {
+  constexpr int LD = D + 2;  // padded row length in elements (rows stay 4-byte aligned)
+  __shared__ __attribute__((aligned(16))) uint16_t tile[ST * LD];
+  const int i = blockIdx.x / H, h = blockIdx.x % H;
+  if (i >= plan.header[1]) return;
+  const int row0 = plan.ttile[2 * i], nrows = plan.ttile[2 * i + 1];
+  const int64_t cols = (int64_t)ST * plan.max_stiles;
+  const int tid = threadIdx.x;
+  for (int c = tid; c < ST * (D / 8); c += 256) {
+    const int r = c / (D / 8), ch = c % (D / 8);
+    u32x4 v = {0u, 0u, 0u, 0u};
+    if (r < nrows) v = *(const u32x4*)(src + ((int64_t)(row0 + r) * H + h) * D + ch * 8);
+    uint32_t* t = (uint32_t*)(tile + r * LD + ch * 8);
+    t[0] = v[0]; t[1] = v[1]; t[2] = v[2]; t[3] = v[3];
+  }
+  __syncthreads();
+  for (int c = tid; c < D * 8; c += 256) {
+    const int d = c >> 3, q = c & 7;                 // output row d, 16-byte chunk q of its 64 columns
+    const int base = (q >> 1) * 16 + (q & 1) * 4;    // rows base+0..3 and base+8..11
+    uint16_t e[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) e[j] = tile[(base + (j & 3) + ((j >> 2) << 3)) * LD + d];
+    u32x4 v;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) v[j] = (uint32_t)e[2 * j] | ((uint32_t)e[2 * j + 1] << 16);
+    *(u32x4*)(dst + ((int64_t)h * D + d) * cols + (int64_t)ST * i + q * 8) = v;
+  }
+}
 
 }  // namespace
 
-int tile_rows_bf16(int pass) {
-  return 32 * (pass == PASS_FWD ? FWD_NW : (pass == PASS_DKDV ? DKDV_NW : DQ_NW));
+int waves_bf16(int pass, int64_t owner_rows, int heads) {
+  if (pass == PASS_FWD) return (owner_rows / 256) * heads >= 2048 ? 8 : 4;
+  return 4;
 }
 
 #define HSTU_DISPATCH_D(KERNEL, NW)                                                     \
@@ -992,14 +1143,30 @@ int tile_rows_bf16(int pass) {
     return hipGetLastError();                                                           \
   } while (0)
 
+hipError_t launch_transpose_bf16(const void* src, void* dst, const Plan& plan, int num_heads, int d,
+                                 hipStream_t stream) {
+  const dim3 grid((unsigned)((int64_t)plan.max_stiles * num_heads)), block(256);
+  const uint16_t* s = (const uint16_t*)src;
+  uint16_t* t = (uint16_t*)dst;
+  if (d == 128) hipLaunchKernelGGL((hstu_transpose_bf16<128>), grid, block, 0, stream, s, t, plan, num_heads);
+  else if (d == 64) hipLaunchKernelGGL((hstu_transpose_bf16<64>), grid, block, 0, stream, s, t, plan, num_heads);
+  else if (d == 32) hipLaunchKernelGGL((hstu_transpose_bf16<32>), grid, block, 0, stream, s, t, plan, num_heads);
+  else return hipErrorInvalidValue;
+  return hipGetLastError();
+}
+
 hipError_t launch_fwd_bf16(const AttnArgs& a, int d_qk, int d_v, hipStream_t stream) {
-  HSTU_DISPATCH_D(hstu_fwd_bf16, FWD_NW);
+  if (a.waves == 8) HSTU_DISPATCH_D(hstu_fwd_bf16, 8);
+  if (a.waves == 4) HSTU_DISPATCH_D(hstu_fwd_bf16, 4);
+  return hipErrorInvalidValue;
 }
 hipError_t launch_dkdv_bf16(const AttnArgs& a, int d_qk, int d_v, hipStream_t stream) {
-  HSTU_DISPATCH_D(hstu_dkdv_bf16, DKDV_NW);
+  if (a.waves != 4) return hipErrorInvalidValue;
+  HSTU_DISPATCH_D(hstu_dkdv_bf16, 4);
 }
 hipError_t launch_dq_bf16(const AttnArgs& a, int d_qk, int d_v, hipStream_t stream) {
-  HSTU_DISPATCH_D(hstu_dq_bf16, DQ_NW);
+  if (a.waves != 4) return hipErrorInvalidValue;
+  HSTU_DISPATCH_D(hstu_dq_bf16, 4);
 }
 
 }  // namespace hstu

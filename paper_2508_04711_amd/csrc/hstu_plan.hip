@@ -62,83 +62,145 @@ __device__ inline void seq_range(const int32_t* off, int b, int total_rows, int&
   e = clampi(off[b + 1], s, total_rows);
 }
 
+constexpr int STILE = 64;  // rows per tile of the streamed side (what the kernels stage in LDS)
+
 __device__ inline int tiles_of(const Side& s, int tile) {
   return (s.len[0] + tile - 1) / tile + (s.len[1] + tile - 1) / tile;
 }
 
 // Inclusive scan of one value per thread across the block; returns the inclusive prefix and
-// leaves the block total in *total.  `buf` has PLAN_THREADS ints.
+// leaves the block total in *total.  `buf` has at least PLAN_THREADS / 64 ints.  Shuffles
+// inside each wavefront, then one pass over the wavefront totals.
 __device__ inline int block_scan(int v, int* buf, int* total) {
-  const int tid = threadIdx.x;
-  buf[tid] = v;
-  __syncthreads();
-  for (int d = 1; d < PLAN_THREADS; d <<= 1) {
-    int t = tid >= d ? buf[tid - d] : 0;
-    __syncthreads();
-    buf[tid] += t;
-    __syncthreads();
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  int x = v;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const int y = __shfl_up(x, d, 64);
+    if (lane >= d) x += y;
   }
-  int r = buf[tid];
-  *total = buf[PLAN_THREADS - 1];
+  if (lane == 63) buf[wave] = x;
   __syncthreads();
-  return r;
+  int base = 0, tot = 0;
+#pragma unroll
+  for (int w = 0; w < PLAN_THREADS / 64; ++w) {
+    const int t = buf[w];
+    if (w < wave) base += t;
+    tot += t;
+  }
+  *total = tot;
+  __syncthreads();
+  return x + base;
 }
 
-__global__ void __launch_bounds__(PLAN_THREADS) plan_kernel(PlanArgs a) {
-  __shared__ int scan_buf[PLAN_THREADS];
+// Per-sequence arrays are kept in LDS when the batch fits (the common case) so that the binary
+// searches and base lookups of the later passes do not pay global-memory latency.
+constexpr int LDS_BATCH = 2047;
+
+__device__ __forceinline__ void plan_body(const PlanArgs& a);
+
+__global__ void __launch_bounds__(PLAN_THREADS) plan_kernel(PlanArgs a0, PlanArgs a1) {
+  plan_body(blockIdx.x == 0 ? a0 : a1);
+}
+
+__device__ __forceinline__ void plan_body(const PlanArgs& a) {
+  __shared__ int scan_buf[PLAN_THREADS / 64];
+  __shared__ int s_off[LDS_BATCH + 2], s_owner[LDS_BATCH + 1], s_streamed[LDS_BATCH + 1];
+  __shared__ int s_tile[LDS_BATCH + 2], s_stile[LDS_BATCH + 2];
+  const bool in_lds = a.batch <= LDS_BATCH;
+  // the arrays the later passes read: LDS copies when they fit, the workspace otherwise
+  const int* r_off = in_lds ? s_off : a.off;
+  const int* r_owner = in_lds ? s_owner : a.owner_base;
+  const int* r_streamed = in_lds ? s_streamed : a.streamed_base;
+  const int* r_tile = in_lds ? s_tile : a.tile_base;
+  const int* r_stile = in_lds ? s_stile : a.stile_base;
   __shared__ int hist[NBINS];
   __shared__ int num_items_s;
+  __shared__ int num_stiles_s;
   const int tid = threadIdx.x;
 
   // ---- pass 1: per-sequence bases (prefix sums over the batch) --------------------------
-  int carry_owner = 0, carry_streamed = 0, carry_tiles = 0;
+  int carry_owner = 0, carry_streamed = 0, carry_tiles = 0, carry_stiles = 0;
   for (int b0 = 0; b0 < a.batch; b0 += PLAN_THREADS) {
     const int b = b0 + tid;
-    int orows = 0, srows = 0, ntile = 0, s = 0, e = 0;
+    int orows = 0, srows = 0, ntile = 0, nstile = 0, s = 0, e = 0;
     if (b < a.batch) {
       seq_range(a.off, b, a.total_rows, s, e);
       const Side so = make_side(e - s, a.cp, a.owner_rank);
       const Side ss = make_side(e - s, a.cp, a.streamed_rank);
-      orows = so.rows; srows = ss.rows; ntile = tiles_of(so, a.tile);
+      orows = so.rows; srows = ss.rows; ntile = tiles_of(so, a.tile); nstile = tiles_of(ss, STILE);
     }
     int tot;
     const int io = block_scan(orows, scan_buf, &tot);   const int tot_o = tot;
     const int is = block_scan(srows, scan_buf, &tot);   const int tot_s = tot;
     const int it = block_scan(ntile, scan_buf, &tot);   const int tot_t = tot;
+    const int iu = block_scan(nstile, scan_buf, &tot);  const int tot_u = tot;
     if (b < a.batch) {
       // global layouts keep the caller's offsets; local layouts are packed rank rows
-      a.owner_base[b] = a.owner_rank < 0 ? s : carry_owner + io - orows;
-      a.streamed_base[b] = a.streamed_rank < 0 ? s : carry_streamed + is - srows;
-      a.tile_base[b] = carry_tiles + it - ntile;
+      const int ob = a.owner_rank < 0 ? s : carry_owner + io - orows;
+      const int sb = a.streamed_rank < 0 ? s : carry_streamed + is - srows;
+      const int tb = carry_tiles + it - ntile, ub = carry_stiles + iu - nstile;
+      if (in_lds) {
+        s_off[b] = a.off[b]; s_owner[b] = ob; s_streamed[b] = sb; s_tile[b] = tb; s_stile[b] = ub;
+        if (b == a.batch - 1) s_off[b + 1] = a.off[b + 1];
+      } else {
+        a.owner_base[b] = ob; a.streamed_base[b] = sb; a.tile_base[b] = tb; a.stile_base[b] = ub;
+      }
     }
-    carry_owner += tot_o; carry_streamed += tot_s; carry_tiles += tot_t;
+    carry_owner += tot_o; carry_streamed += tot_s; carry_tiles += tot_t; carry_stiles += tot_u;
   }
   if (tid == 0) {
-    a.tile_base[a.batch] = carry_tiles;
+    if (in_lds) { s_tile[a.batch] = carry_tiles; s_stile[a.batch] = carry_stiles; }
+    else { a.tile_base[a.batch] = carry_tiles; a.stile_base[a.batch] = carry_stiles; }
     num_items_s = carry_tiles < a.max_items ? carry_tiles : a.max_items;
+    num_stiles_s = carry_stiles < a.max_stiles ? carry_stiles : a.max_stiles;
   }
   for (int i = tid; i < NBINS; i += PLAN_THREADS) hist[i] = 0;
   __syncthreads();
   const int num_items = num_items_s;
+  const int num_stiles = num_stiles_s;
+
+  // ---- pass 1b: the 64-row tiles of the streamed side (what the transposed copies are cut into)
+  for (int i = tid; i < num_stiles; i += PLAN_THREADS) {
+    int lo = 0, hi = a.batch;
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (r_stile[mid] <= i) lo = mid; else hi = mid;
+    }
+    const int b = lo;
+    int s, e;
+    seq_range(r_off, b, a.total_rows, s, e);
+    const Side ss = make_side(e - s, a.cp, a.streamed_rank);
+    int t = i - r_stile[b];
+    const int nt0 = (ss.len[0] + STILE - 1) / STILE;
+    const int g = t < nt0 ? 0 : 1;
+    if (g) t -= nt0;
+    const int row0 = r_streamed[b] + (g ? ss.len[0] : 0) + t * STILE;
+    int nrows = ss.len[g] - t * STILE;
+    if (nrows > STILE) nrows = STILE;
+    nrows = clampi((long long)a.streamed_rows - row0, 0, nrows);
+    a.ttile[2 * i] = row0;
+    a.ttile[2 * i + 1] = nrows;
+  }
 
   // ---- pass 2: describe every item, histogram its cost -----------------------------------
   for (int i = tid; i < num_items; i += PLAN_THREADS) {
     int lo = 0, hi = a.batch;  // largest b with tile_base[b] <= i
     while (hi - lo > 1) {
       const int mid = (lo + hi) >> 1;
-      if (a.tile_base[mid] <= i) lo = mid; else hi = mid;
+      if (r_tile[mid] <= i) lo = mid; else hi = mid;
     }
     const int b = lo;
     int s, e;
-    seq_range(a.off, b, a.total_rows, s, e);
+    seq_range(r_off, b, a.total_rows, s, e);
     const Side so = make_side(e - s, a.cp, a.owner_rank);
     const Side ss = make_side(e - s, a.cp, a.streamed_rank);
-    int t = i - a.tile_base[b];
+    int t = i - r_tile[b];
     const int nt0 = (so.len[0] + a.tile - 1) / a.tile;
     const int u = t < nt0 ? 0 : 1;
     if (u) t -= nt0;
     Item it;
-    it.row0 = a.owner_base[b] + (u ? so.len[0] : 0) + t * a.tile;
+    it.row0 = r_owner[b] + (u ? so.len[0] : 0) + t * a.tile;
     it.nrows = so.len[u] - t * a.tile;
     if (it.nrows > a.tile) it.nrows = a.tile;
     it.pos0 = so.pos[u] + t * a.tile;
@@ -146,8 +208,10 @@ __global__ void __launch_bounds__(PLAN_THREADS) plan_kernel(PlanArgs a) {
     it.nrows = clampi((long long)a.owner_rows - it.row0, 0, it.nrows);
     it.nseg = 0;
     it.cost = 0;
-    for (int g = 0; g < 2; ++g) { it.seg_row0[g] = 0; it.seg_len[g] = 0; it.seg_pos0[g] = 0; }
-    int srow = a.streamed_base[b];
+    for (int g = 0; g < 2; ++g) {
+      it.seg_row0[g] = 0; it.seg_len[g] = 0; it.seg_pos0[g] = 0; it.seg_tcol0[g] = 0;
+    }
+    int srow = r_streamed[b];
     for (int g = 0; g < ss.nseg; ++g) {
       int len = clampi((long long)a.streamed_rows - srow, 0, ss.len[g]);
       int vis;  // streamed rows that at least one owner row sees
@@ -161,11 +225,12 @@ __global__ void __launch_bounds__(PLAN_THREADS) plan_kernel(PlanArgs a) {
       if (it.nrows > 0 && vis > 0) {
         const int n = it.nseg++;
         it.seg_row0[n] = srow; it.seg_len[n] = len; it.seg_pos0[n] = ss.pos[g];
+        it.seg_tcol0[n] = STILE * (r_stile[b] + (g ? (ss.len[0] + STILE - 1) / STILE : 0));
         it.cost += (vis + 31) >> 5;
       }
       srow += ss.len[g];
     }
-    it.pad = 0;
+    it.pad[0] = it.pad[1] = it.pad[2] = 0;
     a.items[i] = it;
     int bin = it.cost >> a.cost_shift;
     if (bin > NBINS - 1) bin = NBINS - 1;
@@ -190,14 +255,18 @@ __global__ void __launch_bounds__(PLAN_THREADS) plan_kernel(PlanArgs a) {
     const int pos = atomicAdd(&hist[NBINS - 1 - bin], 1);
     a.order[pos] = i;
   }
-  if (tid == 0) a.header[0] = num_items;
+  if (tid == 0) {
+    a.header[0] = num_items;
+    a.header[1] = num_stiles;
+  }
 }
 
 }  // namespace
 
-hipError_t launch_plan(const PlanArgs& a, hipStream_t stream) {
+hipError_t launch_plans(const PlanArgs* a, int count, hipStream_t stream) {
   static_assert(NBINS == 2 * PLAN_THREADS, "pass 3 handles two bins per thread");
-  hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(PLAN_THREADS), 0, stream, a);
+  if (count < 1 || count > 2) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(plan_kernel, dim3(count), dim3(PLAN_THREADS), 0, stream, a[0], a[count - 1]);
   return hipGetLastError();
 }
 

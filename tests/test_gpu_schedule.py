@@ -76,7 +76,7 @@ def test_full_attention_schedule(lengths, causal, side):
     lengths = [int(x) for x in lengths]
     T = sum(lengths)
     off = torch.tensor(np.concatenate([[0], np.cumsum(lengths)]), dtype=torch.int32, device="cuda")
-    tile = lib.hstu_schedule_tile_rows(0, 128, 128, side)
+    tile = lib.hstu_schedule_tile_rows(0, 128, 128, side, T, 2)
     got = lib.hstu_debug_dump_schedule(off, T, 2, 128, 128, causal, 0, side)
     want = _expected_items(lengths, tile, causal, side)
     assert sorted(map(tuple, got.tolist())) == sorted(want)
