@@ -208,7 +208,7 @@ def main() -> int:
         "roofline": roofline,
     }
     if not args.no_cpu_baseline:
-        prefix = args.cpu_prefix_rows or {2: 1024, 3: 1536, 4: 2048, 5: 2048}[cfg]
+        prefix = args.cpu_prefix_rows or {2: 1024, 3: 4096, 4: 4096, 5: 4096}[cfg]
         out["cpu_baseline"] = _cpu_baseline(w, prefix)
     print(json.dumps(out))
     return 0
