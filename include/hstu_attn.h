@@ -34,6 +34,9 @@
  *     allocates nothing and keeps no state between calls; calls are
  *     asynchronous on `hip_stream` (a hipStream_t, NULL = the default stream)
  *     and calls on different streams with different workspaces may overlap.
+ *   - Environment: HSTU_ATTN_FWD_TILE=128 or 256 overrides the query-tile height the bf16
+ *     forward pass picks from the problem size (testing and tuning only; results are the same
+ *     to rounding).
  *   - Return value: HSTU_OK (0) or a negative hstu_status.  Nothing is launched
  *     when an error is returned.  batch == 0 or total_rows == 0 is HSTU_OK and
  *     launches nothing.  No exception or abort crosses this boundary.

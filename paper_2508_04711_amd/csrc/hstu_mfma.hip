@@ -25,6 +25,7 @@
 // SiLU, its derivative and the mask are evaluated in fp32 on the accumulator registers; P and
 // dS are rounded to bf16 only as operands of the second product; alpha and 1/max_len are
 // folded into one fp32 scale at the output, which is rounded to bf16 once.
+#include <cstdlib>
 #include <type_traits>
 
 #include "hstu_common.h"
@@ -42,9 +43,6 @@ typedef __attribute__((__vector_size__(2 * sizeof(uint32_t)))) uint32_t u32x2;
 
 #define HSTU_LDS(T, p) ((__attribute__((address_space(3))) T*)(p))
 
-#ifndef HSTU_ABLATE
-#define HSTU_ABLATE 0
-#endif
 constexpr int ST = 64;  // streamed rows per LDS tile
 
 // Swizzle of the 16-byte chunk index by the row.  LDS has 64 banks of 4 bytes, i.e. 16 chunk
@@ -69,31 +67,11 @@ __device__ __forceinline__ int lds_off_rb(int row, int chunk) {
 template <int D>
 __device__ __forceinline__ int lds_off(int row, int chunk) { return lds_off_rb<D * 2>(row, chunk); }
 
-// Row-wise A operand: 8 consecutive elements [col8*8, col8*8+8) of row `row`.
-template <int D>
-__device__ __forceinline__ bf16x8 lds_read_rows(const char* tile, int row, int col8) {
-  return *HSTU_LDS(bf16x8, tile + lds_off<D>(row, col8));
-}
-
-// Transposed operand for one 32x32x16 product: lane (n, hh) receives, for column
-// col0 + n, the rows row0 + 4*hh + {0,1,2,3} and row0 + 8 + 4*hh + {0,1,2,3}: exactly the
-// streamed rows a lane's accumulator registers 8c..8c+7 belong to when row0 = 32*blk + 16*c.
-template <int D>
-__device__ __forceinline__ bf16x8 lds_read_cols(const char* tile, int row0, int col0, int lane) {
-  const int i = lane & 15, g = lane >> 4;
-  const int row = row0 + ((g >> 1) << 2) + (i >> 2);
-  const int col = col0 + ((g & 1) << 4) + ((i & 3) << 2);  // element column of this lane's 8 bytes
-  const int within = (col & 7) << 1;
-  const char* p0 = tile + lds_off<D>(row, col >> 3) + within;
-  const char* p1 = tile + lds_off<D>(row + 8, col >> 3) + within;
-  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(HSTU_LDS(s16x4, p0));
-  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(HSTU_LDS(s16x4, p1));
-  typedef __attribute__((__vector_size__(8 * sizeof(short)))) short s16x8;
-  const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-  return __builtin_bit_cast(bf16x8, both);
-}
-
-// Per-lane byte offsets of operand reads inside a tile, computed once per kernel.  The swizzle
+// Per-lane byte offsets of operand reads inside a tile, computed once per kernel.  A row-wise
+// operand is 8 consecutive elements of one row (one 16-byte chunk); a transposed operand for a
+// 32x32x16 product gives lane (n, hh), for column col0 + n, the rows 4*hh + {0..3} and
+// 8 + 4*hh + {0..3} of a 16-row group: exactly the streamed rows a lane's accumulator registers
+// 8c..8c+7 belong to.  The swizzle
 // depends on row mod 16 only, so a read of block blk (rows 32*blk + ...) is the same offset plus
 // a constant, which the compiler folds into the instruction's immediate offset.
 template <int D>
@@ -104,11 +82,7 @@ struct RowAddr {  // row-wise operand reads of row n (+32*blk): one address per 
     for (int ks = 0; ks < D / 16; ++ks) a[ks] = lds_off<D>(n, ks * 2 + hh);
   }
   __device__ __forceinline__ bf16x8 read(const char* tile, int blk, int ks) const {
-#if HSTU_ABLATE == 5 || HSTU_ABLATE == 6
-    bf16x8 r; for (int e = 0; e < 8; ++e) r[e] = (__bf16)(float)(a[ks] + blk); return r;
-#else
     return *HSTU_LDS(bf16x8, tile + blk * 32 * D * 2 + a[ks]);
-#endif
   }
 };
 
@@ -153,11 +127,7 @@ struct TrAddr {  // lane (n, hh): row n (+32*cb), chunk 2*half16 + hh for half16
   }
   // operand for streamed rows 16*half16 .. +15 of the tile and output columns 32*cb .. +31
   __device__ __forceinline__ bf16x8 read(const char* tile, int half16, int cb) const {
-#if HSTU_ABLATE == 5 || HSTU_ABLATE == 6
-    bf16x8 r; for (int e = 0; e < 8; ++e) r[e] = (__bf16)(float)(a[half16] + cb); return r;
-#else
     return *HSTU_LDS(bf16x8, tile + cb * 32 * TRB + a[half16]);
-#endif
   }
 };
 
@@ -179,40 +149,6 @@ __device__ __forceinline__ void ttile_copy_async(char* tile, const __bf16* src, 
                                              row * rs + chunk * 16, 0, 0, 0);
   }
 }
-
-// A streamed tile on its way from global memory to LDS, held in registers meanwhile.
-template <int D, int NT>
-struct TileRegs {
-  static constexpr int CPR = D / 8;                        // 16-byte chunks per row
-  static constexpr int CHUNKS = ST * CPR;
-  static constexpr int ITERS = (CHUNKS + NT - 1) / NT;
-  u32x4 r[ITERS];
-
-  // base: element pointer to (row 0 of the tile, this head); rows >= valid read as zero.  The
-  // loads go through a buffer resource that covers exactly the valid rows, so the hardware's
-  // range check supplies the zeros and no lane needs a branch.
-  __device__ __forceinline__ void load(const __bf16* base, int64_t row_stride, int valid, int tid) {
-    const int rs = (int)row_stride * 2;  // bytes
-    const int rows = valid < 0 ? 0 : (valid < ST ? valid : ST);
-    const __amdgpu_buffer_rsrc_t rsrc =
-        __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, rows * rs, 0x00020000);
-#pragma unroll
-    for (int i = 0; i < ITERS; ++i) {
-      const int c = tid + i * NT;
-      const int row = c / CPR, chunk = c % CPR;
-      const int off = c < CHUNKS ? row * rs + chunk * 16 : 0x7fffffff;
-      r[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, off, 0, 0);
-    }
-  }
-  __device__ __forceinline__ void store(char* tile, int tid) const {
-#pragma unroll
-    for (int i = 0; i < ITERS; ++i) {
-      const int c = tid + i * NT;
-      const int row = c / CPR, chunk = c % CPR;
-      if (c < CHUNKS) *HSTU_LDS(u32x4, tile + lds_off<D>(row, chunk)) = r[i];
-    }
-  }
-};
 
 // Asynchronous copy of one streamed tile (ST rows of one head) from global memory straight into
 // its swizzled LDS layout: each wave-wide load moves 64 x 16 bytes into 1 KB of consecutive LDS
@@ -252,35 +188,21 @@ __device__ __forceinline__ void tile_copy_wait() {
   __builtin_amdgcn_s_waitcnt(0x0f70 | N);
 }
 
+// Workgroup barrier between tiles without the memory fence of __syncthreads(), which would wait
+// for every outstanding load and with it for the tile copies that are meant to stay in flight.
+// What has to be complete is waited for explicitly with tile_copy_wait<>() just before: a wave's
+// own copies of the next tile (other waves see them after the barrier) - its LDS operand reads of
+// the current tile have already been consumed by matrix instructions.  The empty asm statements
+// keep the compiler from moving memory accesses across the barrier.
+__device__ __forceinline__ void tile_barrier() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+
 // The owner rows are fetched with ordinary loads before the first tile copy is issued; waiting
 // for them first keeps the in-flight counts of the tile copies exact.
 __device__ __forceinline__ void load_owner_wait() { __builtin_amdgcn_s_waitcnt(0x0f70); }
-
-// Register-staged tile copy (alternative to the asynchronous LDS copy): R rows of RB bytes.
-template <int R, int RB, int NT>
-struct StagedTile {
-  static constexpr int CPR = RB / 16, CHUNKS = R * CPR, ITERS = (CHUNKS + NT - 1) / NT;
-  u32x4 r[ITERS];
-  __device__ __forceinline__ void load(const void* base, int rs_bytes, int valid_rows, int tid) {
-    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
-        (void*)base, 0, __builtin_amdgcn_readfirstlane((valid_rows - 1) * rs_bytes + RB), 0x00020000);
-#pragma unroll
-    for (int i = 0; i < ITERS; ++i) {
-      const int c = tid + i * NT;
-      const int row = c / CPR, chunk = c % CPR;
-      const int off = (c < CHUNKS && row < valid_rows) ? row * rs_bytes + chunk * 16 : 0x7fffffff;
-      r[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, off, 0, 0);
-    }
-  }
-  __device__ __forceinline__ void store(char* tile, int tid) const {
-#pragma unroll
-    for (int i = 0; i < ITERS; ++i) {
-      const int c = tid + i * NT;
-      const int row = c / CPR, chunk = c % CPR;
-      if (c < CHUNKS) *HSTU_LDS(u32x4, tile + lds_off_rb<RB>(row, chunk)) = r[i];
-    }
-  }
-};
 
 // 32 owner rows of one head as B operands: lane (n, hh) holds row n, elements 16*s + 8*hh + e.
 // base points at (row 0 of the owner tile, this head); rows >= nrows read as zero.
@@ -303,11 +225,7 @@ __device__ __forceinline__ f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c) {
 
 // sigmoid(alpha * s) with c1 = -alpha * log2(e).  exp2 overflow gives rcp(inf) = 0.
 __device__ __forceinline__ float sigmoid_scaled(float s, float c1) {
-#if HSTU_ABLATE == 1 || HSTU_ABLATE == 6
-  return c1;
-#else
   return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(s * c1));
-#endif
 }
 
 __device__ __forceinline__ bf16x8 pack8(const float* x) {
@@ -585,7 +503,7 @@ __global__ void __launch_bounds__(NW * 64, 2) hstu_fwd_bf16(AttnArgs a) {
   if (st.total > 0) copy_tile(0, 0);
   if (PD > 1 && st.total > 1) copy_tile(1, 1);
   if (PD > 1 && st.total > 1) tile_copy_wait<LPT>(); else tile_copy_wait<0>();
-  __syncthreads();
+  tile_barrier();
 
   RowAddr<DQK> ra;
   TrAddr<DV> ca;
@@ -598,19 +516,8 @@ __global__ void __launch_bounds__(NW * 64, 2) hstu_fwd_bf16(AttnArgs a) {
     constexpr int BUF = decltype(buf_tag)::value;
     const TileRef tj = tile_ref(it, st, j);
     // buffer (BUF + PD) % NBUF held tile j-1: every wave finished it before the barrier that ended j-1
-    const bool more = HSTU_ABLATE != 3 && j + PD < st.total;
-#if HSTU_ABLATE == 7
-    StagedTile<ST, DQK * 2, NW * 64> ks_;
-    StagedTile<DV, TRB, NW * 64> vs_;
-    if (more) {
-      const TileRef t = tile_ref(it, st, j + PD);
-      const int vr = t.valid < 0 ? 0 : (t.valid < ST ? t.valid : ST);
-      ks_.load(kg + (int64_t)t.row * sq, (int)sq * 2, vr, tid);
-      vs_.load(vtg + t.tcol, (int)tcols * 2, DV, tid);
-    }
-#else
+    const bool more = j + PD < st.total;
     if (more) copy_tile(j + PD, (BUF + PD) % NBUF);
-#endif
     const char* kt = kbuf(BUF);
     const char* vt = vbuf(BUF);
     if (wave_on) {
@@ -627,12 +534,8 @@ __global__ void __launch_bounds__(NW * 64, 2) hstu_fwd_bf16(AttnArgs a) {
       }
     }
     // tile j+1 must have landed; with three buffers the copy just issued may stay in flight
-#if HSTU_ABLATE == 7
-    if (more) { ks_.store(kbuf((BUF + PD) % NBUF), tid); vs_.store(vbuf((BUF + PD) % NBUF), tid); }
-#else
     if (PD > 1 && more) tile_copy_wait<LPT>(); else tile_copy_wait<0>();
-#endif
-    __syncthreads();
+    tile_barrier();
   };
   for (int j = 0; j < st.total; j += NBUF) {
     step(j, std::integral_constant<int, 0>{});
@@ -842,8 +745,8 @@ __global__ void __launch_bounds__(NW * 64) hstu_dkdv_bf16(AttnArgs a) {
     tile_copy_async<DQK, NW>(qbuf(0), qg + (int64_t)t0.row * sq, sq, t0.valid, wave, lane);
     tile_copy_async<DV, NW>(gbuf(0), gg + (int64_t)t0.row * sv, sv, t0.valid, wave, lane);
   }
-  tile_copy_wait();
-  __syncthreads();
+  tile_copy_wait<0>();
+  tile_barrier();
 
   auto step = [&](int j, auto buf_tag) {
     constexpr int BUF = decltype(buf_tag)::value;
@@ -869,7 +772,7 @@ __global__ void __launch_bounds__(NW * 64) hstu_dkdv_bf16(AttnArgs a) {
       }
     }
     tile_copy_wait();
-    __syncthreads();
+    tile_barrier();
   };
   for (int j = 0; j < st.total; j += 2) {
     step(j, std::integral_constant<int, 0>{});
@@ -1045,7 +948,7 @@ __global__ void __launch_bounds__(NW * 64, 2) hstu_dq_bf16(AttnArgs a) {
     tile_copy_async<DV, NW>(vbuf(0), vg + (int64_t)t0.row * sv, sv, t0.valid, wave, lane);
   }
   tile_copy_wait<0>();
-  __syncthreads();
+  tile_barrier();
 
   auto step = [&](int j, auto buf_tag) {
     constexpr int BUF = decltype(buf_tag)::value;
@@ -1071,7 +974,7 @@ __global__ void __launch_bounds__(NW * 64, 2) hstu_dq_bf16(AttnArgs a) {
       }
     }
     tile_copy_wait<0>();
-    __syncthreads();
+    tile_barrier();
   };
   for (int j = 0; j < st.total; j += 2) {
     step(j, std::integral_constant<int, 0>{});
@@ -1123,7 +1026,14 @@ __global__ void __launch_bounds__(256) hstu_transpose_bf16(const uint16_t* __res
 }  // namespace
 
 int waves_bf16(int pass, int64_t owner_rows, int heads) {
-  if (pass == PASS_FWD) return (owner_rows / 256) * heads >= 2048 ? 8 : 4;
+  if (pass == PASS_FWD) {
+    // HSTU_ATTN_FWD_TILE=128|256 overrides the choice (testing and tuning)
+    if (const char* e = getenv("HSTU_ATTN_FWD_TILE")) {
+      if (e[0] == '1') return 4;
+      if (e[0] == '2') return 8;
+    }
+    return (owner_rows / 256) * heads >= 2048 ? 8 : 4;
+  }
   return 4;
 }
 

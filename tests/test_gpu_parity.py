@@ -266,3 +266,29 @@ def test_binding_rejects_bad_tensors():
     q48 = torch.zeros((8, 2, 48), dtype=torch.bfloat16, device="cuda")
     with pytest.raises(lib.HstuError):
         lib.hstu_jagged_attn_fwd(q48, q48, q48, off, 8, 0.5)    # unsupported head dimension
+
+
+@pytest.mark.parametrize("causal", [True, False])
+@pytest.mark.parametrize("name,lengths,H,dqk,dv", [
+    ("wide_a", [700, 255, 256, 257, 1, 0, 513, 90], 2, 128, 128),
+    ("wide_b", [300, 65, 640], 2, 64, 128),
+    ("wide_c", [520, 31], 1, 32, 32),
+    ("wide_d", [260, 511], 2, 128, 64),
+])
+def test_wide_forward_tiles(name, lengths, H, dqk, dv, causal, monkeypatch):
+    # the 256-row forward tiles (eight wavefronts, three tile buffers) are chosen for large
+    # problems only; force them here so that small cases with ragged tails exercise them too
+    monkeypatch.setenv("HSTU_ATTN_FWD_TILE", "256")
+    w = workloads.custom(name, lengths, H, dqk, dv, max_len=max(lengths), dtype="bf16", seed=21)
+    print("wide", name, causal, flush=True)
+    _run_full(w, causal=causal, backward=False)
+    lib = _lib()
+    vals = _dev(workloads.values(w))
+    off = torch.from_numpy(w.seq_offsets()).cuda()
+    wide = lib.hstu_jagged_attn_fwd(vals["q"], vals["k"], vals["v"], off, w.max_len, w.alpha, causal,
+                                    out_dtype=torch.float32)
+    monkeypatch.setenv("HSTU_ATTN_FWD_TILE", "128")
+    narrow = lib.hstu_jagged_attn_fwd(vals["q"], vals["k"], vals["v"], off, w.max_len, w.alpha, causal,
+                                      out_dtype=torch.float32)
+    scale = narrow.abs().max().item()
+    assert (wide - narrow).abs().max().item() <= 1e-5 * scale   # same sums, another order
