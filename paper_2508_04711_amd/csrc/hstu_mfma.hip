@@ -415,6 +415,9 @@ __device__ __forceinline__ void fwd_tile_full(const char* kt, const char* vt,
 
 #pragma unroll
   for (int ks = 0; ks < KS; ++ks) ka[ks] = ra.read(kt, 0, ks);
+  // Favour the wave that is computing over the one on the same SIMD that is issuing copies or
+  // sitting at the barrier.
+  __builtin_amdgcn_s_setprio(1);
 #pragma unroll
   for (int ks = 0; ks < KS; ++ks) s0 = mfma(ka[ks], qreg[ks], s0);
 
@@ -447,6 +450,7 @@ __device__ __forceinline__ void fwd_tile_full(const char* kt, const char* vt,
   pb1 = pack8(p1 + 8);
 #pragma unroll
   for (int i = 0; i < NPV; ++i) oacc[i >> 1] = mfma(vb[i], (i & 1) ? pb1 : pb0, oacc[i >> 1]);
+  __builtin_amdgcn_s_setprio(0);
 }
 
 template <int DQK, int DV, int NW>
