@@ -3,7 +3,8 @@
 
 One step = one pass of the whole hot path over one synthetic jagged batch: schedule build,
 forward, dk/dv pass, dq pass (forward only for the forward-only workload; for the
-context-parallel workload every rank's partial, ranks one after the other on the one GPU).
+context-parallel workload every rank's reorder into its local layout, its partial and the
+reorder back, ranks one after the other on the one GPU).
 Inputs are resident in HBM before the timed region starts.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg5|cfg3|cfg2|cfg4]
@@ -100,28 +101,34 @@ def main() -> int:
         cp = w.cp_size
         ranks = []
         for r in range(cp):
-            rows = []
-            for b, L in enumerate(w.lengths):
+            n = 0
+            for L in w.lengths:
                 c = -(-L // (2 * cp))
-                for m in (r, 2 * cp - 1 - r):
-                    lo, hi = min(m * c, L), min((m + 1) * c, L)
-                    rows.append(torch.arange(off_np[b] + lo, off_np[b] + hi))
-            idx = torch.cat(rows).to(dev)
+                n += sum(min((m + 1) * c, L) - min(m * c, L) for m in (r, 2 * cp - 1 - r))
             ranks.append({
-                "q": vals["q"][idx].contiguous(), "d_o": vals["d_o"][idx].contiguous(),
-                "o": torch.empty((len(idx), H, w.d_v), dtype=dt, device=dev),
-                "dq": torch.empty((len(idx), H, w.d_qk), dtype=dt, device=dev),
+                "n": n,
+                "q": torch.empty((n, H, w.d_qk), dtype=dt, device=dev),
+                "d_o": torch.empty((n, H, w.d_v), dtype=dt, device=dev),
+                "o": torch.empty((n, H, w.d_v), dtype=dt, device=dev),
+                "dq": torch.empty((n, H, w.d_qk), dtype=dt, device=dev),
                 "dk": torch.empty((T, H, w.d_qk), dtype=dt, device=dev),
                 "dv": torch.empty((T, H, w.d_v), dtype=dt, device=dev),
             })
+        o_glob = torch.empty((T, H, w.d_v), dtype=dt, device=dev)
+        dq_glob = torch.empty((T, H, w.d_qk), dtype=dt, device=dev)
         ws = torch.empty(lib.hstu_jagged_attn_workspace_bytes(
             (w.batch, H, w.d_qk, w.d_v, w.max_len, w.alpha, True, 0, T), 2), dtype=torch.uint8, device=dev)
 
         def step():
+            # per rank: reorder kernel global -> local (q, d_o), the partial, local -> global (o, dq)
             for r, rk in enumerate(ranks):
+                lib.hstu_cp_reorder([vals["q"], vals["d_o"]], off, T, cp, r, rk["n"],
+                                    out=[rk["q"], rk["d_o"]])
                 lib.hstu_jagged_attn_cp_partial(rk["q"], vals["k"], vals["v"], rk["d_o"], off, T,
                                                 w.max_len, w.alpha, True, cp, r, -1,
                                                 out=(rk["o"], rk["dq"], rk["dk"], rk["dv"]), workspace=ws)
+                lib.hstu_cp_reorder([rk["o"], rk["dq"]], off, T, cp, r, rk["n"], scatter=True,
+                                    out=[o_glob, dq_glob])
     else:
         o = torch.empty((T, H, w.d_v), dtype=dt, device=dev)
         dq = torch.empty((T, H, w.d_qk), dtype=dt, device=dev)
@@ -187,6 +194,10 @@ def main() -> int:
                         if k in hw else None}
                     for k in avg_ms},
     }
+    if "reorder" in avg_ms:
+        # two tensors of H*d bf16 rows per launch, read once and written once
+        moved = 2.0 * (T / w.cp_size) * H * (w.d_qk + w.d_v) * 2
+        roofline["kernels"]["reorder"]["algorithmic_gbs"] = moved / (avg_ms["reorder"] * 1e-3) / 1e9
     if cfg == 2:
         # below the ridge: report the forward against HBM bandwidth over algorithmic bytes
         bytes_alg = 2.0 * T * H * (2 * w.d_qk + 2 * w.d_v)

@@ -142,6 +142,23 @@ int hstu_jagged_attn_cp_partial(const hstu_attn_params* params, const hstu_cp_de
                                 void* o_local, void* dq_local, void* dk_part, void* dv_part,
                                 void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* Memory reorder for the load-balanced split (section 2.3: the "data shuffling ... memory
+ * reordering" kernels that replace chunk + concatenate; section 3 credits them with +37 % QPS).
+ * Moves whole rows between the global jagged layout and `rank`'s local layout (see hstu_cp_desc),
+ * for up to four tensors at once (e.g. q, k, v, d_o), each with its own row length in bytes.
+ *   scatter == 0 (gather):  dst[t][r] = src[t][g(r)]   dst: local [local_rows, ...], src: global
+ *   scatter == 1:           dst[t][g(r)] = src[t][r]   dst: global, src: local (only the rank's
+ *                           rows of dst are written; the gradient path back to the global layout)
+ * where g(r) is the global row of local row r.  row_bytes[t] must be a multiple of 16; pointers
+ * 16-byte aligned.  Bit-exact copy; rows beyond local_rows / total_rows are never touched.
+ * One kernel launch on hip_stream; needs no workspace and allocates nothing.  seq_offsets is a
+ * device pointer to batch + 1 int32 (the global offsets), read by the kernel only.
+ */
+int hstu_cp_reorder(int32_t batch, int64_t total_rows, int32_t cp_size, int32_t rank, int32_t scatter,
+                    int32_t num_tensors, const void* const* src, void* const* dst,
+                    const int64_t* row_bytes, int64_t local_rows, const int32_t* seq_offsets,
+                    void* hip_stream);
+
 /* Bytes of workspace the given entry point needs for `params` (an upper bound
  * that depends on batch, total_rows and num_heads only; 0 on invalid params).
  * `which` is a hstu_ws_kind. */
@@ -174,7 +191,8 @@ int hstu_debug_dump_schedule(const hstu_attn_params* params, const hstu_cp_desc*
  * launched on.  This is the one piece of (thread-local) state the library ever keeps.
  *   begin: max_records in [1, 65536]; launches beyond it are not recorded.
  *   end:   waits for the recorded launches, writes per launch, in launch order, its kind
- *          (0 forward, 1 dk/dv pass, 2 dq pass, 3 schedule build, 4 transposed copy) and its duration in
+ *          (0 forward, 1 dk/dv pass, 2 dq pass, 3 schedule build, 4 transposed copy,
+ *          5 reorder) and its duration in
  *          milliseconds; returns the number written (<= capacity) or a status < 0.
  */
 int hstu_debug_timing_begin(int max_records);

@@ -5,6 +5,7 @@ Everything is computed by the HIP kernels in csrc/; this package only marshals a
 from .binding import (  # noqa: F401
     HstuError,
     hstu_attn_status_string,
+    hstu_cp_reorder,
     hstu_debug_dump_schedule,
     hstu_debug_timing_begin,
     hstu_debug_timing_end,

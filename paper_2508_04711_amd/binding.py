@@ -80,6 +80,10 @@ def load_library():
     lib.hstu_debug_timing_begin.argtypes = [ctypes.c_int]
     lib.hstu_debug_timing_end.restype = ctypes.c_int
     lib.hstu_debug_timing_end.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int]
+    lib.hstu_cp_reorder.restype = ctypes.c_int
+    lib.hstu_cp_reorder.argtypes = [ctypes.c_int32, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32,
+                                    ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p,
+                                    ctypes.c_void_p, ctypes.c_int64, i32p, vp]
     lib.hstu_schedule_tile_rows.restype = ctypes.c_int
     lib.hstu_schedule_tile_rows.argtypes = [pp, ctypes.c_int]
     _lib = lib
@@ -302,7 +306,7 @@ def hstu_debug_dump_schedule(seq_offsets: torch.Tensor, total_rows: int, num_hea
     return buf[:n].copy()
 
 
-KERNEL_KINDS = {0: "fwd", 1: "dkdv", 2: "dq", 3: "plan", 4: "transpose"}
+KERNEL_KINDS = {0: "fwd", 1: "dkdv", 2: "dq", 3: "plan", 4: "transpose", 5: "reorder"}
 
 
 def hstu_debug_timing_begin(max_records: int = 4096) -> None:
@@ -320,3 +324,43 @@ def hstu_debug_timing_end(capacity: int = 4096):
     if n < 0:
         raise HstuError(n, "hstu_debug_timing_end")
     return [(KERNEL_KINDS.get(int(kinds[i]), "?"), float(ms[i])) for i in range(n)]
+
+
+def hstu_cp_reorder(tensors, seq_offsets: torch.Tensor, total_rows: int, cp_size: int, rank: int,
+                    local_rows: int, scatter: bool = False, out=None, stream=None):
+    """Moves rows between the global jagged layout and `rank`'s local layout (up to 4 tensors).
+
+    gather (scatter=False): tensors are global [total_rows, ...]; returns local [local_rows, ...].
+    scatter=True: tensors are local; `out` must give the global tensors to write the rank's rows into.
+    """
+    tensors = list(tensors)
+    n = len(tensors)
+    if not 1 <= n <= 4:
+        raise ValueError("1 to 4 tensors per call")
+    rows_in = local_rows if scatter else total_rows
+    rows_out = total_rows if scatter else local_rows
+    for t in tensors:
+        if not t.is_cuda or not t.is_contiguous() or t.shape[0] != rows_in:
+            raise ValueError("tensors must be contiguous device tensors with %d rows" % rows_in)
+    if out is None:
+        if scatter:
+            raise ValueError("scatter needs the global tensors to write into")
+        out = [torch.empty((rows_out,) + tuple(t.shape[1:]), dtype=t.dtype, device=t.device) for t in tensors]
+    out = list(out)
+    for t, o in zip(tensors, out):
+        if (not o.is_cuda or not o.is_contiguous() or o.shape[0] != rows_out or o.dtype != t.dtype
+                or tuple(o.shape[1:]) != tuple(t.shape[1:])):
+            raise ValueError("output tensors must match the inputs in dtype and row shape")
+    B = seq_offsets.numel() - 1
+    lib = load_library()
+    src = (ctypes.c_void_p * n)(*[t.data_ptr() for t in tensors])
+    dst = (ctypes.c_void_p * n)(*[o.data_ptr() for o in out])
+    rb = (ctypes.c_int64 * n)(*[int(np.prod(t.shape[1:], dtype=np.int64)) * t.element_size()
+                                for t in tensors])
+    rc = lib.hstu_cp_reorder(B, int(total_rows), int(cp_size), int(rank), int(bool(scatter)), n,
+                             ctypes.cast(src, ctypes.c_void_p), ctypes.cast(dst, ctypes.c_void_p),
+                             ctypes.cast(rb, ctypes.c_void_p), int(local_rows), _ptr(seq_offsets),
+                             _stream(stream))
+    if rc != 0:
+        raise HstuError(rc, "hstu_cp_reorder")
+    return out

@@ -416,6 +416,41 @@ int hstu_jagged_attn_cp_partial(const hstu_attn_params* params, const hstu_cp_de
   return HSTU_OK;
 }
 
+int hstu_cp_reorder(int32_t batch, int64_t total_rows, int32_t cp_size, int32_t rank, int32_t scatter,
+                    int32_t num_tensors, const void* const* src, void* const* dst,
+                    const int64_t* row_bytes, int64_t local_rows, const int32_t* seq_offsets,
+                    void* hip_stream) {
+  if (batch < 0 || total_rows < 0 || total_rows >= (1ll << 31) || local_rows < 0)
+    return HSTU_ERR_BAD_SHAPE;
+  if (cp_size < 1 || rank < 0 || rank >= cp_size || (int64_t)cp_size * 2 >= (1ll << 31))
+    return HSTU_ERR_BAD_CP;
+  if (num_tensors < 1 || num_tensors > 4) return HSTU_ERR_BAD_SHAPE;
+  if (!src || !dst || !row_bytes) return HSTU_ERR_NULL_PTR;
+  ReorderArgs ra = {};
+  for (int t = 0; t < num_tensors; ++t) {
+    if (!src[t] || !dst[t]) return HSTU_ERR_NULL_PTR;
+    if (row_bytes[t] < 16 || row_bytes[t] % 16 != 0) return HSTU_ERR_BAD_SHAPE;
+    if (!aligned16(src[t]) || !aligned16(dst[t])) return HSTU_ERR_MISALIGNED;
+    ra.src[t] = (const char*)src[t];
+    ra.dst[t] = (char*)dst[t];
+    ra.row_bytes[t] = row_bytes[t];
+  }
+  if (batch == 0 || total_rows == 0 || local_rows == 0) return HSTU_OK;
+  if (!seq_offsets) return HSTU_ERR_NULL_PTR;
+  const int64_t lr = clamp_rows(local_rows, total_rows);
+  // at most two segments per sequence, each with one ragged last tile
+  const int64_t max_tiles = max_items_bound(lr, batch, 2, 64);
+  if (max_tiles >= (1ll << 31)) return HSTU_ERR_BAD_SHAPE;
+  ra.off = seq_offsets;
+  ra.count = num_tensors;
+  ra.scatter = scatter ? 1 : 0;
+  ra.batch = batch; ra.total_rows = (int32_t)total_rows; ra.local_rows = (int32_t)lr;
+  ra.cp = cp_size; ra.rank = rank;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  TimedLaunch timed(5, stream);
+  return launch_reorder(ra, max_tiles, stream) == hipSuccess ? HSTU_OK : HSTU_ERR_HIP;
+}
+
 int hstu_debug_timing_begin(int max_records) {
   Timing& t = g_timing;
   if (t.on || max_records < 1 || max_records > (1 << 16)) return HSTU_ERR_BAD_SHAPE;

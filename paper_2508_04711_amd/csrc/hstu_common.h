@@ -127,6 +127,20 @@ int tile_rows_f32(int pass);
 hipError_t launch_transpose_bf16(const void* src, void* dst, const Plan& plan, int num_heads, int d,
                                  hipStream_t stream);
 
+// Load-balance reorder (section 2.3): copies the 64-row tiles of a rank's local layout from / to
+// their place in the global layout, for `count` tensors whose rows are row_bytes[i] long.
+struct ReorderArgs {
+  const char* src[4];
+  char* dst[4];
+  int64_t row_bytes[4];
+  const int32_t* off;
+  int32_t count;
+  int32_t scatter;  // 0: dst is local, src global (gather); 1: dst is global, src local
+  int32_t batch, total_rows, local_rows, cp, rank;
+};
+// max_tiles: an upper bound on the 64-row tiles of the local layout (the grid's first dimension).
+hipError_t launch_reorder(const ReorderArgs& a, int64_t max_tiles, hipStream_t stream);
+
 hipError_t launch_fwd_bf16(const AttnArgs& a, int d_qk, int d_v, hipStream_t stream);
 hipError_t launch_dkdv_bf16(const AttnArgs& a, int d_qk, int d_v, hipStream_t stream);
 hipError_t launch_dq_bf16(const AttnArgs& a, int d_qk, int d_v, hipStream_t stream);

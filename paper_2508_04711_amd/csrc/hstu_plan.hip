@@ -263,6 +263,97 @@ __device__ __forceinline__ void plan_body(const PlanArgs& a) {
 
 }  // namespace
 
+namespace {
+
+constexpr int REORDER_THREADS = 256;
+
+// Load-balance reorder (section 2.3).  One workgroup per (64-row tile of the rank's local layout,
+// tensor).  The workgroup finds its tile from the offsets by itself: every thread sums the tile
+// and row counts of a contiguous share of the sequences, a scan over the 256 partial sums tells
+// which thread's share holds tile blockIdx.x, and that thread walks its share to the sequence.
+// No table is built beforehand, so the call is this one launch and needs no workspace.  Inside
+// a tile the rows are consecutive in both layouts: the tile is one contiguous span on either
+// side and the copy runs at full memory width, 16 bytes per lane, four loads in flight.
+__global__ void __launch_bounds__(REORDER_THREADS) reorder_kernel(ReorderArgs a) {
+  __shared__ int wave_tiles[REORDER_THREADS / 64], wave_rows[REORDER_THREADS / 64];
+  __shared__ int found[3];  // first local row, rows, first global row of this workgroup's tile
+  const int i = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (tid == 0) found[1] = 0;
+  const int per = (a.batch + REORDER_THREADS - 1) / REORDER_THREADS;
+  const int b_lo = tid * per < a.batch ? tid * per : a.batch;
+  const int b_hi = b_lo + per < a.batch ? b_lo + per : a.batch;
+  int tiles = 0, rows = 0;
+  for (int b = b_lo; b < b_hi; ++b) {
+    int s, e;
+    seq_range(a.off, b, a.total_rows, s, e);
+    const Side sd = make_side(e - s, a.cp, a.rank);
+    tiles += tiles_of(sd, STILE);
+    rows += sd.rows;
+  }
+  int xt = tiles, xr = rows;  // inclusive prefixes across the block
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const int yt = __shfl_up(xt, d, 64), yr = __shfl_up(xr, d, 64);
+    if (lane >= d) { xt += yt; xr += yr; }
+  }
+  if (lane == 63) { wave_tiles[wave] = xt; wave_rows[wave] = xr; }
+  __syncthreads();
+  for (int w = 0; w < wave; ++w) { xt += wave_tiles[w]; xr += wave_rows[w]; }
+  int tile0 = xt - tiles, row0 = xr - rows;  // first tile and first local row of this thread's share
+  if (i >= tile0 && i < xt) {
+    for (int b = b_lo; b < b_hi; ++b) {
+      int s, e;
+      seq_range(a.off, b, a.total_rows, s, e);
+      const Side sd = make_side(e - s, a.cp, a.rank);
+      const int nt = tiles_of(sd, STILE);
+      if (i < tile0 + nt) {
+        int t = i - tile0;
+        const int nt0 = (sd.len[0] + STILE - 1) / STILE;
+        const int g = t < nt0 ? 0 : 1;
+        if (g) t -= nt0;
+        const int local = row0 + (g ? sd.len[0] : 0) + t * STILE;
+        int n = sd.len[g] - t * STILE;
+        if (n > STILE) n = STILE;
+        found[0] = local;
+        found[1] = clampi((long long)a.local_rows - local, 0, n);
+        found[2] = s + sd.pos[g] + t * STILE;
+        break;
+      }
+      tile0 += nt; row0 += sd.rows;
+    }
+  }
+  __syncthreads();
+  const int64_t local_row = found[0], nrows = found[1], global_row = found[2];
+  if (nrows == 0) return;  // beyond the last tile, or beyond the declared local rows
+  const int64_t rb = a.row_bytes[blockIdx.y];
+  const char* src = a.src[blockIdx.y] + (a.scatter ? local_row : global_row) * rb;
+  char* dst = a.dst[blockIdx.y] + (a.scatter ? global_row : local_row) * rb;
+  const int64_t chunks = nrows * rb / 16;
+  typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
+  constexpr int N = REORDER_THREADS;
+  int64_t c = tid;
+  for (; c + 3 * N < chunks; c += 4 * N) {
+    const u32x4 v0 = *(const u32x4*)(src + c * 16);
+    const u32x4 v1 = *(const u32x4*)(src + (c + N) * 16);
+    const u32x4 v2 = *(const u32x4*)(src + (c + 2 * N) * 16);
+    const u32x4 v3 = *(const u32x4*)(src + (c + 3 * N) * 16);
+    *(u32x4*)(dst + c * 16) = v0;
+    *(u32x4*)(dst + (c + N) * 16) = v1;
+    *(u32x4*)(dst + (c + 2 * N) * 16) = v2;
+    *(u32x4*)(dst + (c + 3 * N) * 16) = v3;
+  }
+  for (; c < chunks; c += N) *(u32x4*)(dst + c * 16) = *(const u32x4*)(src + c * 16);
+}
+
+}  // namespace
+
+hipError_t launch_reorder(const ReorderArgs& a, int64_t max_tiles, hipStream_t stream) {
+  if (a.count < 1 || a.count > 4 || max_tiles < 1 || max_tiles >= (1ll << 31)) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(reorder_kernel, dim3((unsigned)max_tiles, (unsigned)a.count),
+                     dim3(REORDER_THREADS), 0, stream, a);
+  return hipGetLastError();
+}
+
 hipError_t launch_plans(const PlanArgs* a, int count, hipStream_t stream) {
   static_assert(NBINS == 2 * PLAN_THREADS, "pass 3 handles two bins per thread");
   if (count < 1 || count > 2) return hipErrorInvalidValue;

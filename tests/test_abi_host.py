@@ -85,6 +85,26 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     assert rc == -5
 
 
+def test_reorder_rejects_bad_arguments_on_the_host(lib):
+    fake = 0x1000
+    def call(batch=2, total=100, cp=2, rank=0, n=1, src=(fake,), dst=(fake,), rb=(256,), local=50,
+             off=ctypes.cast(fake, ctypes.POINTER(ctypes.c_int32))):
+        s = (ctypes.c_void_p * 4)(*src)
+        d = (ctypes.c_void_p * 4)(*dst)
+        r = (ctypes.c_int64 * 4)(*rb)
+        return lib.hstu_cp_reorder(batch, total, cp, rank, 0, n, ctypes.cast(s, ctypes.c_void_p),
+                                   ctypes.cast(d, ctypes.c_void_p), ctypes.cast(r, ctypes.c_void_p),
+                                   local, off, None)
+    assert call(cp=0) == -5 and call(rank=2) == -5 and call(rank=-1) == -5
+    assert call(total=-1) == -2 and call(total=1 << 31) == -2 and call(local=-1) == -2
+    assert call(n=0) == -2 and call(n=5) == -2
+    assert call(rb=(24,)) == -2 and call(rb=(0,)) == -2
+    assert call(src=(None,)) == -1 and call(dst=(None,)) == -1
+    assert call(src=(0x1008,)) == -7
+    assert call(off=None) == -1
+    assert call(total=0, off=None) == 0 and call(local=0, off=None) == 0      # nothing to move
+
+
 def test_workspace_query(lib):
     from paper_2508_04711_amd import binding
     p = _params(binding, batch=16, total_rows=37117, d_qk=128, d_v=128)

@@ -1,0 +1,138 @@
+"""Load-balance memory reorder on the GPU (section 2.3) against the oracle's row permutation.
+
+The reorder is a pure row copy, so the bar is bit-exactness: the gathered tensor is the global
+tensor indexed by the oracle's list of the rank's global rows; the scatter writes exactly those
+rows of the global tensor and leaves every other row as it was.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads
+
+pytestmark = pytest.mark.gpu
+
+LENGTH_SETS = {
+    "mixed": [160, 5, 233, 1, 0, 384, 77],
+    "shorter_than_chunks": [3, 1, 0, 2, 7, 15],
+    "one_long": [4099],
+    "ragged_tiles": [64, 65, 127, 128, 129, 1023, 1025],
+}
+
+
+def _bytes(t):
+    return t.contiguous().view(torch.uint8).cpu().numpy()
+
+
+def _tensors(T, seed):
+    g = torch.Generator().manual_seed(seed)
+    a = torch.randn((T, 2, 64), generator=g).to(torch.bfloat16)          # 256 B rows
+    b = torch.randn((T, 3, 32), generator=g)                             # fp32, 384 B rows
+    c = torch.randint(0, 255, (T, 16), generator=g, dtype=torch.uint8)   # 16 B rows: the minimum
+    d = torch.randn((T, 4, 128), generator=g).to(torch.bfloat16)         # 1 KiB rows
+    return [a, b, c, d]
+
+
+@pytest.mark.parametrize("cp", [1, 2, 4, 8])
+@pytest.mark.parametrize("name", sorted(LENGTH_SETS))
+def test_gather_and_scatter_are_the_oracle_permutation(name, cp):
+    import paper_2508_04711_amd as lib
+    lengths = LENGTH_SETS[name]
+    off_np = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int32)
+    T = int(off_np[-1])
+    off = torch.from_numpy(off_np).cuda()
+    host = _tensors(T, seed=cp)
+    dev = [t.cuda() for t in host]
+    seen = np.zeros(T, dtype=np.int64)
+    back = [torch.full_like(t, 0).view(torch.uint8).fill_(0xA5).view(t.dtype).reshape(t.shape) for t in dev]
+    for r in range(cp):
+        rows = oracle.cp_global_rows(off_np, cp, r)
+        print("reorder", name, cp, r, len(rows), flush=True)
+        seen[rows] += 1
+        local = lib.hstu_cp_reorder(dev, off, T, cp, r, len(rows))
+        for t, l in zip(host, local):
+            assert l.shape[0] == len(rows)
+            np.testing.assert_array_equal(_bytes(l), _bytes(t[torch.from_numpy(rows)]))
+        # scatter into a sentinel-filled global tensor: only this rank's rows change
+        before = [_bytes(b).copy() for b in back]
+        lib.hstu_cp_reorder(local, off, T, cp, r, len(rows), scatter=True, out=back)
+        mask = np.zeros(T, dtype=bool)
+        mask[rows] = True
+        for t, b, b0 in zip(host, back, before):
+            got = _bytes(b).reshape(T, -1)
+            np.testing.assert_array_equal(got[mask], _bytes(t).reshape(T, -1)[mask])
+            np.testing.assert_array_equal(got[~mask], b0.reshape(T, -1)[~mask])
+    # the ranks partition the rows, so after every rank's scatter the round trip is the identity
+    assert np.all(seen == 1)
+    for t, b in zip(host, back):
+        np.testing.assert_array_equal(_bytes(b), _bytes(t))
+
+
+def test_cp1_is_the_identity():
+    import paper_2508_04711_amd as lib
+    w = workloads.config(1)
+    off_np = w.seq_offsets()
+    q = workloads.values(w)["q"].cuda()
+    (loc,) = lib.hstu_cp_reorder([q], torch.from_numpy(off_np).cuda(), w.total_rows, 1, 0, w.total_rows)
+    assert torch.equal(loc, q)
+
+
+def test_full_size_context_parallel_workload():
+    """The context-parallel benchmark shape: q, k, v, d_o of every rank in one call each."""
+    import paper_2508_04711_amd as lib
+    w = workloads.config(4)
+    off_np = w.seq_offsets()
+    off = torch.from_numpy(off_np).cuda()
+    T = w.total_rows
+    vals = {k: v.cuda() for k, v in workloads.values(w).items()}
+    names = ["q", "k", "v", "d_o"]
+    back = [torch.zeros_like(vals[n]) for n in names]
+    for r in range(w.cp_size):
+        rows = torch.from_numpy(oracle.cp_global_rows(off_np, w.cp_size, r)).cuda()
+        print("reorder cfg4 rank", r, len(rows), flush=True)
+        local = lib.hstu_cp_reorder([vals[n] for n in names], off, T, w.cp_size, r, len(rows))
+        for n, l in zip(names, local):
+            assert torch.equal(l, vals[n][rows])
+        lib.hstu_cp_reorder(local, off, T, w.cp_size, r, len(rows), scatter=True, out=back)
+    for n, b in zip(names, back):
+        assert torch.equal(b, vals[n])
+
+
+def test_declared_local_rows_bound_what_is_written():
+    """A local tensor declared shorter than the rank's share is filled up to its end only."""
+    import paper_2508_04711_amd as lib
+    off_np = np.array([0, 200, 500], dtype=np.int32)
+    off = torch.from_numpy(off_np).cuda()
+    T = 500
+    src = torch.randn((T, 1, 64), device="cuda").to(torch.bfloat16)
+    rows_full = oracle.cp_global_rows(off_np, 2, 0)     # 100 rows of the first sequence, 150 of the second
+    local_decl = 130                                    # ends inside the second sequence's first chunk
+    dst = torch.full((local_decl + 64, 1, 64), 7.0, device="cuda", dtype=torch.bfloat16)
+    lib.hstu_cp_reorder([src], off, T, 2, 0, local_decl, out=[dst[:local_decl]])
+    torch.cuda.synchronize()
+    assert torch.all(dst[local_decl:] == 7.0)
+    assert torch.equal(dst[:local_decl], src[torch.from_numpy(rows_full[:local_decl]).cuda()])
+    # and the scatter reads no further than that
+    back = torch.full((T, 1, 64), 3.0, device="cuda", dtype=torch.bfloat16)
+    lib.hstu_cp_reorder([dst[:local_decl]], off, T, 2, 0, local_decl, scatter=True, out=[back])
+    mask = torch.zeros(T, dtype=torch.bool)
+    mask[torch.from_numpy(rows_full[:local_decl])] = True
+    assert torch.equal(back.cpu()[mask], src.cpu()[mask])
+    assert torch.all(back.cpu()[~mask] == 3.0)
+
+
+def test_argument_errors():
+    import paper_2508_04711_amd as lib
+    off = torch.tensor([0, 64], dtype=torch.int32, device="cuda")
+    good = torch.zeros((64, 8), dtype=torch.bfloat16, device="cuda")       # 16-byte rows
+    with pytest.raises(lib.HstuError) as e:
+        lib.hstu_cp_reorder([torch.zeros((64, 6), dtype=torch.bfloat16, device="cuda")], off, 64, 2, 0, 32)
+    assert e.value.status == -2
+    with pytest.raises(lib.HstuError) as e:
+        lib.hstu_cp_reorder([good], off, 64, 2, 2, 32)
+    assert e.value.status == -5
+    with pytest.raises(ValueError):
+        lib.hstu_cp_reorder([good] * 5, off, 64, 2, 0, 32)
+    with pytest.raises(ValueError):
+        lib.hstu_cp_reorder([good[:32]], off, 64, 2, 0, 32, scatter=True)
