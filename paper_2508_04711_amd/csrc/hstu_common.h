@@ -137,6 +137,7 @@ struct ReorderArgs {
   int32_t count;
   int32_t scatter;  // 0: dst is local, src global (gather); 1: dst is global, src local
   int32_t batch, total_rows, local_rows, cp, rank;
+  int32_t split;    // workgroups per 64-row tile (a divisor of 64)
 };
 // max_tiles: an upper bound on the 64-row tiles of the local layout (the grid's first dimension).
 hipError_t launch_reorder(const ReorderArgs& a, int64_t max_tiles, hipStream_t stream);
