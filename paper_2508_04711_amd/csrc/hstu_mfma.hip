@@ -3,8 +3,8 @@
 // Paper, section 2.1: O = Mask(SiLU(alpha * Q K^T)) V (bias absent), here divided by max_len.
 // All three kernels share one shape.  A workgroup takes one schedule item for one head: a
 // tile of "owner" rows, 32 per wavefront, whose data a wave keeps in registers as MFMA B
-// operands, and streams the other side's rows through LDS in tiles of 64, double buffered,
-// as MFMA A operands.  Scores are produced transposed with respect to the owner rows so that
+// operands, and streams the other side's rows through LDS in tiles of 64 (two or three tile
+// buffers, filled by asynchronous copies one or two tiles ahead) as MFMA A operands.  Scores are produced transposed with respect to the owner rows so that
 // the accumulator registers of the first product are, lane for lane, the B (or A) operand of
 // the second one; nothing but the streamed tiles ever goes through LDS.
 //
@@ -364,100 +364,69 @@ __device__ __forceinline__ bool fetch_item(const Plan& plan, int slot, Item& it)
 //   O^T += V^T P^T (A = V tile transposed read, B = P^T registers)
 // =============================================================================================
 
-// One 32-key block of a tile on the diagonal: blocks wholly above the wave's rows are skipped,
-// the block the diagonal crosses is masked element by element.
-template <int DQK, int DV>
-__device__ __forceinline__ void fwd_block_masked(const char* kt, const char* vt, int blk,
-                                                 const RowAddr<DQK>& ra, const TrAddr<DV>& ca,
-                                                 const bf16x8 (&qreg)[DQK / 16],
-                                                 f32x16 (&oacc)[DV / 32], float c1, int k_lo,
-                                                 int q_lo, bool mask, int n, int hh) {
-  f32x16 s;
-#pragma unroll
-  for (int r = 0; r < 16; ++r) s[r] = 0.f;
-#pragma unroll
-  for (int ks = 0; ks < DQK / 16; ++ks) s = mfma(ra.read(kt, blk, ks), qreg[ks], s);
-  float p[16];
-#pragma unroll
-  for (int r = 0; r < 16; ++r) p[r] = s[r] * sigmoid_scaled(s[r], c1);
-  if (mask) {
-    const int qpos = q_lo + n;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int kpos = k_lo + 8 * (r >> 2) + 4 * hh + (r & 3);
-      p[r] = kpos <= qpos ? p[r] : 0.f;
-    }
-  }
-  const bf16x8 pb0 = pack8(p), pb1 = pack8(p + 8);
-#pragma unroll
-  for (int dvb = 0; dvb < DV / 32; ++dvb) {
-    oacc[dvb] = mfma(ca.read(vt, blk * 2, dvb), pb0, oacc[dvb]);
-    oacc[dvb] = mfma(ca.read(vt, blk * 2 + 1, dvb), pb1, oacc[dvb]);
-  }
-}
-
-// A whole 64-key tile with nothing to mask (every key precedes every query row of the wave, or
-// the problem is not causal; rows beyond the segment are zero in LDS and contribute nothing).
-// Operands are fetched from LDS a whole product ahead, and the SiLU of one block is interleaved
-// with the matrix instructions of its neighbours: S(1) runs while P(0) is formed, P(0) V runs
-// while P(1) is formed.
-template <int DQK, int DV>
-__device__ __forceinline__ void fwd_tile_full(const char* kt, const char* vt,
-                                              const RowAddr<DQK>& ra, const TrAddr<DV>& ca,
-                                              const bf16x8 (&qreg)[DQK / 16],
-                                              f32x16 (&oacc)[DV / 32], float c1) {
-  constexpr int KS = DQK / 16, NPV = DV / 16;
-  constexpr int EQK = 16 / KS, EPV = 16 / NPV;  // SiLU elements per interleaved matrix instruction
+// The stream of keys is processed in blocks of 32, software-pipelined across blocks and tiles.
+// Step i issues, interleaved and independent of each other,
+//   the matrix instructions of S(i+1) = K(i+1) Q^T              (DQK/16 instructions),
+//   the matrix instructions of O^T += V(i-1)^T P(i-1)^T          (DV/16 instructions),
+//   the SiLU that turns S(i) into P(i)                           (vector instructions),
+// so that every wave's instruction stream is an even mix of matrix and vector work: two waves
+// of a SIMD then keep both pipes busy whatever their relative phase (a matrix instruction
+// holds its own wave's issue for a while, the other wave's vector instructions fill that time).
+// Two S accumulator sets and two P operand sets alternate by block parity.
+//
+// Causal mask: key r (accumulator element) of block i is visible to the lane's query iff
+// 8*(r/4) + 4*hh + r%4 <= rel, rel = query position - block position; applied to the finished
+// P under a wave-uniform branch, so the matrix instructions follow one path whether or not a
+// block is masked.  A block none of whose keys is visible comes out as zeros.
+template <int DQK, int DV, bool PV>
+__device__ __forceinline__ void fwd_step(const char* kn, int bn, const char* vp, int bp,
+                                         const RowAddr<DQK>& ra, const TrAddr<DV>& ca,
+                                         const bf16x8 (&qreg)[DQK / 16], const f32x16& s_in,
+                                         f32x16& s_out, const bf16x8 (&p_prev)[2],
+                                         bf16x8 (&p_cur)[2], f32x16 (&oacc)[DV / 32], float c1,
+                                         bool mask, int rel, int hh) {
+  constexpr int KS = DQK / 16, NPV = DV / 16, NSL = KS > NPV ? KS : NPV;
+  constexpr int AHEAD = 3;  // operand reads in flight ahead of their use
   bf16x8 ka[KS], va[NPV];
-  f32x16 s0, s1;
+  auto fence = [] { __builtin_amdgcn_sched_barrier(0); };
 #pragma unroll
-  for (int r = 0; r < 16; ++r) { s0[r] = 0.f; s1[r] = 0.f; }
-
+  for (int r = 0; r < 16; ++r) s_out[r] = 0.f;
 #pragma unroll
-  for (int ks = 0; ks < KS; ++ks) ka[ks] = ra.read(kt, 0, ks);
-  // Favour the wave that is computing over the one on the same SIMD that is issuing copies or
-  // sitting at the barrier.
-  __builtin_amdgcn_s_setprio(1);
-#pragma unroll
-  for (int ks = 0; ks < KS; ++ks) s0 = mfma(ka[ks], qreg[ks], s0);
-
-#pragma unroll
-  for (int ks = 0; ks < KS; ++ks) ka[ks] = ra.read(kt, 1, ks);
-#pragma unroll
-  for (int i = 0; i < NPV; ++i) va[i] = ca.read(vt, i & 1, i >> 1);
-
+  for (int m = 0; m < AHEAD; ++m) {
+    if (m < KS) ka[m] = ra.read(kn, bn, m);
+    if (PV && m < NPV) va[m] = ca.read(vp, bp * 2 + (m & 1), m >> 1);
+  }
+  fence();
   float p[16];
 #pragma unroll
-  for (int ks = 0; ks < KS; ++ks) {
-    s1 = mfma(ka[ks], qreg[ks], s1);
+  for (int m = 0; m < NSL; ++m) {
+    const int e0 = m * 16 / NSL, e1 = (m + 1) * 16 / NSL, em = (e0 + e1 + 1) / 2;
+    if (m < KS) s_out = mfma(ka[m], qreg[m], s_out);
+    if (m + AHEAD < KS) ka[m + AHEAD] = ra.read(kn, bn, m + AHEAD);
 #pragma unroll
-    for (int e = ks * EQK; e < (ks + 1) * EQK; ++e) p[e] = s0[e] * sigmoid_scaled(s0[e], c1);
+    for (int e = e0; e < em; ++e) p[e] = s_in[e] * sigmoid_scaled(s_in[e], c1);
+    fence();
+    if (PV && m < NPV) oacc[m >> 1] = mfma(va[m], p_prev[m & 1], oacc[m >> 1]);
+    if (PV && m + AHEAD < NPV) va[m + AHEAD] = ca.read(vp, bp * 2 + ((m + AHEAD) & 1), (m + AHEAD) >> 1);
+#pragma unroll
+    for (int e = em; e < e1; ++e) p[e] = s_in[e] * sigmoid_scaled(s_in[e], c1);
+    fence();
   }
-  bf16x8 pb0 = pack8(p), pb1 = pack8(p + 8);
-
-  bf16x8 vb[NPV];
+  if (mask) {
+    asm volatile("" ::: "memory");  // not speculable: keeps the selects off the unmasked path
 #pragma unroll
-  for (int i = 0; i < NPV; ++i) vb[i] = ca.read(vt, 2 + (i & 1), i >> 1);
-
-  float p1[16];
-#pragma unroll
-  for (int i = 0; i < NPV; ++i) {
-    oacc[i >> 1] = mfma(va[i], (i & 1) ? pb1 : pb0, oacc[i >> 1]);
-#pragma unroll
-    for (int e = i * EPV; e < (i + 1) * EPV; ++e) p1[e] = s1[e] * sigmoid_scaled(s1[e], c1);
+    for (int r = 0; r < 16; ++r) p[r] = (8 * (r >> 2) + 4 * hh + (r & 3) <= rel) ? p[r] : 0.f;
   }
-  pb0 = pack8(p1);
-  pb1 = pack8(p1 + 8);
-#pragma unroll
-  for (int i = 0; i < NPV; ++i) oacc[i >> 1] = mfma(vb[i], (i & 1) ? pb1 : pb0, oacc[i >> 1]);
-  __builtin_amdgcn_s_setprio(0);
+  p_cur[0] = pack8(p);
+  p_cur[1] = pack8(p + 8);
+  fence();
 }
 
 template <int DQK, int DV, int NW>
 __global__ void __launch_bounds__(NW * 64, 2) hstu_fwd_bf16(AttnArgs a) {
   constexpr int KB = ST * DQK * 2, VB = ST * DV * 2;
-  // NBUF tile buffers: the copy of tile j+NBUF-1 is in flight while tile j is computed.  Eight
-  // waves share three buffers (one workgroup per CU), four waves two (two workgroups per CU).
+  // NBUF buffers each for the K tiles and the transposed V tiles; copies run PD tiles ahead.
+  // Eight waves (one workgroup per CU) use three, four waves (two workgroups per CU) two.
   // One array per buffer: the compiler can then see that a copy into one buffer cannot alias
   // the operand reads from another.
   constexpr int NBUF = NW >= 8 ? 3 : 2, PD = NBUF - 1;
@@ -492,59 +461,104 @@ __global__ void __launch_bounds__(NW * 64, 2) hstu_fwd_bf16(AttnArgs a) {
     for (int r = 0; r < 16; ++r) oacc[i][r] = 0.f;
 
   const Stream st = make_stream<0>(it, a.causal);
+  const int T = st.total, NB = 2 * T;  // tiles and 32-key blocks of the stream
   const float c1 = -a.alpha * 1.4426950408889634f;
   const int q_lo = it.pos0 + wave * 32, q_hi = q_lo + 31;
 
-  auto copy_tile = [&](int j, int buf) {
-    const TileRef t = tile_ref(it, st, j);
-    tile_copy_async<DQK, NW>(kbuf(buf), kg + (int64_t)t.row * sq, sq, t.valid, wave, lane);
-    ttile_copy_async<DV, NW>(vbuf(buf), vtg + t.tcol, tcols, wave, lane);
+  // K tile t lives in K buffer t % NBUF, V tile t in V buffer t % NBUF.
+  auto copy_k = [&](int t, int buf) {
+    const TileRef r = tile_ref(it, st, t);
+    tile_copy_async<DQK, NW>(kbuf(buf), kg + (int64_t)r.row * sq, sq, r.valid, wave, lane);
   };
-  // wave-wide loads one wave issues per tile copy (the in-flight count the waits below allow)
-  constexpr int LPT = (tile_loads<DQK>() + NW - 1) / NW + (DV / 8 + NW - 1) / NW;
-
-  load_owner_wait();
-  if (st.total > 0) copy_tile(0, 0);
-  if (PD > 1 && st.total > 1) copy_tile(1, 1);
-  if (PD > 1 && st.total > 1) tile_copy_wait<LPT>(); else tile_copy_wait<0>();
-  tile_barrier();
+  auto copy_v = [&](int t, int buf) {
+    const TileRef r = tile_ref(it, st, t);
+    ttile_copy_async<DV, NW>(vbuf(buf), vtg + r.tcol, tcols, wave, lane);
+  };
+  // Position of block i (i in [0, NB)); positions grow with i.
+  auto block_pos = [&](int i) { return tile_ref(it, st, i >> 1).pos + (i & 1) * 32; };
+  // Does any key of block i precede (or equal) a query of this wave?  Once false it stays false.
+  auto block_on = [&](int i) { return wave_on && i < NB && (!a.causal || block_pos(i) <= q_hi); };
 
   RowAddr<DQK> ra;
   TrAddr<DV> ca;
   ra.init(n, hh);
   ca.init(n, hh);
+  // wave-wide loads one wave issues per iteration (the in-flight count the waits below allow)
+  constexpr int LPT = (tile_loads<DQK>() + NW - 1) / NW + (DV / 8 + NW - 1) / NW;
 
-  // One tile of the stream; BUF is a compile-time buffer index so that every LDS address is a
-  // per-lane register plus an immediate.
-  auto step = [&](int j, auto buf_tag) {
-    constexpr int BUF = decltype(buf_tag)::value;
-    const TileRef tj = tile_ref(it, st, j);
-    // buffer (BUF + PD) % NBUF held tile j-1: every wave finished it before the barrier that ended j-1
-    const bool more = j + PD < st.total;
-    if (more) copy_tile(j + PD, (BUF + PD) % NBUF);
-    const char* kt = kbuf(BUF);
-    const char* vt = vbuf(BUF);
-    if (wave_on) {
-      if (!a.causal || tj.pos + ST - 1 <= q_lo) {
-        fwd_tile_full<DQK, DV>(kt, vt, ra, ca, qreg, oacc, c1);
-      } else {
+  load_owner_wait();
+  // Iteration j of the main loop reads K tile j+1 and V tile j; K(0) is read before it.
+  if (T > 0) { copy_k(0, 0); copy_v(0, 0); }
+  if (T > 1) copy_k(1, 1);
+  if (PD > 1 && T > 1) copy_v(1, 1);
+  if (PD > 1 && T > 2) copy_k(2, 2);
+  tile_copy_wait<0>();
+  tile_barrier();
+
+  if (T > 0) {
+    f32x16 sacc[2];   // S of the blocks of even / odd index
+    bf16x8 pb[2][2];  // P (two 16-key halves) of the blocks of even / odd index
 #pragma unroll
-        for (int blk = 0; blk < ST / 32; ++blk) {
-          const int k_lo = tj.pos + blk * 32;
-          if (blk * 32 >= tj.valid || k_lo > q_hi) continue;
-          fwd_block_masked<DQK, DV>(kt, vt, blk, ra, ca, qreg, oacc, c1, k_lo, q_lo,
-                                    k_lo + 31 > q_lo, n, hh);
-        }
+    for (int x = 0; x < 2; ++x) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sacc[x][r] = 0.f;
+#pragma unroll
+      for (int y = 0; y < 2; ++y)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) pb[x][y][e] = (__bf16)0.f;
+    }
+    auto mask_of = [&](int i) { return a.causal && block_pos(i) + 31 > q_lo; };
+    auto rel_of = [&](int i) { return q_lo + n - block_pos(i); };
+
+    // S of block 0 on its own, then step 0 (nothing to multiply by V yet)
+    if (block_on(0)) {
+#pragma unroll
+      for (int ks = 0; ks < DQK / 16; ++ks) sacc[0] = mfma(ra.read(kbuf(0), 0, ks), qreg[ks], sacc[0]);
+      fwd_step<DQK, DV, false>(kbuf(0), 1, vbuf(0), 0, ra, ca, qreg, sacc[0], sacc[1], pb[1], pb[0], oacc,
+                               c1, mask_of(0), rel_of(0), hh);
+    }
+    tile_barrier();  // iteration 0 copies over K tile 0, which the lines above read
+
+    // Iteration j: steps 2j+1 and 2j+2.  Step i runs while block i-1 is visible: it finishes
+    // P(i-1) V(i-1); whatever it computes for invisible blocks is masked to zero or unused.
+    auto iter = [&](int j, auto buf_tag) {
+      constexpr int B0 = decltype(buf_tag)::value, B1 = (B0 + 1) % NBUF;
+      // tiles j-1 (V) and j (K) were left by every wave before the last barrier
+      const bool both = j + 1 + PD < T;
+      if (both) copy_k(j + 1 + PD, (B0 + 1 + PD) % NBUF);
+      if (j + PD < T) copy_v(j + PD, (B0 + PD) % NBUF);
+      {
+        const int i = 2 * j + 1;  // S of (tile j+1, block 0), P V of (tile j, block 0)
+        if (block_on(i - 1))
+          fwd_step<DQK, DV, true>(kbuf(B1), 0, vbuf(B0), 0, ra, ca, qreg, sacc[1], sacc[0], pb[0], pb[1],
+                                  oacc, c1, mask_of(i), rel_of(i), hh);
+      }
+      if (j + 1 < T) {
+        const int i = 2 * j + 2;  // S of (tile j+1, block 1), P V of (tile j, block 1)
+        if (block_on(i - 1))
+          fwd_step<DQK, DV, true>(kbuf(B1), 1, vbuf(B0), 1, ra, ca, qreg, sacc[0], sacc[1], pb[1], pb[0],
+                                  oacc, c1, mask_of(i), rel_of(i), hh);
+      }
+      // what the next iteration reads must have landed; with copies two tiles ahead the ones
+      // just issued may stay in flight
+      if (PD > 1 && both) tile_copy_wait<LPT>(); else tile_copy_wait<0>();
+      tile_barrier();
+    };
+    for (int j = 0; j < T; j += NBUF) {
+      iter(j, std::integral_constant<int, 0>{});
+      if (j + 1 < T) iter(j + 1, std::integral_constant<int, 1>{});
+      if (NBUF > 2 && j + 2 < T) iter(j + 2, std::integral_constant<int, (NBUF > 2 ? 2 : 0)>{});
+    }
+
+    // P V of the last block (tile T-1, block 1) on its own
+    if (block_on(NB - 1)) {
+      const char* vt = vbuf((T - 1) % NBUF);
+#pragma unroll
+      for (int dvb = 0; dvb < DV / 32; ++dvb) {
+        oacc[dvb] = mfma(ca.read(vt, 2, dvb), pb[1][0], oacc[dvb]);
+        oacc[dvb] = mfma(ca.read(vt, 3, dvb), pb[1][1], oacc[dvb]);
       }
     }
-    // tile j+1 must have landed; with three buffers the copy just issued may stay in flight
-    if (PD > 1 && more) tile_copy_wait<LPT>(); else tile_copy_wait<0>();
-    tile_barrier();
-  };
-  for (int j = 0; j < st.total; j += NBUF) {
-    step(j, std::integral_constant<int, 0>{});
-    if (j + 1 < st.total) step(j + 1, std::integral_constant<int, 1>{});
-    if (NBUF > 2 && j + 2 < st.total) step(j + 2, std::integral_constant<int, (NBUF > 2 ? 2 : 0)>{});
   }
 
   // O^T accumulators: lane holds query row n, elements dvb*32 + 8*(r/4) + 4*hh + r%4.
@@ -569,144 +583,94 @@ __device__ __forceinline__ void bwd_elem(float s, float dp, float c1, float alph
   ds = dp * (sg + alpha * p * (1.0f - sg));
 }
 
-// One 32-query block of a tile the diagonal touches.
-template <int DQK, int DV>
-__device__ __forceinline__ void dkdv_block_masked(const char* qt, const char* gt, int blk,
-                                                  const RowAddr<DQK>& raq, const RowAddr<DV>& rag,
-                                                  const ColAddr<DQK>& caq, const ColAddr<DV>& cag,
-                                                  const bf16x8 (&kreg)[DQK / 16],
-                                                  const bf16x8 (&vreg)[DV / 16],
-                                                  f32x16 (&dkacc)[DQK / 32], f32x16 (&dvacc)[DV / 32],
-                                                  float c1, float alpha, int q_lo, int k_lo, bool mask,
-                                                  int n, int hh) {
-  f32x16 s, dp;
+// The stream of query rows is processed in blocks of 32 rows, software-pipelined across blocks
+// and across tiles.  Step i issues, interleaved,
+//   the matrix instructions of the scores of block i+1       (S, dP: KS + VS instructions),
+//   the matrix instructions of the contraction of block i-1  (dV, dK: VS + KS instructions),
+//   the elementwise work that turns S(i), dP(i) into P(i), dS(i) (vector instructions),
+// which are independent of each other, so the matrix pipe and the vector pipe are both busy for
+// the whole step.  (With one wave per SIMD nothing else overlaps them: a tile-at-a-time order has
+// the first and the last quarter of every tile without vector work and the middle half bound by
+// it.)  Two accumulator sets for S/dP and two operand sets for P/dS alternate by block parity.
+//
+// Causal mask of a block the diagonal touches: query row r (accumulator element) of the block is
+// visible to the lane's key iff rel <= 8*(r/4) + 4*hh + r%4, rel = key position - block position.
+// It is applied to the finished elementwise results under a wave-uniform branch, so the matrix
+// instructions and their accumulators follow one path whether or not a block is masked; a block
+// no row of which is visible comes out as zeros and contributes nothing.
+template <int DQK, int DV, bool CONTR>
+__device__ __forceinline__ void dkdv_step(const char* qn, const char* gn, int bn,
+                                          const char* qp, const char* gp, int bp,
+                                          const RowAddr<DQK>& raq, const RowAddr<DV>& rag,
+                                          const ColAddr<DQK>& caq, const ColAddr<DV>& cag,
+                                          const bf16x8 (&kreg)[DQK / 16],
+                                          const bf16x8 (&vreg)[DV / 16],
+                                          const f32x16& s_in, const f32x16& d_in,
+                                          f32x16& s_out, f32x16& d_out,
+                                          const bf16x8 (&pd_prev)[4], bf16x8 (&pd_cur)[4],
+                                          f32x16 (&dkacc)[DQK / 32], f32x16 (&dvacc)[DV / 32],
+                                          float c1, float alpha, bool mask, int rel, int hh) {
+  constexpr int KS = DQK / 16, VS = DV / 16, NS = KS + VS;
+  constexpr int AHEAD = NS < 4 ? NS : 4;  // operand reads in flight ahead of their use
+  constexpr int GRP = 4;                  // slots between scheduling fences
+  bf16x8 op[NS];  // row-wise operands of block i+1: Q rows, then dO rows
+  bf16x8 tp[NS];  // transposed operands of block i-1: dO^T, then Q^T
+  auto read_rows = [&](int m) { return m < KS ? raq.read(qn, bn, m) : rag.read(gn, bn, m - KS); };
+  auto read_cols = [&](int m) {
+    return m < VS ? cag.read(gp, bp * 2 + (m & 1), m >> 1)
+                  : caq.read(qp, bp * 2 + ((m - VS) & 1), (m - VS) >> 1);
+  };
+  auto fence = [] { __builtin_amdgcn_sched_barrier(0); };
 #pragma unroll
-  for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
+  for (int r = 0; r < 16; ++r) { s_out[r] = 0.f; d_out[r] = 0.f; }
 #pragma unroll
-  for (int ks = 0; ks < DQK / 16; ++ks) s = mfma(raq.read(qt, blk, ks), kreg[ks], s);
-#pragma unroll
-  for (int ks = 0; ks < DV / 16; ++ks) dp = mfma(rag.read(gt, blk, ks), vreg[ks], dp);
+  for (int m = 0; m < AHEAD; ++m) {
+    op[m] = read_rows(m);
+    if (CONTR) tp[m] = read_cols(m);
+  }
+  fence();
   float p[16], ds[16];
 #pragma unroll
-  for (int r = 0; r < 16; ++r) bwd_elem(s[r], dp[r], c1, alpha, p[r], ds[r]);
+  for (int m = 0; m < NS; ++m) {
+    if (m < KS) s_out = mfma(op[m], kreg[m], s_out);
+    else d_out = mfma(op[m], vreg[m - KS], d_out);
+    if (CONTR) {
+      if (m < VS) dvacc[m >> 1] = mfma(pd_prev[m & 1], tp[m], dvacc[m >> 1]);
+      else dkacc[(m - VS) >> 1] = mfma(pd_prev[2 + ((m - VS) & 1)], tp[m], dkacc[(m - VS) >> 1]);
+    }
+    if (m + AHEAD < NS) {
+      op[m + AHEAD] = read_rows(m + AHEAD);
+      if (CONTR) tp[m + AHEAD] = read_cols(m + AHEAD);
+    }
+#pragma unroll
+    for (int e = m * 16 / NS; e < (m + 1) * 16 / NS; ++e) bwd_elem(s_in[e], d_in[e], c1, alpha, p[e], ds[e]);
+    if (m % GRP == GRP - 1) fence();
+  }
   if (mask) {
-    const int kpos = k_lo + n;
+    asm volatile("" ::: "memory");  // not speculable: keeps the selects off the unmasked path
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-      const int qpos = q_lo + 8 * (r >> 2) + 4 * hh + (r & 3);
-      const bool vis = kpos <= qpos;
+      const bool vis = rel <= 8 * (r >> 2) + 4 * hh + (r & 3);
       p[r] = vis ? p[r] : 0.f;
       ds[r] = vis ? ds[r] : 0.f;
     }
   }
-  const bf16x8 pb0 = pack8(p), pb1 = pack8(p + 8);
-  const bf16x8 db0 = pack8(ds), db1 = pack8(ds + 8);
-#pragma unroll
-  for (int c = 0; c < DV / 32; ++c) {
-    dvacc[c] = mfma(pb0, cag.read(gt, blk * 2, c), dvacc[c]);
-    dvacc[c] = mfma(pb1, cag.read(gt, blk * 2 + 1, c), dvacc[c]);
-  }
-#pragma unroll
-  for (int c = 0; c < DQK / 32; ++c) {
-    dkacc[c] = mfma(db0, caq.read(qt, blk * 2, c), dkacc[c]);
-    dkacc[c] = mfma(db1, caq.read(qt, blk * 2 + 1, c), dkacc[c]);
-  }
-}
-
-// A whole 64-query tile in which every query sees every key of the wave.  Four stages of
-// KS + VS matrix instructions each: scores of block 0, scores of block 1, dV/dK of block 0,
-// dV/dK of block 1.  The elementwise work of block 0 is issued between the matrix instructions
-// of the second stage and that of block 1 between those of the third; LDS operand reads run a
-// few instructions ahead of their use and are spread over all stages instead of arriving in
-// bursts (with one wave per SIMD nothing else would hide them).  A scheduling fence after every
-// slot keeps the compiler from regrouping the three instruction streams.
-template <int DQK, int DV>
-__device__ __forceinline__ void dkdv_tile_full(const char* qt, const char* gt,
-                                               const RowAddr<DQK>& raq, const RowAddr<DV>& rag,
-                                               const ColAddr<DQK>& caq, const ColAddr<DV>& cag,
-                                               const bf16x8 (&kreg)[DQK / 16],
-                                               const bf16x8 (&vreg)[DV / 16],
-                                               f32x16 (&dkacc)[DQK / 32], f32x16 (&dvacc)[DV / 32],
-                                               float c1, float alpha) {
-  constexpr int KS = DQK / 16, VS = DV / 16, NS = KS + VS;
-  constexpr int AHEAD = NS < 4 ? NS : 4;  // operand reads in flight ahead of the first use
-  bf16x8 op[NS];   // row-wise operands: Q rows then dO rows of the block being scored
-  bf16x8 tp[NS];   // transposed operands: dO^T then Q^T of the block being contracted
-  f32x16 s0, d0, s1, d1;
-#pragma unroll
-  for (int r = 0; r < 16; ++r) { s0[r] = 0.f; d0[r] = 0.f; s1[r] = 0.f; d1[r] = 0.f; }
-
-  auto read_rows = [&](int blk, int m) {
-    return m < KS ? raq.read(qt, blk, m) : rag.read(gt, blk, m - KS);
-  };
-  auto read_cols = [&](int blk, int m) {  // m < VS: dO^T operand m; else Q^T operand m - VS
-    return m < VS ? cag.read(gt, blk * 2 + (m & 1), m >> 1)
-                  : caq.read(qt, blk * 2 + ((m - VS) & 1), (m - VS) >> 1);
-  };
-  auto fence = [] { __builtin_amdgcn_sched_barrier(0); };
-
-  // ---- stage 1: scores of block 0; operands of block 1 follow each use
-#pragma unroll
-  for (int m = 0; m < AHEAD; ++m) op[m] = read_rows(0, m);
+  pd_cur[0] = pack8(p); pd_cur[1] = pack8(p + 8);
+  pd_cur[2] = pack8(ds); pd_cur[3] = pack8(ds + 8);
   fence();
-#pragma unroll
-  for (int m = 0; m < NS; ++m) {
-    if (m < KS) s0 = mfma(op[m], kreg[m], s0);
-    else d0 = mfma(op[m], vreg[m - KS], d0);
-    if (m + AHEAD < NS) op[m + AHEAD] = read_rows(0, m + AHEAD);
-    if (m >= AHEAD) op[m - AHEAD] = read_rows(1, m - AHEAD);
-    fence();
-  }
-#pragma unroll
-  for (int m = NS - AHEAD; m < NS; ++m) op[m] = read_rows(1, m);
-  fence();
-
-  // ---- stage 2: scores of block 1 | elementwise of block 0 | transposed operands of block 0
-  // (fences every GRP slots: inside a group the scheduler interleaves the independent
-  // elementwise chains, which hides the latency of the transcendental instructions)
-  constexpr int GRP = 4;
-  float p[16], ds[16];
-#pragma unroll
-  for (int m = 0; m < NS; ++m) {
-    if (m < KS) s1 = mfma(op[m], kreg[m], s1);
-    else d1 = mfma(op[m], vreg[m - KS], d1);
-    tp[m] = read_cols(0, m);
-#pragma unroll
-    for (int e = m * 16 / NS; e < (m + 1) * 16 / NS; ++e) bwd_elem(s0[e], d0[e], c1, alpha, p[e], ds[e]);
-    if (m % GRP == GRP - 1) fence();
-  }
-  bf16x8 pb0 = pack8(p), pb1 = pack8(p + 8), db0 = pack8(ds), db1 = pack8(ds + 8);
-  fence();
-
-  // ---- stage 3: dV/dK of block 0 | elementwise of block 1 | transposed operands of block 1
-  float p1[16], ds1[16];
-#pragma unroll
-  for (int m = 0; m < NS; ++m) {
-    if (m < VS) dvacc[m >> 1] = mfma((m & 1) ? pb1 : pb0, tp[m], dvacc[m >> 1]);
-    else dkacc[(m - VS) >> 1] = mfma(((m - VS) & 1) ? db1 : db0, tp[m], dkacc[(m - VS) >> 1]);
-    tp[m] = read_cols(1, m);
-#pragma unroll
-    for (int e = m * 16 / NS; e < (m + 1) * 16 / NS; ++e) bwd_elem(s1[e], d1[e], c1, alpha, p1[e], ds1[e]);
-    if (m % GRP == GRP - 1) fence();
-  }
-  pb0 = pack8(p1); pb1 = pack8(p1 + 8); db0 = pack8(ds1); db1 = pack8(ds1 + 8);
-  fence();
-
-  // ---- stage 4: dV/dK of block 1
-#pragma unroll
-  for (int m = 0; m < NS; ++m) {
-    if (m < VS) dvacc[m >> 1] = mfma((m & 1) ? pb1 : pb0, tp[m], dvacc[m >> 1]);
-    else dkacc[(m - VS) >> 1] = mfma(((m - VS) & 1) ? db1 : db0, tp[m], dkacc[(m - VS) >> 1]);
-  }
 }
 
 template <int DQK, int DV, int NW>
 __global__ void __launch_bounds__(NW * 64) hstu_dkdv_bf16(AttnArgs a) {
   constexpr int QB = ST * DQK * 2, GB = ST * DV * 2;
+  // Three tile buffers: an iteration of the main loop touches tiles j and j+1 while the copy of
+  // tile j+2 is in flight.  One array per buffer, so that the compiler can see that a copy into
+  // one cannot alias operand reads from another.
   __shared__ __attribute__((aligned(1024))) char smem0[QB + GB];
   __shared__ __attribute__((aligned(1024))) char smem1[QB + GB];
-  auto qbuf = [&](int b) { return b ? smem1 : smem0; };
-  auto gbuf = [&](int b) { return (b ? smem1 : smem0) + QB; };
+  __shared__ __attribute__((aligned(1024))) char smem2[QB + GB];
+  auto qbuf = [&](int b) { return b == 0 ? smem0 : (b == 1 ? smem1 : smem2); };
+  auto gbuf = [&](int b) { return qbuf(b) + QB; };
 
   const int H = a.num_heads;
   const int slot = blockIdx.x / H, h = blockIdx.x % H;
@@ -738,50 +702,105 @@ __global__ void __launch_bounds__(NW * 64) hstu_dkdv_bf16(AttnArgs a) {
     for (int r = 0; r < 16; ++r) dvacc[i][r] = 0.f;
 
   const Stream st = make_stream<1>(it, a.causal);
+  const int T = st.total, NB = 2 * T;  // tiles and 32-row blocks of the stream
   const float c1 = -a.alpha * 1.4426950408889634f;
   const int k_lo = it.pos0 + wave * 32, k_hi = k_lo + 31;
 
   RowAddr<DQK> raq; RowAddr<DV> rag; ColAddr<DQK> caq; ColAddr<DV> cag;
   raq.init(n, hh); rag.init(n, hh); caq.init(lane); cag.init(lane);
 
-  if (st.total > 0) {
-    const TileRef t0 = tile_ref(it, st, 0);
-    tile_copy_async<DQK, NW>(qbuf(0), qg + (int64_t)t0.row * sq, sq, t0.valid, wave, lane);
-    tile_copy_async<DV, NW>(gbuf(0), gg + (int64_t)t0.row * sv, sv, t0.valid, wave, lane);
-  }
+  auto copy_tile = [&](int j, int buf) {
+    const TileRef t = tile_ref(it, st, j);
+    tile_copy_async<DQK, NW>(qbuf(buf), qg + (int64_t)t.row * sq, sq, t.valid, wave, lane);
+    tile_copy_async<DV, NW>(gbuf(buf), gg + (int64_t)t.row * sv, sv, t.valid, wave, lane);
+  };
+  // Position of block i of the stream (i in [0, NB)); the positions grow with i.
+  auto block_pos = [&](int i) { return tile_ref(it, st, i >> 1).pos + (i & 1) * 32; };
+  // Does any query of block i see a key of this wave?  Once true it stays true.
+  auto block_on = [&](int i) { return wave_on && (!a.causal || block_pos(i) + 31 >= k_lo); };
+
+  load_owner_wait();
+  if (T > 0) copy_tile(0, 0);
+  if (T > 1) copy_tile(1, 1);
   tile_copy_wait<0>();
   tile_barrier();
+  if (T > 0) {  // (no visible query at all: a context-parallel pair with every query before the keys)
 
-  auto step = [&](int j, auto buf_tag) {
-    constexpr int BUF = decltype(buf_tag)::value;
-    const TileRef tj = tile_ref(it, st, j);
-    if (j + 1 < st.total) {
-      const TileRef tn = tile_ref(it, st, j + 1);
-      tile_copy_async<DQK, NW>(qbuf(BUF ^ 1), qg + (int64_t)tn.row * sq, sq, tn.valid, wave, lane);
-      tile_copy_async<DV, NW>(gbuf(BUF ^ 1), gg + (int64_t)tn.row * sv, sv, tn.valid, wave, lane);
-    }
-    const char* qt = qbuf(BUF);
-    const char* gt = gbuf(BUF);
-    if (wave_on) {
-      if (!a.causal || tj.pos >= k_hi) {
-        dkdv_tile_full<DQK, DV>(qt, gt, raq, rag, caq, cag, kreg, vreg, dkacc, dvacc, c1, a.alpha);
-      } else {
+  f32x16 sacc[2], dacc[2];  // S and dP of the blocks of even / odd index
+  bf16x8 pd[2][4];          // P (2 halves) and dS (2 halves) of the blocks of even / odd index
 #pragma unroll
-        for (int blk = 0; blk < ST / 32; ++blk) {
-          const int q_lo = tj.pos + blk * 32;
-          if (blk * 32 >= tj.valid || q_lo + 31 < k_lo) continue;  // every query precedes every key
-          dkdv_block_masked<DQK, DV>(qt, gt, blk, raq, rag, caq, cag, kreg, vreg, dkacc, dvacc, c1,
-                                     a.alpha, q_lo, k_lo, q_lo < k_hi, n, hh);
-        }
+  for (int x = 0; x < 2; ++x) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { sacc[x][r] = 0.f; dacc[x][r] = 0.f; }
+#pragma unroll
+    for (int y = 0; y < 4; ++y)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) pd[x][y][e] = (__bf16)0.f;
+  }
+
+  // scores of block 0 on their own
+  if (block_on(0)) {
+#pragma unroll
+    for (int ks = 0; ks < DQK / 16; ++ks) sacc[0] = mfma(raq.read(qbuf(0), 0, ks), kreg[ks], sacc[0]);
+#pragma unroll
+    for (int ks = 0; ks < DV / 16; ++ks) dacc[0] = mfma(rag.read(gbuf(0), 0, ks), vreg[ks], dacc[0]);
+  }
+  // step 0: scores of block 1, elementwise of block 0, nothing to contract yet
+  if (block_on(1)) {
+    const int pos = block_pos(0);
+    dkdv_step<DQK, DV, false>(qbuf(0), gbuf(0), 1, qbuf(0), gbuf(0), 0, raq, rag, caq, cag, kreg, vreg,
+                              sacc[0], dacc[0], sacc[1], dacc[1], pd[1], pd[0], dkacc, dvacc, c1,
+                              a.alpha, a.causal && pos < k_hi, k_lo + n - pos, hh);
+  }
+
+  // Iteration j: steps 2j+1 and 2j+2, which touch tiles j and j+1 only.
+  auto iter = [&](int j, auto buf_tag) {
+    constexpr int B0 = decltype(buf_tag)::value, B1 = (B0 + 1) % 3, B2 = (B0 + 2) % 3;
+    if (j + 2 < T) copy_tile(j + 2, B2);  // every wave left tile j-1 before the last barrier
+    {
+      const int i = 2 * j + 1;  // scores of (tile j+1, block 0), contraction of (tile j, block 0)
+      if (block_on(i + 1 < NB ? i + 1 : i)) {
+        const int pos = block_pos(i);
+        dkdv_step<DQK, DV, true>(qbuf(B1), gbuf(B1), 0, qbuf(B0), gbuf(B0), 0, raq, rag, caq, cag,
+                                 kreg, vreg, sacc[1], dacc[1], sacc[0], dacc[0], pd[0], pd[1], dkacc,
+                                 dvacc, c1, a.alpha, a.causal && pos < k_hi, k_lo + n - pos, hh);
       }
     }
-    tile_copy_wait();
+    if (j + 1 < T) {
+      const int i = 2 * j + 2;  // scores of (tile j+1, block 1), contraction of (tile j, block 1)
+      if (block_on(i + 1)) {
+        const int pos = block_pos(i);
+        dkdv_step<DQK, DV, true>(qbuf(B1), gbuf(B1), 1, qbuf(B0), gbuf(B0), 1, raq, rag, caq, cag,
+                                 kreg, vreg, sacc[0], dacc[0], sacc[1], dacc[1], pd[1], pd[0], dkacc,
+                                 dvacc, c1, a.alpha, a.causal && pos < k_hi, k_lo + n - pos, hh);
+      }
+    }
+    tile_copy_wait<0>();
     tile_barrier();
   };
-  for (int j = 0; j < st.total; j += 2) {
-    step(j, std::integral_constant<int, 0>{});
-    if (j + 1 < st.total) step(j + 1, std::integral_constant<int, 1>{});
+  for (int j = 0; j < T; j += 3) {
+    iter(j, std::integral_constant<int, 0>{});
+    if (j + 1 < T) iter(j + 1, std::integral_constant<int, 1>{});
+    if (j + 2 < T) iter(j + 2, std::integral_constant<int, 2>{});
   }
+
+  // contraction of the last block (tile T-1, block 1) on its own
+  if (block_on(NB - 1)) {
+    const int lb = (T - 1) % 3;
+    const char* qt = qbuf(lb);
+    const char* gt = gbuf(lb);
+#pragma unroll
+    for (int c = 0; c < DV / 32; ++c) {
+      dvacc[c] = mfma(pd[1][0], cag.read(gt, 2, c), dvacc[c]);
+      dvacc[c] = mfma(pd[1][1], cag.read(gt, 3, c), dvacc[c]);
+    }
+#pragma unroll
+    for (int c = 0; c < DQK / 32; ++c) {
+      dkacc[c] = mfma(pd[1][2], caq.read(qt, 2, c), dkacc[c]);
+      dkacc[c] = mfma(pd[1][3], caq.read(qt, 3, c), dkacc[c]);
+    }
+  }
+  }  // T > 0
 
   // Accumulators: lane holds column c*32 + n of key rows 8*(r/4) + 4*hh + r%4 of its wave.
   if (wave_on) {
@@ -808,9 +827,16 @@ __global__ void __launch_bounds__(NW * 64) hstu_dkdv_bf16(AttnArgs a) {
 //   dP^T = V dO^T  (A = V tile rows, B = dO registers)
 //   dQ^T += K^T dS^T (A = K tile transposed read, B = dS^T registers)
 // A second recomputation of S instead of atomics: dq is deterministic.
+//
+// One 32-key block at a time: scores, elementwise, contraction.  Two workgroups share a CU, so
+// every SIMD has two waves of different workgroups, which are at unrelated points of this
+// sequence and fill each other's gaps.  Keeping two blocks in flight per wave instead (as the
+// other two passes do) needs more than the 256 registers a wave may have at this occupancy; the
+// spills it caused cost more than the overlap gained (their reloads also wait for the tile
+// copy in flight, because vector memory operations complete in order).
 // =============================================================================================
 template <int DQK, int DV>
-__device__ __forceinline__ void dq_block_masked(const char* kt, const char* vt, int blk,
+__device__ __forceinline__ void dq_block(const char* kt, const char* vt, int blk,
                                                 const RowAddr<DQK>& rak, const RowAddr<DV>& rav,
                                                 const ColAddr<DQK>& cak,
                                                 const bf16x8 (&qreg)[DQK / 16],
@@ -844,66 +870,6 @@ __device__ __forceinline__ void dq_block_masked(const char* kt, const char* vt, 
     dqacc[c] = mfma(cak.read(kt, blk * 2, c), db0, dqacc[c]);
     dqacc[c] = mfma(cak.read(kt, blk * 2 + 1, c), db1, dqacc[c]);
   }
-}
-
-template <int DQK, int DV>
-__device__ __forceinline__ void dq_tile_full(const char* kt, const char* vt,
-                                             const RowAddr<DQK>& rak, const RowAddr<DV>& rav,
-                                             const ColAddr<DQK>& cak,
-                                             const bf16x8 (&qreg)[DQK / 16],
-                                             const bf16x8 (&greg)[DV / 16],
-                                             f32x16 (&dqacc)[DQK / 32], float c1, float alpha) {
-  constexpr int KS = DQK / 16, VS = DV / 16, NS = KS + VS;
-  bf16x8 ka[KS], va[VS], kT[KS];
-  f32x16 s0, d0, s1, d1;
-#pragma unroll
-  for (int r = 0; r < 16; ++r) { s0[r] = 0.f; d0[r] = 0.f; s1[r] = 0.f; d1[r] = 0.f; }
-
-#pragma unroll
-  for (int ks = 0; ks < KS; ++ks) ka[ks] = rak.read(kt, 0, ks);
-#pragma unroll
-  for (int ks = 0; ks < VS; ++ks) va[ks] = rav.read(vt, 0, ks);
-#pragma unroll
-  for (int ks = 0; ks < KS; ++ks) s0 = mfma(ka[ks], qreg[ks], s0);
-#pragma unroll
-  for (int ks = 0; ks < VS; ++ks) d0 = mfma(va[ks], greg[ks], d0);
-
-#pragma unroll
-  for (int ks = 0; ks < KS; ++ks) ka[ks] = rak.read(kt, 1, ks);
-#pragma unroll
-  for (int ks = 0; ks < VS; ++ks) va[ks] = rav.read(vt, 1, ks);
-#pragma unroll
-  for (int i = 0; i < KS; ++i) kT[i] = cak.read(kt, i & 1, i >> 1);
-
-  float ds[16];
-#pragma unroll
-  for (int m = 0; m < NS; ++m) {
-    if (m < KS) s1 = mfma(ka[m], qreg[m], s1);
-    else d1 = mfma(va[m - KS], greg[m - KS], d1);
-#pragma unroll
-    for (int e = m * 16 / NS; e < (m + 1) * 16 / NS; ++e) {
-      float p;
-      bwd_elem(s0[e], d0[e], c1, alpha, p, ds[e]);
-    }
-  }
-  bf16x8 db0 = pack8(ds), db1 = pack8(ds + 8);
-
-  float ds1[16];
-#pragma unroll
-  for (int i = 0; i < KS; ++i) {
-    dqacc[i >> 1] = mfma(kT[i], (i & 1) ? db1 : db0, dqacc[i >> 1]);
-#pragma unroll
-    for (int e = i * 16 / KS; e < (i + 1) * 16 / KS; ++e) {
-      float p;
-      bwd_elem(s1[e], d1[e], c1, alpha, p, ds1[e]);
-    }
-  }
-#pragma unroll
-  for (int i = 0; i < KS; ++i) kT[i] = cak.read(kt, 2 + (i & 1), i >> 1);
-  db0 = pack8(ds1);
-  db1 = pack8(ds1 + 8);
-#pragma unroll
-  for (int i = 0; i < KS; ++i) dqacc[i >> 1] = mfma(kT[i], (i & 1) ? db1 : db0, dqacc[i >> 1]);
 }
 
 template <int DQK, int DV, int NW>
@@ -965,16 +931,12 @@ __global__ void __launch_bounds__(NW * 64, 2) hstu_dq_bf16(AttnArgs a) {
     const char* kt = kbuf(BUF);
     const char* vt = vbuf(BUF);
     if (wave_on) {
-      if (!a.causal || tj.pos + ST - 1 <= q_lo) {
-        dq_tile_full<DQK, DV>(kt, vt, rak, rav, cak, qreg, greg, dqacc, c1, a.alpha);
-      } else {
 #pragma unroll
-        for (int blk = 0; blk < ST / 32; ++blk) {
-          const int k_lo = tj.pos + blk * 32;
-          if (blk * 32 >= tj.valid || k_lo > q_hi) continue;
-          dq_block_masked<DQK, DV>(kt, vt, blk, rak, rav, cak, qreg, greg, dqacc, c1, a.alpha, k_lo,
-                                   q_lo, k_lo + 31 > q_lo, n, hh);
-        }
+      for (int blk = 0; blk < ST / 32; ++blk) {
+        const int k_lo = tj.pos + blk * 32;
+        if (blk * 32 >= tj.valid || (a.causal && k_lo > q_hi)) continue;  // no key of the block is visible
+        dq_block<DQK, DV>(kt, vt, blk, rak, rav, cak, qreg, greg, dqacc, c1, a.alpha, k_lo, q_lo,
+                          a.causal && k_lo + 31 > q_lo, n, hh);
       }
     }
     tile_copy_wait<0>();
@@ -1084,3 +1046,4 @@ hipError_t launch_dq_bf16(const AttnArgs& a, int d_qk, int d_v, hipStream_t stre
 }
 
 }  // namespace hstu
+
