@@ -69,7 +69,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="cfg5", choices=["cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--workload", default="cfg5", choices=["cfg2", "cfg3", "cfg4", "cfg4_ring", "cfg5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-prefix-rows", type=int, default=0, help="rows per sequence in the CPU sample")
     args = ap.parse_args()
@@ -84,7 +84,8 @@ def main() -> int:
     import paper_2508_04711_amd as lib
     lib.load_library()  # fail loudly if the HIP library is not built
 
-    cfg = int(args.workload[3:])
+    ring = args.workload.endswith("_ring")
+    cfg = int(args.workload[3:4])
     w = workloads.config(cfg)
     dev = torch.device("cuda:0")
     vals = {k: v.to(dev) for k, v in workloads.values(w).items()}
@@ -119,7 +120,38 @@ def main() -> int:
         ws = torch.empty(lib.hstu_jagged_attn_workspace_bytes(
             (w.batch, H, w.d_qk, w.d_v, w.max_len, w.alpha, True, 0, T), 2), dtype=torch.uint8, device=dev)
 
+        if ring:
+            # the ring variant: every rank's K/V part resident in its local layout (as on its own
+            # GPU), fetched part by part on a second stream while the previous step computes;
+            # o and dq accumulate in fp32 across the steps
+            kparts, vparts = [], []
+            for r, rk in enumerate(ranks):
+                kl, vl = lib.hstu_cp_reorder([vals["k"], vals["v"]], off, T, cp, r, rk["n"])
+                kparts.append(kl); vparts.append(vl)
+            recv_rows = max(rk["n"] for rk in ranks)
+            recv = [torch.empty((recv_rows, H, d), dtype=dt, device=dev) for d in (w.d_qk, w.d_qk, w.d_v, w.d_v)]
+            for rk in ranks:
+                rk["o32"] = torch.empty((rk["n"], H, w.d_v), dtype=torch.float32, device=dev)
+                rk["dq32"] = torch.empty((rk["n"], H, w.d_qk), dtype=torch.float32, device=dev)
+            dks = [torch.empty((rk["n"], H, w.d_qk), dtype=torch.float32, device=dev) for rk in ranks]
+            dvs = [torch.empty((rk["n"], H, w.d_v), dtype=torch.float32, device=dev) for rk in ranks]
+            o_glob = torch.empty((T, H, w.d_v), dtype=torch.float32, device=dev)
+            dq_glob = torch.empty((T, H, w.d_qk), dtype=torch.float32, device=dev)
+            copy_stream = torch.cuda.Stream(device=dev)
+
+        def step_ring():
+            for r, rk in enumerate(ranks):
+                lib.hstu_cp_reorder([vals["q"], vals["d_o"]], off, T, cp, r, rk["n"],
+                                    out=[rk["q"], rk["d_o"]])
+                lib.hstu_cp_ring_pass(rk["q"], rk["d_o"], kparts, vparts, off, T, w.max_len, w.alpha, True,
+                                      cp, r, out=(rk["o32"], rk["dq32"], dks, dvs), recv=recv,
+                                      workspace=ws, copy_stream=copy_stream)
+                lib.hstu_cp_reorder([rk["o32"], rk["dq32"]], off, T, cp, r, rk["n"], scatter=True,
+                                    out=[o_glob, dq_glob])
+
         def step():
+            if ring:
+                return step_ring()
             # per rank: reorder kernel global -> local (q, d_o), the partial, local -> global (o, dq)
             for r, rk in enumerate(ranks):
                 lib.hstu_cp_reorder([vals["q"], vals["d_o"]], off, T, cp, r, rk["n"],
@@ -159,10 +191,11 @@ def main() -> int:
     # Per-kernel durations over the same steps: HIP events recorded by the library on the
     # stream it launches on, one pair per kernel launch.
     prof_steps = max(1, min(args.steps, 10))
-    lib.hstu_debug_timing_begin(64 * prof_steps * max(1, w.cp_size))
+    nrec = 64 * prof_steps * max(1, w.cp_size) * (max(1, w.cp_size) if ring else 1)
+    lib.hstu_debug_timing_begin(nrec)
     for _ in range(prof_steps):
         step()
-    recs = lib.hstu_debug_timing_end(64 * prof_steps * max(1, w.cp_size))
+    recs = lib.hstu_debug_timing_end(nrec)
     per_kind = {}
     for kind, ms in recs:
         per_kind.setdefault(kind, []).append(ms)
@@ -211,7 +244,7 @@ def main() -> int:
         "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": w.name, "batch": w.batch, "total_rows": T, "num_heads": H,
+        "config": {"workload": w.name + ("_ring" if ring else ""), "batch": w.batch, "total_rows": T, "num_heads": H,
                    "d_qk": w.d_qk, "d_v": w.d_v, "max_len": w.max_len, "causal": True,
                    "cp_size": w.cp_size, "pairs_per_head": w.pairs_per_head,
                    "flops_per_step": step_flops},

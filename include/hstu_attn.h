@@ -142,6 +142,43 @@ int hstu_jagged_attn_cp_partial(const hstu_attn_params* params, const hstu_cp_de
                                 void* o_local, void* dq_local, void* dk_part, void* dv_part,
                                 void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* One rank's whole context-parallel pass as a ring of cp_size steps (section 3 names ring
+ * attention as the variant for longer sequences; the partials are the ones of section 2.3).
+ * Step s works on the K/V part of rank (q_rank - s) mod cp_size: the rank's own part first,
+ * read in place, then the parts in the order they would arrive from the previous rank.  While a
+ * step computes on `compute_stream`, the transfer of the next part runs on `copy_stream` into one
+ * of two receive buffers (on one GPU a device-to-device copy stands in for the link; the
+ * k_parts / v_parts pointers stand for the peers' memory).  o_local and dq_local are overwritten
+ * by step 0 and accumulated by the later steps: give them fp32 (params->out_dtype) unless bf16
+ * rounding between steps is acceptable.  The rank's contribution to the key-side gradients of
+ * each part goes to dk_parts[r] / dv_parts[r] (added to them when accumulate_dkv != 0, as the
+ * gradient buffer that travels with a part would be).
+ * All arrays of the descriptor are host arrays of cp_size entries; the pointers in them are
+ * device pointers.  Both streams must be distinct; on return everything is enqueued, the
+ * compute stream carries the results, and the copy stream has been made to wait for the work
+ * queued on the compute stream before the call.  Workspace as for hstu_jagged_attn_cp_partial.
+ */
+typedef struct hstu_cp_ring_desc {
+  int32_t cp_size;
+  int32_t q_rank;
+  int32_t accumulate_dkv;        /* 0: overwrite dk_parts / dv_parts, 1: add to them */
+  int32_t reserved;              /* must be 0 */
+  int64_t q_rows;                /* rows of q_local (and d_o_local, o_local, dq_local) */
+  int64_t recv_rows;             /* rows each receive buffer can hold (>= every other part) */
+  const int64_t* part_rows;      /* rows of each rank's K/V part */
+  const void* const* k_parts;    /* [part_rows[r], H, d_qk] */
+  const void* const* v_parts;    /* [part_rows[r], H, d_v] */
+  void* k_recv[2];               /* [recv_rows, H, d_qk] each */
+  void* v_recv[2];               /* [recv_rows, H, d_v] each */
+  void* const* dk_parts;         /* [part_rows[r], H, d_qk], out_dtype; NULL for forward only */
+  void* const* dv_parts;         /* [part_rows[r], H, d_v] */
+} hstu_cp_ring_desc;
+
+int hstu_cp_ring_pass(const hstu_attn_params* params, const hstu_cp_ring_desc* ring,
+                      const void* q_local, const void* d_o_local, const int32_t* seq_offsets_global,
+                      void* o_local, void* dq_local, void* workspace, size_t workspace_bytes,
+                      void* compute_stream, void* copy_stream);
+
 /* Memory reorder for the load-balanced split (section 2.3: the "data shuffling ... memory
  * reordering" kernels that replace chunk + concatenate; section 3 credits them with +37 % QPS).
  * Moves whole rows between the global jagged layout and `rank`'s local layout (see hstu_cp_desc),

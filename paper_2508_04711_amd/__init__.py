@@ -6,6 +6,7 @@ from .binding import (  # noqa: F401
     HstuError,
     hstu_attn_status_string,
     hstu_cp_reorder,
+    hstu_cp_ring_pass,
     hstu_debug_dump_schedule,
     hstu_debug_timing_begin,
     hstu_debug_timing_end,

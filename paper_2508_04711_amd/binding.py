@@ -44,6 +44,16 @@ class _CpDesc(ctypes.Structure):
     ]
 
 
+class _RingDesc(ctypes.Structure):
+    _fields_ = [
+        ("cp_size", ctypes.c_int32), ("q_rank", ctypes.c_int32), ("accumulate_dkv", ctypes.c_int32),
+        ("reserved", ctypes.c_int32), ("q_rows", ctypes.c_int64), ("recv_rows", ctypes.c_int64),
+        ("part_rows", ctypes.c_void_p), ("k_parts", ctypes.c_void_p), ("v_parts", ctypes.c_void_p),
+        ("k_recv", ctypes.c_void_p * 2), ("v_recv", ctypes.c_void_p * 2),
+        ("dk_parts", ctypes.c_void_p), ("dv_parts", ctypes.c_void_p),
+    ]
+
+
 def library_path() -> str:
     return _LIB_PATH
 
@@ -80,6 +90,9 @@ def load_library():
     lib.hstu_debug_timing_begin.argtypes = [ctypes.c_int]
     lib.hstu_debug_timing_end.restype = ctypes.c_int
     lib.hstu_debug_timing_end.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int]
+    lib.hstu_cp_ring_pass.restype = ctypes.c_int
+    lib.hstu_cp_ring_pass.argtypes = [pp, ctypes.POINTER(_RingDesc), vp, vp, i32p, vp, vp, vp,
+                                      ctypes.c_size_t, vp, vp]
     lib.hstu_cp_reorder.restype = ctypes.c_int
     lib.hstu_cp_reorder.argtypes = [ctypes.c_int32, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32,
                                     ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p,
@@ -364,3 +377,90 @@ def hstu_cp_reorder(tensors, seq_offsets: torch.Tensor, total_rows: int, cp_size
     if rc != 0:
         raise HstuError(rc, "hstu_cp_reorder")
     return out
+
+
+_copy_streams = {}
+
+
+def hstu_cp_ring_pass(q_local: torch.Tensor, d_o_local: Optional[torch.Tensor], k_parts, v_parts,
+                      seq_offsets_global: torch.Tensor, total_rows: int, max_len: int, alpha: float,
+                      causal: bool, cp_size: int, q_rank: int, out_dtype: torch.dtype = torch.float32,
+                      accumulate_dkv: bool = False, out: Optional[tuple] = None, recv=None,
+                      workspace: Optional[torch.Tensor] = None, stream=None, copy_stream=None):
+    """One rank's context-parallel pass as a ring over the K/V parts of all ranks.
+
+    k_parts / v_parts: one tensor per rank (its rows of K and V in its local layout), standing
+    for the peers' memory.  Returns (o_local, dq_local, dk_parts, dv_parts); the gradients are
+    None when d_o_local is None.  `out` may pass them (needed when accumulate_dkv is set), `recv`
+    the four receive buffers (k0, k1, v0, v1).
+    """
+    nq, H, dqk = q_local.shape
+    dv = v_parts[0].shape[2]
+    dt = q_local.dtype
+    dev = q_local.device
+    if len(k_parts) != cp_size or len(v_parts) != cp_size:
+        raise ValueError("one K part and one V part per rank")
+    _check_tensor(q_local, "q_local", nq, H, dqk, dt)
+    if d_o_local is not None:
+        _check_tensor(d_o_local, "d_o_local", nq, H, dv, dt)
+    rows = [int(k.shape[0]) for k in k_parts]
+    for r in range(cp_size):
+        _check_tensor(k_parts[r], "k_parts[%d]" % r, rows[r], H, dqk, dt)
+        _check_tensor(v_parts[r], "v_parts[%d]" % r, rows[r], H, dv, dt)
+    so = seq_offsets_global
+    if so.dtype != torch.int32 or not so.is_cuda or not so.is_contiguous():
+        raise ValueError("seq_offsets_global must be a contiguous int32 device tensor")
+    backward = d_o_local is not None
+    if out is not None:
+        o, dq, dks, dvs = out
+        out_dtype = next(t for t in (o, dq) if t is not None).dtype
+    else:
+        if accumulate_dkv:
+            raise ValueError("accumulate_dkv needs the key-side gradients to add to")
+        o = torch.empty((nq, H, dv), dtype=out_dtype, device=dev)
+        dq = torch.empty((nq, H, dqk), dtype=out_dtype, device=dev) if backward else None
+        dks = [torch.empty((rows[r], H, dqk), dtype=out_dtype, device=dev) for r in range(cp_size)] if backward else None
+        dvs = [torch.empty((rows[r], H, dv), dtype=out_dtype, device=dev) for r in range(cp_size)] if backward else None
+    if o is not None:
+        _check_tensor(o, "o_local", nq, H, dv, out_dtype)
+    if backward:
+        _check_tensor(dq, "dq_local", nq, H, dqk, out_dtype)
+        for r in range(cp_size):
+            _check_tensor(dks[r], "dk_parts[%d]" % r, rows[r], H, dqk, out_dtype)
+            _check_tensor(dvs[r], "dv_parts[%d]" % r, rows[r], H, dv, out_dtype)
+    recv_rows = max([rows[r] for r in range(cp_size) if r != q_rank] + [0])
+    if recv is None:
+        recv = [torch.empty((max(recv_rows, 1), H, d), dtype=dt, device=dev) for d in (dqk, dqk, dv, dv)]
+    else:
+        recv_rows = min(int(t.shape[0]) for t in recv)
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    if copy_stream is None:
+        key = (dev.index, stream.cuda_stream)
+        if key not in _copy_streams:
+            _copy_streams[key] = torch.cuda.Stream(device=dev)  # default priority
+        copy_stream = _copy_streams[key]
+    p = _params(so.numel() - 1, H, dqk, dv, max_len, alpha, causal, _dtype_code(q_local), total_rows,
+                _code(out_dtype))
+    arr = lambda ts: (ctypes.c_void_p * cp_size)(*[t.data_ptr() if t is not None and t.numel() else None for t in ts])
+    part_rows = (ctypes.c_int64 * cp_size)(*rows)
+    kp, vp_ = arr(k_parts), arr(v_parts)
+    dkp = arr(dks) if backward else None
+    dvp = arr(dvs) if backward else None
+    desc = _RingDesc(int(cp_size), int(q_rank), int(bool(accumulate_dkv)), 0, int(nq), int(recv_rows),
+                     ctypes.cast(part_rows, ctypes.c_void_p), ctypes.cast(kp, ctypes.c_void_p),
+                     ctypes.cast(vp_, ctypes.c_void_p),
+                     (ctypes.c_void_p * 2)(recv[0].data_ptr(), recv[1].data_ptr()),
+                     (ctypes.c_void_p * 2)(recv[2].data_ptr(), recv[3].data_ptr()),
+                     ctypes.cast(dkp, ctypes.c_void_p) if backward else None,
+                     ctypes.cast(dvp, ctypes.c_void_p) if backward else None)
+    ws = _workspace(p, HSTU_WS_CP, workspace, dev)
+    rc = load_library().hstu_cp_ring_pass(
+        ctypes.byref(p), ctypes.byref(desc), _ptr(q_local), _ptr(d_o_local), _ptr(so), _ptr(o), _ptr(dq),
+        _ptr(ws), ws.numel(), ctypes.c_void_p(stream.cuda_stream), ctypes.c_void_p(copy_stream.cuda_stream))
+    if rc != 0:
+        raise HstuError(rc, "hstu_cp_ring_pass")
+    # the receive buffers and the parts are read by work still in flight on the copy stream
+    for t in list(recv) + list(k_parts) + list(v_parts):
+        t.record_stream(copy_stream)
+    return o, dq, dks, dvs

@@ -353,11 +353,15 @@ int hstu_jagged_attn_bwd(const hstu_attn_params* params, const void* q, const vo
   return run_pass(params, PASS_DQ, b, stream);
 }
 
-int hstu_jagged_attn_cp_partial(const hstu_attn_params* params, const hstu_cp_desc* cp,
-                                const void* q_local, const void* k_part, const void* v_part,
-                                const void* d_o_local, const int32_t* seq_offsets_global,
-                                void* o_local, void* dq_local, void* dk_part, void* dv_part,
-                                void* workspace, size_t workspace_bytes, void* hip_stream) {
+// The partial of one (query rank, key rank) pair.  acc_q: add to o_local / dq_local;
+// acc_kv: add to dk_part / dv_part (the two differ in a ring: a rank's own accumulators run
+// over the steps, the key-side gradients belong to the part that is visiting).
+static int cp_partial_impl(const hstu_attn_params* params, const hstu_cp_desc* cp,
+                           const void* q_local, const void* k_part, const void* v_part,
+                           const void* d_o_local, const int32_t* seq_offsets_global,
+                           void* o_local, void* dq_local, void* dk_part, void* dv_part,
+                           int acc_q, int acc_kv, void* workspace, size_t workspace_bytes,
+                           void* hip_stream) {
   int rc = check_params(params);
   if (rc != HSTU_OK) return rc;
   rc = check_cp(params, cp);
@@ -374,46 +378,165 @@ int hstu_jagged_attn_cp_partial(const hstu_attn_params* params, const hstu_cp_de
     return HSTU_ERR_WORKSPACE_TOO_SMALL;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   char* ws = (char*)workspace;
-  const int acc = cp->accumulate ? 1 : 0;
-  size_t base = 0;
-  if (o_local && cp->q_rows > 0) {
-    BuiltPlan pf;
-    rc = build_plan(params, cp->cp_size, cp_side(params, cp, 0, PASS_FWD), seq_offsets_global, ws,
-                    workspace_bytes, base, stream, &pf);
+  // the (up to) three schedules are built by one launch
+  const bool do_f = o_local && cp->q_rows > 0, do_k = backward && cp->kv_rows > 0,
+             do_q = backward && cp->q_rows > 0;
+  PlanArgs pa[3];
+  BuiltPlan pf, pk, pq;
+  int np = 0;
+  size_t base = 0, tbase = 0;
+  if (do_f) {
+    const SideSpec sf = cp_side(params, cp, 0, PASS_FWD);
+    rc = prepare_plan(params, cp->cp_size, sf, seq_offsets_global, ws, workspace_bytes, base, &pa[np++], &pf);
     if (rc != HSTU_OK) return rc;
-    base = pf.end;
-    AttnArgs a = base_args(params, pf, acc);
+    tbase = pf.end;  // the transposed copy of V follows its schedule
+    base = align_up(pf.end, 256) + tcopy_bytes(params, sf, params->d_v);
+  }
+  if (do_k) {
+    rc = prepare_plan(params, cp->cp_size, cp_side(params, cp, 1, PASS_DKDV), seq_offsets_global, ws,
+                      workspace_bytes, base, &pa[np++], &pk);
+    if (rc != HSTU_OK) return rc;
+    base = pk.end;
+  }
+  if (do_q) {
+    rc = prepare_plan(params, cp->cp_size, cp_side(params, cp, 0, PASS_DQ), seq_offsets_global, ws,
+                      workspace_bytes, base, &pa[np++], &pq);
+    if (rc != HSTU_OK) return rc;
+  }
+  if (np == 0) return HSTU_OK;
+  rc = launch_built(pa, np, stream);
+  if (rc != HSTU_OK) return rc;
+  if (do_f) {
+    AttnArgs a = base_args(params, pf, acc_q);
     a.q = q_local; a.k = k_part; a.v = v_part; a.o = o_local;
     rc = make_tcopy(params, cp_side(params, cp, 0, PASS_FWD), pf, v_part, params->d_v, ws,
-                    workspace_bytes, &base, stream, &a.vt);
+                    workspace_bytes, &tbase, stream, &a.vt);
     if (rc != HSTU_OK) return rc;
     rc = run_pass(params, PASS_FWD, a, stream);
     if (rc != HSTU_OK) return rc;
   }
-  if (backward) {
-    if (cp->kv_rows > 0) {
-      BuiltPlan pk;
-      rc = build_plan(params, cp->cp_size, cp_side(params, cp, 1, PASS_DKDV), seq_offsets_global,
-                      ws, workspace_bytes, base, stream, &pk);
-      if (rc != HSTU_OK) return rc;
-      base = pk.end;
-      AttnArgs a = base_args(params, pk, acc);
-      a.q = q_local; a.k = k_part; a.v = v_part; a.d_o = d_o_local; a.dk = dk_part; a.dv = dv_part;
-      rc = run_pass(params, PASS_DKDV, a, stream);
-      if (rc != HSTU_OK) return rc;
-    }
-    if (cp->q_rows > 0) {
-      BuiltPlan pq;
-      rc = build_plan(params, cp->cp_size, cp_side(params, cp, 0, PASS_DQ), seq_offsets_global, ws,
-                      workspace_bytes, base, stream, &pq);
-      if (rc != HSTU_OK) return rc;
-      AttnArgs b = base_args(params, pq, acc);
-      b.q = q_local; b.k = k_part; b.v = v_part; b.d_o = d_o_local; b.dq = dq_local;
-      rc = run_pass(params, PASS_DQ, b, stream);
-      if (rc != HSTU_OK) return rc;
-    }
+  if (do_k) {
+    AttnArgs a = base_args(params, pk, acc_kv);
+    a.q = q_local; a.k = k_part; a.v = v_part; a.d_o = d_o_local; a.dk = dk_part; a.dv = dv_part;
+    rc = run_pass(params, PASS_DKDV, a, stream);
+    if (rc != HSTU_OK) return rc;
+  }
+  if (do_q) {
+    AttnArgs b = base_args(params, pq, acc_q);
+    b.q = q_local; b.k = k_part; b.v = v_part; b.d_o = d_o_local; b.dq = dq_local;
+    rc = run_pass(params, PASS_DQ, b, stream);
+    if (rc != HSTU_OK) return rc;
   }
   return HSTU_OK;
+}
+
+int hstu_jagged_attn_cp_partial(const hstu_attn_params* params, const hstu_cp_desc* cp,
+                                const void* q_local, const void* k_part, const void* v_part,
+                                const void* d_o_local, const int32_t* seq_offsets_global,
+                                void* o_local, void* dq_local, void* dk_part, void* dv_part,
+                                void* workspace, size_t workspace_bytes, void* hip_stream) {
+  const int acc = (cp && cp->accumulate) ? 1 : 0;
+  return cp_partial_impl(params, cp, q_local, k_part, v_part, d_o_local, seq_offsets_global, o_local,
+                         dq_local, dk_part, dv_part, acc, acc, workspace, workspace_bytes, hip_stream);
+}
+
+int hstu_cp_ring_pass(const hstu_attn_params* params, const hstu_cp_ring_desc* ring,
+                      const void* q_local, const void* d_o_local, const int32_t* seq_offsets_global,
+                      void* o_local, void* dq_local, void* workspace, size_t workspace_bytes,
+                      void* compute_stream, void* copy_stream) {
+  int rc = check_params(params);
+  if (rc != HSTU_OK) return rc;
+  if (!ring) return HSTU_ERR_NULL_PTR;
+  const int cp = ring->cp_size, me = ring->q_rank;
+  if (cp < 1 || (int64_t)cp * 2 >= (1ll << 31) || me < 0 || me >= cp || ring->q_rows < 0 ||
+      ring->recv_rows < 0)
+    return HSTU_ERR_BAD_CP;
+  if (ring->reserved != 0) return HSTU_ERR_UNSUPPORTED;
+  if (!ring->part_rows || !ring->k_parts || !ring->v_parts) return HSTU_ERR_NULL_PTR;
+  const bool backward = d_o_local != nullptr;
+  if (backward && (!ring->dk_parts || !ring->dv_parts)) return HSTU_ERR_NULL_PTR;
+  if (compute_stream == copy_stream) return HSTU_ERR_UNSUPPORTED;  // the overlap needs two streams
+  const size_t eb = params->dtype == HSTU_BF16 ? 2 : 4;
+  const size_t krow = (size_t)params->num_heads * params->d_qk * eb;
+  const size_t vrow = (size_t)params->num_heads * params->d_v * eb;
+  for (int r = 0; r < cp; ++r) {
+    if (ring->part_rows[r] < 0) return HSTU_ERR_BAD_CP;
+    if (ring->part_rows[r] > 0 && (!ring->k_parts[r] || !ring->v_parts[r])) return HSTU_ERR_NULL_PTR;
+    if (backward && ring->part_rows[r] > 0 && (!ring->dk_parts[r] || !ring->dv_parts[r]))
+      return HSTU_ERR_NULL_PTR;
+    if (r != me && ring->part_rows[r] > ring->recv_rows) return HSTU_ERR_BAD_CP;
+  }
+  if (cp > 1 && ring->recv_rows > 0)
+    for (int b = 0; b < 2; ++b)
+      if (!ring->k_recv[b] || !ring->v_recv[b]) return HSTU_ERR_NULL_PTR;
+  if (params->batch == 0 || params->total_rows == 0) return HSTU_OK;
+
+  hipStream_t cs = static_cast<hipStream_t>(compute_stream), xs = static_cast<hipStream_t>(copy_stream);
+  // landed[b]: the part in receive buffer b has arrived; released[b]: the step that read
+  // buffer b has been issued to the end (its kernels are ordered on the compute stream).
+  hipEvent_t landed[2] = {nullptr, nullptr}, released[2] = {nullptr, nullptr}, start = nullptr;
+  auto cleanup = [&](int code) {
+    for (int b = 0; b < 2; ++b) {
+      if (landed[b]) (void)hipEventDestroy(landed[b]);
+      if (released[b]) (void)hipEventDestroy(released[b]);
+    }
+    if (start) (void)hipEventDestroy(start);
+    return code;
+  };
+  for (int b = 0; b < 2; ++b) {
+    if (hipEventCreateWithFlags(&landed[b], hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&released[b], hipEventDisableTiming) != hipSuccess)
+      return cleanup(HSTU_ERR_HIP);
+  }
+  if (hipEventCreateWithFlags(&start, hipEventDisableTiming) != hipSuccess) return cleanup(HSTU_ERR_HIP);
+  // the copy stream must not run ahead of what the caller queued on the compute stream
+  if (hipEventRecord(start, cs) != hipSuccess || hipStreamWaitEvent(xs, start, 0) != hipSuccess)
+    return cleanup(HSTU_ERR_HIP);
+
+  // Step s works on the part of rank (me - s) mod cp: the rank's own part first, then the
+  // parts as they would arrive from the previous rank of the ring.  The transfer of step
+  // s + 1's part runs on the copy stream while step s computes.
+  auto part_of = [&](int s) { return ((me - s) % cp + cp) % cp; };
+  auto fetch = [&](int s) -> int {  // start the transfer for step s (s >= 1) into buffer s & 1
+    const int r = part_of(s), b = s & 1;
+    if (s >= 3 && hipStreamWaitEvent(xs, released[b], 0) != hipSuccess) return HSTU_ERR_HIP;
+    const size_t rows = (size_t)ring->part_rows[r];
+    if (rows > 0) {
+      if (hipMemcpyAsync(ring->k_recv[b], ring->k_parts[r], rows * krow, hipMemcpyDeviceToDevice, xs) != hipSuccess ||
+          hipMemcpyAsync(ring->v_recv[b], ring->v_parts[r], rows * vrow, hipMemcpyDeviceToDevice, xs) != hipSuccess)
+        return HSTU_ERR_HIP;
+    }
+    return hipEventRecord(landed[b], xs) == hipSuccess ? HSTU_OK : HSTU_ERR_HIP;
+  };
+  for (int s = 1; s <= 2 && s < cp; ++s) {  // both buffers are free at the start
+    rc = fetch(s);
+    if (rc != HSTU_OK) return cleanup(rc);
+  }
+  for (int s = 0; s < cp; ++s) {
+    const int r = part_of(s), b = s & 1;
+    const void* kp = s == 0 ? ring->k_parts[r] : ring->k_recv[b];
+    const void* vp = s == 0 ? ring->v_parts[r] : ring->v_recv[b];
+    if (s > 0 && hipStreamWaitEvent(cs, landed[b], 0) != hipSuccess) return cleanup(HSTU_ERR_HIP);
+    hstu_cp_desc d = {};
+    d.cp_size = cp; d.q_rank = me; d.kv_rank = r; d.accumulate = 0;
+    d.q_rows = ring->q_rows; d.kv_rows = ring->part_rows[r];
+    if (ring->part_rows[r] > 0 || s == 0) {
+      // a rank with no rows in some part still has to clear its own outputs once
+      // (pointers of an empty part are never dereferenced; any valid one satisfies the checks)
+      void* dkp = backward ? (ring->dk_parts[r] ? ring->dk_parts[r] : dq_local) : nullptr;
+      void* dvp = backward ? (ring->dv_parts[r] ? ring->dv_parts[r] : dq_local) : nullptr;
+      rc = cp_partial_impl(params, &d, q_local, kp ? kp : q_local, vp ? vp : q_local, d_o_local,
+                           seq_offsets_global, o_local, dq_local, dkp, dvp, s > 0 ? 1 : 0,
+                           ring->accumulate_dkv ? 1 : 0, workspace, workspace_bytes, cs);
+      if (rc != HSTU_OK) return cleanup(rc);
+    }
+    if (s > 0 && hipEventRecord(released[b], cs) != hipSuccess) return cleanup(HSTU_ERR_HIP);
+    if (s > 0 && s + 2 < cp) {
+      rc = fetch(s + 2);  // into the buffer this step read; the transfer waits for released[b]
+      if (rc != HSTU_OK) return cleanup(rc);
+    }
+  }
+  return cleanup(HSTU_OK);
 }
 
 int hstu_cp_reorder(int32_t batch, int64_t total_rows, int32_t cp_size, int32_t rank, int32_t scatter,

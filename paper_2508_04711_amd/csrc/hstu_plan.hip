@@ -99,8 +99,8 @@ constexpr int LDS_BATCH = 2047;
 
 __device__ __forceinline__ void plan_body(const PlanArgs& a);
 
-__global__ void __launch_bounds__(PLAN_THREADS) plan_kernel(PlanArgs a0, PlanArgs a1) {
-  plan_body(blockIdx.x == 0 ? a0 : a1);
+__global__ void __launch_bounds__(PLAN_THREADS) plan_kernel(PlanArgs a0, PlanArgs a1, PlanArgs a2) {
+  plan_body(blockIdx.x == 0 ? a0 : (blockIdx.x == 1 ? a1 : a2));
 }
 
 __device__ __forceinline__ void plan_body(const PlanArgs& a) {
@@ -361,8 +361,9 @@ hipError_t launch_reorder(const ReorderArgs& a, int64_t max_tiles, hipStream_t s
 
 hipError_t launch_plans(const PlanArgs* a, int count, hipStream_t stream) {
   static_assert(NBINS == 2 * PLAN_THREADS, "pass 3 handles two bins per thread");
-  if (count < 1 || count > 2) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(plan_kernel, dim3(count), dim3(PLAN_THREADS), 0, stream, a[0], a[count - 1]);
+  if (count < 1 || count > 3) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(plan_kernel, dim3(count), dim3(PLAN_THREADS), 0, stream, a[0],
+                     a[count > 1 ? 1 : 0], a[count - 1]);
   return hipGetLastError();
 }
 
