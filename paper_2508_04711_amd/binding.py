@@ -289,9 +289,9 @@ def hstu_jagged_attn_cp_partial(q_local: torch.Tensor, k_part: torch.Tensor, v_p
 
 
 def hstu_schedule_tile_rows(dtype_code: int, d_qk: int, d_v: int, side: int, total_rows: int = 1,
-                            num_heads: int = 1) -> int:
+                            num_heads: int = 1, batch: int = 1) -> int:
     """Owner rows per schedule item on `side` for a whole-batch problem of the given size."""
-    p = _params(1, num_heads, d_qk, d_v, 1, 1.0, True, dtype_code, total_rows)
+    p = _params(batch, num_heads, d_qk, d_v, 1, 1.0, True, dtype_code, total_rows)
     return int(load_library().hstu_schedule_tile_rows(ctypes.byref(p), int(side)))
 
 

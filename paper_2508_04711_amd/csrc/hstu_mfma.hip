@@ -378,9 +378,9 @@ __device__ __forceinline__ bool fetch_item(const Plan& plan, int slot, Item& it)
 // 8*(r/4) + 4*hh + r%4 <= rel, rel = query position - block position; applied to the finished
 // P under a wave-uniform branch, so the matrix instructions follow one path whether or not a
 // block is masked.  A block none of whose keys is visible comes out as zeros.
-template <int DQK, int DV, bool PV>
+template <int DQK, int DV, bool PV, class VAddr>
 __device__ __forceinline__ void fwd_step(const char* kn, int bn, const char* vp, int bp,
-                                         const RowAddr<DQK>& ra, const TrAddr<DV>& ca,
+                                         const RowAddr<DQK>& ra, const VAddr& ca,
                                          const bf16x8 (&qreg)[DQK / 16], const f32x16& s_in,
                                          f32x16& s_out, const bf16x8 (&p_prev)[2],
                                          bf16x8 (&p_cur)[2], f32x16 (&oacc)[DV / 32], float c1,
@@ -422,8 +422,11 @@ __device__ __forceinline__ void fwd_step(const char* kn, int bn, const char* vp,
   fence();
 }
 
-template <int DQK, int DV, int NW>
-__global__ void __launch_bounds__(NW * 64, 2) hstu_fwd_bf16(AttnArgs a) {
+// VT: the V tiles come from the transposed copy (plain row reads, one LDS instruction per matrix
+// instruction); otherwise from V itself, row-major, through transposing reads (two per matrix
+// instruction, but no transposed copy has to be built first: the choice for small problems).
+template <int DQK, int DV, int NW, bool VT>
+__device__ __forceinline__ void fwd_body(const AttnArgs& a) {
   constexpr int KB = ST * DQK * 2, VB = ST * DV * 2;
   // NBUF buffers each for the K tiles and the transposed V tiles; copies run PD tiles ahead.
   // Eight waves (one workgroup per CU) use three, four waves (two workgroups per CU) two.
@@ -448,6 +451,7 @@ __global__ void __launch_bounds__(NW * 64, 2) hstu_fwd_bf16(AttnArgs a) {
   const __bf16* kg = (const __bf16*)a.k + h * DQK;
   const int64_t tcols = (int64_t)ST * a.plan.max_stiles;           // columns of the transposed copy
   const __bf16* vtg = (const __bf16*)a.vt + (int64_t)h * DV * tcols;  // V^T of this head: [DV][tcols]
+  const __bf16* vg = (const __bf16*)a.v + h * DV;
 
   const int orow = wave * 32 + n;  // this lane's owner row inside the tile
   const bool wave_on = wave * 32 < it.nrows;
@@ -472,7 +476,8 @@ __global__ void __launch_bounds__(NW * 64, 2) hstu_fwd_bf16(AttnArgs a) {
   };
   auto copy_v = [&](int t, int buf) {
     const TileRef r = tile_ref(it, st, t);
-    ttile_copy_async<DV, NW>(vbuf(buf), vtg + r.tcol, tcols, wave, lane);
+    if (VT) ttile_copy_async<DV, NW>(vbuf(buf), vtg + r.tcol, tcols, wave, lane);
+    else tile_copy_async<DV, NW>(vbuf(buf), vg + (int64_t)r.row * sv, sv, r.valid, wave, lane);
   };
   // Position of block i (i in [0, NB)); positions grow with i.
   auto block_pos = [&](int i) { return tile_ref(it, st, i >> 1).pos + (i & 1) * 32; };
@@ -480,9 +485,10 @@ __global__ void __launch_bounds__(NW * 64, 2) hstu_fwd_bf16(AttnArgs a) {
   auto block_on = [&](int i) { return wave_on && i < NB && (!a.causal || block_pos(i) <= q_hi); };
 
   RowAddr<DQK> ra;
-  TrAddr<DV> ca;
   ra.init(n, hh);
-  ca.init(n, hh);
+  typename std::conditional<VT, TrAddr<DV>, ColAddr<DV>>::type ca;
+  if constexpr (VT) ca.init(n, hh); else ca.init(lane);
+  static_assert(tile_loads<DV>() == DV / 8, "both kinds of V tile take the same number of loads");
   // wave-wide loads one wave issues per iteration (the in-flight count the waits below allow)
   constexpr int LPT = (tile_loads<DQK>() + NW - 1) / NW + (DV / 8 + NW - 1) / NW;
 
@@ -565,6 +571,15 @@ __global__ void __launch_bounds__(NW * 64, 2) hstu_fwd_bf16(AttnArgs a) {
   if (orow < it.nrows)
     store_owner_major<DV>(a.o, ((int64_t)it.row0 + orow) * sv + h * DV, oacc, a.alpha * a.inv_n, hh,
                           a.accumulate, a.out_f32);
+}
+
+template <int DQK, int DV, int NW>
+__global__ void __launch_bounds__(NW * 64, 2) hstu_fwd_bf16(AttnArgs a) {
+  fwd_body<DQK, DV, NW, true>(a);
+}
+template <int DQK, int DV, int NW>
+__global__ void __launch_bounds__(NW * 64, 2) hstu_fwd_rowv_bf16(AttnArgs a) {
+  fwd_body<DQK, DV, NW, false>(a);
 }
 
 // =============================================================================================
@@ -1032,6 +1047,10 @@ hipError_t launch_transpose_bf16(const void* src, void* dst, const Plan& plan, i
 }
 
 hipError_t launch_fwd_bf16(const AttnArgs& a, int d_qk, int d_v, hipStream_t stream) {
+  if (a.vt == nullptr) {  // no transposed copy of V was built
+    if (a.waves != 4) return hipErrorInvalidValue;
+    HSTU_DISPATCH_D(hstu_fwd_rowv_bf16, 4);
+  }
   if (a.waves == 8) HSTU_DISPATCH_D(hstu_fwd_bf16, 8);
   if (a.waves == 4) HSTU_DISPATCH_D(hstu_fwd_bf16, 4);
   return hipErrorInvalidValue;

@@ -93,9 +93,33 @@ __device__ inline int block_scan(int v, int* buf, int* total) {
   return x + base;
 }
 
+// atomicAdd(&hist[bin], 1) for every active lane, returning the old value, with the lanes of a
+// wave that hit the same bin combined into one atomic (batches of short sequences put thousands
+// of items into a handful of bins, and same-address LDS atomics serialise).  Up to four distinct
+// bins per wave are combined, the rest fall back to one atomic per lane.  Must be called by all
+// lanes of the wave.
+__device__ inline int combined_atomic_inc(int* hist, int bin, bool active) {
+  const int lane = threadIdx.x & 63;
+  int pos = -1;
+  for (int round = 0; round < 4; ++round) {
+    const unsigned long long todo = __ballot(active && pos < 0);
+    if (todo == 0) break;
+    const int leader = __ffsll((long long)todo) - 1;
+    const int lb = __shfl(bin, leader, 64);
+    const bool mine = active && pos < 0 && bin == lb;
+    const unsigned long long same = __ballot(mine);
+    int base = 0;
+    if (lane == leader) base = atomicAdd(&hist[lb], __popcll(same));
+    base = __shfl(base, leader, 64);
+    if (mine) pos = base + __popcll(same & ((1ull << lane) - 1ull));
+  }
+  if (active && pos < 0) pos = atomicAdd(&hist[bin], 1);
+  return pos;
+}
+
 // Per-sequence arrays are kept in LDS when the batch fits (the common case) so that the binary
 // searches and base lookups of the later passes do not pay global-memory latency.
-constexpr int LDS_BATCH = 2047;
+constexpr int LDS_BATCH = 6143;
 
 __device__ __forceinline__ void plan_body(const PlanArgs& a);
 
@@ -184,7 +208,11 @@ __device__ __forceinline__ void plan_body(const PlanArgs& a) {
   }
 
   // ---- pass 2: describe every item, histogram its cost -----------------------------------
-  for (int i = tid; i < num_items; i += PLAN_THREADS) {
+  for (int i0 = 0; i0 < num_items; i0 += PLAN_THREADS) {
+    const int i = i0 + tid;
+    const bool active = i < num_items;
+    int bin = 0;
+    if (active) {
     int lo = 0, hi = a.batch;  // largest b with tile_base[b] <= i
     while (hi - lo > 1) {
       const int mid = (lo + hi) >> 1;
@@ -206,35 +234,48 @@ __device__ __forceinline__ void plan_body(const PlanArgs& a) {
     it.pos0 = so.pos[u] + t * a.tile;
     // never beyond the rows the caller declared for its buffers
     it.nrows = clampi((long long)a.owner_rows - it.row0, 0, it.nrows);
-    it.nseg = 0;
-    it.cost = 0;
-    for (int g = 0; g < 2; ++g) {
-      it.seg_row0[g] = 0; it.seg_len[g] = 0; it.seg_pos0[g] = 0; it.seg_tcol0[g] = 0;
-    }
+    // The visible streamed segments, compacted to the front.  Written without run-time array
+    // indices so that the item stays in registers (indexed, it would live in scratch memory).
+    int vrow[2] = {0, 0}, vlen[2] = {0, 0}, vpos[2] = {0, 0}, vcol[2] = {0, 0}, vcost[2] = {0, 0};
+    bool von[2] = {false, false};
     int srow = r_streamed[b];
-    for (int g = 0; g < ss.nseg; ++g) {
-      int len = clampi((long long)a.streamed_rows - srow, 0, ss.len[g]);
-      int vis;  // streamed rows that at least one owner row sees
-      if (!a.causal) {
-        vis = len;
-      } else if (a.side == 0) {  // keys at positions <= last query position
-        vis = clampi((long long)it.pos0 + it.nrows - ss.pos[g], 0, len);
-      } else {                   // queries at positions >= first key position
-        vis = len - clampi((long long)it.pos0 - ss.pos[g], 0, len);
+#pragma unroll
+    for (int g = 0; g < 2; ++g) {
+      if (g < ss.nseg) {
+        const int len = clampi((long long)a.streamed_rows - srow, 0, ss.len[g]);
+        int vis;  // streamed rows that at least one owner row sees
+        if (!a.causal) {
+          vis = len;
+        } else if (a.side == 0) {  // keys at positions <= last query position
+          vis = clampi((long long)it.pos0 + it.nrows - ss.pos[g], 0, len);
+        } else {                   // queries at positions >= first key position
+          vis = len - clampi((long long)it.pos0 - ss.pos[g], 0, len);
+        }
+        von[g] = it.nrows > 0 && vis > 0;
+        vrow[g] = srow; vlen[g] = len; vpos[g] = ss.pos[g];
+        vcol[g] = STILE * (r_stile[b] + (g ? (ss.len[0] + STILE - 1) / STILE : 0));
+        vcost[g] = (vis + 31) >> 5;
+        srow += ss.len[g];
       }
-      if (it.nrows > 0 && vis > 0) {
-        const int n = it.nseg++;
-        it.seg_row0[n] = srow; it.seg_len[n] = len; it.seg_pos0[n] = ss.pos[g];
-        it.seg_tcol0[n] = STILE * (r_stile[b] + (g ? (ss.len[0] + STILE - 1) / STILE : 0));
-        it.cost += (vis + 31) >> 5;
-      }
-      srow += ss.len[g];
     }
+    const bool first1 = !von[0] && von[1];  // only the second segment is visible: it moves to slot 0
+    it.nseg = (von[0] ? 1 : 0) + (von[1] ? 1 : 0);
+    it.cost = (von[0] ? vcost[0] : 0) + (von[1] ? vcost[1] : 0);
+    it.seg_row0[0] = von[0] ? vrow[0] : (first1 ? vrow[1] : 0);
+    it.seg_len[0] = von[0] ? vlen[0] : (first1 ? vlen[1] : 0);
+    it.seg_pos0[0] = von[0] ? vpos[0] : (first1 ? vpos[1] : 0);
+    it.seg_tcol0[0] = von[0] ? vcol[0] : (first1 ? vcol[1] : 0);
+    const bool second = von[0] && von[1];
+    it.seg_row0[1] = second ? vrow[1] : 0;
+    it.seg_len[1] = second ? vlen[1] : 0;
+    it.seg_pos0[1] = second ? vpos[1] : 0;
+    it.seg_tcol0[1] = second ? vcol[1] : 0;
     it.pad[0] = it.pad[1] = it.pad[2] = 0;
     a.items[i] = it;
-    int bin = it.cost >> a.cost_shift;
+    bin = it.cost >> a.cost_shift;
     if (bin > NBINS - 1) bin = NBINS - 1;
-    atomicAdd(&hist[NBINS - 1 - bin], 1);  // reversed: heavy items get the low indices
+    }
+    combined_atomic_inc(hist, NBINS - 1 - bin, active);  // reversed: heavy items get the low indices
   }
   __syncthreads();
 
@@ -249,11 +290,13 @@ __device__ __forceinline__ void plan_body(const PlanArgs& a) {
   __syncthreads();
 
   // ---- pass 4: scatter item indices into schedule order ----------------------------------
-  for (int i = tid; i < num_items; i += PLAN_THREADS) {
-    int bin = a.items[i].cost >> a.cost_shift;
+  for (int i0 = 0; i0 < num_items; i0 += PLAN_THREADS) {
+    const int i = i0 + tid;
+    const bool active = i < num_items;
+    int bin = active ? a.items[i].cost >> a.cost_shift : 0;
     if (bin > NBINS - 1) bin = NBINS - 1;
-    const int pos = atomicAdd(&hist[NBINS - 1 - bin], 1);
-    a.order[pos] = i;
+    const int pos = combined_atomic_inc(hist, NBINS - 1 - bin, active);
+    if (active) a.order[pos] = i;
   }
   if (tid == 0) {
     a.header[0] = num_items;

@@ -197,7 +197,7 @@ def test_large_batch_of_short_sequences():
     # allowance of 2^-7 instead (operand rounding plus output rounding).
     lib = _lib()
     rng = np.random.default_rng(77)
-    lengths = [int(x) for x in rng.integers(0, 24, size=2600)]
+    lengths = [int(x) for x in rng.integers(0, 24, size=6500)]
     w32 = workloads.custom("many_short", lengths, 1, 32, 32, 24, dtype="f32", scale=1.0, seed=5)
     print("many_short", w32.total_rows, flush=True)
     _run_full(w32, causal=True, backward=True)

@@ -66,6 +66,11 @@ CASES = [
     ([1, 0, 129, 128, 127, 0, 700, 3], True),
     ([300, 5, 260], False),
     (list(np.random.default_rng(5).integers(0, 600, size=70)), True),
+    # batches larger than one pass of the schedule kernel's 1024 threads, kept in LDS ...
+    (list(np.random.default_rng(6).integers(0, 300, size=1500)), True),
+    (list(np.random.default_rng(7).integers(32, 257, size=4096)), True),
+    # ... and larger than what it keeps in LDS (per-sequence bases in the workspace)
+    (list(np.random.default_rng(8).integers(0, 40, size=7000)), True),
 ]
 
 
@@ -76,12 +81,15 @@ def test_full_attention_schedule(lengths, causal, side):
     lengths = [int(x) for x in lengths]
     T = sum(lengths)
     off = torch.tensor(np.concatenate([[0], np.cumsum(lengths)]), dtype=torch.int32, device="cuda")
-    tile = lib.hstu_schedule_tile_rows(0, 128, 128, side, T, 2)
+    tile = lib.hstu_schedule_tile_rows(0, 128, 128, side, T, 2, len(lengths))
     got = lib.hstu_debug_dump_schedule(off, T, 2, 128, 128, causal, 0, side)
     want = _expected_items(lengths, tile, causal, side)
     assert sorted(map(tuple, got.tolist())) == sorted(want)
     costs = got[:, 10]
-    assert np.all(costs[:-1] >= costs[1:]), "heavy tiles first"
+    # heavy tiles first, unless even the heaviest tile is small against what one of the 512
+    # workgroup slots gets in total: then the library keeps the natural order, and any order is fine
+    if costs.max() * 8 * 512 > costs.sum() * 2:
+        assert np.all(costs[:-1] >= costs[1:]), "heavy tiles first"
     covered = np.zeros(T, dtype=np.int64)
     for it in got:
         covered[it[0]:it[0] + it[1]] += 1
