@@ -114,9 +114,12 @@ def test_workspace_query(lib):
     assert vt < sizes[0] < 1.2 * vt and 0 < sizes[1] < (1 << 20) and vt < sizes[2] < 1.5 * vt
     assert lib.hstu_jagged_attn_workspace_bytes(ctypes.byref(p), 9) == 0
     assert lib.hstu_jagged_attn_workspace_bytes(ctypes.byref(_params(binding, d_v=5)), 0) == 0
-    # grows with the batch and with the rows, not with the heads
-    big = _params(binding, batch=1000, total_rows=10 ** 6, d_qk=128, d_v=128)
+    # grows with the batch and with the rows
+    big = _params(binding, batch=500, total_rows=10 ** 6, d_qk=128, d_v=128)
     assert lib.hstu_jagged_attn_workspace_bytes(ctypes.byref(big), 0) > sizes[0]
+    # batches of short sequences (mean length <= 1024) need no transposed copy: schedules only
+    short = _params(binding, batch=4096, total_rows=600000, d_qk=128, d_v=128)
+    assert 0 < lib.hstu_jagged_attn_workspace_bytes(ctypes.byref(short), 0) < (4 << 20)
 
 
 def test_validate_offsets_host(lib):
