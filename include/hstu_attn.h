@@ -35,8 +35,9 @@
  *     asynchronous on `hip_stream` (a hipStream_t, NULL = the default stream)
  *     and calls on different streams with different workspaces may overlap.
  *   - Environment: HSTU_ATTN_FWD_TILE=128 or 256 overrides the query-tile height the bf16
- *     forward pass picks from the problem size (testing and tuning only; results are the same
- *     to rounding).
+ *     forward pass picks from the problem size, and makes it use the transposed copy of V
+ *     whatever the mean sequence length (testing and tuning only; results are the same to
+ *     rounding; set it before the workspace query too, which it affects).
  *   - Return value: HSTU_OK (0) or a negative hstu_status.  Nothing is launched
  *     when an error is returned.  batch == 0 or total_rows == 0 is HSTU_OK and
  *     launches nothing.  No exception or abort crosses this boundary.
@@ -197,7 +198,9 @@ int hstu_cp_reorder(int32_t batch, int64_t total_rows, int32_t cp_size, int32_t 
                     void* hip_stream);
 
 /* Bytes of workspace the given entry point needs for `params` (an upper bound
- * that depends on batch, total_rows and num_heads only; 0 on invalid params).
+ * that depends on batch, total_rows, num_heads, d_v and dtype only; 0 on invalid params).
+ * Schedules, plus for bf16 forward passes over batches whose mean sequence length
+ * total_rows / batch exceeds 1024 a transposed copy of V.
  * `which` is a hstu_ws_kind. */
 size_t hstu_jagged_attn_workspace_bytes(const hstu_attn_params* params, int which);
 
