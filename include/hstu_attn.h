@@ -38,6 +38,9 @@
  *     forward pass picks from the problem size, and makes it use the transposed copy of V
  *     whatever the mean sequence length (testing and tuning only; results are the same to
  *     rounding; set it before the workspace query too, which it affects).
+ *     HSTU_ATTN_NO_SPLIT (any value) keeps the forward and dQ passes from cutting heavy query
+ *     tiles along the keys when a problem has too few tiles to fill the chip; with it the
+ *     result of a query row does not depend on how many other rows the call has (bit for bit).
  *   - Return value: HSTU_OK (0) or a negative hstu_status.  Nothing is launched
  *     when an error is returned.  batch == 0 or total_rows == 0 is HSTU_OK and
  *     launches nothing.  No exception or abort crosses this boundary.
@@ -232,7 +235,7 @@ int hstu_debug_dump_schedule(const hstu_attn_params* params, const hstu_cp_desc*
  *   begin: max_records in [1, 65536]; launches beyond it are not recorded.
  *   end:   waits for the recorded launches, writes per launch, in launch order, its kind
  *          (0 forward, 1 dk/dv pass, 2 dq pass, 3 schedule build, 4 transposed copy,
- *          5 reorder) and its duration in
+ *          5 reorder, 6 sum of the partial results of split tiles) and its duration in
  *          milliseconds; returns the number written (<= capacity) or a status < 0.
  */
 int hstu_debug_timing_begin(int max_records);

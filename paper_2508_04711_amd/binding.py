@@ -297,18 +297,20 @@ def hstu_schedule_tile_rows(dtype_code: int, d_qk: int, d_v: int, side: int, tot
 
 def hstu_debug_dump_schedule(seq_offsets: torch.Tensor, total_rows: int, num_heads: int, d_qk: int,
                              d_v: int, causal: bool, dtype_code: int, side: int,
-                             cp: Optional[Tuple[int, int, int, int, int]] = None) -> np.ndarray:
+                             cp: Optional[Tuple[int, int, int, int, int]] = None,
+                             max_len: int = 1) -> np.ndarray:
     """The device-built schedule as an int32 array [n_items, 12] in schedule order.
 
-    cp = (cp_size, q_rank, kv_rank, q_rows, kv_rows) for a context-parallel problem.
+    cp = (cp_size, q_rank, kv_rank, q_rows, kv_rows) for a context-parallel problem.  The last
+    column is 0, or p > 0 for an item that covers a part of its tile's keys (partial slot p - 1).
     """
     B = seq_offsets.numel() - 1
-    p = _params(B, num_heads, d_qk, d_v, 1, 1.0, causal, dtype_code, total_rows)
+    p = _params(B, num_heads, d_qk, d_v, max_len, 1.0, causal, dtype_code, total_rows)
     desc = None
     if cp is not None:
         desc = _CpDesc(int(cp[0]), int(cp[1]), int(cp[2]), 0, int(cp[3]), int(cp[4]))
     ws = _workspace(p, HSTU_WS_CP if cp is not None else HSTU_WS_FWD, None, seq_offsets.device)
-    max_items = int(total_rows) // 32 + 2 * B + 8
+    max_items = int(total_rows) // 32 + 2 * B + 8 + 2048
     buf = np.zeros((max_items, 12), dtype=np.int32)
     n = load_library().hstu_debug_dump_schedule(
         ctypes.byref(p), ctypes.byref(desc) if desc is not None else None, int(side),
@@ -319,7 +321,7 @@ def hstu_debug_dump_schedule(seq_offsets: torch.Tensor, total_rows: int, num_hea
     return buf[:n].copy()
 
 
-KERNEL_KINDS = {0: "fwd", 1: "dkdv", 2: "dq", 3: "plan", 4: "transpose", 5: "reorder"}
+KERNEL_KINDS = {0: "fwd", 1: "dkdv", 2: "dq", 3: "plan", 4: "transpose", 5: "reorder", 6: "reduce"}
 
 
 def hstu_debug_timing_begin(max_records: int = 4096) -> None:

@@ -86,7 +86,9 @@ struct SideSpec {
 
 struct BuiltPlan {
   Plan plan;
-  int64_t max_items;
+  int64_t max_items;  // items the kernels may see (grid bound), parts of split tiles included
+  int64_t max_tiles;  // owner tiles (bound on the reduce table)
+  int split;          // parts an owner tile may be cut into (1: none)
   size_t end;
   int waves;
 };
@@ -103,8 +105,47 @@ int64_t stiles_bound(const hstu_attn_params* p, const SideSpec& s) {
   return max_items_bound(s.streamed_rows, p->batch, s.ssegs, 64);
 }
 
+// Query-side passes (forward, dQ) on a problem with too few owner tiles to fill the chip cut
+// their heavy tiles along the keys into up to this many parts, each an item of its own that
+// writes an fp32 partial result; a small kernel then sums the parts in a fixed order.  What is
+// gained: with fewer workgroups than slots the pass lasts as long as its heaviest tile, which
+// under a causal mask sees twice the average number of keys (a context-parallel rank's share
+// and small batches of long sequences are such problems).
+constexpr int SPLIT_BLOCKS = 64;  // a part covers at least this many visible 32-row blocks
+int split_of(const hstu_attn_params* p, const SideSpec& s) {
+  if (p->dtype != HSTU_BF16 || s.side != 0 || getenv("HSTU_ATTN_NO_SPLIT")) return 1;
+  // no sequence is long enough for two parts (when the lengths respect max_len)
+  if ((int64_t)p->max_len < 2 * SPLIT_BLOCKS * 32) return 1;
+  const int64_t wgs = items_bound(p, s) * p->num_heads;
+  const int64_t slots = pass_waves(p, s.pass, s.owner_rows) == 8 ? 256 : 512;
+  // Measured on the context-parallel workload (548 workgroups for 512 slots): two parts of at
+  // least 64 blocks 574 TFLOP/s for the step, four parts of 16 blocks 522, none 507; on the
+  // 16-sequence workload (1224 workgroups) splitting loses to the cost of the partial results.
+  const int64_t n = (2 * slots + wgs - 1) / wgs;
+  return n < 1 ? 1 : (n > 8 ? 8 : (int)n);
+}
+
+// Bounds for the workspace query that hold for every number of owner rows up to s.owner_rows
+// (a context-parallel rank's share is not known when the workspace is sized):
+// tiles * split <= tiles + 2 * slots / heads + 1 because split <= 2 * slots / (tiles * heads) + 1.
+int64_t split_items_bound(const hstu_attn_params* p, const SideSpec& s) {
+  const int64_t tiles = items_bound(p, s);
+  if (p->dtype != HSTU_BF16 || s.side != 0 || getenv("HSTU_ATTN_NO_SPLIT")) return tiles;
+  return tiles + 2 * 512 / p->num_heads + 1;
+}
+
 size_t plan_bytes(const hstu_attn_params* p, const SideSpec& s, size_t base) {
-  return plan_layout(base, p->batch, items_bound(p, s), stiles_bound(p, s)).end;
+  return plan_layout(base, p->batch, split_items_bound(p, s), stiles_bound(p, s), items_bound(p, s)).end;
+}
+
+// Bytes of the partial results of a pass whose outputs have head dimension d: exact for a call
+// (slots = the schedule's item bound), an upper bound for the workspace query.
+size_t partial_bytes(const hstu_attn_params* p, int64_t slots, int tile, int d) {
+  return align_up((size_t)slots * p->num_heads * tile * d * 4, 256);
+}
+size_t partial_bytes_bound(const hstu_attn_params* p, const SideSpec& s, int d) {
+  if (split_items_bound(p, s) == items_bound(p, s)) return 0;
+  return partial_bytes(p, split_items_bound(p, s), 256, d);
 }
 
 // Bytes of one transposed copy of a streamed tensor with head dimension d (bf16 only).
@@ -117,11 +158,12 @@ size_t tcopy_bytes(const hstu_attn_params* p, const SideSpec& s, int d) {
 // its build (launched by launch_built).
 int prepare_plan(const hstu_attn_params* p, int cp_size, const SideSpec& s, const int32_t* off,
                  char* ws, size_t ws_bytes, size_t base, PlanArgs* args, BuiltPlan* out) {
-  const int64_t max_items = items_bound(p, s), max_stiles = stiles_bound(p, s);
+  const int split = split_of(p, s);
+  const int64_t max_tiles = items_bound(p, s), max_items = max_tiles * split, max_stiles = stiles_bound(p, s);
   if (max_items * p->num_heads >= (1ll << 31) || max_stiles * p->num_heads >= (1ll << 31) ||
       max_stiles * 64 * 2 * 128 >= (1ll << 31))  // transposed rows are addressed with 32-bit byte offsets
     return HSTU_ERR_BAD_SHAPE;
-  const PlanLayout l = plan_layout(base, p->batch, max_items, max_stiles);
+  const PlanLayout l = plan_layout(base, p->batch, max_items, max_stiles, max_tiles);
   if (l.end > ws_bytes) return HSTU_ERR_WORKSPACE_TOO_SMALL;
   PlanArgs a;
   a.off = off;
@@ -150,6 +192,9 @@ int prepare_plan(const hstu_attn_params* p, int cp_size, const SideSpec& s, cons
   const int64_t per_slot = s.owner_rows * p->num_heads / 32 / 512;
   if ((longest / 32 + 4) * 8 < per_slot) shift = 30;
   a.cost_shift = shift;
+  a.split_max = split;
+  a.split_blocks = SPLIT_BLOCKS;
+  a.red = reinterpret_cast<int32_t*>(ws + l.red);
   a.header = reinterpret_cast<int32_t*>(ws + l.header);
   a.owner_base = reinterpret_cast<int32_t*>(ws + l.owner_base);
   a.streamed_base = reinterpret_cast<int32_t*>(ws + l.streamed_base);
@@ -163,8 +208,11 @@ int prepare_plan(const hstu_attn_params* p, int cp_size, const SideSpec& s, cons
   out->plan.order = a.order;
   out->plan.items = a.items;
   out->plan.ttile = a.ttile;
+  out->plan.red = a.red;
   out->plan.max_stiles = a.max_stiles;
   out->max_items = max_items;
+  out->max_tiles = max_tiles;
+  out->split = split;
   out->waves = pass_waves(p, s.pass, s.owner_rows);
   out->end = l.end;
   return HSTU_OK;
@@ -230,6 +278,27 @@ int run_pass(const hstu_attn_params* p, int pass, const AttnArgs& a, hipStream_t
   return e == hipSuccess ? HSTU_OK : HSTU_ERR_HIP;
 }
 
+// A query-side pass (forward or dQ) whose schedule may contain parts of split tiles: carves the
+// partial results out of the workspace at *base, runs the pass, then sums the parts into `out`
+// (head dimension d).
+int run_query_pass(const hstu_attn_params* p, int pass, AttnArgs& a, const BuiltPlan& bp,
+                   const SideSpec& s, void* out, int d, char* ws, size_t ws_bytes, size_t* base,
+                   hipStream_t stream) {
+  a.partial = nullptr;
+  (void)s;
+  if (bp.split > 1) {
+    const size_t at = align_up(*base, 256), bytes = partial_bytes(p, bp.max_items, 32 * bp.waves, d);
+    if (at + bytes > ws_bytes) return HSTU_ERR_WORKSPACE_TOO_SMALL;
+    a.partial = reinterpret_cast<float*>(ws + at);
+    *base = at + bytes;
+  }
+  int rc = run_pass(p, pass, a, stream);
+  if (rc != HSTU_OK || bp.split <= 1) return rc;
+  TimedLaunch timed(6, stream);
+  return launch_reduce_partials(bp.plan, bp.max_tiles, a.partial, out, p->num_heads, d, 32 * bp.waves,
+                                a.accumulate, a.out_f32, stream) == hipSuccess ? HSTU_OK : HSTU_ERR_HIP;
+}
+
 SideSpec full_side(const hstu_attn_params* p, int side, int pass) {
   return SideSpec{side, pass, -1, -1, p->total_rows, p->total_rows, 1, 1};
 }
@@ -291,24 +360,25 @@ size_t hstu_jagged_attn_workspace_bytes(const hstu_attn_params* params, int whic
   const hstu_attn_params* p = params;
   size_t end = 0;
   // Each pass: its schedule, then the transposed copies of the tensors it streams (bf16 only).
-  auto pass_bytes = [&](const SideSpec& s, int d_a, int d_b) {
+  // d_t: head dimension of the transposed copy, d_p: of the partial results (0: none)
+  auto pass_bytes = [&](const SideSpec& s, int d_t, int d_p) {
     end = plan_bytes(p, s, end);
-    if (d_a) end = align_up(end, 256) + tcopy_bytes(p, s, d_a);
-    if (d_b) end = align_up(end, 256) + tcopy_bytes(p, s, d_b);
+    if (d_t) end = align_up(end, 256) + tcopy_bytes(p, s, d_t);
+    if (d_p) end = align_up(end, 256) + partial_bytes_bound(p, s, d_p);
   };
   if (which == HSTU_WS_FWD) {
-    pass_bytes(full_side(p, 0, PASS_FWD), p->d_v, 0);
+    pass_bytes(full_side(p, 0, PASS_FWD), p->d_v, p->d_v);
   } else if (which == HSTU_WS_BWD) {
     pass_bytes(full_side(p, 1, PASS_DKDV), 0, 0);
-    pass_bytes(full_side(p, 0, PASS_DQ), 0, 0);
+    pass_bytes(full_side(p, 0, PASS_DQ), 0, p->d_qk);
   } else if (which == HSTU_WS_CP) {
     // rank-local sides never hold more rows than the whole batch
     SideSpec s{0, PASS_FWD, 0, 0, p->total_rows, p->total_rows, 2, 2};
-    pass_bytes(s, p->d_v, 0);
+    pass_bytes(s, p->d_v, p->d_v);
     s.pass = PASS_DKDV; s.side = 1;
     pass_bytes(s, 0, 0);
     s.pass = PASS_DQ; s.side = 0;
-    pass_bytes(s, 0, 0);
+    pass_bytes(s, 0, p->d_qk);
   } else {
     return 0;
   }
@@ -337,7 +407,8 @@ int hstu_jagged_attn_fwd(const hstu_attn_params* params, const void* q, const vo
   rc = make_tcopy(params, full_side(params, 0, PASS_FWD), bp, v, params->d_v, (char*)workspace,
                   workspace_bytes, &base, stream, &a.vt);
   if (rc != HSTU_OK) return rc;
-  return run_pass(params, PASS_FWD, a, stream);
+  return run_query_pass(params, PASS_FWD, a, bp, full_side(params, 0, PASS_FWD), o, params->d_v,
+                        (char*)workspace, workspace_bytes, &base, stream);
 }
 
 int hstu_jagged_attn_bwd(const hstu_attn_params* params, const void* q, const void* k,
@@ -371,7 +442,9 @@ int hstu_jagged_attn_bwd(const hstu_attn_params* params, const void* q, const vo
   if (rc != HSTU_OK) return rc;
   AttnArgs b = base_args(params, pq, 0);
   b.q = q; b.k = k; b.v = v; b.d_o = d_o; b.dq = dq;
-  return run_pass(params, PASS_DQ, b, stream);
+  size_t base = pq.end;
+  return run_query_pass(params, PASS_DQ, b, pq, full_side(params, 0, PASS_DQ), dq, params->d_qk,
+                        (char*)workspace, workspace_bytes, &base, stream);
 }
 
 // The partial of one (query rank, key rank) pair.  acc_q: add to o_local / dq_local;
@@ -405,13 +478,14 @@ static int cp_partial_impl(const hstu_attn_params* params, const hstu_cp_desc* c
   PlanArgs pa[3];
   BuiltPlan pf, pk, pq;
   int np = 0;
-  size_t base = 0, tbase = 0;
+  size_t base = 0, tbase = 0, qbase = 0;
+  const SideSpec sf = cp_side(params, cp, 0, PASS_FWD), sq = cp_side(params, cp, 0, PASS_DQ);
   if (do_f) {
-    const SideSpec sf = cp_side(params, cp, 0, PASS_FWD);
     rc = prepare_plan(params, cp->cp_size, sf, seq_offsets_global, ws, workspace_bytes, base, &pa[np++], &pf);
     if (rc != HSTU_OK) return rc;
-    tbase = pf.end;  // the transposed copy of V follows its schedule
+    tbase = pf.end;  // the transposed copy of V and the partial results follow the schedule
     base = align_up(pf.end, 256) + tcopy_bytes(params, sf, params->d_v);
+    if (pf.split > 1) base = align_up(base, 256) + partial_bytes(params, pf.max_items, 32 * pf.waves, params->d_v);
   }
   if (do_k) {
     rc = prepare_plan(params, cp->cp_size, cp_side(params, cp, 1, PASS_DKDV), seq_offsets_global, ws,
@@ -420,9 +494,9 @@ static int cp_partial_impl(const hstu_attn_params* params, const hstu_cp_desc* c
     base = pk.end;
   }
   if (do_q) {
-    rc = prepare_plan(params, cp->cp_size, cp_side(params, cp, 0, PASS_DQ), seq_offsets_global, ws,
-                      workspace_bytes, base, &pa[np++], &pq);
+    rc = prepare_plan(params, cp->cp_size, sq, seq_offsets_global, ws, workspace_bytes, base, &pa[np++], &pq);
     if (rc != HSTU_OK) return rc;
+    qbase = pq.end;
   }
   if (np == 0) return HSTU_OK;
   rc = launch_built(pa, np, stream);
@@ -430,10 +504,9 @@ static int cp_partial_impl(const hstu_attn_params* params, const hstu_cp_desc* c
   if (do_f) {
     AttnArgs a = base_args(params, pf, acc_q);
     a.q = q_local; a.k = k_part; a.v = v_part; a.o = o_local;
-    rc = make_tcopy(params, cp_side(params, cp, 0, PASS_FWD), pf, v_part, params->d_v, ws,
-                    workspace_bytes, &tbase, stream, &a.vt);
+    rc = make_tcopy(params, sf, pf, v_part, params->d_v, ws, workspace_bytes, &tbase, stream, &a.vt);
     if (rc != HSTU_OK) return rc;
-    rc = run_pass(params, PASS_FWD, a, stream);
+    rc = run_query_pass(params, PASS_FWD, a, pf, sf, o_local, params->d_v, ws, workspace_bytes, &tbase, stream);
     if (rc != HSTU_OK) return rc;
   }
   if (do_k) {
@@ -445,7 +518,7 @@ static int cp_partial_impl(const hstu_attn_params* params, const hstu_cp_desc* c
   if (do_q) {
     AttnArgs b = base_args(params, pq, acc_q);
     b.q = q_local; b.k = k_part; b.v = v_part; b.d_o = d_o_local; b.dq = dq_local;
-    rc = run_pass(params, PASS_DQ, b, stream);
+    rc = run_query_pass(params, PASS_DQ, b, pq, sq, dq_local, params->d_qk, ws, workspace_bytes, &qbase, stream);
     if (rc != HSTU_OK) return rc;
   }
   return HSTU_OK;
@@ -676,7 +749,7 @@ int hstu_debug_dump_schedule(const hstu_attn_params* params, const hstu_cp_desc*
     dst[4] = it.seg_row0[0]; dst[5] = it.seg_row0[1];
     dst[6] = it.seg_len[0]; dst[7] = it.seg_len[1];
     dst[8] = it.seg_pos0[0]; dst[9] = it.seg_pos0[1];
-    dst[10] = it.cost; dst[11] = 0;
+    dst[10] = it.cost; dst[11] = it.part;
   }
   return n;
 }

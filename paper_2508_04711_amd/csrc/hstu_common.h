@@ -21,13 +21,17 @@ struct Item {
   int32_t seg_pos0[2];  // in-sequence position of each segment's first row
   int32_t seg_tcol0[2]; // column of each segment's first row in the transposed streamed copies
   int32_t cost;         // visible 32-row streamed blocks (the sort key)
-  int32_t pad[3];
+  int32_t part;         // 0: the item writes its output rows; p > 0: it covers only a part of the
+                        // streamed rows and writes an fp32 partial result into slot p - 1
+  int32_t pad[2];
 };
 static_assert(sizeof(Item) == 64, "Item is one 64-byte record");
 
 // Device view of a built schedule.
 struct Plan {
-  const int32_t* header;  // [0] = number of items, [1] = number of 64-row streamed tiles
+  const int32_t* header;  // [0] = number of items, [1] = number of 64-row streamed tiles,
+                          // [2] = number of owner tiles whose partial results have to be summed
+  const int32_t* red;     // per such tile: first owner row, rows, first partial slot, slots
   const int32_t* order;   // order[slot] = item index, non-increasing cost
   const Item* items;
   const int32_t* ttile;   // per 64-row streamed tile: first row, valid rows
@@ -36,12 +40,14 @@ struct Plan {
 
 // Byte offsets of one schedule's arrays inside the workspace.
 struct PlanLayout {
-  size_t header, owner_base, streamed_base, tile_base, stile_base, ttile, order, items, end;
+  size_t header, owner_base, streamed_base, tile_base, stile_base, ttile, order, items, red, end;
 };
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-inline PlanLayout plan_layout(size_t base, int64_t batch, int64_t max_items, int64_t max_stiles) {
+// max_items bounds the items the kernels see (parts included), max_tiles the owner tiles.
+inline PlanLayout plan_layout(size_t base, int64_t batch, int64_t max_items, int64_t max_stiles,
+                              int64_t max_tiles = 0) {
   PlanLayout l;
   size_t p = align_up(base, 256);
   l.header = p;        p += 64;
@@ -52,6 +58,7 @@ inline PlanLayout plan_layout(size_t base, int64_t batch, int64_t max_items, int
   l.ttile = p;         p = align_up(p + (size_t)max_stiles * 8, 64);
   l.order = p;         p = align_up(p + (size_t)max_items * 4, 64);
   l.items = p;         p = align_up(p + (size_t)max_items * sizeof(Item), 64);
+  l.red = p;           p = align_up(p + (size_t)max_tiles * 16, 64);
   l.end = p;
   return l;
 }
@@ -74,9 +81,13 @@ struct PlanArgs {
   int32_t causal;
   int32_t owner_rows;     // rows the caller declared for the owner-side buffers
   int32_t streamed_rows;  // rows the caller declared for the streamed-side buffers
-  int32_t max_items;
+  int32_t max_items;      // bound on the items written (parts of split tiles included)
   int32_t max_stiles;     // bound on the 64-row tiles of the streamed side
   int32_t cost_shift;     // cost >> cost_shift selects the sort bin
+  int32_t split_max;      // an owner tile is cut into at most this many parts along its streamed
+                          // rows (1: never); side 0 only
+  int32_t split_blocks;   // ... of at least this many visible 32-row blocks each
+  int32_t* red;           // reduce table (see Plan), split_max > 1 only
   int32_t* header;
   int32_t* owner_base;
   int32_t* streamed_base;
@@ -108,6 +119,7 @@ struct AttnArgs {
   int32_t max_items;
   int32_t waves;    // wavefronts per workgroup (bf16 kernels): owner tile = 32 * waves rows
   int32_t out_f32;  // outputs are fp32 (bf16 kernels only; the fp32 kernels always write fp32)
+  float* partial;   // partial results of split tiles: [slot][head][tile row][d] fp32 (or null)
   float alpha;
   float inv_n;
 };
@@ -141,6 +153,12 @@ struct ReorderArgs {
 };
 // max_tiles: an upper bound on the 64-row tiles of the local layout (the grid's first dimension).
 hipError_t launch_reorder(const ReorderArgs& a, int64_t max_tiles, hipStream_t stream);
+
+// Sums the partial results of split owner tiles (in slot order: deterministic) into `out`
+// [rows, H, d] with the output conventions of the attention kernels.
+hipError_t launch_reduce_partials(const Plan& plan, int64_t max_tiles, const float* partial, void* out,
+                                  int num_heads, int d, int tile_rows, int accumulate, int out_f32,
+                                  hipStream_t stream);
 
 hipError_t launch_fwd_bf16(const AttnArgs& a, int d_qk, int d_v, hipStream_t stream);
 hipError_t launch_dkdv_bf16(const AttnArgs& a, int d_qk, int d_v, hipStream_t stream);

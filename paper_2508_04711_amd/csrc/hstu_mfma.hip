@@ -355,6 +355,7 @@ __device__ __forceinline__ bool fetch_item(const Plan& plan, int slot, Item& it)
     it.seg_tcol0[g] = __builtin_amdgcn_readfirstlane(src->seg_tcol0[g]);
   }
   it.cost = 0;
+  it.part = __builtin_amdgcn_readfirstlane(src->part);
   return it.nrows > 0;
 }
 
@@ -426,18 +427,22 @@ __device__ __forceinline__ void fwd_step(const char* kn, int bn, const char* vp,
 // instruction); otherwise from V itself, row-major, through transposing reads (two per matrix
 // instruction, but no transposed copy has to be built first: the choice for small problems).
 template <int DQK, int DV, int NW, bool VT>
-__device__ __forceinline__ void fwd_body(const AttnArgs& a) {
+__global__ void __launch_bounds__(NW * 64, 2) hstu_fwd_bf16(AttnArgs a) {
   constexpr int KB = ST * DQK * 2, VB = ST * DV * 2;
   // NBUF buffers each for the K tiles and the transposed V tiles; copies run PD tiles ahead.
   // Eight waves (one workgroup per CU) use three, four waves (two workgroups per CU) two.
-  // One array per buffer: the compiler can then see that a copy into one buffer cannot alias
-  // the operand reads from another.
+  // One array per buffer, K and V apart (an iteration reads the K tile of one index and the V
+  // tile of another while copies into the remaining ones are in flight): the compiler can then
+  // see that a copy cannot alias the operand reads, and does not wait for it before them.
   constexpr int NBUF = NW >= 8 ? 3 : 2, PD = NBUF - 1;
-  __shared__ __attribute__((aligned(1024))) char smem0[KB + VB];
-  __shared__ __attribute__((aligned(1024))) char smem1[KB + VB];
-  __shared__ __attribute__((aligned(1024))) char smem2[NBUF > 2 ? KB + VB : 1024];
-  auto kbuf = [&](int b) { return b == 0 ? smem0 : (b == 1 ? smem1 : smem2); };
-  auto vbuf = [&](int b) { return kbuf(b) + KB; };
+  __shared__ __attribute__((aligned(1024))) char kmem0[KB];
+  __shared__ __attribute__((aligned(1024))) char kmem1[KB];
+  __shared__ __attribute__((aligned(1024))) char kmem2[NBUF > 2 ? KB : 1024];
+  __shared__ __attribute__((aligned(1024))) char vmem0[VB];
+  __shared__ __attribute__((aligned(1024))) char vmem1[VB];
+  __shared__ __attribute__((aligned(1024))) char vmem2[NBUF > 2 ? VB : 1024];
+  auto kbuf = [&](int b) { return b == 0 ? kmem0 : (b == 1 ? kmem1 : kmem2); };
+  auto vbuf = [&](int b) { return b == 0 ? vmem0 : (b == 1 ? vmem1 : vmem2); };
 
   const int H = a.num_heads;
   const int slot = blockIdx.x / H, h = blockIdx.x % H;
@@ -568,19 +573,16 @@ __device__ __forceinline__ void fwd_body(const AttnArgs& a) {
   }
 
   // O^T accumulators: lane holds query row n, elements dvb*32 + 8*(r/4) + 4*hh + r%4.
-  if (orow < it.nrows)
-    store_owner_major<DV>(a.o, ((int64_t)it.row0 + orow) * sv + h * DV, oacc, a.alpha * a.inv_n, hh,
-                          a.accumulate, a.out_f32);
+  if (orow < it.nrows) {
+    if (it.part > 0)  // one part of a split tile: an fp32 partial result, summed by the reduce kernel
+      store_owner_major<DV>(a.partial, (((int64_t)(it.part - 1) * H + h) * (NW * 32) + orow) * DV, oacc,
+                            a.alpha * a.inv_n, hh, 0, 1);
+    else
+      store_owner_major<DV>(a.o, ((int64_t)it.row0 + orow) * sv + h * DV, oacc, a.alpha * a.inv_n, hh,
+                            a.accumulate, a.out_f32);
+  }
 }
 
-template <int DQK, int DV, int NW>
-__global__ void __launch_bounds__(NW * 64, 2) hstu_fwd_bf16(AttnArgs a) {
-  fwd_body<DQK, DV, NW, true>(a);
-}
-template <int DQK, int DV, int NW>
-__global__ void __launch_bounds__(NW * 64, 2) hstu_fwd_rowv_bf16(AttnArgs a) {
-  fwd_body<DQK, DV, NW, false>(a);
-}
 
 // =============================================================================================
 // dk/dv pass: owners are key rows (K and V rows in registers), Q and dO are streamed.
@@ -963,9 +965,14 @@ __global__ void __launch_bounds__(NW * 64, 2) hstu_dq_bf16(AttnArgs a) {
   }
 
   // dQ^T accumulators: lane holds query row n, elements c*32 + 8*(r/4) + 4*hh + r%4.
-  if (orow < it.nrows)
-    store_owner_major<DQK>(a.dq, ((int64_t)it.row0 + orow) * sq + h * DQK, dqacc, a.alpha * a.inv_n,
-                           hh, a.accumulate, a.out_f32);
+  if (orow < it.nrows) {
+    if (it.part > 0)
+      store_owner_major<DQK>(a.partial, (((int64_t)(it.part - 1) * H + h) * (NW * 32) + orow) * DQK, dqacc,
+                             a.alpha * a.inv_n, hh, 0, 1);
+    else
+      store_owner_major<DQK>(a.dq, ((int64_t)it.row0 + orow) * sq + h * DQK, dqacc, a.alpha * a.inv_n,
+                             hh, a.accumulate, a.out_f32);
+  }
 }
 
 // =============================================================================================
@@ -1018,18 +1025,18 @@ int waves_bf16(int pass, int64_t owner_rows, int heads) {
   return 4;
 }
 
-#define HSTU_DISPATCH_D(KERNEL, NW)                                                     \
+#define HSTU_DISPATCH_D(KERNEL, NW, ...)                                                \
   do {                                                                                  \
     const dim3 grid((unsigned)((int64_t)a.max_items * a.num_heads)), block(NW * 64);    \
-    if (d_qk == 128 && d_v == 128) hipLaunchKernelGGL((KERNEL<128, 128, NW>), grid, block, 0, stream, a); \
-    else if (d_qk == 64 && d_v == 64) hipLaunchKernelGGL((KERNEL<64, 64, NW>), grid, block, 0, stream, a); \
-    else if (d_qk == 32 && d_v == 32) hipLaunchKernelGGL((KERNEL<32, 32, NW>), grid, block, 0, stream, a); \
-    else if (d_qk == 128 && d_v == 64) hipLaunchKernelGGL((KERNEL<128, 64, NW>), grid, block, 0, stream, a); \
-    else if (d_qk == 64 && d_v == 128) hipLaunchKernelGGL((KERNEL<64, 128, NW>), grid, block, 0, stream, a); \
-    else if (d_qk == 128 && d_v == 32) hipLaunchKernelGGL((KERNEL<128, 32, NW>), grid, block, 0, stream, a); \
-    else if (d_qk == 32 && d_v == 128) hipLaunchKernelGGL((KERNEL<32, 128, NW>), grid, block, 0, stream, a); \
-    else if (d_qk == 64 && d_v == 32) hipLaunchKernelGGL((KERNEL<64, 32, NW>), grid, block, 0, stream, a); \
-    else if (d_qk == 32 && d_v == 64) hipLaunchKernelGGL((KERNEL<32, 64, NW>), grid, block, 0, stream, a); \
+    if (d_qk == 128 && d_v == 128) hipLaunchKernelGGL((KERNEL<128, 128, __VA_ARGS__>), grid, block, 0, stream, a); \
+    else if (d_qk == 64 && d_v == 64) hipLaunchKernelGGL((KERNEL<64, 64, __VA_ARGS__>), grid, block, 0, stream, a); \
+    else if (d_qk == 32 && d_v == 32) hipLaunchKernelGGL((KERNEL<32, 32, __VA_ARGS__>), grid, block, 0, stream, a); \
+    else if (d_qk == 128 && d_v == 64) hipLaunchKernelGGL((KERNEL<128, 64, __VA_ARGS__>), grid, block, 0, stream, a); \
+    else if (d_qk == 64 && d_v == 128) hipLaunchKernelGGL((KERNEL<64, 128, __VA_ARGS__>), grid, block, 0, stream, a); \
+    else if (d_qk == 128 && d_v == 32) hipLaunchKernelGGL((KERNEL<128, 32, __VA_ARGS__>), grid, block, 0, stream, a); \
+    else if (d_qk == 32 && d_v == 128) hipLaunchKernelGGL((KERNEL<32, 128, __VA_ARGS__>), grid, block, 0, stream, a); \
+    else if (d_qk == 64 && d_v == 32) hipLaunchKernelGGL((KERNEL<64, 32, __VA_ARGS__>), grid, block, 0, stream, a); \
+    else if (d_qk == 32 && d_v == 64) hipLaunchKernelGGL((KERNEL<32, 64, __VA_ARGS__>), grid, block, 0, stream, a); \
     else return hipErrorInvalidValue;                                                   \
     return hipGetLastError();                                                           \
   } while (0)
@@ -1049,19 +1056,19 @@ hipError_t launch_transpose_bf16(const void* src, void* dst, const Plan& plan, i
 hipError_t launch_fwd_bf16(const AttnArgs& a, int d_qk, int d_v, hipStream_t stream) {
   if (a.vt == nullptr) {  // no transposed copy of V was built
     if (a.waves != 4) return hipErrorInvalidValue;
-    HSTU_DISPATCH_D(hstu_fwd_rowv_bf16, 4);
+    HSTU_DISPATCH_D(hstu_fwd_bf16, 4, 4, false);
   }
-  if (a.waves == 8) HSTU_DISPATCH_D(hstu_fwd_bf16, 8);
-  if (a.waves == 4) HSTU_DISPATCH_D(hstu_fwd_bf16, 4);
+  if (a.waves == 8) HSTU_DISPATCH_D(hstu_fwd_bf16, 8, 8, true);
+  if (a.waves == 4) HSTU_DISPATCH_D(hstu_fwd_bf16, 4, 4, true);
   return hipErrorInvalidValue;
 }
 hipError_t launch_dkdv_bf16(const AttnArgs& a, int d_qk, int d_v, hipStream_t stream) {
   if (a.waves != 4) return hipErrorInvalidValue;
-  HSTU_DISPATCH_D(hstu_dkdv_bf16, 4);
+  HSTU_DISPATCH_D(hstu_dkdv_bf16, 4, 4);
 }
 hipError_t launch_dq_bf16(const AttnArgs& a, int d_qk, int d_v, hipStream_t stream) {
   if (a.waves != 4) return hipErrorInvalidValue;
-  HSTU_DISPATCH_D(hstu_dq_bf16, 4);
+  HSTU_DISPATCH_D(hstu_dq_bf16, 4, 4);
 }
 
 }  // namespace hstu

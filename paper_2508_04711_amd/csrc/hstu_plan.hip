@@ -208,10 +208,13 @@ __device__ __forceinline__ void plan_body(const PlanArgs& a) {
   }
 
   // ---- pass 2: describe every item, histogram its cost -----------------------------------
+  int carry_sub = 0, carry_red = 0, carry_slot = 0;  // running totals of parts, split tiles, slots
   for (int i0 = 0; i0 < num_items; i0 += PLAN_THREADS) {
     const int i = i0 + tid;
     const bool active = i < num_items;
     int bin = 0;
+    Item it = {};
+    int pvis[2] = {0, 0};
     if (active) {
     int lo = 0, hi = a.batch;  // largest b with tile_base[b] <= i
     while (hi - lo > 1) {
@@ -227,7 +230,6 @@ __device__ __forceinline__ void plan_body(const PlanArgs& a) {
     const int nt0 = (so.len[0] + a.tile - 1) / a.tile;
     const int u = t < nt0 ? 0 : 1;
     if (u) t -= nt0;
-    Item it;
     it.row0 = r_owner[b] + (u ? so.len[0] : 0) + t * a.tile;
     it.nrows = so.len[u] - t * a.tile;
     if (it.nrows > a.tile) it.nrows = a.tile;
@@ -237,6 +239,7 @@ __device__ __forceinline__ void plan_body(const PlanArgs& a) {
     // The visible streamed segments, compacted to the front.  Written without run-time array
     // indices so that the item stays in registers (indexed, it would live in scratch memory).
     int vrow[2] = {0, 0}, vlen[2] = {0, 0}, vpos[2] = {0, 0}, vcol[2] = {0, 0}, vcost[2] = {0, 0};
+    int vvis[2] = {0, 0};
     bool von[2] = {false, false};
     int srow = r_streamed[b];
 #pragma unroll
@@ -255,6 +258,7 @@ __device__ __forceinline__ void plan_body(const PlanArgs& a) {
         vrow[g] = srow; vlen[g] = len; vpos[g] = ss.pos[g];
         vcol[g] = STILE * (r_stile[b] + (g ? (ss.len[0] + STILE - 1) / STILE : 0));
         vcost[g] = (vis + 31) >> 5;
+        vvis[g] = vis;
         srow += ss.len[g];
       }
     }
@@ -270,13 +274,76 @@ __device__ __forceinline__ void plan_body(const PlanArgs& a) {
     it.seg_len[1] = second ? vlen[1] : 0;
     it.seg_pos0[1] = second ? vpos[1] : 0;
     it.seg_tcol0[1] = second ? vcol[1] : 0;
-    it.pad[0] = it.pad[1] = it.pad[2] = 0;
-    a.items[i] = it;
-    bin = it.cost >> a.cost_shift;
-    if (bin > NBINS - 1) bin = NBINS - 1;
+    it.part = 0;
+    it.pad[0] = it.pad[1] = 0;
+    // visible rows of the (compacted) segments, for cutting the tile into parts
+    pvis[0] = von[0] ? vvis[0] : (first1 ? vvis[1] : 0);
+    pvis[1] = second ? vvis[1] : 0;
     }
-    combined_atomic_inc(hist, NBINS - 1 - bin, active);  // reversed: heavy items get the low indices
+    if (a.split_max <= 1) {
+      if (active) a.items[i] = it;
+      bin = it.cost >> a.cost_shift;
+      if (bin > NBINS - 1) bin = NBINS - 1;
+      combined_atomic_inc(hist, NBINS - 1 - bin, active);  // reversed: heavy items get the low indices
+      continue;
+    }
+    // ---- heavy owner tiles are cut along their streamed rows into ns parts of whole 64-row
+    // tiles; each part becomes an item of its own that writes an fp32 partial result
+    const int nt0 = (pvis[0] + STILE - 1) / STILE, nt = nt0 + (pvis[1] + STILE - 1) / STILE;
+    int ns = active ? it.cost / a.split_blocks : 0;
+    if (ns > a.split_max) ns = a.split_max;
+    if (ns > nt) ns = nt;
+    if (active && ns < 1) ns = 1;
+    int tot_n, tot_r, tot_p;
+    const int u0 = carry_sub + block_scan(ns, scan_buf, &tot_n) - ns;
+    const int isr = ns > 1 ? 1 : 0;
+    const int r0 = carry_red + block_scan(isr, scan_buf, &tot_r) - isr;
+    const int p0 = carry_slot + block_scan(isr ? ns : 0, scan_buf, &tot_p) - (isr ? ns : 0);
+    carry_sub += tot_n; carry_red += tot_r; carry_slot += tot_p;
+    if (isr) {
+      a.red[4 * r0] = it.row0; a.red[4 * r0 + 1] = it.nrows; a.red[4 * r0 + 2] = p0; a.red[4 * r0 + 3] = ns;
+    }
+    for (int k = 0; k < a.split_max; ++k) {
+      const bool on = k < ns;
+      Item sub = it;
+      if (on && ns > 1) {
+        const int lo = (int)((long long)k * nt / ns), hi = (int)((long long)(k + 1) * nt / ns);
+        int srow2[2], slen2[2], spos2[2], scol2[2], scost = 0, n2 = 0;
+        bool son[2];
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+          const int base = c ? nt0 : 0, ntc = c ? nt - nt0 : nt0;
+          const int l = clampi(lo - base, 0, ntc), h = clampi(hi - base, 0, ntc);
+          son[c] = h > l;
+          const int skip = l * STILE;
+          int len = it.seg_len[c] - skip;
+          if (len > (h - l) * STILE) len = (h - l) * STILE;
+          int vis = pvis[c] - skip;
+          if (vis > (h - l) * STILE) vis = (h - l) * STILE;
+          srow2[c] = it.seg_row0[c] + skip; slen2[c] = len; spos2[c] = it.seg_pos0[c] + skip;
+          scol2[c] = it.seg_tcol0[c] + skip;
+          if (son[c]) { scost += (vis + 31) >> 5; ++n2; }
+        }
+        const bool f1 = !son[0] && son[1], both = son[0] && son[1];
+        sub.nseg = n2; sub.cost = scost; sub.part = p0 + k + 1;
+        sub.seg_row0[0] = son[0] ? srow2[0] : (f1 ? srow2[1] : 0);
+        sub.seg_len[0] = son[0] ? slen2[0] : (f1 ? slen2[1] : 0);
+        sub.seg_pos0[0] = son[0] ? spos2[0] : (f1 ? spos2[1] : 0);
+        sub.seg_tcol0[0] = son[0] ? scol2[0] : (f1 ? scol2[1] : 0);
+        sub.seg_row0[1] = both ? srow2[1] : 0;
+        sub.seg_len[1] = both ? slen2[1] : 0;
+        sub.seg_pos0[1] = both ? spos2[1] : 0;
+        sub.seg_tcol0[1] = both ? scol2[1] : 0;
+      }
+      const bool emit = on && u0 + k < a.max_items;
+      if (emit) a.items[u0 + k] = sub;
+      bin = sub.cost >> a.cost_shift;
+      if (bin > NBINS - 1) bin = NBINS - 1;
+      combined_atomic_inc(hist, NBINS - 1 - bin, emit);
+    }
   }
+  // items the kernels will see (the scans' totals are the same in every thread)
+  const int items_final = a.split_max > 1 ? (carry_sub < a.max_items ? carry_sub : a.max_items) : num_items;
   __syncthreads();
 
   // ---- pass 3: bin start positions (exclusive scan over the reversed histogram) ----------
@@ -290,17 +357,18 @@ __device__ __forceinline__ void plan_body(const PlanArgs& a) {
   __syncthreads();
 
   // ---- pass 4: scatter item indices into schedule order ----------------------------------
-  for (int i0 = 0; i0 < num_items; i0 += PLAN_THREADS) {
+  for (int i0 = 0; i0 < items_final; i0 += PLAN_THREADS) {
     const int i = i0 + tid;
-    const bool active = i < num_items;
+    const bool active = i < items_final;
     int bin = active ? a.items[i].cost >> a.cost_shift : 0;
     if (bin > NBINS - 1) bin = NBINS - 1;
     const int pos = combined_atomic_inc(hist, NBINS - 1 - bin, active);
     if (active) a.order[pos] = i;
   }
   if (tid == 0) {
-    a.header[0] = num_items;
+    a.header[0] = items_final;
     a.header[1] = num_stiles;
+    a.header[2] = a.split_max > 1 ? carry_red : 0;
   }
 }
 
@@ -399,6 +467,54 @@ hipError_t launch_reorder(const ReorderArgs& a, int64_t max_tiles, hipStream_t s
   if (a.split < 1 || STILE % a.split != 0 || max_tiles * a.split >= (1ll << 31)) return hipErrorInvalidValue;
   hipLaunchKernelGGL(reorder_kernel, dim3((unsigned)(max_tiles * a.split), (unsigned)a.count),
                      dim3(REORDER_THREADS), 0, stream, a);
+  return hipGetLastError();
+}
+
+namespace {
+
+// Sum of the partial results of one split owner tile and head, in slot order.
+__global__ void __launch_bounds__(256) reduce_partials_kernel(Plan plan, const float* partial, void* out,
+                                                              int H, int d, int tile_rows,
+                                                              int accumulate, int out_f32) {
+  const int r = blockIdx.x / H, h = blockIdx.x % H;
+  if (r >= plan.header[2]) return;
+  const int row0 = plan.red[4 * r], nrows = plan.red[4 * r + 1], slot0 = plan.red[4 * r + 2],
+            ns = plan.red[4 * r + 3];
+  const int64_t slot_stride = (int64_t)H * tile_rows * d;
+  const float* src = partial + ((int64_t)slot0 * H + h) * tile_rows * d;
+  const int n4 = nrows * d / 4;
+  for (int i = threadIdx.x; i < n4; i += 256) {
+    float4 acc = *(const float4*)(src + (int64_t)i * 4);
+    for (int k = 1; k < ns; ++k) {
+      const float4 v = *(const float4*)(src + k * slot_stride + (int64_t)i * 4);
+      acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+    }
+    const int row = (i * 4) / d, col = (i * 4) % d;
+    const int64_t e = ((int64_t)(row0 + row) * H + h) * d + col;
+    if (out_f32) {
+      float4* o = (float4*)((float*)out + e);
+      if (accumulate) { const float4 p = *o; acc.x += p.x; acc.y += p.y; acc.z += p.z; acc.w += p.w; }
+      *o = acc;
+    } else {
+      __bf16* o = (__bf16*)out + e;
+      float x[4] = {acc.x, acc.y, acc.z, acc.w};
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        if (accumulate) x[c] += (float)o[c];
+        o[c] = (__bf16)x[c];
+      }
+    }
+  }
+}
+
+}  // namespace
+
+hipError_t launch_reduce_partials(const Plan& plan, int64_t max_tiles, const float* partial, void* out,
+                                  int num_heads, int d, int tile_rows, int accumulate, int out_f32,
+                                  hipStream_t stream) {
+  if (max_tiles < 1 || max_tiles * num_heads >= (1ll << 31)) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)(max_tiles * num_heads)), dim3(256), 0,
+                     stream, plan, partial, out, num_heads, d, tile_rows, accumulate, out_f32);
   return hipGetLastError();
 }
 

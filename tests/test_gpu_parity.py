@@ -217,6 +217,38 @@ def test_large_batch_of_short_sequences():
         assert (np.abs(g - ref) <= 2e-2 * rms + np.abs(ref) * 2.0 ** -7).all(), name
 
 
+@pytest.mark.parametrize("causal", [True, False])
+def test_heavy_tiles_cut_along_the_keys(causal, monkeypatch):
+    # few query tiles and long sequences: the forward and dQ passes cut heavy tiles into parts
+    # that write fp32 partial results, summed by a second kernel; against the oracle, and
+    # against the same passes with the cutting switched off (another summation order)
+    lib = _lib()
+    w = workloads.custom("split", [4700, 300, 4100], 1, 64, 128, max_len=4700, dtype="bf16", seed=31)
+    print("split", causal, flush=True)
+    _run_full(w, causal=causal, backward=True)
+    d = _dev(workloads.values(w))
+    off = torch.from_numpy(w.seq_offsets()).cuda()
+    args = (d["q"], d["k"], d["v"])
+    o = lib.hstu_jagged_attn_fwd(*args, off, w.max_len, w.alpha, causal, out_dtype=torch.float32)
+    dq, dk, dv = lib.hstu_jagged_attn_bwd(*args, d["d_o"], off, w.max_len, w.alpha, causal,
+                                          out_dtype=torch.float32)
+    # accumulate mode goes through the same sum of parts (the one-rank partial is the whole pass)
+    for odt in (torch.float32, torch.bfloat16):
+        o2 = (0.5 * o).to(odt)
+        lib.hstu_jagged_attn_cp_partial(*args, None, off, w.total_rows, w.max_len, w.alpha, causal, 1, 0, 0,
+                                        accumulate=True, out=(o2, None, None, None))
+        tol = 1e-5 if odt == torch.float32 else 2.0 ** -7
+        assert (o2.float() - 1.5 * o).abs().max().item() <= tol * o.abs().max().item() * 1.5
+    monkeypatch.setenv("HSTU_ATTN_NO_SPLIT", "1")
+    o_ref = lib.hstu_jagged_attn_fwd(*args, off, w.max_len, w.alpha, causal, out_dtype=torch.float32)
+    dq_ref, dk_ref, dv_ref = lib.hstu_jagged_attn_bwd(*args, d["d_o"], off, w.max_len, w.alpha, causal,
+                                                      out_dtype=torch.float32)
+    assert torch.equal(dk, dk_ref) and torch.equal(dv, dv_ref)      # the key-side pass is never cut
+    assert not torch.equal(o, o_ref), "the cutting was expected to be active here"
+    for a, b in ((o, o_ref), (dq, dq_ref)):
+        assert (a - b).abs().max().item() <= 1e-5 * b.abs().max().item()
+
+
 def test_accumulate_adds_to_existing_outputs():
     # accumulate = 1 adds to what the output buffers hold (fp32 and bf16 outputs)
     lib = _lib()

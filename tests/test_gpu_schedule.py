@@ -127,3 +127,44 @@ def test_inconsistent_offsets_never_leave_the_declared_rows():
         assert 0 <= it[0] and it[0] + it[1] <= 300
         for g in range(it[3]):
             assert 0 <= it[4 + g] and it[4 + g] + it[6 + g] <= 300
+
+
+@pytest.mark.parametrize("cp", [None, (2, 1, -1)])
+def test_heavy_query_tiles_are_cut_along_the_keys(cp):
+    """Few query tiles, long sequences: heavy tiles appear as several items, each covering a run of
+    whole 64-key tiles, which together cover the tile's visible keys exactly once."""
+    import oracle
+    import paper_2508_04711_amd as lib
+    lengths = [9000, 5000, 700, 64]
+    T = sum(lengths)
+    off_np = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int32)
+    off = torch.from_numpy(off_np).cuda()
+    if cp is None:
+        got = lib.hstu_debug_dump_schedule(off, T, 1, 128, 128, True, 0, 0, max_len=9000)
+    else:
+        nq = len(oracle.cp_global_rows(off_np, cp[0], cp[1]))
+        got = lib.hstu_debug_dump_schedule(off, T, 1, 128, 128, True, 0, 0,
+                                           cp=(cp[0], cp[1], cp[2], nq, T), max_len=9000)
+    parts = got[got[:, 11] > 0]
+    whole = got[got[:, 11] == 0]
+    assert len(parts) > 0, "the long sequences must produce split tiles"
+    assert len(set(parts[:, 11].tolist())) == len(parts), "every part has a partial slot of its own"
+    by_tile = {}
+    for it in parts:
+        by_tile.setdefault((int(it[0]), int(it[1]), int(it[2])), []).append(it)
+    for (row0, nrows, pos0), its in by_tile.items():
+        assert len(its) >= 2
+        slots = sorted(int(it[11]) for it in its)
+        assert slots == list(range(slots[0], slots[0] + len(its))), "consecutive slots, summed in order"
+        # visible key positions of this query tile: 0 .. pos0 + nrows - 1 (causal, whole sequence streamed)
+        seen = np.zeros(pos0 + nrows, dtype=np.int64)
+        for it in its:
+            for g in range(int(it[3])):
+                spos, slen = int(it[8 + g]), int(it[6 + g])
+                assert spos % 64 == 0 or cp is not None
+                hi = min(spos + slen, pos0 + nrows)
+                seen[spos:hi] += 1
+        assert np.all(seen == 1), (row0, seen.min(), seen.max())
+    # a tile is either whole or in parts, never both
+    whole_tiles = {(int(it[0]), int(it[1])) for it in whole}
+    assert not (whole_tiles & {(k[0], k[1]) for k in by_tile})
