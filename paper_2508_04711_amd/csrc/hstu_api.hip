@@ -130,7 +130,9 @@ int split_of(const hstu_attn_params* p, const SideSpec& s) {
 // tiles * split <= tiles + 2 * slots / heads + 1 because split <= 2 * slots / (tiles * heads) + 1.
 int64_t split_items_bound(const hstu_attn_params* p, const SideSpec& s) {
   const int64_t tiles = items_bound(p, s);
-  if (p->dtype != HSTU_BF16 || s.side != 0 || getenv("HSTU_ATTN_NO_SPLIT")) return tiles;
+  if (p->dtype != HSTU_BF16 || s.side != 0 || getenv("HSTU_ATTN_NO_SPLIT") ||
+      (int64_t)p->max_len < 2 * SPLIT_BLOCKS * 32)
+    return tiles;
   return tiles + 2 * 512 / p->num_heads + 1;
 }
 
@@ -145,7 +147,9 @@ size_t partial_bytes(const hstu_attn_params* p, int64_t slots, int tile, int d) 
 }
 size_t partial_bytes_bound(const hstu_attn_params* p, const SideSpec& s, int d) {
   if (split_items_bound(p, s) == items_bound(p, s)) return 0;
-  return partial_bytes(p, split_items_bound(p, s), 256, d);
+  // 128-row tiles: the 256-row forward is chosen only for problems with thousands of tiles,
+  // which are never cut
+  return partial_bytes(p, split_items_bound(p, s), 128, d);
 }
 
 // Bytes of one transposed copy of a streamed tensor with head dimension d (bf16 only).

@@ -112,6 +112,15 @@ def test_workspace_query(lib):
     # forward and context-parallel workspaces hold a transposed bf16 copy of V: [H, d_v, ~T]
     vt = 2 * 128 * 37117 * 2
     assert vt < sizes[0] < 1.2 * vt and 0 < sizes[1] < (1 << 20) and vt < sizes[2] < 1.5 * vt
+    # with sequences long enough to be cut along the keys (max_len >= 4096) the query-side passes
+    # add room for fp32 partial results: at most (tiles + 1024 / H + 1) slots of 128 rows
+    long_p = _params(binding, batch=16, total_rows=37117, d_qk=128, d_v=128, max_len=8192)
+    slots = 37117 // 128 + 16 + 1 + 1024 // 2 + 1
+    part = slots * 2 * 128 * 128 * 4
+    grown = [lib.hstu_jagged_attn_workspace_bytes(ctypes.byref(long_p), k) for k in (0, 1, 2)]
+    assert sizes[0] + 0.9 * part < grown[0] < sizes[0] + 1.1 * part
+    assert 0.9 * part < grown[1] < 1.1 * part + (1 << 20)
+    assert grown[2] > sizes[2] + 1.8 * part
     assert lib.hstu_jagged_attn_workspace_bytes(ctypes.byref(p), 9) == 0
     assert lib.hstu_jagged_attn_workspace_bytes(ctypes.byref(_params(binding, d_v=5)), 0) == 0
     # grows with the batch and with the rows
