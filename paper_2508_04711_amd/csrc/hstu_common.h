@@ -98,7 +98,7 @@ struct PlanArgs {
   Item* items;
 };
 
-// Builds one or two schedules in one launch (one workgroup each).
+// Builds up to three schedules in one launch (one workgroup each).
 hipError_t launch_plans(const PlanArgs* a, int count, hipStream_t stream);
 
 // Arguments of the attention kernels.

@@ -4,9 +4,10 @@
 // All three kernels share one shape.  A workgroup takes one schedule item for one head: a
 // tile of "owner" rows, 32 per wavefront, whose data a wave keeps in registers as MFMA B
 // operands, and streams the other side's rows through LDS in tiles of 64 (two or three tile
-// buffers, filled by asynchronous copies one or two tiles ahead) as MFMA A operands.  Scores are produced transposed with respect to the owner rows so that
-// the accumulator registers of the first product are, lane for lane, the B (or A) operand of
-// the second one; nothing but the streamed tiles ever goes through LDS.
+// buffers, filled by asynchronous copies one or two tiles ahead) as MFMA A operands.  Scores
+// are produced transposed with respect to the owner rows so that the accumulator registers of
+// the first product are, lane for lane, the B (or A) operand of the second one; nothing but
+// the streamed tiles ever goes through LDS.
 //
 //   v_mfma_f32_32x32x16_bf16  D[32x32] += A[32x16] * B[16x32]   (lane l: n = l%32, hh = l/32)
 //     A: lane holds row n,    k = 8*hh .. 8*hh+7          B: lane holds column n, same k
