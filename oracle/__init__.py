@@ -19,16 +19,18 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "hstu_oracle.c")
+_SRC_BIAS = os.path.join(_HERE, "hstu_oracle_bias.c")
 _LIB = os.path.join(_HERE, "libhstu_oracle.so")
 _lib = None
 
 
 def build(force: bool = False) -> str:
     """Compile the C oracle with the host compiler; returns the library path."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+    newest = max(os.path.getmtime(_SRC), os.path.getmtime(_SRC_BIAS))
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < newest:
         tmp = _LIB + ".tmp%d" % os.getpid()
         subprocess.run(
-            ["gcc", "-O2", "-std=c99", "-fopenmp", "-fPIC", "-shared", "-o", tmp, _SRC, "-lm"],
+            ["gcc", "-O2", "-std=c99", "-fopenmp", "-fPIC", "-shared", "-o", tmp, _SRC, _SRC_BIAS, "-lm"],
             check=True,
         )
         os.replace(tmp, _LIB)
@@ -202,3 +204,36 @@ def cp_partial(q_local, k_part, v_part, d_o_local, off, max_len: int, alpha: flo
         sk.ctypes.data_as(_i64p) if sk is not None else None)
     _check(rc, "hstu_oracle_cp_partial")
     return o, dq, dk, dvv
+
+
+def bias_bucket(ts_i: int, ts_j: int, nb: int, f: int) -> int:
+    """Bucket of a timestamp difference (the reading in hstu_oracle_bias.c)."""
+    lib = _load()
+    lib.hstu_oracle_bias_bucket.restype = ctypes.c_int32
+    return int(lib.hstu_oracle_bias_bucket(ctypes.c_int64(int(ts_i)), ctypes.c_int64(int(ts_j)),
+                                           ctypes.c_int32(nb), ctypes.c_int32(f)))
+
+
+def bias_attention(q, k, v, d_o, off, ts, w, f: int, max_len: int, alpha: float, causal: bool = True):
+    """Attention with the timestamp bias: returns (o, dq, dk, dv, dw), the gradients None when
+    d_o is None.  ts: int32 [T]; w: the bucket table [NB]; f: bits of groups per octave."""
+    q, k, v, off = _d(q), _d(k), _d(v), _off(off)
+    T, H, dqk, dv, B = _dims(q, v, off)
+    ts = np.ascontiguousarray(ts, dtype=np.int32)
+    w = _d(w)
+    assert ts.shape == (T,)
+    nb = len(w)
+    o = np.zeros((T, H, dv), dtype=np.float64)
+    back = d_o is not None
+    d_o = _d(d_o) if back else None
+    dq = np.zeros((T, H, dqk), dtype=np.float64) if back else None
+    dk = np.zeros((T, H, dqk), dtype=np.float64) if back else None
+    dvv = np.zeros((T, H, dv), dtype=np.float64) if back else None
+    dw = np.zeros(nb, dtype=np.float64) if back else None
+    rc = _load().hstu_oracle_bias(
+        ctypes.c_int32(B), ctypes.c_int32(H), ctypes.c_int32(dqk), ctypes.c_int32(dv),
+        ctypes.c_int32(max_len), ctypes.c_double(alpha), ctypes.c_int32(int(causal)),
+        off.ctypes.data_as(_i32p), ts.ctypes.data_as(_i32p), ctypes.c_int32(nb), ctypes.c_int32(f),
+        _p(w), _p(q), _p(k), _p(v), _p(d_o), _p(o), _p(dq), _p(dk), _p(dvv), _p(dw))
+    _check(rc, "hstu_oracle_bias")
+    return o, dq, dk, dvv, dw
