@@ -127,6 +127,47 @@ int hstu_jagged_attn_bwd(const hstu_attn_params* params, const void* q, const vo
                          void* dk, void* dv, void* workspace, size_t workspace_bytes,
                          void* hip_stream);
 
+/* Timestamp bias.  Section 2.1's equation has "+ Bias" inside the SiLU and describes the bias in
+ * words only: differences of the rows' timestamps are transformed and grouped into bucket
+ * indices, which select entries of a learnable table.  The transformation and the grouping are
+ * not given; this library's reading (PARITY WITH THE PAPER IS UNPINNED for it) is
+ *     delta  = |timestamps[i] - timestamps[j]|                    (exact, up to 2^32 - 1)
+ *     bucket = 0                                  if delta <= 1
+ *            = min(num_buckets - 1, e * 2^f + m)  otherwise, e = floor(log2 delta), m = the f
+ *              bits below delta's leading one (delta < 2^f: delta shifted up), f = groups_log2,
+ *     x_ij   = alpha * (<Q_i, K_j> + ts_weights[bucket_ij])        (one table for all heads)
+ * all in integer arithmetic, so no rounding decides a bucket.  With an all-zero table the
+ * results equal those of the entry points without bias up to the order of fp32 additions.
+ * Timestamps need not be sorted; blocks of pairs that fall into one bucket (the common case
+ * for sorted timestamps away from the diagonal) take a faster path. */
+typedef struct {
+  const int32_t* timestamps;  /* device, [total_rows]: one per row, same layout as the rows     */
+  const float* ts_weights;    /* device, [num_buckets] fp32: the table                          */
+  float* d_ts_weights;        /* device, [num_buckets] fp32: backward output (overwritten: the
+                                 sum over all visible pairs and heads of alpha * dS); NULL is
+                                 allowed in the forward call.  Summed with fp32 atomics: the
+                                 last bits vary from run to run                                 */
+  int32_t num_buckets;        /* 1..512                                                         */
+  int32_t groups_log2;        /* f: 0..8                                                        */
+} hstu_ts_bias;
+
+/* Workspace of the two calls below (which: HSTU_WS_FWD or HSTU_WS_BWD; 0 for invalid input). */
+size_t hstu_jagged_attn_bias_workspace_bytes(const hstu_attn_params* params, int which);
+
+/* hstu_jagged_attn_fwd / hstu_jagged_attn_bwd with the bias above; same arguments, layouts and
+ * errors, plus: bf16 inputs only and d_qk == d_v (otherwise HSTU_ERR_UNSUPPORTED),
+ * num_buckets or groups_log2 out of range HSTU_ERR_BAD_SHAPE, a NULL field of `bias` (other
+ * than d_ts_weights in the forward call) HSTU_ERR_NULL_PTR.  dq, dk, dv are deterministic as in
+ * hstu_jagged_attn_bwd; d_ts_weights is not (see above). */
+int hstu_jagged_attn_bias_fwd(const hstu_attn_params* params, const hstu_ts_bias* bias,
+                              const void* q, const void* k, const void* v,
+                              const int32_t* seq_offsets, void* o, void* workspace,
+                              size_t workspace_bytes, void* hip_stream);
+int hstu_jagged_attn_bias_bwd(const hstu_attn_params* params, const hstu_ts_bias* bias,
+                              const void* q, const void* k, const void* v, const void* d_o,
+                              const int32_t* seq_offsets, void* dq, void* dk, void* dv,
+                              void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* One context-parallel rank's partial (section 2.3): the query rows of
  * `q_rank` against the keys of `kv_rank` (or all keys), masked on positions
  * inside the whole sequence, every visible (query chunk, key chunk) pair in one
@@ -235,8 +276,8 @@ int hstu_debug_dump_schedule(const hstu_attn_params* params, const hstu_cp_desc*
  *   begin: max_records in [1, 65536]; launches beyond it are not recorded.
  *   end:   waits for the recorded launches, writes per launch, in launch order, its kind
  *          (0 forward, 1 dk/dv pass, 2 dq pass, 3 schedule build, 4 transposed copy,
- *          5 reorder, 6 sum of the partial results of split tiles) and its duration in
- *          milliseconds; returns the number written (<= capacity) or a status < 0.
+ *          5 reorder, 6 sum of the partial results of split tiles, 7 timestamp records)
+ *          and its duration in milliseconds; returns the number written (<= capacity) or a status < 0.
  */
 int hstu_debug_timing_begin(int max_records);
 int hstu_debug_timing_end(int32_t* kinds, float* milliseconds, int capacity);

@@ -10,6 +10,9 @@ from .binding import (  # noqa: F401
     hstu_debug_dump_schedule,
     hstu_debug_timing_begin,
     hstu_debug_timing_end,
+    hstu_jagged_attn_bias_bwd,
+    hstu_jagged_attn_bias_fwd,
+    hstu_jagged_attn_bias_workspace_bytes,
     hstu_jagged_attn_bwd,
     hstu_jagged_attn_cp_partial,
     hstu_jagged_attn_fwd,

@@ -44,6 +44,14 @@ class _CpDesc(ctypes.Structure):
     ]
 
 
+class _TsBias(ctypes.Structure):
+    _fields_ = [
+        ("timestamps", ctypes.c_void_p), ("ts_weights", ctypes.c_void_p),
+        ("d_ts_weights", ctypes.c_void_p), ("num_buckets", ctypes.c_int32),
+        ("groups_log2", ctypes.c_int32),
+    ]
+
+
 class _RingDesc(ctypes.Structure):
     _fields_ = [
         ("cp_size", ctypes.c_int32), ("q_rank", ctypes.c_int32), ("accumulate_dkv", ctypes.c_int32),
@@ -97,6 +105,14 @@ def load_library():
     lib.hstu_cp_reorder.argtypes = [ctypes.c_int32, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32,
                                     ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p,
                                     ctypes.c_void_p, ctypes.c_int64, i32p, vp]
+    bp = ctypes.POINTER(_TsBias)
+    lib.hstu_jagged_attn_bias_workspace_bytes.restype = ctypes.c_size_t
+    lib.hstu_jagged_attn_bias_workspace_bytes.argtypes = [pp, ctypes.c_int]
+    lib.hstu_jagged_attn_bias_fwd.restype = ctypes.c_int
+    lib.hstu_jagged_attn_bias_fwd.argtypes = [pp, bp, vp, vp, vp, i32p, vp, vp, ctypes.c_size_t, vp]
+    lib.hstu_jagged_attn_bias_bwd.restype = ctypes.c_int
+    lib.hstu_jagged_attn_bias_bwd.argtypes = [pp, bp, vp, vp, vp, vp, i32p, vp, vp, vp, vp,
+                                              ctypes.c_size_t, vp]
     lib.hstu_schedule_tile_rows.restype = ctypes.c_int
     lib.hstu_schedule_tile_rows.argtypes = [pp, ctypes.c_int]
     _lib = lib
@@ -235,6 +251,100 @@ def hstu_jagged_attn_bwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, d_o:
     return dq, dk, dvv
 
 
+def hstu_jagged_attn_bias_workspace_bytes(params_or_tuple, which: int) -> int:
+    """Bytes of device workspace of the calls with timestamp bias (`which`: 0 fwd, 1 bwd)."""
+    p = params_or_tuple if isinstance(params_or_tuple, _Params) else _params(*params_or_tuple)
+    return int(load_library().hstu_jagged_attn_bias_workspace_bytes(ctypes.byref(p), int(which)))
+
+
+def _bias_desc(timestamps, ts_weights, d_ts_weights, groups_log2, rows) -> _TsBias:
+    if timestamps.dtype != torch.int32 or not timestamps.is_cuda or not timestamps.is_contiguous() \
+            or tuple(timestamps.shape) != (rows,):
+        raise ValueError("timestamps must be a contiguous int32 device tensor of one entry per row")
+    for name, t in (("ts_weights", ts_weights), ("d_ts_weights", d_ts_weights)):
+        if t is None:
+            continue
+        if t.dtype != torch.float32 or not t.is_cuda or not t.is_contiguous() or t.dim() != 1:
+            raise ValueError("%s must be a contiguous 1-d fp32 device tensor" % name)
+    if d_ts_weights is not None and d_ts_weights.numel() != ts_weights.numel():
+        raise ValueError("d_ts_weights must have one entry per bucket")
+    return _TsBias(timestamps.data_ptr(), ts_weights.data_ptr(),
+                   d_ts_weights.data_ptr() if d_ts_weights is not None else None,
+                   int(ts_weights.numel()), int(groups_log2))
+
+
+def _bias_workspace(params: _Params, which: int, workspace, device) -> torch.Tensor:
+    if workspace is None:
+        need = hstu_jagged_attn_bias_workspace_bytes(params, which)
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=device)
+    return workspace
+
+
+def hstu_jagged_attn_bias_fwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor,
+                              seq_offsets: torch.Tensor, timestamps: torch.Tensor,
+                              ts_weights: torch.Tensor, groups_log2: int, max_len: int, alpha: float,
+                              causal: bool = True, out: Optional[torch.Tensor] = None,
+                              workspace: Optional[torch.Tensor] = None, stream=None,
+                              out_dtype: Optional[torch.dtype] = None) -> torch.Tensor:
+    """hstu_jagged_attn_fwd with the timestamp bias: x = alpha * (q.k + ts_weights[bucket])."""
+    T, H, dqk = q.shape
+    dv = v.shape[2]
+    _check_tensor(q, "q", T, H, dqk, q.dtype); _check_tensor(k, "k", T, H, dqk, q.dtype)
+    _check_tensor(v, "v", T, H, dv, q.dtype)
+    if seq_offsets.dtype != torch.int32 or not seq_offsets.is_cuda or not seq_offsets.is_contiguous():
+        raise ValueError("seq_offsets must be a contiguous int32 device tensor")
+    B = seq_offsets.numel() - 1
+    odt = out.dtype if out is not None else _out_dtype(q.dtype, out_dtype)
+    if out is None:
+        out = torch.empty((T, H, dv), dtype=odt, device=q.device)
+    else:
+        _check_tensor(out, "out", T, H, dv, odt)
+    p = _params(B, H, dqk, dv, max_len, alpha, causal, _dtype_code(q), T, _code(odt))
+    bias = _bias_desc(timestamps, ts_weights, None, groups_log2, T)
+    ws = _bias_workspace(p, HSTU_WS_FWD, workspace, q.device)
+    rc = load_library().hstu_jagged_attn_bias_fwd(ctypes.byref(p), ctypes.byref(bias), _ptr(q), _ptr(k),
+                                                  _ptr(v), _ptr(seq_offsets), _ptr(out), _ptr(ws),
+                                                  ws.numel(), _stream(stream))
+    if rc != 0:
+        raise HstuError(rc, "hstu_jagged_attn_bias_fwd")
+    return out
+
+
+def hstu_jagged_attn_bias_bwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, d_o: torch.Tensor,
+                              seq_offsets: torch.Tensor, timestamps: torch.Tensor,
+                              ts_weights: torch.Tensor, groups_log2: int, max_len: int, alpha: float,
+                              causal: bool = True, out: Optional[tuple] = None,
+                              workspace: Optional[torch.Tensor] = None, stream=None,
+                              out_dtype: Optional[torch.dtype] = None):
+    """(dQ, dK, dV, d_ts_weights) of sum(O * d_o) for the forward with bias; `out` may pass the four."""
+    T, H, dqk = q.shape
+    dv = v.shape[2]
+    _check_tensor(q, "q", T, H, dqk, q.dtype); _check_tensor(k, "k", T, H, dqk, q.dtype)
+    _check_tensor(v, "v", T, H, dv, q.dtype); _check_tensor(d_o, "d_o", T, H, dv, q.dtype)
+    if seq_offsets.dtype != torch.int32 or not seq_offsets.is_cuda or not seq_offsets.is_contiguous():
+        raise ValueError("seq_offsets must be a contiguous int32 device tensor")
+    B = seq_offsets.numel() - 1
+    odt = out[0].dtype if out is not None else _out_dtype(q.dtype, out_dtype)
+    if out is None:
+        dq = torch.empty_like(q, dtype=odt); dk = torch.empty_like(k, dtype=odt)
+        dvv = torch.empty_like(v, dtype=odt)
+        dw = torch.empty_like(ts_weights)
+    else:
+        dq, dk, dvv, dw = out
+        _check_tensor(dq, "dq", T, H, dqk, odt); _check_tensor(dk, "dk", T, H, dqk, odt)
+        _check_tensor(dvv, "dv", T, H, dv, odt)
+    p = _params(B, H, dqk, dv, max_len, alpha, causal, _dtype_code(q), T, _code(odt))
+    bias = _bias_desc(timestamps, ts_weights, dw, groups_log2, T)
+    ws = _bias_workspace(p, HSTU_WS_BWD, workspace, q.device)
+    rc = load_library().hstu_jagged_attn_bias_bwd(ctypes.byref(p), ctypes.byref(bias), _ptr(q), _ptr(k),
+                                                  _ptr(v), _ptr(d_o), _ptr(seq_offsets), _ptr(dq),
+                                                  _ptr(dk), _ptr(dvv), _ptr(ws), ws.numel(),
+                                                  _stream(stream))
+    if rc != 0:
+        raise HstuError(rc, "hstu_jagged_attn_bias_bwd")
+    return dq, dk, dvv, dw
+
+
 def hstu_jagged_attn_cp_partial(q_local: torch.Tensor, k_part: torch.Tensor, v_part: torch.Tensor,
                                 d_o_local: Optional[torch.Tensor], seq_offsets_global: torch.Tensor,
                                 total_rows: int, max_len: int, alpha: float, causal: bool,
@@ -321,7 +431,8 @@ def hstu_debug_dump_schedule(seq_offsets: torch.Tensor, total_rows: int, num_hea
     return buf[:n].copy()
 
 
-KERNEL_KINDS = {0: "fwd", 1: "dkdv", 2: "dq", 3: "plan", 4: "transpose", 5: "reorder", 6: "reduce"}
+KERNEL_KINDS = {0: "fwd", 1: "dkdv", 2: "dq", 3: "plan", 4: "transpose", 5: "reorder", 6: "reduce",
+                7: "ts_records"}
 
 
 def hstu_debug_timing_begin(max_records: int = 4096) -> None:

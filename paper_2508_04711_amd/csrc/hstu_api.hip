@@ -303,6 +303,34 @@ int run_query_pass(const hstu_attn_params* p, int pass, AttnArgs& a, const Built
                                 a.accumulate, a.out_f32, stream) == hipSuccess ? HSTU_OK : HSTU_ERR_HIP;
 }
 
+// Timestamp bias: argument checks and the per-row records at the start of the workspace.
+int check_bias(const hstu_attn_params* p, const hstu_ts_bias* b, bool backward) {
+  if (!b) return HSTU_ERR_NULL_PTR;
+  if (p->dtype != HSTU_BF16 || p->d_qk != p->d_v) return HSTU_ERR_UNSUPPORTED;
+  if (b->num_buckets < 1 || b->num_buckets > MAX_TS_BUCKETS || b->groups_log2 < 0 || b->groups_log2 > 8)
+    return HSTU_ERR_BAD_SHAPE;
+  if (!b->timestamps || !b->ts_weights || (backward && !b->d_ts_weights)) return HSTU_ERR_NULL_PTR;
+  return HSTU_OK;
+}
+size_t ts_record_bytes(const hstu_attn_params* p) {
+  return align_up((size_t)(p->total_rows + 64) * sizeof(TsRecord), 256);
+}
+// Builds the records at the start of the workspace (and clears the table gradient).
+int build_ts_records(const hstu_attn_params* p, const hstu_ts_bias* b, const int32_t* off, char* ws,
+                     bool backward, hipStream_t stream) {
+  TimedLaunch timed(7, stream);
+  return launch_ts_records(b->timestamps, off, p->batch, p->total_rows, reinterpret_cast<TsRecord*>(ws),
+                           backward ? b->d_ts_weights : nullptr, b->num_buckets, stream) == hipSuccess
+             ? HSTU_OK : HSTU_ERR_HIP;
+}
+void set_bias(AttnArgs& a, const hstu_ts_bias* b, const char* ws) {
+  a.ts_rec = reinterpret_cast<const TsRecord*>(ws);
+  a.ts_w = b->ts_weights;
+  a.d_ts_w = b->d_ts_weights;
+  a.nb = b->num_buckets;
+  a.fbits = b->groups_log2;
+}
+
 SideSpec full_side(const hstu_attn_params* p, int side, int pass) {
   return SideSpec{side, pass, -1, -1, p->total_rows, p->total_rows, 1, 1};
 }
@@ -389,25 +417,38 @@ size_t hstu_jagged_attn_workspace_bytes(const hstu_attn_params* params, int whic
   return end + 4096;  // slack for the 256-byte alignment of each piece
 }
 
-int hstu_jagged_attn_fwd(const hstu_attn_params* params, const void* q, const void* k,
-                         const void* v, const int32_t* seq_offsets, void* o, void* workspace,
-                         size_t workspace_bytes, void* hip_stream) {
+size_t hstu_jagged_attn_bias_workspace_bytes(const hstu_attn_params* params, int which) {
+  if (which != HSTU_WS_FWD && which != HSTU_WS_BWD) return 0;
+  const size_t plain = hstu_jagged_attn_workspace_bytes(params, which);
+  return plain ? plain + ts_record_bytes(params) : 0;
+}
+
+// Forward over the whole batch, with the timestamp bias if `bias` is not null.
+static int fwd_impl(const hstu_attn_params* params, const hstu_ts_bias* bias, const void* q,
+                    const void* k, const void* v, const int32_t* seq_offsets, void* o,
+                    void* workspace, size_t workspace_bytes, void* hip_stream) {
   int rc = check_params(params);
   if (rc != HSTU_OK) return rc;
+  if (bias && (rc = check_bias(params, bias, false)) != HSTU_OK) return rc;
   if (params->batch == 0 || params->total_rows == 0) return HSTU_OK;
   if (!q || !k || !v || !o || !seq_offsets || !workspace) return HSTU_ERR_NULL_PTR;
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(workspace))
     return HSTU_ERR_MISALIGNED;
-  if (workspace_bytes < hstu_jagged_attn_workspace_bytes(params, HSTU_WS_FWD))
+  if (workspace_bytes < (bias ? hstu_jagged_attn_bias_workspace_bytes(params, HSTU_WS_FWD)
+                              : hstu_jagged_attn_workspace_bytes(params, HSTU_WS_FWD)))
     return HSTU_ERR_WORKSPACE_TOO_SMALL;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const size_t first = bias ? ts_record_bytes(params) : 0;  // the records come first
+  if (bias && (rc = build_ts_records(params, bias, seq_offsets, (char*)workspace, false, stream)) != HSTU_OK)
+    return rc;
   BuiltPlan bp;
   rc = build_plan(params, 1, full_side(params, 0, PASS_FWD), seq_offsets, (char*)workspace,
-                  workspace_bytes, 0, stream, &bp);
+                  workspace_bytes, first, stream, &bp);
   if (rc != HSTU_OK) return rc;
   size_t base = bp.end;
   AttnArgs a = base_args(params, bp, 0);
   a.q = q; a.k = k; a.v = v; a.o = o;
+  if (bias) set_bias(a, bias, (const char*)workspace);
   rc = make_tcopy(params, full_side(params, 0, PASS_FWD), bp, v, params->d_v, (char*)workspace,
                   workspace_bytes, &base, stream, &a.vt);
   if (rc != HSTU_OK) return rc;
@@ -415,25 +456,45 @@ int hstu_jagged_attn_fwd(const hstu_attn_params* params, const void* q, const vo
                         (char*)workspace, workspace_bytes, &base, stream);
 }
 
-int hstu_jagged_attn_bwd(const hstu_attn_params* params, const void* q, const void* k,
-                         const void* v, const void* d_o, const int32_t* seq_offsets, void* dq,
-                         void* dk, void* dv, void* workspace, size_t workspace_bytes,
-                         void* hip_stream) {
+int hstu_jagged_attn_fwd(const hstu_attn_params* params, const void* q, const void* k,
+                         const void* v, const int32_t* seq_offsets, void* o, void* workspace,
+                         size_t workspace_bytes, void* hip_stream) {
+  return fwd_impl(params, nullptr, q, k, v, seq_offsets, o, workspace, workspace_bytes, hip_stream);
+}
+
+int hstu_jagged_attn_bias_fwd(const hstu_attn_params* params, const hstu_ts_bias* bias,
+                              const void* q, const void* k, const void* v,
+                              const int32_t* seq_offsets, void* o, void* workspace,
+                              size_t workspace_bytes, void* hip_stream) {
+  if (!bias) return HSTU_ERR_NULL_PTR;
+  return fwd_impl(params, bias, q, k, v, seq_offsets, o, workspace, workspace_bytes, hip_stream);
+}
+
+// Backward over the whole batch, with the timestamp bias if `bias` is not null.
+static int bwd_impl(const hstu_attn_params* params, const hstu_ts_bias* bias, const void* q,
+                    const void* k, const void* v, const void* d_o, const int32_t* seq_offsets,
+                    void* dq, void* dk, void* dv, void* workspace, size_t workspace_bytes,
+                    void* hip_stream) {
   int rc = check_params(params);
   if (rc != HSTU_OK) return rc;
+  if (bias && (rc = check_bias(params, bias, true)) != HSTU_OK) return rc;
   if (params->batch == 0 || params->total_rows == 0) return HSTU_OK;
   if (!q || !k || !v || !d_o || !dq || !dk || !dv || !seq_offsets || !workspace)
     return HSTU_ERR_NULL_PTR;
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(d_o) || !aligned16(dq) ||
       !aligned16(dk) || !aligned16(dv) || !aligned16(workspace))
     return HSTU_ERR_MISALIGNED;
-  if (workspace_bytes < hstu_jagged_attn_workspace_bytes(params, HSTU_WS_BWD))
+  if (workspace_bytes < (bias ? hstu_jagged_attn_bias_workspace_bytes(params, HSTU_WS_BWD)
+                              : hstu_jagged_attn_workspace_bytes(params, HSTU_WS_BWD)))
     return HSTU_ERR_WORKSPACE_TOO_SMALL;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const size_t first = bias ? ts_record_bytes(params) : 0;  // the records come first
+  if (bias && (rc = build_ts_records(params, bias, seq_offsets, (char*)workspace, true, stream)) != HSTU_OK)
+    return rc;
   BuiltPlan pk, pq;
   PlanArgs pa[2];
   rc = prepare_plan(params, 1, full_side(params, 1, PASS_DKDV), seq_offsets, (char*)workspace,
-                    workspace_bytes, 0, &pa[0], &pk);
+                    workspace_bytes, first, &pa[0], &pk);
   if (rc != HSTU_OK) return rc;
   rc = prepare_plan(params, 1, full_side(params, 0, PASS_DQ), seq_offsets, (char*)workspace,
                     workspace_bytes, pk.end, &pa[1], &pq);
@@ -442,13 +503,32 @@ int hstu_jagged_attn_bwd(const hstu_attn_params* params, const void* q, const vo
   if (rc != HSTU_OK) return rc;
   AttnArgs a = base_args(params, pk, 0);
   a.q = q; a.k = k; a.v = v; a.d_o = d_o; a.dk = dk; a.dv = dv;
+  if (bias) set_bias(a, bias, (const char*)workspace);
   rc = run_pass(params, PASS_DKDV, a, stream);
   if (rc != HSTU_OK) return rc;
   AttnArgs b = base_args(params, pq, 0);
   b.q = q; b.k = k; b.v = v; b.d_o = d_o; b.dq = dq;
+  if (bias) set_bias(b, bias, (const char*)workspace);
   size_t base = pq.end;
   return run_query_pass(params, PASS_DQ, b, pq, full_side(params, 0, PASS_DQ), dq, params->d_qk,
                         (char*)workspace, workspace_bytes, &base, stream);
+}
+
+int hstu_jagged_attn_bwd(const hstu_attn_params* params, const void* q, const void* k,
+                         const void* v, const void* d_o, const int32_t* seq_offsets, void* dq,
+                         void* dk, void* dv, void* workspace, size_t workspace_bytes,
+                         void* hip_stream) {
+  return bwd_impl(params, nullptr, q, k, v, d_o, seq_offsets, dq, dk, dv, workspace, workspace_bytes,
+                  hip_stream);
+}
+
+int hstu_jagged_attn_bias_bwd(const hstu_attn_params* params, const hstu_ts_bias* bias,
+                              const void* q, const void* k, const void* v, const void* d_o,
+                              const int32_t* seq_offsets, void* dq, void* dk, void* dv,
+                              void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!bias) return HSTU_ERR_NULL_PTR;
+  return bwd_impl(params, bias, q, k, v, d_o, seq_offsets, dq, dk, dv, workspace, workspace_bytes,
+                  hip_stream);
 }
 
 // The partial of one (query rank, key rank) pair.  acc_q: add to o_local / dq_local;

@@ -101,6 +101,20 @@ struct PlanArgs {
 // Builds up to three schedules in one launch (one workgroup each).
 hipError_t launch_plans(const PlanArgs* a, int count, hipStream_t stream);
 
+// What the kernels need to know about a row's timestamp: the timestamp itself and the range of
+// the timestamps of the (up to) 32 rows of the same sequence that start at this row, from which
+// a 32-row block whose first row this is decides whether one bucket covers all its pairs.
+struct TsRecord {
+  int32_t ts, lo, hi, pad;
+};
+static_assert(sizeof(TsRecord) == 16, "one 16-byte record per row");
+constexpr int MAX_TS_BUCKETS = 512;
+
+// Builds the records of all rows (rec has total_rows + 64 entries; the surplus is cleared) and,
+// if d_w is not null, clears the nb entries of the table gradient.
+hipError_t launch_ts_records(const int32_t* ts, const int32_t* off, int batch, int64_t total_rows,
+                             TsRecord* rec, float* d_w, int nb, hipStream_t stream);
+
 // Arguments of the attention kernels.
 struct AttnArgs {
   const void* q;
@@ -122,6 +136,12 @@ struct AttnArgs {
   float* partial;   // partial results of split tiles: [slot][head][tile row][d] fp32 (or null)
   float alpha;
   float inv_n;
+  // Timestamp bias (bf16 kernels, whole-batch layout only; ts_rec == null: no bias).
+  const TsRecord* ts_rec;  // per row, built by launch_ts_records
+  const float* ts_w;       // bucket table, nb entries
+  float* d_ts_w;           // its gradient (dq pass: added with atomics), or null
+  int32_t nb;              // buckets
+  int32_t fbits;           // log2 of the groups per octave
 };
 
 // Owner rows per item each kernel family expects (pass: 0 forward, 1 dk/dv, 2 dq); the

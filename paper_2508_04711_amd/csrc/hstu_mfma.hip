@@ -361,6 +361,130 @@ __device__ __forceinline__ bool fetch_item(const Plan& plan, int slot, Item& it)
 }
 
 // =============================================================================================
+// Timestamp bias.  Paper, section 2.1: the scores get "+ Bias" inside the SiLU, the bias being a
+// learnable table indexed by a bucket of the difference of two rows' timestamps; the bucket
+// function (a logarithm with 2^f groups per octave, in integers) is this library's reading:
+//   delta = |ts_i - ts_j|;  bucket = 0 if delta <= 1, else min(nb - 1, e * 2^f + m) with
+//   e = floor(log2 delta) and m the f bits below delta's leading one.
+// The bias of a 32x32 block of pairs is written into the accumulator of the score product before
+// its first matrix instruction, so that the elementwise code sees scores that already contain it
+// (x = alpha * (q.k + w) in the forward pass and in both backward passes alike).
+// The bucket grows with delta, so when the smallest and the largest difference a block can contain
+// (from the ranges of the two sides' timestamps) fall into one bucket, the whole block takes that
+// one table entry; otherwise every lane works out the buckets of its 16 pairs.
+// =============================================================================================
+constexpr int REC_TILE = ST * (int)sizeof(TsRecord);  // bytes of the records of one streamed tile
+
+// Asynchronous copy of the records of one streamed tile (one wave-wide load; rows >= valid
+// arrive as zeros).  Called by one wave.
+__device__ __forceinline__ void rec_copy_async(char* tile, const TsRecord* rec, int valid, int lane) {
+  const int rows = valid < 0 ? 0 : (valid < ST ? valid : ST);
+  const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      (void*)rec, 0, __builtin_amdgcn_readfirstlane(rows * (int)sizeof(TsRecord)), 0x00020000);
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, HSTU_LDS(void, tile), 16, lane * 16, 0, 0, 0);
+}
+
+__device__ __forceinline__ int bias_bucket(uint32_t delta, int nb, int f) {
+  if (delta <= 1u) return 0;
+  const int e = 31 - __builtin_clz(delta);
+  const uint32_t top = e >= f ? delta >> (e - f) : delta << (f - e);
+  const int b = (e << f) + (int)top - (1 << f);
+  return b < nb - 1 ? b : nb - 1;
+}
+
+__device__ __forceinline__ uint32_t abs_diff(int a, int b) {
+  return a > b ? (uint32_t)a - (uint32_t)b : (uint32_t)b - (uint32_t)a;
+}
+
+__device__ __forceinline__ int wave_min(int x) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) { const int y = __shfl_xor(x, m); x = y < x ? y : x; }
+  return __builtin_amdgcn_readfirstlane(x);
+}
+__device__ __forceinline__ int wave_max(int x) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) { const int y = __shfl_xor(x, m); x = y > x ? y : x; }
+  return __builtin_amdgcn_readfirstlane(x);
+}
+__device__ __forceinline__ float wave_sum(float x) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) x += __shfl_xor(x, m);
+  return x;
+}
+
+// What a wave knows about the bias: its own rows' timestamps and the table (in LDS).
+struct BiasCtx {
+  const float* wtab;  // LDS copy of the table
+  int t_own;          // timestamp of the lane's owner row
+  int o_lo, o_hi;     // range of the timestamps of the wave's valid owner rows (uniform)
+  int nb, f, hh;
+};
+
+// Bias of block blk of a streamed tile whose records are at trec (LDS): s[r] = w[bucket of the
+// pair (lane's owner row, streamed row 8*(r/4) + 4*hh + r%4 of the block)].  b0, b1: the buckets
+// of the smallest and largest difference the block can contain (uniform); bk: the buckets of the
+// lane's pairs when b0 != b1.  Records that were never written (a tile past the end of the
+// stream, whose scores are computed and discarded) give arbitrary but in-range buckets.
+__device__ __forceinline__ void bias_block(f32x16& s, const char* trec, int blk, const BiasCtx& c,
+                                           int& b0, int& b1, int (&bk)[16]) {
+  const u32x4 head = *HSTU_LDS(u32x4, trec + blk * 32 * (int)sizeof(TsRecord));
+  const int s_lo = __builtin_amdgcn_readfirstlane((int)head[1]);
+  const int s_hi = __builtin_amdgcn_readfirstlane((int)head[2]);
+  const int64_t d1 = (int64_t)c.o_hi - s_lo, d2 = (int64_t)s_hi - c.o_lo;
+  const int64_t dmax = d1 > d2 ? d1 : d2;
+  const int64_t dmin = c.o_lo > s_hi ? (int64_t)c.o_lo - s_hi : (s_lo > c.o_hi ? (int64_t)s_lo - c.o_hi : 0);
+  b0 = bias_bucket((uint32_t)dmin, c.nb, c.f);
+  b1 = bias_bucket((uint32_t)dmax, c.nb, c.f);
+  if (b0 == b1) {
+    const float wb = *HSTU_LDS(float, c.wtab + b0);
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { s[r] = wb; bk[r] = b0; }
+  } else {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int row = blk * 32 + 8 * (r >> 2) + 4 * c.hh + (r & 3);
+      const int t = *HSTU_LDS(int, trec + row * (int)sizeof(TsRecord));
+      bk[r] = bias_bucket(abs_diff(c.t_own, t), c.nb, c.f);
+      s[r] = *HSTU_LDS(float, c.wtab + bk[r]);
+    }
+  }
+}
+
+// Initial value of a score accumulator: zero, or the bias of the block.
+template <bool BIAS>
+struct ScoreInit {
+  const BiasCtx* c;
+  const char* trec;
+  int blk;
+  __device__ __forceinline__ void operator()(f32x16& s) const {
+    if constexpr (BIAS) {
+      int b0, b1, bk[16];
+      bias_block(s, trec, blk, *c, b0, b1, bk);
+    } else {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s[r] = 0.f;
+    }
+  }
+};
+
+// Loads the table into LDS and works out the wave's owner-side context.  All threads of the
+// workgroup call it (it contains a barrier).
+template <int NT>
+__device__ __forceinline__ BiasCtx bias_setup(const AttnArgs& a, float* wtab, const Item& it, int orow,
+                                              int tid, int hh) {
+  for (int i = tid; i < a.nb; i += NT) wtab[i] = a.ts_w[i];
+  BiasCtx c;
+  c.wtab = wtab;
+  c.nb = a.nb; c.f = a.fbits; c.hh = hh;
+  const bool ok = orow < it.nrows;
+  c.t_own = ok ? a.ts_rec[it.row0 + orow].ts : 0;
+  c.o_lo = wave_min(ok ? c.t_own : 0x7fffffff);
+  c.o_hi = wave_max(ok ? c.t_own : (int)0x80000000);
+  __syncthreads();
+  return c;
+}
+
+// =============================================================================================
 // Forward: owners are query rows, keys and values are streamed.
 //   S^T = K Q^T (A = K tile rows, B = Q registers)  ->  P^T in accumulator layout
 //   O^T += V^T P^T (A = V tile transposed read, B = P^T registers)
@@ -380,8 +504,8 @@ __device__ __forceinline__ bool fetch_item(const Plan& plan, int slot, Item& it)
 // 8*(r/4) + 4*hh + r%4 <= rel, rel = query position - block position; applied to the finished
 // P under a wave-uniform branch, so the matrix instructions follow one path whether or not a
 // block is masked.  A block none of whose keys is visible comes out as zeros.
-template <int DQK, int DV, bool PV, class VAddr>
-__device__ __forceinline__ void fwd_step(const char* kn, int bn, const char* vp, int bp,
+template <int DQK, int DV, bool PV, class VAddr, class Init>
+__device__ __forceinline__ void fwd_step(const Init& init, const char* kn, int bn, const char* vp, int bp,
                                          const RowAddr<DQK>& ra, const VAddr& ca,
                                          const bf16x8 (&qreg)[DQK / 16], const f32x16& s_in,
                                          f32x16& s_out, const bf16x8 (&p_prev)[2],
@@ -391,8 +515,7 @@ __device__ __forceinline__ void fwd_step(const char* kn, int bn, const char* vp,
   constexpr int AHEAD = 3;  // operand reads in flight ahead of their use
   bf16x8 ka[KS], va[NPV];
   auto fence = [] { __builtin_amdgcn_sched_barrier(0); };
-#pragma unroll
-  for (int r = 0; r < 16; ++r) s_out[r] = 0.f;
+  init(s_out);
 #pragma unroll
   for (int m = 0; m < AHEAD; ++m) {
     if (m < KS) ka[m] = ra.read(kn, bn, m);
@@ -427,7 +550,8 @@ __device__ __forceinline__ void fwd_step(const char* kn, int bn, const char* vp,
 // VT: the V tiles come from the transposed copy (plain row reads, one LDS instruction per matrix
 // instruction); otherwise from V itself, row-major, through transposing reads (two per matrix
 // instruction, but no transposed copy has to be built first: the choice for small problems).
-template <int DQK, int DV, int NW, bool VT>
+// BIAS: with the timestamp bias (the records of the streamed rows travel with the K tiles).
+template <int DQK, int DV, int NW, bool VT, bool BIAS>
 __global__ void __launch_bounds__(NW * 64, 2) hstu_fwd_bf16(AttnArgs a) {
   constexpr int KB = ST * DQK * 2, VB = ST * DV * 2;
   // NBUF buffers each for the K tiles and the transposed V tiles; copies run PD tiles ahead.
@@ -442,8 +566,13 @@ __global__ void __launch_bounds__(NW * 64, 2) hstu_fwd_bf16(AttnArgs a) {
   __shared__ __attribute__((aligned(1024))) char vmem0[VB];
   __shared__ __attribute__((aligned(1024))) char vmem1[VB];
   __shared__ __attribute__((aligned(1024))) char vmem2[NBUF > 2 ? VB : 1024];
+  __shared__ __attribute__((aligned(1024))) char tmem0[BIAS ? REC_TILE : 16];
+  __shared__ __attribute__((aligned(1024))) char tmem1[BIAS ? REC_TILE : 16];
+  __shared__ __attribute__((aligned(1024))) char tmem2[BIAS && NBUF > 2 ? REC_TILE : 16];
+  __shared__ float wtab[BIAS ? MAX_TS_BUCKETS : 1];
   auto kbuf = [&](int b) { return b == 0 ? kmem0 : (b == 1 ? kmem1 : kmem2); };
   auto vbuf = [&](int b) { return b == 0 ? vmem0 : (b == 1 ? vmem1 : vmem2); };
+  auto tbuf = [&](int b) { return b == 0 ? tmem0 : (b == 1 ? tmem1 : tmem2); };
 
   const int H = a.num_heads;
   const int slot = blockIdx.x / H, h = blockIdx.x % H;
@@ -463,6 +592,9 @@ __global__ void __launch_bounds__(NW * 64, 2) hstu_fwd_bf16(AttnArgs a) {
   const bool wave_on = wave * 32 < it.nrows;
   bf16x8 qreg[DQK / 16];
   load_owner<DQK>(qreg, qg, sq, orow, it.nrows, hh);
+  BiasCtx bias = {};
+  if constexpr (BIAS) bias = bias_setup<NW * 64>(a, wtab, it, orow, tid, hh);
+  auto init_of = [&](const char* trec, int blk) { return ScoreInit<BIAS>{&bias, trec, blk}; };
 
   f32x16 oacc[DV / 32];
 #pragma unroll
@@ -479,6 +611,7 @@ __global__ void __launch_bounds__(NW * 64, 2) hstu_fwd_bf16(AttnArgs a) {
   auto copy_k = [&](int t, int buf) {
     const TileRef r = tile_ref(it, st, t);
     tile_copy_async<DQK, NW>(kbuf(buf), kg + (int64_t)r.row * sq, sq, r.valid, wave, lane);
+    if (BIAS && wave == 0) rec_copy_async(tbuf(buf), a.ts_rec + r.row, r.valid, lane);
   };
   auto copy_v = [&](int t, int buf) {
     const TileRef r = tile_ref(it, st, t);
@@ -524,10 +657,11 @@ __global__ void __launch_bounds__(NW * 64, 2) hstu_fwd_bf16(AttnArgs a) {
 
     // S of block 0 on its own, then step 0 (nothing to multiply by V yet)
     if (block_on(0)) {
+      init_of(tbuf(0), 0)(sacc[0]);
 #pragma unroll
       for (int ks = 0; ks < DQK / 16; ++ks) sacc[0] = mfma(ra.read(kbuf(0), 0, ks), qreg[ks], sacc[0]);
-      fwd_step<DQK, DV, false>(kbuf(0), 1, vbuf(0), 0, ra, ca, qreg, sacc[0], sacc[1], pb[1], pb[0], oacc,
-                               c1, mask_of(0), rel_of(0), hh);
+      fwd_step<DQK, DV, false>(init_of(tbuf(0), 1), kbuf(0), 1, vbuf(0), 0, ra, ca, qreg, sacc[0], sacc[1],
+                               pb[1], pb[0], oacc, c1, mask_of(0), rel_of(0), hh);
     }
     tile_barrier();  // iteration 0 copies over K tile 0, which the lines above read
 
@@ -542,14 +676,14 @@ __global__ void __launch_bounds__(NW * 64, 2) hstu_fwd_bf16(AttnArgs a) {
       {
         const int i = 2 * j + 1;  // S of (tile j+1, block 0), P V of (tile j, block 0)
         if (block_on(i - 1))
-          fwd_step<DQK, DV, true>(kbuf(B1), 0, vbuf(B0), 0, ra, ca, qreg, sacc[1], sacc[0], pb[0], pb[1],
-                                  oacc, c1, mask_of(i), rel_of(i), hh);
+          fwd_step<DQK, DV, true>(init_of(tbuf(B1), 0), kbuf(B1), 0, vbuf(B0), 0, ra, ca, qreg, sacc[1],
+                                  sacc[0], pb[0], pb[1], oacc, c1, mask_of(i), rel_of(i), hh);
       }
       if (j + 1 < T) {
         const int i = 2 * j + 2;  // S of (tile j+1, block 1), P V of (tile j, block 1)
         if (block_on(i - 1))
-          fwd_step<DQK, DV, true>(kbuf(B1), 1, vbuf(B0), 1, ra, ca, qreg, sacc[0], sacc[1], pb[1], pb[0],
-                                  oacc, c1, mask_of(i), rel_of(i), hh);
+          fwd_step<DQK, DV, true>(init_of(tbuf(B1), 1), kbuf(B1), 1, vbuf(B0), 1, ra, ca, qreg, sacc[0],
+                                  sacc[1], pb[1], pb[0], oacc, c1, mask_of(i), rel_of(i), hh);
       }
       // what the next iteration reads must have landed; with copies two tiles ahead the ones
       // just issued may stay in flight
@@ -616,8 +750,8 @@ __device__ __forceinline__ void bwd_elem(float s, float dp, float c1, float alph
 // It is applied to the finished elementwise results under a wave-uniform branch, so the matrix
 // instructions and their accumulators follow one path whether or not a block is masked; a block
 // no row of which is visible comes out as zeros and contributes nothing.
-template <int DQK, int DV, bool CONTR>
-__device__ __forceinline__ void dkdv_step(const char* qn, const char* gn, int bn,
+template <int DQK, int DV, bool CONTR, class Init>
+__device__ __forceinline__ void dkdv_step(const Init& init, const char* qn, const char* gn, int bn,
                                           const char* qp, const char* gp, int bp,
                                           const RowAddr<DQK>& raq, const RowAddr<DV>& rag,
                                           const ColAddr<DQK>& caq, const ColAddr<DV>& cag,
@@ -639,8 +773,9 @@ __device__ __forceinline__ void dkdv_step(const char* qn, const char* gn, int bn
                   : caq.read(qp, bp * 2 + ((m - VS) & 1), (m - VS) >> 1);
   };
   auto fence = [] { __builtin_amdgcn_sched_barrier(0); };
+  init(s_out);
 #pragma unroll
-  for (int r = 0; r < 16; ++r) { s_out[r] = 0.f; d_out[r] = 0.f; }
+  for (int r = 0; r < 16; ++r) d_out[r] = 0.f;
 #pragma unroll
   for (int m = 0; m < AHEAD; ++m) {
     op[m] = read_rows(m);
@@ -678,7 +813,7 @@ __device__ __forceinline__ void dkdv_step(const char* qn, const char* gn, int bn
   fence();
 }
 
-template <int DQK, int DV, int NW>
+template <int DQK, int DV, int NW, bool BIAS>
 __global__ void __launch_bounds__(NW * 64) hstu_dkdv_bf16(AttnArgs a) {
   constexpr int QB = ST * DQK * 2, GB = ST * DV * 2;
   // Three tile buffers: an iteration of the main loop touches tiles j and j+1 while the copy of
@@ -687,8 +822,13 @@ __global__ void __launch_bounds__(NW * 64) hstu_dkdv_bf16(AttnArgs a) {
   __shared__ __attribute__((aligned(1024))) char smem0[QB + GB];
   __shared__ __attribute__((aligned(1024))) char smem1[QB + GB];
   __shared__ __attribute__((aligned(1024))) char smem2[QB + GB];
+  __shared__ __attribute__((aligned(1024))) char tmem0[BIAS ? REC_TILE : 16];
+  __shared__ __attribute__((aligned(1024))) char tmem1[BIAS ? REC_TILE : 16];
+  __shared__ __attribute__((aligned(1024))) char tmem2[BIAS ? REC_TILE : 16];
+  __shared__ float wtab[BIAS ? MAX_TS_BUCKETS : 1];
   auto qbuf = [&](int b) { return b == 0 ? smem0 : (b == 1 ? smem1 : smem2); };
   auto gbuf = [&](int b) { return qbuf(b) + QB; };
+  auto tbuf = [&](int b) { return b == 0 ? tmem0 : (b == 1 ? tmem1 : tmem2); };
 
   const int H = a.num_heads;
   const int slot = blockIdx.x / H, h = blockIdx.x % H;
@@ -708,6 +848,9 @@ __global__ void __launch_bounds__(NW * 64) hstu_dkdv_bf16(AttnArgs a) {
   bf16x8 kreg[DQK / 16], vreg[DV / 16];
   load_owner<DQK>(kreg, kg, sq, orow, it.nrows, hh);
   load_owner<DV>(vreg, vg, sv, orow, it.nrows, hh);
+  BiasCtx bias = {};
+  if constexpr (BIAS) bias = bias_setup<NW * 64>(a, wtab, it, orow, tid, hh);
+  auto init_of = [&](const char* trec, int blk) { return ScoreInit<BIAS>{&bias, trec, blk}; };
 
   f32x16 dkacc[DQK / 32], dvacc[DV / 32];
 #pragma unroll
@@ -731,6 +874,7 @@ __global__ void __launch_bounds__(NW * 64) hstu_dkdv_bf16(AttnArgs a) {
     const TileRef t = tile_ref(it, st, j);
     tile_copy_async<DQK, NW>(qbuf(buf), qg + (int64_t)t.row * sq, sq, t.valid, wave, lane);
     tile_copy_async<DV, NW>(gbuf(buf), gg + (int64_t)t.row * sv, sv, t.valid, wave, lane);
+    if (BIAS && wave == 0) rec_copy_async(tbuf(buf), a.ts_rec + t.row, t.valid, lane);
   };
   // Position of block i of the stream (i in [0, NB)); the positions grow with i.
   auto block_pos = [&](int i) { return tile_ref(it, st, i >> 1).pos + (i & 1) * 32; };
@@ -758,6 +902,7 @@ __global__ void __launch_bounds__(NW * 64) hstu_dkdv_bf16(AttnArgs a) {
 
   // scores of block 0 on their own
   if (block_on(0)) {
+    init_of(tbuf(0), 0)(sacc[0]);
 #pragma unroll
     for (int ks = 0; ks < DQK / 16; ++ks) sacc[0] = mfma(raq.read(qbuf(0), 0, ks), kreg[ks], sacc[0]);
 #pragma unroll
@@ -766,9 +911,9 @@ __global__ void __launch_bounds__(NW * 64) hstu_dkdv_bf16(AttnArgs a) {
   // step 0: scores of block 1, elementwise of block 0, nothing to contract yet
   if (block_on(1)) {
     const int pos = block_pos(0);
-    dkdv_step<DQK, DV, false>(qbuf(0), gbuf(0), 1, qbuf(0), gbuf(0), 0, raq, rag, caq, cag, kreg, vreg,
-                              sacc[0], dacc[0], sacc[1], dacc[1], pd[1], pd[0], dkacc, dvacc, c1,
-                              a.alpha, a.causal && pos < k_hi, k_lo + n - pos, hh);
+    dkdv_step<DQK, DV, false>(init_of(tbuf(0), 1), qbuf(0), gbuf(0), 1, qbuf(0), gbuf(0), 0, raq, rag,
+                              caq, cag, kreg, vreg, sacc[0], dacc[0], sacc[1], dacc[1], pd[1], pd[0],
+                              dkacc, dvacc, c1, a.alpha, a.causal && pos < k_hi, k_lo + n - pos, hh);
   }
 
   // Iteration j: steps 2j+1 and 2j+2, which touch tiles j and j+1 only.
@@ -779,18 +924,20 @@ __global__ void __launch_bounds__(NW * 64) hstu_dkdv_bf16(AttnArgs a) {
       const int i = 2 * j + 1;  // scores of (tile j+1, block 0), contraction of (tile j, block 0)
       if (block_on(i + 1 < NB ? i + 1 : i)) {
         const int pos = block_pos(i);
-        dkdv_step<DQK, DV, true>(qbuf(B1), gbuf(B1), 0, qbuf(B0), gbuf(B0), 0, raq, rag, caq, cag,
-                                 kreg, vreg, sacc[1], dacc[1], sacc[0], dacc[0], pd[0], pd[1], dkacc,
-                                 dvacc, c1, a.alpha, a.causal && pos < k_hi, k_lo + n - pos, hh);
+        dkdv_step<DQK, DV, true>(init_of(tbuf(B1), 0), qbuf(B1), gbuf(B1), 0, qbuf(B0), gbuf(B0), 0, raq,
+                                 rag, caq, cag, kreg, vreg, sacc[1], dacc[1], sacc[0], dacc[0], pd[0],
+                                 pd[1], dkacc, dvacc, c1, a.alpha, a.causal && pos < k_hi,
+                                 k_lo + n - pos, hh);
       }
     }
     if (j + 1 < T) {
       const int i = 2 * j + 2;  // scores of (tile j+1, block 1), contraction of (tile j, block 1)
       if (block_on(i + 1)) {
         const int pos = block_pos(i);
-        dkdv_step<DQK, DV, true>(qbuf(B1), gbuf(B1), 1, qbuf(B0), gbuf(B0), 1, raq, rag, caq, cag,
-                                 kreg, vreg, sacc[0], dacc[0], sacc[1], dacc[1], pd[1], pd[0], dkacc,
-                                 dvacc, c1, a.alpha, a.causal && pos < k_hi, k_lo + n - pos, hh);
+        dkdv_step<DQK, DV, true>(init_of(tbuf(B1), 1), qbuf(B1), gbuf(B1), 1, qbuf(B0), gbuf(B0), 1, raq,
+                                 rag, caq, cag, kreg, vreg, sacc[0], dacc[0], sacc[1], dacc[1], pd[1],
+                                 pd[0], dkacc, dvacc, c1, a.alpha, a.causal && pos < k_hi,
+                                 k_lo + n - pos, hh);
       }
     }
     tile_copy_wait<0>();
@@ -853,8 +1000,26 @@ __global__ void __launch_bounds__(NW * 64) hstu_dkdv_bf16(AttnArgs a) {
 // spills it caused cost more than the overlap gained (their reloads also wait for the tile
 // copy in flight, because vector memory operations complete in order).
 // =============================================================================================
-template <int DQK, int DV>
-__device__ __forceinline__ void dq_block(const char* kt, const char* vt, int blk,
+// Sum of dS per bucket for the gradient of the bias table (dq pass only: it visits every pair once).
+// A run of blocks that fall into one bucket adds up in a register per lane and goes to the
+// workgroup's LDS table when the bucket changes; the pairs of a block that spans several
+// buckets go there one by one.
+struct DwAcc {
+  float* dwl;   // LDS, one entry per bucket
+  float sum;    // per lane: dS of the current run
+  int cur;      // bucket of the current run (uniform; -1: none)
+  __device__ __forceinline__ void flush(int lane) {
+    if (cur >= 0) {
+      const float t = wave_sum(sum);
+      if (lane == 0) atomicAdd(dwl + cur, t);
+    }
+    sum = 0.f;
+  }
+};
+
+template <int DQK, int DV, bool BIAS>
+__device__ __forceinline__ void dq_block(const BiasCtx& bias, const char* trec, DwAcc& dwa,
+                                                const char* kt, const char* vt, int blk,
                                                 const RowAddr<DQK>& rak, const RowAddr<DV>& rav,
                                                 const ColAddr<DQK>& cak,
                                                 const bf16x8 (&qreg)[DQK / 16],
@@ -862,8 +1027,10 @@ __device__ __forceinline__ void dq_block(const char* kt, const char* vt, int blk
                                                 f32x16 (&dqacc)[DQK / 32], float c1, float alpha,
                                                 int k_lo, int q_lo, bool mask, int n, int hh) {
   f32x16 s, dp;
+  int b0 = 0, b1 = 0, bk[16];
 #pragma unroll
   for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
+  if constexpr (BIAS) bias_block(s, trec, blk, bias, b0, b1, bk);
 #pragma unroll
   for (int ks = 0; ks < DQK / 16; ++ks) s = mfma(rak.read(kt, blk, ks), qreg[ks], s);
 #pragma unroll
@@ -882,6 +1049,21 @@ __device__ __forceinline__ void dq_block(const char* kt, const char* vt, int blk
       ds[r] = kpos <= qpos ? ds[r] : 0.f;
     }
   }
+  if constexpr (BIAS) {
+    if (b0 == b1) {
+      if (b0 != dwa.cur) {
+        dwa.flush(n + 32 * hh);
+        dwa.cur = b0;
+      }
+      float t = 0.f;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) t += ds[r];
+      dwa.sum += t;
+    } else {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) atomicAdd(dwa.dwl + bk[r], ds[r]);
+    }
+  }
   const bf16x8 db0 = pack8(ds), db1 = pack8(ds + 8);
 #pragma unroll
   for (int c = 0; c < DQK / 32; ++c) {
@@ -890,13 +1072,18 @@ __device__ __forceinline__ void dq_block(const char* kt, const char* vt, int blk
   }
 }
 
-template <int DQK, int DV, int NW>
+template <int DQK, int DV, int NW, bool BIAS>
 __global__ void __launch_bounds__(NW * 64, 2) hstu_dq_bf16(AttnArgs a) {
   constexpr int KB = ST * DQK * 2, VB = ST * DV * 2;
   __shared__ __attribute__((aligned(1024))) char smem0[KB + VB];
   __shared__ __attribute__((aligned(1024))) char smem1[KB + VB];
+  __shared__ __attribute__((aligned(1024))) char tmem0[BIAS ? REC_TILE : 16];
+  __shared__ __attribute__((aligned(1024))) char tmem1[BIAS ? REC_TILE : 16];
+  __shared__ float wtab[BIAS ? MAX_TS_BUCKETS : 1];
+  __shared__ float dwl[BIAS ? MAX_TS_BUCKETS : 1];
   auto kbuf = [&](int b) { return b ? smem1 : smem0; };
   auto vbuf = [&](int b) { return (b ? smem1 : smem0) + KB; };
+  auto tbuf = [&](int b) { return b ? tmem1 : tmem0; };
 
   const int H = a.num_heads;
   const int slot = blockIdx.x / H, h = blockIdx.x % H;
@@ -916,6 +1103,12 @@ __global__ void __launch_bounds__(NW * 64, 2) hstu_dq_bf16(AttnArgs a) {
   bf16x8 qreg[DQK / 16], greg[DV / 16];
   load_owner<DQK>(qreg, qg, sq, orow, it.nrows, hh);
   load_owner<DV>(greg, gg, sv, orow, it.nrows, hh);
+  BiasCtx bias = {};
+  DwAcc dwa = {dwl, 0.f, -1};
+  if constexpr (BIAS) {
+    for (int i = tid; i < a.nb; i += NW * 64) dwl[i] = 0.f;
+    bias = bias_setup<NW * 64>(a, wtab, it, orow, tid, hh);
+  }
 
   f32x16 dqacc[DQK / 32];
 #pragma unroll
@@ -934,6 +1127,7 @@ __global__ void __launch_bounds__(NW * 64, 2) hstu_dq_bf16(AttnArgs a) {
     const TileRef t0 = tile_ref(it, st, 0);
     tile_copy_async<DQK, NW>(kbuf(0), kg + (int64_t)t0.row * sq, sq, t0.valid, wave, lane);
     tile_copy_async<DV, NW>(vbuf(0), vg + (int64_t)t0.row * sv, sv, t0.valid, wave, lane);
+    if (BIAS && wave == 0) rec_copy_async(tbuf(0), a.ts_rec + t0.row, t0.valid, lane);
   }
   tile_copy_wait<0>();
   tile_barrier();
@@ -945,6 +1139,7 @@ __global__ void __launch_bounds__(NW * 64, 2) hstu_dq_bf16(AttnArgs a) {
       const TileRef tn = tile_ref(it, st, j + 1);
       tile_copy_async<DQK, NW>(kbuf(BUF ^ 1), kg + (int64_t)tn.row * sq, sq, tn.valid, wave, lane);
       tile_copy_async<DV, NW>(vbuf(BUF ^ 1), vg + (int64_t)tn.row * sv, sv, tn.valid, wave, lane);
+      if (BIAS && wave == 0) rec_copy_async(tbuf(BUF ^ 1), a.ts_rec + tn.row, tn.valid, lane);
     }
     const char* kt = kbuf(BUF);
     const char* vt = vbuf(BUF);
@@ -953,8 +1148,8 @@ __global__ void __launch_bounds__(NW * 64, 2) hstu_dq_bf16(AttnArgs a) {
       for (int blk = 0; blk < ST / 32; ++blk) {
         const int k_lo = tj.pos + blk * 32;
         if (blk * 32 >= tj.valid || (a.causal && k_lo > q_hi)) continue;  // no key of the block is visible
-        dq_block<DQK, DV>(kt, vt, blk, rak, rav, cak, qreg, greg, dqacc, c1, a.alpha, k_lo, q_lo,
-                          a.causal && k_lo + 31 > q_lo, n, hh);
+        dq_block<DQK, DV, BIAS>(bias, tbuf(BUF), dwa, kt, vt, blk, rak, rav, cak, qreg, greg, dqacc, c1,
+                                a.alpha, k_lo, q_lo, a.causal && k_lo + 31 > q_lo, n, hh);
       }
     }
     tile_copy_wait<0>();
@@ -963,6 +1158,16 @@ __global__ void __launch_bounds__(NW * 64, 2) hstu_dq_bf16(AttnArgs a) {
   for (int j = 0; j < st.total; j += 2) {
     step(j, std::integral_constant<int, 0>{});
     if (j + 1 < st.total) step(j + 1, std::integral_constant<int, 1>{});
+  }
+
+  if constexpr (BIAS) {
+    // the workgroup's sums go to the table gradient (fp32 atomics: the order of the additions,
+    // and with it the last bits of the result, varies from run to run)
+    dwa.flush(lane);
+    __syncthreads();
+    const float scale = a.alpha * a.inv_n;
+    for (int i = tid; i < a.nb; i += NW * 64)
+      if (dwl[i] != 0.f) atomicAdd(a.d_ts_w + i, dwl[i] * scale);
   }
 
   // dQ^T accumulators: lane holds query row n, elements c*32 + 8*(r/4) + 4*hh + r%4.
@@ -1042,6 +1247,18 @@ int waves_bf16(int pass, int64_t owner_rows, int heads) {
     return hipGetLastError();                                                           \
   } while (0)
 
+// The kernels with the timestamp bias exist for equal head dimensions of Q/K and V only.
+#define HSTU_DISPATCH_BIAS(KERNEL, NW, ...)                                             \
+  do {                                                                                  \
+    const dim3 grid((unsigned)((int64_t)a.max_items * a.num_heads)), block(NW * 64);    \
+    if (a.nb < 1 || a.nb > MAX_TS_BUCKETS || !a.ts_w) return hipErrorInvalidValue;      \
+    if (d_qk == 128 && d_v == 128) hipLaunchKernelGGL((KERNEL<128, 128, __VA_ARGS__>), grid, block, 0, stream, a); \
+    else if (d_qk == 64 && d_v == 64) hipLaunchKernelGGL((KERNEL<64, 64, __VA_ARGS__>), grid, block, 0, stream, a); \
+    else if (d_qk == 32 && d_v == 32) hipLaunchKernelGGL((KERNEL<32, 32, __VA_ARGS__>), grid, block, 0, stream, a); \
+    else return hipErrorInvalidValue;                                                   \
+    return hipGetLastError();                                                           \
+  } while (0)
+
 hipError_t launch_transpose_bf16(const void* src, void* dst, const Plan& plan, int num_heads, int d,
                                  hipStream_t stream) {
   const dim3 grid((unsigned)((int64_t)plan.max_stiles * num_heads)), block(256);
@@ -1057,19 +1274,31 @@ hipError_t launch_transpose_bf16(const void* src, void* dst, const Plan& plan, i
 hipError_t launch_fwd_bf16(const AttnArgs& a, int d_qk, int d_v, hipStream_t stream) {
   if (a.vt == nullptr) {  // no transposed copy of V was built
     if (a.waves != 4) return hipErrorInvalidValue;
-    HSTU_DISPATCH_D(hstu_fwd_bf16, 4, 4, false);
+    if (a.ts_rec) HSTU_DISPATCH_BIAS(hstu_fwd_bf16, 4, 4, false, true);
+    HSTU_DISPATCH_D(hstu_fwd_bf16, 4, 4, false, false);
   }
-  if (a.waves == 8) HSTU_DISPATCH_D(hstu_fwd_bf16, 8, 8, true);
-  if (a.waves == 4) HSTU_DISPATCH_D(hstu_fwd_bf16, 4, 4, true);
+  if (a.waves == 8) {
+    if (a.ts_rec) HSTU_DISPATCH_BIAS(hstu_fwd_bf16, 8, 8, true, true);
+    HSTU_DISPATCH_D(hstu_fwd_bf16, 8, 8, true, false);
+  }
+  if (a.waves == 4) {
+    if (a.ts_rec) HSTU_DISPATCH_BIAS(hstu_fwd_bf16, 4, 4, true, true);
+    HSTU_DISPATCH_D(hstu_fwd_bf16, 4, 4, true, false);
+  }
   return hipErrorInvalidValue;
 }
 hipError_t launch_dkdv_bf16(const AttnArgs& a, int d_qk, int d_v, hipStream_t stream) {
   if (a.waves != 4) return hipErrorInvalidValue;
-  HSTU_DISPATCH_D(hstu_dkdv_bf16, 4, 4);
+  if (a.ts_rec) HSTU_DISPATCH_BIAS(hstu_dkdv_bf16, 4, 4, true);
+  HSTU_DISPATCH_D(hstu_dkdv_bf16, 4, 4, false);
 }
 hipError_t launch_dq_bf16(const AttnArgs& a, int d_qk, int d_v, hipStream_t stream) {
   if (a.waves != 4) return hipErrorInvalidValue;
-  HSTU_DISPATCH_D(hstu_dq_bf16, 4, 4);
+  if (a.ts_rec) {
+    if (!a.d_ts_w) return hipErrorInvalidValue;
+    HSTU_DISPATCH_BIAS(hstu_dq_bf16, 4, 4, true);
+  }
+  HSTU_DISPATCH_D(hstu_dq_bf16, 4, 4, false);
 }
 
 }  // namespace hstu

@@ -518,6 +518,50 @@ hipError_t launch_reduce_partials(const Plan& plan, int64_t max_tiles, const flo
   return hipGetLastError();
 }
 
+namespace {
+
+// Timestamp records (see TsRecord): one thread per row.  The sequence of a row is found by
+// bisection of the offsets; rows outside every sequence (offsets that do not end at the row
+// count) get a range of their own timestamp only.
+__global__ void __launch_bounds__(256) ts_records_kernel(const int32_t* __restrict__ ts,
+                                                         const int32_t* __restrict__ off, int batch,
+                                                         int total, TsRecord* __restrict__ rec,
+                                                         float* __restrict__ d_w, int nb) {
+  const int r = blockIdx.x * 256 + threadIdx.x;
+  if (d_w)
+    for (int i = r; i < nb; i += gridDim.x * 256) d_w[i] = 0.f;
+  if (r >= total + 64) return;
+  TsRecord x = {0, 0, 0, 0};
+  if (r < total) {
+    int lo = 0, hi = batch;  // off[lo] <= r < off[hi] when the offsets are well-formed
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (off[mid] <= r) lo = mid; else hi = mid;
+    }
+    int end = off[hi];
+    end = end < total ? end : total;
+    const int last = r + 32 < end ? r + 32 : end;
+    x.ts = x.lo = x.hi = ts[r];
+    for (int i = r + 1; i < last; ++i) {
+      const int t = ts[i];
+      x.lo = t < x.lo ? t : x.lo;
+      x.hi = t > x.hi ? t : x.hi;
+    }
+  }
+  rec[r] = x;
+}
+
+}  // namespace
+
+hipError_t launch_ts_records(const int32_t* ts, const int32_t* off, int batch, int64_t total_rows,
+                             TsRecord* rec, float* d_w, int nb, hipStream_t stream) {
+  if (batch < 1 || total_rows < 1 || total_rows + 64 >= (1ll << 31)) return hipErrorInvalidValue;
+  const unsigned blocks = (unsigned)((total_rows + 64 + 255) / 256);
+  hipLaunchKernelGGL(ts_records_kernel, dim3(blocks), dim3(256), 0, stream, ts, off, batch,
+                     (int)total_rows, rec, d_w, nb);
+  return hipGetLastError();
+}
+
 hipError_t launch_plans(const PlanArgs* a, int count, hipStream_t stream) {
   static_assert(NBINS == 2 * PLAN_THREADS, "pass 3 handles two bins per thread");
   if (count < 1 || count > 3) return hipErrorInvalidValue;

@@ -1,0 +1,134 @@
+"""Attention with the timestamp bias (forward, dQ/dK/dV and the gradient of the bucket table)
+on the GPU against oracle/hstu_oracle_bias.c, through the C ABI.
+
+Tolerances: o, dq, dk, dv as for the calls without bias (max abs error <= 2e-2 x RMS of the exact
+tensor, plus half a bf16 ulp when the output is bf16).  The table gradient is a sum of fp32 dS
+values that are never rounded to bf16, accumulated in fp32: <= 2e-3 x RMS over the buckets."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads
+from test_gpu_parity import _check, _dev
+
+pytestmark = pytest.mark.gpu
+
+
+def _run(w, kind, nb, f, causal=True, wscale=1.0, out_dtype=torch.float32, seed=0):
+    import paper_2508_04711_amd as lib
+    vals = workloads.values(w)
+    dev = _dev(vals)
+    f64 = {k: workloads.to_f64(v) for k, v in vals.items()}
+    off_np = w.seq_offsets()
+    off = torch.from_numpy(off_np).cuda()
+    ts_np = workloads.timestamps(w, kind, seed)
+    tab_np = workloads.bias_table(nb, seed, wscale)
+    ts, tab = torch.from_numpy(ts_np).cuda(), torch.from_numpy(tab_np).cuda()
+    want = oracle.bias_attention(f64["q"], f64["k"], f64["v"], f64["d_o"], off_np, ts_np,
+                                 tab_np.astype(np.float64), f, w.max_len, w.alpha, causal)
+    tag = "%s/%s/nb%d/f%d/%s" % (w.name, kind, nb, f, "causal" if causal else "full")
+    print("bias", tag, flush=True)
+    o = lib.hstu_jagged_attn_bias_fwd(dev["q"], dev["k"], dev["v"], off, ts, tab, f, w.max_len, w.alpha,
+                                      causal, out_dtype=out_dtype)
+    torch.cuda.synchronize()
+    _check("o", o, want[0], w.dtype, tag)
+    dq, dk, dv, dw = lib.hstu_jagged_attn_bias_bwd(dev["q"], dev["k"], dev["v"], dev["d_o"], off, ts, tab,
+                                                   f, w.max_len, w.alpha, causal, out_dtype=out_dtype)
+    torch.cuda.synchronize()
+    _check("dq", dq, want[1], w.dtype, tag)
+    _check("dk", dk, want[2], w.dtype, tag)
+    _check("dv", dv, want[3], w.dtype, tag)
+    got = dw.double().cpu().numpy()
+    assert np.isfinite(got).all()
+    rms = float(np.sqrt(np.mean(want[4] ** 2)))
+    err = float(np.abs(got - want[4]).max())
+    assert err <= 2e-3 * rms + 1e-30, "%s dw: max|err|/rms = %.3e" % (tag, err / max(rms, 1e-300))
+    # buckets no pair falls into stay exactly zero
+    assert (got[want[4] == 0.0] == 0.0).all()
+    return dw
+
+
+LENGTHS = [700, 130, 1, 519, 0, 64, 33]
+
+
+@pytest.mark.parametrize("kind", ["events", "shuffled", "equal", "wide"])
+@pytest.mark.parametrize("d", [32, 64, 128])
+def test_bias_matches_oracle(kind, d):
+    w = workloads.custom("bias_small", LENGTHS, 2, d, d, 700, dtype="bf16", seed=20 + d)
+    _run(w, kind, nb=40, f=2, causal=True, seed=d)
+
+
+@pytest.mark.parametrize("nb,f", [(1, 0), (7, 0), (33, 1), (512, 4), (300, 8)])
+def test_bias_bucket_shapes(nb, f):
+    w = workloads.custom("bias_buckets", [300, 257, 90], 2, 64, 64, 300, dtype="bf16", seed=5)
+    _run(w, "events", nb=nb, f=f, seed=nb)
+
+
+def test_bias_non_causal_and_bf16_outputs():
+    w = workloads.custom("bias_full", [260, 75, 130], 3, 64, 64, 260, dtype="bf16", seed=6)
+    _run(w, "events", nb=24, f=1, causal=False, seed=1)
+    _run(w, "shuffled", nb=24, f=1, causal=False, seed=2)
+    _run(w, "events", nb=24, f=1, causal=True, out_dtype=torch.bfloat16, seed=3)
+
+
+def test_bias_long_sequence_with_key_split_and_wide_tiles():
+    """One long sequence: the forward and dQ passes cut their heavy query tiles along the keys,
+    and most blocks are far from the diagonal (one bucket per block)."""
+    w = workloads.custom("bias_long", [4700, 300], 1, 64, 64, 4700, dtype="bf16", seed=8)
+    _run(w, "events", nb=64, f=2, seed=4)
+
+
+def test_bias_many_short_sequences():
+    """Mean length below the threshold of the form without a transposed copy of V."""
+    rng = np.random.default_rng(3)
+    lengths = [int(x) for x in rng.integers(1, 200, size=40)]
+    w = workloads.custom("bias_short", lengths, 2, 128, 128, 200, dtype="bf16", seed=9)
+    _run(w, "events", nb=48, f=2, seed=5)
+
+
+def test_zero_table_equals_the_call_without_bias():
+    import paper_2508_04711_amd as lib
+    w = workloads.custom("bias_zero", [700, 130, 519], 2, 64, 64, 700, dtype="bf16", seed=11)
+    dev = _dev(workloads.values(w))
+    off = torch.from_numpy(w.seq_offsets()).cuda()
+    ts = torch.from_numpy(workloads.timestamps(w, "events", 1)).cuda()
+    tab = torch.zeros(32, dtype=torch.float32, device="cuda")
+    o0 = lib.hstu_jagged_attn_fwd(dev["q"], dev["k"], dev["v"], off, w.max_len, w.alpha, True)
+    o1 = lib.hstu_jagged_attn_bias_fwd(dev["q"], dev["k"], dev["v"], off, ts, tab, 2, w.max_len, w.alpha, True)
+    g0 = lib.hstu_jagged_attn_bwd(dev["q"], dev["k"], dev["v"], dev["d_o"], off, w.max_len, w.alpha, True)
+    g1 = lib.hstu_jagged_attn_bias_bwd(dev["q"], dev["k"], dev["v"], dev["d_o"], off, ts, tab, 2, w.max_len,
+                                       w.alpha, True)
+    torch.cuda.synchronize()
+    # adding 0.0 to the accumulator before the products changes no bit
+    assert torch.equal(o0, o1)
+    for a, b in zip(g0, g1[:3]):
+        assert torch.equal(a, b)
+
+
+def test_bias_argument_errors():
+    import paper_2508_04711_amd as lib
+    w = workloads.custom("bias_err", [64, 64], 1, 32, 32, 64, dtype="bf16", seed=1)
+    dev = _dev(workloads.values(w))
+    off = torch.from_numpy(w.seq_offsets()).cuda()
+    ts = torch.from_numpy(workloads.timestamps(w, "events", 1)).cuda()
+    tab = torch.zeros(8, dtype=torch.float32, device="cuda")
+    with pytest.raises(lib.HstuError) as e:      # groups_log2 out of range
+        lib.hstu_jagged_attn_bias_fwd(dev["q"], dev["k"], dev["v"], off, ts, tab, 9, 64, w.alpha, True)
+    assert e.value.status == -2
+    big = torch.zeros(513, dtype=torch.float32, device="cuda")
+    with pytest.raises(lib.HstuError) as e:      # too many buckets
+        lib.hstu_jagged_attn_bias_fwd(dev["q"], dev["k"], dev["v"], off, ts, big, 2, 64, w.alpha, True)
+    assert e.value.status == -2
+    f32 = {k: v.float() for k, v in dev.items()}
+    with pytest.raises(lib.HstuError) as e:      # fp32 inputs are not supported with bias
+        lib.hstu_jagged_attn_bias_fwd(f32["q"], f32["k"], f32["v"], off, ts, tab, 2, 64, w.alpha, True)
+    assert e.value.status == -3
+    small = torch.empty(256, dtype=torch.uint8, device="cuda")
+    with pytest.raises(lib.HstuError) as e:
+        lib.hstu_jagged_attn_bias_fwd(dev["q"], dev["k"], dev["v"], off, ts, tab, 2, 64, w.alpha, True,
+                                      workspace=small)
+    assert e.value.status == -4
+    with pytest.raises(ValueError):              # one timestamp per row
+        lib.hstu_jagged_attn_bias_fwd(dev["q"], dev["k"], dev["v"], off, ts[:-1].contiguous(), tab, 2, 64,
+                                      w.alpha, True)

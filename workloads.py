@@ -134,3 +134,38 @@ def values(w: Workload) -> Dict[str, torch.Tensor]:
 def to_f64(t: torch.Tensor) -> np.ndarray:
     """Exact widening of stored values (bf16 or fp32) to float64 for the oracle."""
     return t.detach().cpu().to(torch.float64).numpy()
+
+
+def timestamps(w: Workload, kind: str = "events", seed: int = 0) -> np.ndarray:
+    """One int32 timestamp per row, for the attention with timestamp bias.
+
+    "events": per sequence a random start plus cumulative heavy-tailed gaps (log-normal seconds
+    with a median of a minute: bursts of activity separated by idle hours), non-decreasing
+    inside a sequence, as a user's interaction history is; "shuffled": the same values in random
+    order inside each sequence (nothing sorted: every block of pairs spans many buckets);
+    "equal": one value per sequence (every difference zero); "wide": differences up to the
+    whole int32 range.
+    """
+    rng = np.random.default_rng(1000 + seed)
+    out = []
+    for L in w.lengths:
+        if kind == "equal":
+            t = np.full(L, rng.integers(0, 2 ** 30), dtype=np.int64)
+        elif kind == "wide":
+            t = np.sort(rng.integers(-2 ** 31, 2 ** 31 - 1, size=L, dtype=np.int64))
+        else:
+            gaps = np.exp(rng.normal(np.log(60.0), 2.0, size=L)).astype(np.int64)
+            t = rng.integers(0, 2 ** 28) + np.cumsum(np.minimum(gaps, 10 ** 6))
+            if kind == "shuffled":
+                t = rng.permutation(t)
+            elif kind != "events":
+                raise ValueError(kind)
+        out.append(t)
+    out.append(np.zeros(0, dtype=np.int64))
+    return np.concatenate(out).astype(np.int32)
+
+
+def bias_table(num_buckets: int, seed: int = 0, scale: float = 1.0) -> np.ndarray:
+    """A bucket table of the timestamp bias: fp32 values ~ N(0,1) * scale."""
+    rng = np.random.default_rng(2000 + seed)
+    return (rng.standard_normal(num_buckets) * scale).astype(np.float32)
