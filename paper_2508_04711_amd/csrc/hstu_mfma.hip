@@ -371,8 +371,14 @@ __device__ __forceinline__ bool fetch_item(const Plan& plan, int slot, Item& it)
 // (x = alpha * (q.k + w) in the forward pass and in both backward passes alike).
 // The bucket grows with delta, so when the smallest and the largest difference a block can contain
 // (from the ranges of the two sides' timestamps) fall into one bucket, the whole block takes that
-// one table entry; otherwise every lane works out the buckets of its 16 pairs.
+// one table entry; otherwise every lane works out the buckets of its 16 pairs.  Which case a
+// block is, and the table entry of the first case, is worked out for 64 blocks of the stream at a
+// time, one block per lane (BlockTable), so that a block of the first case costs two cross-lane
+// reads when its turn comes.  (Measured alternatives: the range through an LDS read and the two
+// buckets in scalar arithmetic per block, or through scalar loads issued a tile ahead, cost 7 to
+// 13 % of a pass even when every block is of the first case.)
 // =============================================================================================
+
 constexpr int REC_TILE = ST * (int)sizeof(TsRecord);  // bytes of the records of one streamed tile
 
 // Asynchronous copy of the records of one streamed tile (one wave-wide load; rows >= valid
@@ -385,11 +391,12 @@ __device__ __forceinline__ void rec_copy_async(char* tile, const TsRecord* rec, 
 }
 
 __device__ __forceinline__ int bias_bucket(uint32_t delta, int nb, int f) {
-  if (delta <= 1u) return 0;
-  const int e = 31 - __builtin_clz(delta);
-  const uint32_t top = e >= f ? delta >> (e - f) : delta << (f - e);
-  const int b = (e << f) + (int)top - (1 << f);
-  return b < nb - 1 ? b : nb - 1;
+  const uint32_t d = delta > 2u ? delta : 2u;  // (no branch: the result for delta <= 1 is selected below)
+  const int e = 31 - __builtin_clz(d);
+  const uint32_t top = e >= f ? d >> (e - f) : d << (f - e);
+  int b = (e << f) + (int)top - (1 << f);
+  b = b < nb - 1 ? b : nb - 1;
+  return delta <= 1u ? 0 : b;
 }
 
 __device__ __forceinline__ uint32_t abs_diff(int a, int b) {
@@ -412,33 +419,83 @@ __device__ __forceinline__ float wave_sum(float x) {
   return x;
 }
 
-// What a wave knows about the bias: its own rows' timestamps and the table (in LDS).
+// What a wave knows about the bias: its own rows' timestamps and the table.
 struct BiasCtx {
-  const float* wtab;  // LDS copy of the table
-  int t_own;          // timestamp of the lane's owner row
-  int o_lo, o_hi;     // range of the timestamps of the wave's valid owner rows (uniform)
+  const float* wtab;     // LDS copy of the table
+  const TsRecord* rec;   // the records of all rows, padded by 64
+  int t_own;             // timestamp of the lane's owner row
+  int o_lo, o_hi;        // range of the timestamps of the wave's valid owner rows (uniform)
   int nb, f, hh;
 };
 
+// The uniform part of a block's bias: whether all its pairs fall into one bucket, that bucket
+// (else the bucket of the smallest difference) and its table entry.
+struct BlockBias {
+  int b0;
+  bool uni;
+  float wb;
+};
+
+// BlockBias of the stream's blocks, one block per lane: blocks [128k, 128k + 64) in set 0,
+// [128k + 64, 128k + 128) in set 1; a set is refilled when the stream enters the other one.
+struct BlockTable {
+  int code0, code1;  // bucket | NONUNIFORM
+  float w0, w1;
+  static constexpr int NONUNIFORM = 1 << 30;
+
+  // Fills the set of blocks [first, first + 64), first a multiple of 64; blocks >= nblocks (past
+  // the end of the stream: their scores are computed and discarded) get a zero bias.
+  __device__ __forceinline__ void fill(const BiasCtx& c, int first, int nblocks, const Item& it,
+                                       const Stream& st, int lane) {
+    const int i = first + lane;
+    int code = 0;
+    float w = 0.f;
+    if (i < nblocks) {
+      const int t = i >> 1;
+      const bool g = t >= st.n[0];
+      const int rel = (g ? st.beg[1] + (t - st.n[0]) * ST : st.beg[0] + t * ST) + (i & 1) * 32;
+      const int row = (g ? it.seg_row0[1] : it.seg_row0[0]) + rel;  // inside the padded table
+      const u32x2 head = *(const u32x2*)&c.rec[row].lo;
+      const int s_lo = (int)head[0], s_hi = (int)head[1];
+      // differences of int32 values as uint32 (exact up to 2^32 - 1); of d1, d2 one is not negative
+      const uint32_t d1 = c.o_hi >= s_lo ? (uint32_t)c.o_hi - (uint32_t)s_lo : 0u;
+      const uint32_t d2 = s_hi >= c.o_lo ? (uint32_t)s_hi - (uint32_t)c.o_lo : 0u;
+      const uint32_t dmax = d1 > d2 ? d1 : d2;
+      const uint32_t dmin = c.o_lo > s_hi ? (uint32_t)c.o_lo - (uint32_t)s_hi
+                                          : (s_lo > c.o_hi ? (uint32_t)s_lo - (uint32_t)c.o_hi : 0u);
+      const int b0 = bias_bucket(dmin, c.nb, c.f), b1 = bias_bucket(dmax, c.nb, c.f);
+      code = b0 | (b0 != b1 ? NONUNIFORM : 0);
+      w = *HSTU_LDS(float, c.wtab + b0);
+    }
+    const bool odd = (first >> 6) & 1;
+    code0 = odd ? code0 : code; w0 = odd ? w0 : w;
+    code1 = odd ? code : code1; w1 = odd ? w : w1;
+  }
+
+  // Block i (uniform), which must be in one of the two sets filled last.
+  __device__ __forceinline__ BlockBias get(int i) const {
+    const int l = i & 63;
+    const bool odd = (i >> 6) & 1;
+    const int c0 = __builtin_amdgcn_readlane(code0, l), c1 = __builtin_amdgcn_readlane(code1, l);
+    const int x0 = __builtin_amdgcn_readlane(__builtin_bit_cast(int, w0), l);
+    const int x1 = __builtin_amdgcn_readlane(__builtin_bit_cast(int, w1), l);
+    const int c = odd ? c1 : c0;
+    BlockBias b;
+    b.b0 = c & (NONUNIFORM - 1);
+    b.uni = (c & NONUNIFORM) == 0;
+    b.wb = __builtin_bit_cast(float, odd ? x1 : x0);
+    return b;
+  }
+};
+
 // Bias of block blk of a streamed tile whose records are at trec (LDS): s[r] = w[bucket of the
-// pair (lane's owner row, streamed row 8*(r/4) + 4*hh + r%4 of the block)].  b0, b1: the buckets
-// of the smallest and largest difference the block can contain (uniform); bk: the buckets of the
-// lane's pairs when b0 != b1.  Records that were never written (a tile past the end of the
-// stream, whose scores are computed and discarded) give arbitrary but in-range buckets.
+// pair (lane's owner row, streamed row 8*(r/4) + 4*hh + r%4 of the block)].  bb: the uniform
+// part; bk: the buckets of the lane's pairs when the block spans several.
 __device__ __forceinline__ void bias_block(f32x16& s, const char* trec, int blk, const BiasCtx& c,
-                                           int& b0, int& b1, int (&bk)[16]) {
-  const u32x4 head = *HSTU_LDS(u32x4, trec + blk * 32 * (int)sizeof(TsRecord));
-  const int s_lo = __builtin_amdgcn_readfirstlane((int)head[1]);
-  const int s_hi = __builtin_amdgcn_readfirstlane((int)head[2]);
-  const int64_t d1 = (int64_t)c.o_hi - s_lo, d2 = (int64_t)s_hi - c.o_lo;
-  const int64_t dmax = d1 > d2 ? d1 : d2;
-  const int64_t dmin = c.o_lo > s_hi ? (int64_t)c.o_lo - s_hi : (s_lo > c.o_hi ? (int64_t)s_lo - c.o_hi : 0);
-  b0 = bias_bucket((uint32_t)dmin, c.nb, c.f);
-  b1 = bias_bucket((uint32_t)dmax, c.nb, c.f);
-  if (b0 == b1) {
-    const float wb = *HSTU_LDS(float, c.wtab + b0);
+                                           const BlockBias& bb, int (&bk)[16]) {
+  if (bb.uni) {
 #pragma unroll
-    for (int r = 0; r < 16; ++r) { s[r] = wb; bk[r] = b0; }
+    for (int r = 0; r < 16; ++r) { s[r] = bb.wb; bk[r] = bb.b0; }
   } else {
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
@@ -456,10 +513,11 @@ struct ScoreInit {
   const BiasCtx* c;
   const char* trec;
   int blk;
+  BlockBias bb;
   __device__ __forceinline__ void operator()(f32x16& s) const {
     if constexpr (BIAS) {
-      int b0, b1, bk[16];
-      bias_block(s, trec, blk, *c, b0, b1, bk);
+      int bk[16];
+      bias_block(s, trec, blk, *c, bb, bk);
     } else {
 #pragma unroll
       for (int r = 0; r < 16; ++r) s[r] = 0.f;
@@ -475,6 +533,7 @@ __device__ __forceinline__ BiasCtx bias_setup(const AttnArgs& a, float* wtab, co
   for (int i = tid; i < a.nb; i += NT) wtab[i] = a.ts_w[i];
   BiasCtx c;
   c.wtab = wtab;
+  c.rec = a.ts_rec;
   c.nb = a.nb; c.f = a.fbits; c.hh = hh;
   const bool ok = orow < it.nrows;
   c.t_own = ok ? a.ts_rec[it.row0 + orow].ts : 0;
@@ -594,7 +653,9 @@ __global__ void __launch_bounds__(NW * 64, 2) hstu_fwd_bf16(AttnArgs a) {
   load_owner<DQK>(qreg, qg, sq, orow, it.nrows, hh);
   BiasCtx bias = {};
   if constexpr (BIAS) bias = bias_setup<NW * 64>(a, wtab, it, orow, tid, hh);
-  auto init_of = [&](const char* trec, int blk) { return ScoreInit<BIAS>{&bias, trec, blk}; };
+  auto init_of = [&](const char* trec, int blk, const BlockBias& bb) {
+    return ScoreInit<BIAS>{&bias, trec, blk, bb};
+  };
 
   f32x16 oacc[DV / 32];
 #pragma unroll
@@ -654,14 +715,20 @@ __global__ void __launch_bounds__(NW * 64, 2) hstu_fwd_bf16(AttnArgs a) {
     }
     auto mask_of = [&](int i) { return a.causal && block_pos(i) + 31 > q_lo; };
     auto rel_of = [&](int i) { return q_lo + n - block_pos(i); };
+    BlockTable tab = {};
+    if constexpr (BIAS) {
+      tab.fill(bias, 0, NB, it, st, lane);
+      tab.fill(bias, 64, NB, it, st, lane);
+    }
+    auto bb_of = [&](int i) { return BIAS ? tab.get(i) : BlockBias{}; };
 
     // S of block 0 on its own, then step 0 (nothing to multiply by V yet)
     if (block_on(0)) {
-      init_of(tbuf(0), 0)(sacc[0]);
+      init_of(tbuf(0), 0, bb_of(0))(sacc[0]);
 #pragma unroll
       for (int ks = 0; ks < DQK / 16; ++ks) sacc[0] = mfma(ra.read(kbuf(0), 0, ks), qreg[ks], sacc[0]);
-      fwd_step<DQK, DV, false>(init_of(tbuf(0), 1), kbuf(0), 1, vbuf(0), 0, ra, ca, qreg, sacc[0], sacc[1],
-                               pb[1], pb[0], oacc, c1, mask_of(0), rel_of(0), hh);
+      fwd_step<DQK, DV, false>(init_of(tbuf(0), 1, bb_of(1)), kbuf(0), 1, vbuf(0), 0, ra, ca, qreg, sacc[0],
+                               sacc[1], pb[1], pb[0], oacc, c1, mask_of(0), rel_of(0), hh);
     }
     tile_barrier();  // iteration 0 copies over K tile 0, which the lines above read
 
@@ -671,18 +738,20 @@ __global__ void __launch_bounds__(NW * 64, 2) hstu_fwd_bf16(AttnArgs a) {
       constexpr int B0 = decltype(buf_tag)::value, B1 = (B0 + 1) % NBUF;
       // tiles j-1 (V) and j (K) were left by every wave before the last barrier
       const bool both = j + 1 + PD < T;
+      if constexpr (BIAS)  // the iteration enters one set of the block table: refill the other
+        if (((2 * j + 2) & 63) == 0) tab.fill(bias, 2 * j + 2 + 64, NB, it, st, lane);
       if (both) copy_k(j + 1 + PD, (B0 + 1 + PD) % NBUF);
       if (j + PD < T) copy_v(j + PD, (B0 + PD) % NBUF);
       {
         const int i = 2 * j + 1;  // S of (tile j+1, block 0), P V of (tile j, block 0)
         if (block_on(i - 1))
-          fwd_step<DQK, DV, true>(init_of(tbuf(B1), 0), kbuf(B1), 0, vbuf(B0), 0, ra, ca, qreg, sacc[1],
+          fwd_step<DQK, DV, true>(init_of(tbuf(B1), 0, bb_of(i + 1)), kbuf(B1), 0, vbuf(B0), 0, ra, ca, qreg, sacc[1],
                                   sacc[0], pb[0], pb[1], oacc, c1, mask_of(i), rel_of(i), hh);
       }
       if (j + 1 < T) {
         const int i = 2 * j + 2;  // S of (tile j+1, block 1), P V of (tile j, block 1)
         if (block_on(i - 1))
-          fwd_step<DQK, DV, true>(init_of(tbuf(B1), 1), kbuf(B1), 1, vbuf(B0), 1, ra, ca, qreg, sacc[0],
+          fwd_step<DQK, DV, true>(init_of(tbuf(B1), 1, bb_of(i + 1)), kbuf(B1), 1, vbuf(B0), 1, ra, ca, qreg, sacc[0],
                                   sacc[1], pb[1], pb[0], oacc, c1, mask_of(i), rel_of(i), hh);
       }
       // what the next iteration reads must have landed; with copies two tiles ahead the ones
@@ -850,7 +919,9 @@ __global__ void __launch_bounds__(NW * 64) hstu_dkdv_bf16(AttnArgs a) {
   load_owner<DV>(vreg, vg, sv, orow, it.nrows, hh);
   BiasCtx bias = {};
   if constexpr (BIAS) bias = bias_setup<NW * 64>(a, wtab, it, orow, tid, hh);
-  auto init_of = [&](const char* trec, int blk) { return ScoreInit<BIAS>{&bias, trec, blk}; };
+  auto init_of = [&](const char* trec, int blk, const BlockBias& bb) {
+    return ScoreInit<BIAS>{&bias, trec, blk, bb};
+  };
 
   f32x16 dkacc[DQK / 32], dvacc[DV / 32];
 #pragma unroll
@@ -900,9 +971,16 @@ __global__ void __launch_bounds__(NW * 64) hstu_dkdv_bf16(AttnArgs a) {
       for (int e = 0; e < 8; ++e) pd[x][y][e] = (__bf16)0.f;
   }
 
+  BlockTable tab = {};
+  if constexpr (BIAS) {
+    tab.fill(bias, 0, NB, it, st, lane);
+    tab.fill(bias, 64, NB, it, st, lane);
+  }
+  auto bb_of = [&](int i) { return BIAS ? tab.get(i) : BlockBias{}; };
+
   // scores of block 0 on their own
   if (block_on(0)) {
-    init_of(tbuf(0), 0)(sacc[0]);
+    init_of(tbuf(0), 0, bb_of(0))(sacc[0]);
 #pragma unroll
     for (int ks = 0; ks < DQK / 16; ++ks) sacc[0] = mfma(raq.read(qbuf(0), 0, ks), kreg[ks], sacc[0]);
 #pragma unroll
@@ -911,7 +989,7 @@ __global__ void __launch_bounds__(NW * 64) hstu_dkdv_bf16(AttnArgs a) {
   // step 0: scores of block 1, elementwise of block 0, nothing to contract yet
   if (block_on(1)) {
     const int pos = block_pos(0);
-    dkdv_step<DQK, DV, false>(init_of(tbuf(0), 1), qbuf(0), gbuf(0), 1, qbuf(0), gbuf(0), 0, raq, rag,
+    dkdv_step<DQK, DV, false>(init_of(tbuf(0), 1, bb_of(1)), qbuf(0), gbuf(0), 1, qbuf(0), gbuf(0), 0, raq, rag,
                               caq, cag, kreg, vreg, sacc[0], dacc[0], sacc[1], dacc[1], pd[1], pd[0],
                               dkacc, dvacc, c1, a.alpha, a.causal && pos < k_hi, k_lo + n - pos, hh);
   }
@@ -919,12 +997,14 @@ __global__ void __launch_bounds__(NW * 64) hstu_dkdv_bf16(AttnArgs a) {
   // Iteration j: steps 2j+1 and 2j+2, which touch tiles j and j+1 only.
   auto iter = [&](int j, auto buf_tag) {
     constexpr int B0 = decltype(buf_tag)::value, B1 = (B0 + 1) % 3, B2 = (B0 + 2) % 3;
+    if constexpr (BIAS)  // the iteration enters one set of the block table: refill the other
+      if (((2 * j + 2) & 63) == 0) tab.fill(bias, 2 * j + 2 + 64, NB, it, st, lane);
     if (j + 2 < T) copy_tile(j + 2, B2);  // every wave left tile j-1 before the last barrier
     {
       const int i = 2 * j + 1;  // scores of (tile j+1, block 0), contraction of (tile j, block 0)
       if (block_on(i + 1 < NB ? i + 1 : i)) {
         const int pos = block_pos(i);
-        dkdv_step<DQK, DV, true>(init_of(tbuf(B1), 0), qbuf(B1), gbuf(B1), 0, qbuf(B0), gbuf(B0), 0, raq,
+        dkdv_step<DQK, DV, true>(init_of(tbuf(B1), 0, bb_of(i + 1)), qbuf(B1), gbuf(B1), 0, qbuf(B0), gbuf(B0), 0, raq,
                                  rag, caq, cag, kreg, vreg, sacc[1], dacc[1], sacc[0], dacc[0], pd[0],
                                  pd[1], dkacc, dvacc, c1, a.alpha, a.causal && pos < k_hi,
                                  k_lo + n - pos, hh);
@@ -934,7 +1014,7 @@ __global__ void __launch_bounds__(NW * 64) hstu_dkdv_bf16(AttnArgs a) {
       const int i = 2 * j + 2;  // scores of (tile j+1, block 1), contraction of (tile j, block 1)
       if (block_on(i + 1)) {
         const int pos = block_pos(i);
-        dkdv_step<DQK, DV, true>(init_of(tbuf(B1), 1), qbuf(B1), gbuf(B1), 1, qbuf(B0), gbuf(B0), 1, raq,
+        dkdv_step<DQK, DV, true>(init_of(tbuf(B1), 1, bb_of(i + 1)), qbuf(B1), gbuf(B1), 1, qbuf(B0), gbuf(B0), 1, raq,
                                  rag, caq, cag, kreg, vreg, sacc[0], dacc[0], sacc[1], dacc[1], pd[1],
                                  pd[0], dkacc, dvacc, c1, a.alpha, a.causal && pos < k_hi,
                                  k_lo + n - pos, hh);
@@ -1003,22 +1083,36 @@ __global__ void __launch_bounds__(NW * 64) hstu_dkdv_bf16(AttnArgs a) {
 // Sum of dS per bucket for the gradient of the bias table (dq pass only: it visits every pair once).
 // A run of blocks that fall into one bucket adds up in a register per lane and goes to the
 // workgroup's LDS table when the bucket changes; the pairs of a block that spans several
-// buckets go there one by one.
+// buckets go there one by one.  The LDS table holds 2^shift copies of every bucket, a lane adds
+// to copy (lane mod 2^shift): lanes that hit the same bucket at once then mostly hit different
+// addresses (same-address LDS atomics are served one after the other).
+constexpr int DW_LDS = 2048;  // floats of the workgroup's table
+__host__ __device__ constexpr int dw_shift(int nb) {
+  int s = 0;
+  while (s < 5 && (nb << (s + 1)) <= DW_LDS) ++s;
+  return s;
+}
 struct DwAcc {
-  float* dwl;   // LDS, one entry per bucket
+  float* dwl;   // LDS, 2^shift entries per bucket
   float sum;    // per lane: dS of the current run
   int cur;      // bucket of the current run (uniform; -1: none)
+  int shift;
+  __device__ __forceinline__ void add(int bucket, int lane, float x) {
+    atomicAdd(dwl + (bucket << shift) + (lane & ((1 << shift) - 1)), x);
+  }
   __device__ __forceinline__ void flush(int lane) {
     if (cur >= 0) {
       const float t = wave_sum(sum);
-      if (lane == 0) atomicAdd(dwl + cur, t);
+      if (lane == 0) atomicAdd(dwl + (cur << shift), t);
     }
     sum = 0.f;
   }
 };
+static_assert(MAX_TS_BUCKETS <= DW_LDS, "one entry per bucket at least");
 
 template <int DQK, int DV, bool BIAS>
-__device__ __forceinline__ void dq_block(const BiasCtx& bias, const char* trec, DwAcc& dwa,
+__device__ __forceinline__ void dq_block(const BiasCtx& bias, const char* trec,
+                                                const BlockBias& bb, DwAcc& dwa,
                                                 const char* kt, const char* vt, int blk,
                                                 const RowAddr<DQK>& rak, const RowAddr<DV>& rav,
                                                 const ColAddr<DQK>& cak,
@@ -1027,10 +1121,10 @@ __device__ __forceinline__ void dq_block(const BiasCtx& bias, const char* trec, 
                                                 f32x16 (&dqacc)[DQK / 32], float c1, float alpha,
                                                 int k_lo, int q_lo, bool mask, int n, int hh) {
   f32x16 s, dp;
-  int b0 = 0, b1 = 0, bk[16];
+  int bk[16];
 #pragma unroll
   for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
-  if constexpr (BIAS) bias_block(s, trec, blk, bias, b0, b1, bk);
+  if constexpr (BIAS) bias_block(s, trec, blk, bias, bb, bk);
 #pragma unroll
   for (int ks = 0; ks < DQK / 16; ++ks) s = mfma(rak.read(kt, blk, ks), qreg[ks], s);
 #pragma unroll
@@ -1050,10 +1144,10 @@ __device__ __forceinline__ void dq_block(const BiasCtx& bias, const char* trec, 
     }
   }
   if constexpr (BIAS) {
-    if (b0 == b1) {
-      if (b0 != dwa.cur) {
+    if (bb.uni) {
+      if (bb.b0 != dwa.cur) {
         dwa.flush(n + 32 * hh);
-        dwa.cur = b0;
+        dwa.cur = bb.b0;
       }
       float t = 0.f;
 #pragma unroll
@@ -1061,7 +1155,7 @@ __device__ __forceinline__ void dq_block(const BiasCtx& bias, const char* trec, 
       dwa.sum += t;
     } else {
 #pragma unroll
-      for (int r = 0; r < 16; ++r) atomicAdd(dwa.dwl + bk[r], ds[r]);
+      for (int r = 0; r < 16; ++r) dwa.add(bk[r], n + 32 * hh, ds[r]);
     }
   }
   const bf16x8 db0 = pack8(ds), db1 = pack8(ds + 8);
@@ -1080,7 +1174,7 @@ __global__ void __launch_bounds__(NW * 64, 2) hstu_dq_bf16(AttnArgs a) {
   __shared__ __attribute__((aligned(1024))) char tmem0[BIAS ? REC_TILE : 16];
   __shared__ __attribute__((aligned(1024))) char tmem1[BIAS ? REC_TILE : 16];
   __shared__ float wtab[BIAS ? MAX_TS_BUCKETS : 1];
-  __shared__ float dwl[BIAS ? MAX_TS_BUCKETS : 1];
+  __shared__ float dwl[BIAS ? DW_LDS : 1];
   auto kbuf = [&](int b) { return b ? smem1 : smem0; };
   auto vbuf = [&](int b) { return (b ? smem1 : smem0) + KB; };
   auto tbuf = [&](int b) { return b ? tmem1 : tmem0; };
@@ -1104,9 +1198,10 @@ __global__ void __launch_bounds__(NW * 64, 2) hstu_dq_bf16(AttnArgs a) {
   load_owner<DQK>(qreg, qg, sq, orow, it.nrows, hh);
   load_owner<DV>(greg, gg, sv, orow, it.nrows, hh);
   BiasCtx bias = {};
-  DwAcc dwa = {dwl, 0.f, -1};
+  DwAcc dwa = {dwl, 0.f, -1, 0};
   if constexpr (BIAS) {
-    for (int i = tid; i < a.nb; i += NW * 64) dwl[i] = 0.f;
+    dwa.shift = dw_shift(a.nb);
+    for (int i = tid; i < (a.nb << dwa.shift); i += NW * 64) dwl[i] = 0.f;
     bias = bias_setup<NW * 64>(a, wtab, it, orow, tid, hh);
   }
 
@@ -1132,9 +1227,17 @@ __global__ void __launch_bounds__(NW * 64, 2) hstu_dq_bf16(AttnArgs a) {
   tile_copy_wait<0>();
   tile_barrier();
 
+  BlockTable tab = {};
+  if constexpr (BIAS) {
+    tab.fill(bias, 0, 2 * st.total, it, st, lane);
+    tab.fill(bias, 64, 2 * st.total, it, st, lane);
+  }
+
   auto step = [&](int j, auto buf_tag) {
     constexpr int BUF = decltype(buf_tag)::value;
     const TileRef tj = tile_ref(it, st, j);
+    if constexpr (BIAS)  // the step enters one set of the block table: refill the other
+      if (j > 0 && ((2 * j) & 63) == 0) tab.fill(bias, 2 * j + 64, 2 * st.total, it, st, lane);
     if (j + 1 < st.total) {
       const TileRef tn = tile_ref(it, st, j + 1);
       tile_copy_async<DQK, NW>(kbuf(BUF ^ 1), kg + (int64_t)tn.row * sq, sq, tn.valid, wave, lane);
@@ -1148,7 +1251,7 @@ __global__ void __launch_bounds__(NW * 64, 2) hstu_dq_bf16(AttnArgs a) {
       for (int blk = 0; blk < ST / 32; ++blk) {
         const int k_lo = tj.pos + blk * 32;
         if (blk * 32 >= tj.valid || (a.causal && k_lo > q_hi)) continue;  // no key of the block is visible
-        dq_block<DQK, DV, BIAS>(bias, tbuf(BUF), dwa, kt, vt, blk, rak, rav, cak, qreg, greg, dqacc, c1,
+        dq_block<DQK, DV, BIAS>(bias, tbuf(BUF), BIAS ? tab.get(2 * j + blk) : BlockBias{}, dwa, kt, vt, blk, rak, rav, cak, qreg, greg, dqacc, c1,
                                 a.alpha, k_lo, q_lo, a.causal && k_lo + 31 > q_lo, n, hh);
       }
     }
@@ -1166,8 +1269,12 @@ __global__ void __launch_bounds__(NW * 64, 2) hstu_dq_bf16(AttnArgs a) {
     dwa.flush(lane);
     __syncthreads();
     const float scale = a.alpha * a.inv_n;
-    for (int i = tid; i < a.nb; i += NW * 64)
-      if (dwl[i] != 0.f) atomicAdd(a.d_ts_w + i, dwl[i] * scale);
+    for (int i = tid; i < a.nb; i += NW * 64) {
+      float t = 0.f;
+      const int cm = (1 << dwa.shift) - 1;  // (rotated by i: neighbouring threads read different banks)
+      for (int c = 0; c <= cm; ++c) t += dwl[(i << dwa.shift) + ((c + i) & cm)];
+      if (t != 0.f) atomicAdd(a.d_ts_w + i, t * scale);
+    }
   }
 
   // dQ^T accumulators: lane holds query row n, elements c*32 + 8*(r/4) + 4*hh + r%4.
