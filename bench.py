@@ -7,7 +7,7 @@ context-parallel workload every rank's reorder into its local layout, its partia
 reorder back, ranks one after the other on the one GPU).
 Inputs are resident in HBM before the timed region starts.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg5|cfg3|cfg2|cfg4]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg5|cfg3|cfg2|cfg4|cfg4_ring|cfg5_bias]
 """
 from __future__ import annotations
 
@@ -69,7 +69,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="cfg5", choices=["cfg2", "cfg3", "cfg4", "cfg4_ring", "cfg5"])
+    ap.add_argument("--workload", default="cfg5", choices=["cfg2", "cfg3", "cfg4", "cfg4_ring", "cfg5", "cfg5_bias"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-prefix-rows", type=int, default=0, help="rows per sequence in the CPU sample")
     args = ap.parse_args()
@@ -85,6 +85,7 @@ def main() -> int:
     lib.load_library()  # fail loudly if the HIP library is not built
 
     ring = args.workload.endswith("_ring")
+    with_bias = args.workload.endswith("_bias")  # the same batch with the timestamp bias
     cfg = int(args.workload[3:4])
     w = workloads.config(cfg)
     dev = torch.device("cuda:0")
@@ -170,7 +171,22 @@ def main() -> int:
         ws = torch.empty(max(lib.hstu_jagged_attn_workspace_bytes(p, 0),
                              lib.hstu_jagged_attn_workspace_bytes(p, 1)), dtype=torch.uint8, device=dev)
 
+        if with_bias:
+            # sorted event timestamps (see workloads.timestamps), 64 buckets, 4 groups per octave
+            ts = torch.from_numpy(workloads.timestamps(w, "events", 0)).to(dev)
+            tab = torch.from_numpy(workloads.bias_table(64, 0, 1.0)).to(dev)
+            dtab = torch.empty_like(tab)
+            ws = torch.empty(max(lib.hstu_jagged_attn_bias_workspace_bytes(p, 0),
+                                 lib.hstu_jagged_attn_bias_workspace_bytes(p, 1)),
+                             dtype=torch.uint8, device=dev)
+
         def step():
+            if with_bias:
+                lib.hstu_jagged_attn_bias_fwd(vals["q"], vals["k"], vals["v"], off, ts, tab, 2, w.max_len,
+                                              w.alpha, True, out=o, workspace=ws)
+                lib.hstu_jagged_attn_bias_bwd(vals["q"], vals["k"], vals["v"], vals["d_o"], off, ts, tab, 2,
+                                              w.max_len, w.alpha, True, out=(dq, dk, dv, dtab), workspace=ws)
+                return
             lib.hstu_jagged_attn_fwd(vals["q"], vals["k"], vals["v"], off, w.max_len, w.alpha, True,
                                      out=o, workspace=ws)
             if w.backward:
@@ -218,7 +234,7 @@ def main() -> int:
     roofline = {
         "bound": "mfma", "kernel": kernel_name, "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
         "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
-        "traffic": _traffic_from_profiles(kernel_name, w.name),
+        "traffic": None if with_bias else _traffic_from_profiles(kernel_name, w.name),
         "avg_launch_ms": dom_ms, "launches_per_step": n_launch,
         "kernels": {k: {"avg_ms": avg_ms[k], "launches_per_step": launches_per_step[k],
                         "algorithmic_tflops": (alg[k] / launches_per_step[k] / (avg_ms[k] * 1e-3) / 1e12)
@@ -244,7 +260,7 @@ def main() -> int:
         "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": w.name + ("_ring" if ring else ""), "batch": w.batch, "total_rows": T, "num_heads": H,
+        "config": {"workload": w.name + ("_ring" if ring else "") + ("_ts_bias" if with_bias else ""), "batch": w.batch, "total_rows": T, "num_heads": H,
                    "d_qk": w.d_qk, "d_v": w.d_v, "max_len": w.max_len, "causal": True,
                    "cp_size": w.cp_size, "pairs_per_head": w.pairs_per_head,
                    "flops_per_step": step_flops},

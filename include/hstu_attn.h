@@ -128,9 +128,11 @@ int hstu_jagged_attn_bwd(const hstu_attn_params* params, const void* q, const vo
                          void* hip_stream);
 
 /* Timestamp bias.  Section 2.1's equation has "+ Bias" inside the SiLU and describes the bias in
- * words only: differences of the rows' timestamps are transformed and grouped into bucket
- * indices, which select entries of a learnable table.  The transformation and the grouping are
- * not given; this library's reading (PARITY WITH THE PAPER IS UNPINNED for it) is
+ * words only: differences of the rows' timestamps (of consecutive elements, the text says) are
+ * transformed and grouped into bucket indices, which select entries of a learnable table.  The
+ * transformation and the grouping are not given, and a term added to Q K^T needs a value per
+ * (query, key) pair; this library's reading (PARITY WITH THE PAPER IS UNPINNED for it) takes the
+ * difference of the pair's two timestamps:
  *     delta  = |timestamps[i] - timestamps[j]|                    (exact, up to 2^32 - 1)
  *     bucket = 0                                  if delta <= 1
  *            = min(num_buckets - 1, e * 2^f + m)  otherwise, e = floor(log2 delta), m = the f

@@ -5,11 +5,14 @@
  *
  * Paper, section 2.1: the attention equation has "+ Bias" inside the SiLU,
  *     HSTUAttention(Q,K,V) = Mask(SiLU((Q K^T + Bias)/sqrt(d_k))) V,
- * and the bias is described only in words: differences of timestamps, "the transformation
- * followed by the grouping" into bucket indices, which select entries of a learnable table
- * ts_weights.  The paper gives neither the transformation nor the number of buckets, so the
- * reading below is this build's own and PARITY WITH THE PAPER IS UNPINNED for it; what the
- * pins in tests/test_oracle_bias_pins.py fix is that this file computes the reading correctly.
+ * and the bias is described only in words: differences of the timestamps ts are taken (the
+ * text speaks of consecutive elements), transformed, then grouped into bucket indices, which
+ * select entries of a learnable table ts_weights.  The paper gives neither the transformation
+ * nor the number of buckets, and a term added to Q K^T needs one value per (query, key) pair,
+ * which differences of neighbouring rows alone do not give; the reading below takes the
+ * difference of the pair's two timestamps (the sum of the consecutive differences between
+ * them).  It is this build's own and PARITY WITH THE PAPER IS UNPINNED for it; what the pins
+ * in tests/test_oracle_bias_pins.py fix is that this file computes the reading correctly.
  *
  * Reading.  Every row carries an int32 timestamp ts.  For a visible pair (query i, key j) of
  * one sequence

@@ -85,6 +85,41 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     assert rc == -5
 
 
+def test_bias_calls_reject_bad_arguments_on_the_host(lib):
+    from paper_2508_04711_amd import binding
+    fake = ctypes.c_void_p(0x1000)      # never dereferenced: every call below fails validation first
+
+    def desc(ts=0x1000, w=0x1000, dw=0x1000, nb=16, f=2):
+        return binding._TsBias(ts, w, dw, nb, f)
+
+    def fwd(p, b, ws_bytes=1 << 20):
+        return lib.hstu_jagged_attn_bias_fwd(ctypes.byref(p), ctypes.byref(b) if b is not None else None,
+                                             fake, fake, fake, fake, fake, fake, ws_bytes, None)
+
+    def bwd(p, b, ws_bytes=1 << 20):
+        return lib.hstu_jagged_attn_bias_bwd(ctypes.byref(p), ctypes.byref(b), fake, fake, fake, fake, fake,
+                                             fake, fake, fake, fake, ws_bytes, None)
+
+    ok = _params(binding)
+    assert fwd(ok, None) == -1                                   # no descriptor
+    assert fwd(ok, desc(ts=None)) == -1 and fwd(ok, desc(w=None)) == -1
+    assert bwd(ok, desc(dw=None)) == -1                          # the backward call needs the gradient buffer
+    assert fwd(ok, desc(nb=0)) == -2 and fwd(ok, desc(nb=513)) == -2
+    assert fwd(ok, desc(f=-1)) == -2 and fwd(ok, desc(f=9)) == -2
+    assert fwd(_params(binding, dtype=1, out_dtype=1), desc()) == -3   # fp32 inputs
+    assert fwd(_params(binding, d_qk=128), desc()) == -3               # unequal head dimensions
+    assert fwd(_params(binding, batch=-1), desc()) == -2               # the common checks come first
+    assert fwd(ok, desc(), ws_bytes=64) == -4 and bwd(ok, desc(), ws_bytes=64) == -4
+    assert fwd(_params(binding, batch=0, total_rows=0), desc()) == 0   # empty batch: nothing to do
+    # workspace: the plain call's plus one 16-byte record per row (and 64 rows of padding)
+    for which in (0, 1):
+        plain = lib.hstu_jagged_attn_workspace_bytes(ctypes.byref(ok), which)
+        with_bias = lib.hstu_jagged_attn_bias_workspace_bytes(ctypes.byref(ok), which)
+        assert with_bias == plain + 16 * (10 + 64) + (-16 * (10 + 64)) % 256
+    assert lib.hstu_jagged_attn_bias_workspace_bytes(ctypes.byref(ok), 2) == 0
+    assert lib.hstu_jagged_attn_bias_workspace_bytes(ctypes.byref(_params(binding, d_qk=48)), 0) == 0
+
+
 def test_reorder_rejects_bad_arguments_on_the_host(lib):
     fake = 0x1000
     def call(batch=2, total=100, cp=2, rank=0, n=1, src=(fake,), dst=(fake,), rb=(256,), local=50,

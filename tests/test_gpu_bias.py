@@ -43,6 +43,7 @@ def _run(w, kind, nb, f, causal=True, wscale=1.0, out_dtype=torch.float32, seed=
     assert np.isfinite(got).all()
     rms = float(np.sqrt(np.mean(want[4] ** 2)))
     err = float(np.abs(got - want[4]).max())
+    print("   dw: max|err|/rms = %.2e" % (err / max(rms, 1e-300)), flush=True)
     assert err <= 2e-3 * rms + 1e-30, "%s dw: max|err|/rms = %.3e" % (tag, err / max(rms, 1e-300))
     # buckets no pair falls into stay exactly zero
     assert (got[want[4] == 0.0] == 0.0).all()
