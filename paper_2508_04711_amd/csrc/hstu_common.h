@@ -115,6 +115,20 @@ constexpr int MAX_TS_BUCKETS = 512;
 hipError_t launch_ts_records(const int32_t* ts, const int32_t* off, int batch, int64_t total_rows,
                              TsRecord* rec, float* d_w, int nb, hipStream_t stream);
 
+// Packed tiles: schedules whose owner tiles are `tile` consecutive rows of the batch whatever
+// sequences they belong to (item t = rows [t * tile, (t + 1) * tile), in natural order), for both
+// sides at once, plus the per-row sequence bounds the kernels' windows come from.  Positions are
+// row numbers.  Rows at or beyond off[batch] (clamped to total_rows) belong to no item.
+struct PackedPlanArgs {
+  const int32_t* off;
+  int32_t batch, total_rows, tile, causal;
+  int2* row_seq;                    // total_rows entries
+  int32_t* header[2];               // per side (0: owners are queries, 1: keys): see Plan
+  int32_t* order[2];
+  Item* items[2];
+};
+hipError_t launch_packed_plan(const PackedPlanArgs& a, hipStream_t stream);
+
 // Arguments of the attention kernels.
 struct AttnArgs {
   const void* q;
@@ -142,6 +156,9 @@ struct AttnArgs {
   float* d_ts_w;           // its gradient (dq pass: added with atomics), or null
   int32_t nb;              // buckets
   int32_t fbits;           // log2 of the groups per octave
+  // Packed tiles (bf16 kernels, whole-batch layout, batches of short sequences; null: not packed):
+  // per row the first row and the end row of its sequence, built by launch_packed_plan.
+  const int2* row_seq;
 };
 
 // Owner rows per item each kernel family expects (pass: 0 forward, 1 dk/dv, 2 dq); the

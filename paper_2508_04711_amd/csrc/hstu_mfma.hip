@@ -201,9 +201,9 @@ __device__ __forceinline__ void tile_barrier() {
   asm volatile("" ::: "memory");
 }
 
-// The owner rows are fetched with ordinary loads before the first tile copy is issued; waiting
-// for them first keeps the in-flight counts of the tile copies exact.
-__device__ __forceinline__ void load_owner_wait() { __builtin_amdgcn_s_waitcnt(0x0f70); }
+// (The owner rows are fetched with ordinary loads just before the first tile copies are issued,
+// and nothing waits in between: the prologue's wait for the first tiles covers them, so a
+// workgroup pays one memory round trip for both.)
 
 // 32 owner rows of one head as B operands: lane (n, hh) holds row n, elements 16*s + 8*hh + e.
 // base points at (row 0 of the owner tile, this head); rows >= nrows read as zero.
@@ -358,6 +358,63 @@ __device__ __forceinline__ bool fetch_item(const Plan& plan, int slot, Item& it)
   it.cost = 0;
   it.part = __builtin_amdgcn_readfirstlane(src->part);
   return it.nrows > 0;
+}
+
+// =============================================================================================
+// Which streamed rows of a 32-row block the lane's owner row sees; r is the accumulator element,
+// i.e. streamed row 8*(r/4) + 4*hh + r%4 of the block.
+// =============================================================================================
+struct VisBefore {  // owners are queries, causal: keys at or before the query; rel = query - block position
+  int rel, hh;
+  __device__ __forceinline__ bool operator()(int r) const { return 8 * (r >> 2) + 4 * hh + (r & 3) <= rel; }
+};
+struct VisAfter {   // owners are keys, causal: queries at or after the key; rel = key - block position
+  int rel, hh;
+  __device__ __forceinline__ bool operator()(int r) const { return rel <= 8 * (r >> 2) + 4 * hh + (r & 3); }
+};
+struct VisWindow {  // packed tiles: positions [lo, lo + span]; base = block position - lo
+  int base;
+  uint32_t span;
+  int hh;
+  __device__ __forceinline__ bool operator()(int r) const {
+    return (uint32_t)(base + 8 * (r >> 2) + 4 * hh + (r & 3)) <= span;
+  }
+};
+
+// Packed tiles (batches of short sequences): an owner tile is 128 consecutive rows of the batch
+// whatever sequences they belong to, the streamed rows run from the start of the first of those
+// sequences to the end of the last, positions are row numbers, and every owner row sees the
+// window of rows [lo, lo + span] of its own sequence (cut at the row itself when causal).
+struct Window {
+  int lo;
+  uint32_t span;
+  int lo_min, lo_max, hi_min, hi_max;  // over the wave's valid rows (uniform)
+  // some row of the block at position b may be hidden from some owner row of the wave
+  __device__ __forceinline__ bool masks(int b) const { return b < lo_max || b + 31 > hi_min; }
+  __device__ __forceinline__ VisWindow vis(int b, int hh) const { return VisWindow{b - lo, span, hh}; }
+};
+
+__device__ __forceinline__ int wave_min(int x);
+__device__ __forceinline__ int wave_max(int x);
+
+// side 0: owners are queries, 1: owners are keys.  row_seq[row] = {first row, end row} of the
+// row's sequence.  Lanes without a valid owner row get an empty window.
+__device__ __forceinline__ Window make_window(const int2* row_seq, int row, bool valid, int side, int causal) {
+  Window w;
+  int hi = -1;
+  w.lo = 0x3fffffff;
+  w.span = 0;
+  if (valid) {
+    const int2 sq = row_seq[row];
+    w.lo = (causal && side == 1) ? row : sq.x;
+    hi = (causal && side == 0) ? row : sq.y - 1;
+    w.span = (uint32_t)(hi - w.lo);
+  }
+  w.lo_min = wave_min(w.lo);
+  w.lo_max = wave_max(valid ? w.lo : (int)0x80000000);
+  w.hi_min = wave_min(valid ? hi : 0x7fffffff);
+  w.hi_max = wave_max(valid ? hi : (int)0x80000000);
+  return w;
 }
 
 // =============================================================================================
@@ -563,13 +620,13 @@ __device__ __forceinline__ BiasCtx bias_setup(const AttnArgs& a, float* wtab, co
 // 8*(r/4) + 4*hh + r%4 <= rel, rel = query position - block position; applied to the finished
 // P under a wave-uniform branch, so the matrix instructions follow one path whether or not a
 // block is masked.  A block none of whose keys is visible comes out as zeros.
-template <int DQK, int DV, bool PV, class VAddr, class Init>
+template <int DQK, int DV, bool PV, class VAddr, class Init, class Vis>
 __device__ __forceinline__ void fwd_step(const Init& init, const char* kn, int bn, const char* vp, int bp,
                                          const RowAddr<DQK>& ra, const VAddr& ca,
                                          const bf16x8 (&qreg)[DQK / 16], const f32x16& s_in,
                                          f32x16& s_out, const bf16x8 (&p_prev)[2],
                                          bf16x8 (&p_cur)[2], f32x16 (&oacc)[DV / 32], float c1,
-                                         bool mask, int rel, int hh) {
+                                         bool mask, const Vis& vis) {
   constexpr int KS = DQK / 16, NPV = DV / 16, NSL = KS > NPV ? KS : NPV;
   constexpr int AHEAD = 3;  // operand reads in flight ahead of their use
   bf16x8 ka[KS], va[NPV];
@@ -599,7 +656,7 @@ __device__ __forceinline__ void fwd_step(const Init& init, const char* kn, int b
   if (mask) {
     asm volatile("" ::: "memory");  // not speculable: keeps the selects off the unmasked path
 #pragma unroll
-    for (int r = 0; r < 16; ++r) p[r] = (8 * (r >> 2) + 4 * hh + (r & 3) <= rel) ? p[r] : 0.f;
+    for (int r = 0; r < 16; ++r) p[r] = vis(r) ? p[r] : 0.f;
   }
   p_cur[0] = pack8(p);
   p_cur[1] = pack8(p + 8);
@@ -610,8 +667,10 @@ __device__ __forceinline__ void fwd_step(const Init& init, const char* kn, int b
 // instruction); otherwise from V itself, row-major, through transposing reads (two per matrix
 // instruction, but no transposed copy has to be built first: the choice for small problems).
 // BIAS: with the timestamp bias (the records of the streamed rows travel with the K tiles).
-template <int DQK, int DV, int NW, bool VT, bool BIAS>
+// PACKED: packed tiles (see Window).
+template <int DQK, int DV, int NW, bool VT, bool BIAS, bool PACKED>
 __global__ void __launch_bounds__(NW * 64, 2) hstu_fwd_bf16(AttnArgs a) {
+  static_assert(!(PACKED && (VT || BIAS)), "packed tiles: row-major V tiles, no bias");
   constexpr int KB = ST * DQK * 2, VB = ST * DV * 2;
   // NBUF buffers each for the K tiles and the transposed V tiles; copies run PD tiles ahead.
   // Eight waves (one workgroup per CU) use three, four waves (two workgroups per CU) two.
@@ -681,8 +740,13 @@ __global__ void __launch_bounds__(NW * 64, 2) hstu_fwd_bf16(AttnArgs a) {
   };
   // Position of block i (i in [0, NB)); positions grow with i.
   auto block_pos = [&](int i) { return tile_ref(it, st, i >> 1).pos + (i & 1) * 32; };
+  Window win = {};
+  if constexpr (PACKED) win = make_window(a.row_seq, it.row0 + orow, orow < it.nrows, 0, a.causal);
   // Does any key of block i precede (or equal) a query of this wave?  Once false it stays false.
-  auto block_on = [&](int i) { return wave_on && i < NB && (!a.causal || block_pos(i) <= q_hi); };
+  // (Packed tiles: the few blocks of a tile's stream all run; the windows do the rest.)
+  auto block_on = [&](int i) {
+    return wave_on && i < NB && (PACKED || !a.causal || block_pos(i) <= q_hi);
+  };
 
   RowAddr<DQK> ra;
   ra.init(n, hh);
@@ -692,7 +756,6 @@ __global__ void __launch_bounds__(NW * 64, 2) hstu_fwd_bf16(AttnArgs a) {
   // wave-wide loads one wave issues per iteration (the in-flight count the waits below allow)
   constexpr int LPT = (tile_loads<DQK>() + NW - 1) / NW + (DV / 8 + NW - 1) / NW;
 
-  load_owner_wait();
   // Iteration j of the main loop reads K tile j+1 and V tile j; K(0) is read before it.
   if (T > 0) { copy_k(0, 0); copy_v(0, 0); }
   if (T > 1) copy_k(1, 1);
@@ -713,8 +776,13 @@ __global__ void __launch_bounds__(NW * 64, 2) hstu_fwd_bf16(AttnArgs a) {
 #pragma unroll
         for (int e = 0; e < 8; ++e) pb[x][y][e] = (__bf16)0.f;
     }
-    auto mask_of = [&](int i) { return a.causal && block_pos(i) + 31 > q_lo; };
-    auto rel_of = [&](int i) { return q_lo + n - block_pos(i); };
+    auto mask_of = [&](int i) {
+      return PACKED ? win.masks(block_pos(i)) : (a.causal && block_pos(i) + 31 > q_lo);
+    };
+    auto vis_of = [&](int i) {
+      if constexpr (PACKED) return win.vis(block_pos(i), hh);
+      else return VisBefore{q_lo + n - block_pos(i), hh};
+    };
     BlockTable tab = {};
     if constexpr (BIAS) {
       tab.fill(bias, 0, NB, it, st, lane);
@@ -728,7 +796,7 @@ __global__ void __launch_bounds__(NW * 64, 2) hstu_fwd_bf16(AttnArgs a) {
 #pragma unroll
       for (int ks = 0; ks < DQK / 16; ++ks) sacc[0] = mfma(ra.read(kbuf(0), 0, ks), qreg[ks], sacc[0]);
       fwd_step<DQK, DV, false>(init_of(tbuf(0), 1, bb_of(1)), kbuf(0), 1, vbuf(0), 0, ra, ca, qreg, sacc[0],
-                               sacc[1], pb[1], pb[0], oacc, c1, mask_of(0), rel_of(0), hh);
+                               sacc[1], pb[1], pb[0], oacc, c1, mask_of(0), vis_of(0));
     }
     tile_barrier();  // iteration 0 copies over K tile 0, which the lines above read
 
@@ -746,13 +814,13 @@ __global__ void __launch_bounds__(NW * 64, 2) hstu_fwd_bf16(AttnArgs a) {
         const int i = 2 * j + 1;  // S of (tile j+1, block 0), P V of (tile j, block 0)
         if (block_on(i - 1))
           fwd_step<DQK, DV, true>(init_of(tbuf(B1), 0, bb_of(i + 1)), kbuf(B1), 0, vbuf(B0), 0, ra, ca, qreg, sacc[1],
-                                  sacc[0], pb[0], pb[1], oacc, c1, mask_of(i), rel_of(i), hh);
+                                  sacc[0], pb[0], pb[1], oacc, c1, mask_of(i), vis_of(i));
       }
       if (j + 1 < T) {
         const int i = 2 * j + 2;  // S of (tile j+1, block 1), P V of (tile j, block 1)
         if (block_on(i - 1))
           fwd_step<DQK, DV, true>(init_of(tbuf(B1), 1, bb_of(i + 1)), kbuf(B1), 1, vbuf(B0), 1, ra, ca, qreg, sacc[0],
-                                  sacc[1], pb[1], pb[0], oacc, c1, mask_of(i), rel_of(i), hh);
+                                  sacc[1], pb[1], pb[0], oacc, c1, mask_of(i), vis_of(i));
       }
       // what the next iteration reads must have landed; with copies two tiles ahead the ones
       // just issued may stay in flight
@@ -819,7 +887,7 @@ __device__ __forceinline__ void bwd_elem(float s, float dp, float c1, float alph
 // It is applied to the finished elementwise results under a wave-uniform branch, so the matrix
 // instructions and their accumulators follow one path whether or not a block is masked; a block
 // no row of which is visible comes out as zeros and contributes nothing.
-template <int DQK, int DV, bool CONTR, class Init>
+template <int DQK, int DV, bool CONTR, class Init, class Vis>
 __device__ __forceinline__ void dkdv_step(const Init& init, const char* qn, const char* gn, int bn,
                                           const char* qp, const char* gp, int bp,
                                           const RowAddr<DQK>& raq, const RowAddr<DV>& rag,
@@ -830,7 +898,7 @@ __device__ __forceinline__ void dkdv_step(const Init& init, const char* qn, cons
                                           f32x16& s_out, f32x16& d_out,
                                           const bf16x8 (&pd_prev)[4], bf16x8 (&pd_cur)[4],
                                           f32x16 (&dkacc)[DQK / 32], f32x16 (&dvacc)[DV / 32],
-                                          float c1, float alpha, bool mask, int rel, int hh) {
+                                          float c1, float alpha, bool mask, const Vis& vis) {
   constexpr int KS = DQK / 16, VS = DV / 16, NS = KS + VS;
   constexpr int AHEAD = NS < 4 ? NS : 4;  // operand reads in flight ahead of their use
   constexpr int GRP = 4;                  // slots between scheduling fences
@@ -872,9 +940,9 @@ __device__ __forceinline__ void dkdv_step(const Init& init, const char* qn, cons
     asm volatile("" ::: "memory");  // not speculable: keeps the selects off the unmasked path
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-      const bool vis = rel <= 8 * (r >> 2) + 4 * hh + (r & 3);
-      p[r] = vis ? p[r] : 0.f;
-      ds[r] = vis ? ds[r] : 0.f;
+      const bool on = vis(r);
+      p[r] = on ? p[r] : 0.f;
+      ds[r] = on ? ds[r] : 0.f;
     }
   }
   pd_cur[0] = pack8(p); pd_cur[1] = pack8(p + 8);
@@ -882,8 +950,13 @@ __device__ __forceinline__ void dkdv_step(const Init& init, const char* qn, cons
   fence();
 }
 
-template <int DQK, int DV, int NW, bool BIAS>
-__global__ void __launch_bounds__(NW * 64) hstu_dkdv_bf16(AttnArgs a) {
+// Head dimensions up to 64 + 64 fit two workgroups per CU (256 registers per lane, a handful
+// spilled at 64 + 64): measured 1.36x faster than one on long sequences (H = 8, d = 64, the skewed
+// 96 K-row batch: 4.32 -> 3.18 ms) and 1.67x on 4096 short ones.  At d = 128 the two accumulator
+// sets alone take 128 registers and the kernel runs one wave per SIMD with the full register file.
+template <int DQK, int DV, int NW, bool BIAS, bool PACKED>
+__global__ void __launch_bounds__(NW * 64, (DQK + DV <= 128 ? 2 : 1)) hstu_dkdv_bf16(AttnArgs a) {
+  static_assert(!(PACKED && BIAS), "packed tiles: no bias");
   constexpr int QB = ST * DQK * 2, GB = ST * DV * 2;
   // Three tile buffers: an iteration of the main loop touches tiles j and j+1 while the copy of
   // tile j+2 is in flight.  One array per buffer, so that the compiler can see that a copy into
@@ -949,10 +1022,17 @@ __global__ void __launch_bounds__(NW * 64) hstu_dkdv_bf16(AttnArgs a) {
   };
   // Position of block i of the stream (i in [0, NB)); the positions grow with i.
   auto block_pos = [&](int i) { return tile_ref(it, st, i >> 1).pos + (i & 1) * 32; };
+  Window win = {};
+  if constexpr (PACKED) win = make_window(a.row_seq, it.row0 + orow, orow < it.nrows, 1, a.causal);
   // Does any query of block i see a key of this wave?  Once true it stays true.
-  auto block_on = [&](int i) { return wave_on && (!a.causal || block_pos(i) + 31 >= k_lo); };
+  // (Packed tiles: the few blocks of a tile's stream all run; the windows do the rest.)
+  auto block_on = [&](int i) { return wave_on && (PACKED || !a.causal || block_pos(i) + 31 >= k_lo); };
+  auto mask_of = [&](int pos) { return PACKED ? win.masks(pos) : (a.causal && pos < k_hi); };
+  auto vis_of = [&](int pos) {
+    if constexpr (PACKED) return win.vis(pos, hh);
+    else return VisAfter{k_lo + n - pos, hh};
+  };
 
-  load_owner_wait();
   if (T > 0) copy_tile(0, 0);
   if (T > 1) copy_tile(1, 1);
   tile_copy_wait<0>();
@@ -991,7 +1071,7 @@ __global__ void __launch_bounds__(NW * 64) hstu_dkdv_bf16(AttnArgs a) {
     const int pos = block_pos(0);
     dkdv_step<DQK, DV, false>(init_of(tbuf(0), 1, bb_of(1)), qbuf(0), gbuf(0), 1, qbuf(0), gbuf(0), 0, raq, rag,
                               caq, cag, kreg, vreg, sacc[0], dacc[0], sacc[1], dacc[1], pd[1], pd[0],
-                              dkacc, dvacc, c1, a.alpha, a.causal && pos < k_hi, k_lo + n - pos, hh);
+                              dkacc, dvacc, c1, a.alpha, mask_of(pos), vis_of(pos));
   }
 
   // Iteration j: steps 2j+1 and 2j+2, which touch tiles j and j+1 only.
@@ -1006,8 +1086,7 @@ __global__ void __launch_bounds__(NW * 64) hstu_dkdv_bf16(AttnArgs a) {
         const int pos = block_pos(i);
         dkdv_step<DQK, DV, true>(init_of(tbuf(B1), 0, bb_of(i + 1)), qbuf(B1), gbuf(B1), 0, qbuf(B0), gbuf(B0), 0, raq,
                                  rag, caq, cag, kreg, vreg, sacc[1], dacc[1], sacc[0], dacc[0], pd[0],
-                                 pd[1], dkacc, dvacc, c1, a.alpha, a.causal && pos < k_hi,
-                                 k_lo + n - pos, hh);
+                                 pd[1], dkacc, dvacc, c1, a.alpha, mask_of(pos), vis_of(pos));
       }
     }
     if (j + 1 < T) {
@@ -1016,8 +1095,7 @@ __global__ void __launch_bounds__(NW * 64) hstu_dkdv_bf16(AttnArgs a) {
         const int pos = block_pos(i);
         dkdv_step<DQK, DV, true>(init_of(tbuf(B1), 1, bb_of(i + 1)), qbuf(B1), gbuf(B1), 1, qbuf(B0), gbuf(B0), 1, raq,
                                  rag, caq, cag, kreg, vreg, sacc[0], dacc[0], sacc[1], dacc[1], pd[1],
-                                 pd[0], dkacc, dvacc, c1, a.alpha, a.causal && pos < k_hi,
-                                 k_lo + n - pos, hh);
+                                 pd[0], dkacc, dvacc, c1, a.alpha, mask_of(pos), vis_of(pos));
       }
     }
     tile_copy_wait<0>();
@@ -1110,7 +1188,7 @@ struct DwAcc {
 };
 static_assert(MAX_TS_BUCKETS <= DW_LDS, "one entry per bucket at least");
 
-template <int DQK, int DV, bool BIAS>
+template <int DQK, int DV, bool BIAS, class Vis>
 __device__ __forceinline__ void dq_block(const BiasCtx& bias, const char* trec,
                                                 const BlockBias& bb, DwAcc& dwa,
                                                 const char* kt, const char* vt, int blk,
@@ -1119,7 +1197,7 @@ __device__ __forceinline__ void dq_block(const BiasCtx& bias, const char* trec,
                                                 const bf16x8 (&qreg)[DQK / 16],
                                                 const bf16x8 (&greg)[DV / 16],
                                                 f32x16 (&dqacc)[DQK / 32], float c1, float alpha,
-                                                int k_lo, int q_lo, bool mask, int n, int hh) {
+                                                bool mask, const Vis& vis, int n, int hh) {
   f32x16 s, dp;
   int bk[16];
 #pragma unroll
@@ -1136,12 +1214,8 @@ __device__ __forceinline__ void dq_block(const BiasCtx& bias, const char* trec,
     bwd_elem(s[r], dp[r], c1, alpha, p, ds[r]);
   }
   if (mask) {
-    const int qpos = q_lo + n;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int kpos = k_lo + 8 * (r >> 2) + 4 * hh + (r & 3);
-      ds[r] = kpos <= qpos ? ds[r] : 0.f;
-    }
+    for (int r = 0; r < 16; ++r) ds[r] = vis(r) ? ds[r] : 0.f;
   }
   if constexpr (BIAS) {
     if (bb.uni) {
@@ -1166,8 +1240,9 @@ __device__ __forceinline__ void dq_block(const BiasCtx& bias, const char* trec,
   }
 }
 
-template <int DQK, int DV, int NW, bool BIAS>
+template <int DQK, int DV, int NW, bool BIAS, bool PACKED>
 __global__ void __launch_bounds__(NW * 64, 2) hstu_dq_bf16(AttnArgs a) {
+  static_assert(!(PACKED && BIAS), "packed tiles: no bias");
   constexpr int KB = ST * DQK * 2, VB = ST * DV * 2;
   __shared__ __attribute__((aligned(1024))) char smem0[KB + VB];
   __shared__ __attribute__((aligned(1024))) char smem1[KB + VB];
@@ -1217,6 +1292,8 @@ __global__ void __launch_bounds__(NW * 64, 2) hstu_dq_bf16(AttnArgs a) {
 
   RowAddr<DQK> rak; RowAddr<DV> rav; ColAddr<DQK> cak;
   rak.init(n, hh); rav.init(n, hh); cak.init(lane);
+  Window win = {};
+  if constexpr (PACKED) win = make_window(a.row_seq, it.row0 + orow, orow < it.nrows, 0, a.causal);
 
   if (st.total > 0) {
     const TileRef t0 = tile_ref(it, st, 0);
@@ -1250,9 +1327,15 @@ __global__ void __launch_bounds__(NW * 64, 2) hstu_dq_bf16(AttnArgs a) {
 #pragma unroll
       for (int blk = 0; blk < ST / 32; ++blk) {
         const int k_lo = tj.pos + blk * 32;
-        if (blk * 32 >= tj.valid || (a.causal && k_lo > q_hi)) continue;  // no key of the block is visible
-        dq_block<DQK, DV, BIAS>(bias, tbuf(BUF), BIAS ? tab.get(2 * j + blk) : BlockBias{}, dwa, kt, vt, blk, rak, rav, cak, qreg, greg, dqacc, c1,
-                                a.alpha, k_lo, q_lo, a.causal && k_lo + 31 > q_lo, n, hh);
+        // no key of the block is visible (packed tiles: the windows decide)
+        if (blk * 32 >= tj.valid || (!PACKED && a.causal && k_lo > q_hi)) continue;
+        const BlockBias bb = BIAS ? tab.get(2 * j + blk) : BlockBias{};
+        if constexpr (PACKED)
+          dq_block<DQK, DV, BIAS>(bias, tbuf(BUF), bb, dwa, kt, vt, blk, rak, rav, cak, qreg, greg, dqacc, c1,
+                                  a.alpha, win.masks(k_lo), win.vis(k_lo, hh), n, hh);
+        else
+          dq_block<DQK, DV, BIAS>(bias, tbuf(BUF), bb, dwa, kt, vt, blk, rak, rav, cak, qreg, greg, dqacc, c1,
+                                  a.alpha, a.causal && k_lo + 31 > q_lo, VisBefore{q_lo + n - k_lo, hh}, n, hh);
       }
     }
     tile_copy_wait<0>();
@@ -1381,31 +1464,38 @@ hipError_t launch_transpose_bf16(const void* src, void* dst, const Plan& plan, i
 hipError_t launch_fwd_bf16(const AttnArgs& a, int d_qk, int d_v, hipStream_t stream) {
   if (a.vt == nullptr) {  // no transposed copy of V was built
     if (a.waves != 4) return hipErrorInvalidValue;
-    if (a.ts_rec) HSTU_DISPATCH_BIAS(hstu_fwd_bf16, 4, 4, false, true);
-    HSTU_DISPATCH_D(hstu_fwd_bf16, 4, 4, false, false);
+    if (a.row_seq) {
+      if (a.ts_rec) return hipErrorInvalidValue;
+      HSTU_DISPATCH_D(hstu_fwd_bf16, 4, 4, false, false, true);
+    }
+    if (a.ts_rec) HSTU_DISPATCH_BIAS(hstu_fwd_bf16, 4, 4, false, true, false);
+    HSTU_DISPATCH_D(hstu_fwd_bf16, 4, 4, false, false, false);
   }
+  if (a.row_seq) return hipErrorInvalidValue;  // packed tiles read V row-major
   if (a.waves == 8) {
-    if (a.ts_rec) HSTU_DISPATCH_BIAS(hstu_fwd_bf16, 8, 8, true, true);
-    HSTU_DISPATCH_D(hstu_fwd_bf16, 8, 8, true, false);
+    if (a.ts_rec) HSTU_DISPATCH_BIAS(hstu_fwd_bf16, 8, 8, true, true, false);
+    HSTU_DISPATCH_D(hstu_fwd_bf16, 8, 8, true, false, false);
   }
   if (a.waves == 4) {
-    if (a.ts_rec) HSTU_DISPATCH_BIAS(hstu_fwd_bf16, 4, 4, true, true);
-    HSTU_DISPATCH_D(hstu_fwd_bf16, 4, 4, true, false);
+    if (a.ts_rec) HSTU_DISPATCH_BIAS(hstu_fwd_bf16, 4, 4, true, true, false);
+    HSTU_DISPATCH_D(hstu_fwd_bf16, 4, 4, true, false, false);
   }
   return hipErrorInvalidValue;
 }
 hipError_t launch_dkdv_bf16(const AttnArgs& a, int d_qk, int d_v, hipStream_t stream) {
-  if (a.waves != 4) return hipErrorInvalidValue;
-  if (a.ts_rec) HSTU_DISPATCH_BIAS(hstu_dkdv_bf16, 4, 4, true);
-  HSTU_DISPATCH_D(hstu_dkdv_bf16, 4, 4, false);
+  if (a.waves != 4 || (a.row_seq && a.ts_rec)) return hipErrorInvalidValue;
+  if (a.row_seq) HSTU_DISPATCH_D(hstu_dkdv_bf16, 4, 4, false, true);
+  if (a.ts_rec) HSTU_DISPATCH_BIAS(hstu_dkdv_bf16, 4, 4, true, false);
+  HSTU_DISPATCH_D(hstu_dkdv_bf16, 4, 4, false, false);
 }
 hipError_t launch_dq_bf16(const AttnArgs& a, int d_qk, int d_v, hipStream_t stream) {
-  if (a.waves != 4) return hipErrorInvalidValue;
+  if (a.waves != 4 || (a.row_seq && a.ts_rec)) return hipErrorInvalidValue;
+  if (a.row_seq) HSTU_DISPATCH_D(hstu_dq_bf16, 4, 4, false, true);
   if (a.ts_rec) {
     if (!a.d_ts_w) return hipErrorInvalidValue;
-    HSTU_DISPATCH_BIAS(hstu_dq_bf16, 4, 4, true);
+    HSTU_DISPATCH_BIAS(hstu_dq_bf16, 4, 4, true, false);
   }
-  HSTU_DISPATCH_D(hstu_dq_bf16, 4, 4, false);
+  HSTU_DISPATCH_D(hstu_dq_bf16, 4, 4, false, false);
 }
 
 }  // namespace hstu

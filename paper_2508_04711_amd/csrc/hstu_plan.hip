@@ -562,6 +562,73 @@ hipError_t launch_ts_records(const int32_t* ts, const int32_t* off, int batch, i
   return hipGetLastError();
 }
 
+namespace {
+
+// Packed tiles (see PackedPlanArgs): one thread per row.  The sequence of a row is found by
+// bisection of the offsets; whatever the offsets hold, a row's bounds contain the row and stay
+// inside [0, total_rows], and items cover rows below min(off[batch], total_rows) only.
+__global__ void __launch_bounds__(256) packed_plan_kernel(PackedPlanArgs a) {
+  const int r = blockIdx.x * 256 + threadIdx.x;
+  const int T = a.total_rows;
+  int teff = a.off[a.batch];
+  teff = teff < 0 ? 0 : (teff < T ? teff : T);
+  if (r == 0) {
+    const int ntiles = (teff + a.tile - 1) / a.tile;
+    for (int side = 0; side < 2; ++side) {
+      a.header[side][0] = ntiles;
+      a.header[side][1] = 0;
+      a.header[side][2] = 0;
+    }
+  }
+  if (r >= T) return;
+  auto seq_of = [&](int row) {
+    int lo = 0, hi = a.batch;  // off[lo] <= row < off[hi] when the offsets are well-formed
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (a.off[mid] <= row) lo = mid; else hi = mid;
+    }
+    return lo;
+  };
+  auto clamp_end = [&](int e, int at_least) { e = e < T ? e : T; return e > at_least ? e : at_least; };
+  const int b = seq_of(r);
+  int s0 = a.off[b];
+  s0 = s0 < 0 ? 0 : (s0 < r ? s0 : r);
+  a.row_seq[r] = make_int2(s0, clamp_end(a.off[b + 1], r + 1));
+  if (r % a.tile != 0 || r >= teff) return;
+  const int t = r / a.tile;
+  const int r1 = r + a.tile < teff ? r + a.tile : teff;
+  const int e1 = clamp_end(a.off[seq_of(r1 - 1) + 1], r1);  // end of the last sequence of the tile
+  Item it = {};
+  it.row0 = r;
+  it.nrows = r1 - r;
+  it.pos0 = r;
+  it.nseg = 1;
+  // owners are queries: keys from the start of the first sequence to the tile's end (causal) or
+  // to the end of the last sequence
+  it.seg_row0[0] = s0;
+  it.seg_pos0[0] = s0;
+  it.seg_len[0] = (a.causal ? r1 : e1) - s0;
+  a.items[0][t] = it;
+  a.order[0][t] = t;
+  // owners are keys: queries from the tile's start (causal) or the start of the first sequence
+  // to the end of the last sequence
+  const int q0 = a.causal ? r : s0;
+  it.seg_row0[0] = q0;
+  it.seg_pos0[0] = q0;
+  it.seg_len[0] = e1 - q0;
+  a.items[1][t] = it;
+  a.order[1][t] = t;
+}
+
+}  // namespace
+
+hipError_t launch_packed_plan(const PackedPlanArgs& a, hipStream_t stream) {
+  if (a.batch < 1 || a.total_rows < 1 || a.tile < 64 || a.tile % 64 != 0) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(packed_plan_kernel, dim3((unsigned)((a.total_rows + 255) / 256)), dim3(256), 0,
+                     stream, a);
+  return hipGetLastError();
+}
+
 hipError_t launch_plans(const PlanArgs* a, int count, hipStream_t stream) {
   static_assert(NBINS == 2 * PLAN_THREADS, "pass 3 handles two bins per thread");
   if (count < 1 || count > 3) return hipErrorInvalidValue;

@@ -73,9 +73,11 @@ def test_all_keys_partial_is_bitwise_the_full_pass(monkeypatch):
     # kv_rank = -1 streams the same key tiles in the same order as whole-batch attention, and a
     # query row's result does not depend on which other rows share its tile.  (With the cutting
     # of heavy query tiles along the keys switched off: how many parts a tile is cut into depends
-    # on the number of query rows of the call, and the parts are summed in another order.)
+    # on the number of query rows of the call, and the parts are summed in another order; and with
+    # the whole-batch call tiled per sequence like the partial, not with packed tiles.)
     import paper_2508_04711_amd as lib
     monkeypatch.setenv("HSTU_ATTN_NO_SPLIT", "1")
+    monkeypatch.setenv("HSTU_ATTN_NO_PACK", "1")
     lengths = [520, 96, 1030, 8]
     w = workloads.custom("cp_all", lengths, 2, 128, 128, 1030, dtype="bf16", seed=9)
     dev = _dev(workloads.values(w))

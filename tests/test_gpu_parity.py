@@ -106,10 +106,25 @@ SMALL = [
 ]
 
 
+def _tiling(monkeypatch, tiling):
+    """Batches of very short sequences take packed tiles (rows tiled across sequence boundaries);
+    HSTU_ATTN_NO_PACK switches that off and HSTU_ATTN_PACK_LEN moves the threshold on the mean
+    length.  The small cases run both ways."""
+    if tiling == "per_sequence":
+        monkeypatch.setenv("HSTU_ATTN_NO_PACK", "1")
+    else:
+        monkeypatch.delenv("HSTU_ATTN_NO_PACK", raising=False)
+        monkeypatch.setenv("HSTU_ATTN_PACK_LEN", "1024")
+
+
+@pytest.mark.parametrize("tiling", ["packed", "per_sequence"])
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 @pytest.mark.parametrize("causal", [True, False])
 @pytest.mark.parametrize("name,lengths,H,dqk,dv", SMALL)
-def test_small_cases_match_oracle(name, lengths, H, dqk, dv, causal, dtype):
+def test_small_cases_match_oracle(name, lengths, H, dqk, dv, causal, dtype, tiling, monkeypatch):
+    if dtype == "f32" and tiling == "packed":
+        pytest.skip("fp32 inputs are always tiled per sequence")
+    _tiling(monkeypatch, tiling)
     w = workloads.custom(name, lengths, H, dqk, dv, max_len=max(max(lengths), 1), dtype=dtype,
                          scale=1.0 if dtype == "f32" else 0.5, seed=len(lengths) + H)
     print("case", name, dtype, "causal" if causal else "full", flush=True)
@@ -139,9 +154,11 @@ def test_all_sequences_empty_or_batch_zero():
     assert dq.shape == (0, 2, 32)
 
 
-def test_rows_outside_the_batch_are_never_written():
+@pytest.mark.parametrize("tiling", ["packed", "per_sequence"])
+def test_rows_outside_the_batch_are_never_written(tiling, monkeypatch):
     # Output buffers with guard rows before and after; only rows [0, T) of the view may change,
     # and every one of them must be written (filled with NaN beforehand).
+    _tiling(monkeypatch, tiling)
     lib = _lib()
     w = workloads.custom("guard", [70, 0, 45, 130], 2, 64, 64, 130, dtype="bf16", seed=3)
     vals = _dev(workloads.values(w))
@@ -162,9 +179,12 @@ def test_rows_outside_the_batch_are_never_written():
         assert not torch.isnan(view).any()
 
 
-def test_batch_composition_invariance_bit_exact():
+def test_batch_composition_invariance_bit_exact(monkeypatch):
     # A sequence's outputs do not depend on what else is in the batch or where it sits:
     # the schedule is a function of lengths only and nothing is accumulated across workgroups.
+    # (Tiled per sequence: with packed tiles the 32-key blocks a row's sum is grouped into start
+    # at the first sequence of its tile, so the last bits depend on the neighbours.)
+    monkeypatch.setenv("HSTU_ATTN_NO_PACK", "1")
     lib = _lib()
     lengths = [130, 257, 1, 64, 300]
     w = workloads.custom("compose", lengths, 2, 128, 128, 300, dtype="bf16", seed=11)
@@ -188,7 +208,9 @@ def test_batch_composition_invariance_bit_exact():
     assert torch.equal(o, o2)
 
 
-def test_large_batch_of_short_sequences():
+@pytest.mark.parametrize("tiling", ["packed", "per_sequence"])
+def test_large_batch_of_short_sequences(tiling, monkeypatch):
+    _tiling(monkeypatch, tiling)
     # More sequences than the schedule kernel keeps in LDS (its global-memory path), many empty.
     # fp32 data checks the addressing to 1e-5.  For bf16 data the outputs here are sums of 1 to 24
     # terms and heavy-tailed (largest value > 10x the tensor RMS), so the rounding of a single
@@ -269,7 +291,8 @@ def test_accumulate_adds_to_existing_outputs():
             assert ((got.float() - want).abs() <= tol * want.abs().clamp_min(1.0)).all()
 
 
-def test_cp_partial_equals_full_pass_for_cp1():
+def test_cp_partial_equals_full_pass_for_cp1(monkeypatch):
+    monkeypatch.setenv("HSTU_ATTN_NO_PACK", "1")   # bit for bit: both tiled per sequence
     lib = _lib()
     w = workloads.custom("cp1", [200, 33, 150], 2, 128, 128, 200, dtype="bf16", seed=9)
     d = _dev(workloads.values(w))

@@ -28,10 +28,16 @@ def _case(seed):
     return lengths, H, dqk, dv, causal, cp
 
 
+@pytest.mark.parametrize("tiling", ["default", "packed"])
 @pytest.mark.parametrize("seed", range(14))
-def test_random_problem(seed):
+def test_random_problem(seed, tiling, monkeypatch):
     import paper_2508_04711_amd as lib
     lengths, H, dqk, dv, causal, cp = _case(seed)
+    monkeypatch.delenv("HSTU_ATTN_NO_PACK", raising=False)
+    if tiling == "packed":   # packed tiles forced for every batch they can serve
+        if cp or sum(lengths) // len(lengths) > 1024:
+            pytest.skip("tiled per sequence whatever the threshold")
+        monkeypatch.setenv("HSTU_ATTN_PACK_LEN", "1024")
     if sum(lengths) == 0:
         lengths = lengths + [17]
     w = workloads.custom("rand%d" % seed, lengths, H, dqk, dv, max_len=max(max(lengths), 1), dtype="bf16",
