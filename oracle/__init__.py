@@ -237,3 +237,28 @@ def bias_attention(q, k, v, d_o, off, ts, w, f: int, max_len: int, alpha: float,
         _p(w), _p(q), _p(k), _p(v), _p(d_o), _p(o), _p(dq), _p(dk), _p(dvv), _p(dw))
     _check(rc, "hstu_oracle_bias")
     return o, dq, dk, dvv, dw
+
+
+def bias_rows(q, k, v, d_o, off, ts, w, f: int, max_len: int, alpha: float, causal: bool, sel):
+    """Attention with the timestamp bias at the global rows `sel` only: (o, dq, dk, dv), each
+    [len(sel), H, d] (the gradients None when d_o is None)."""
+    q, k, v, off = _d(q), _d(k), _d(v), _off(off)
+    T, H, dqk, dv, B = _dims(q, v, off)
+    ts = np.ascontiguousarray(ts, dtype=np.int32)
+    w = _d(w)
+    sel = np.ascontiguousarray(sel, dtype=np.int64)
+    n = len(sel)
+    o = np.zeros((n, H, dv))
+    back = d_o is not None
+    d_o = _d(d_o) if back else None
+    dq = np.zeros((n, H, dqk)) if back else None
+    dk = np.zeros((n, H, dqk)) if back else None
+    dvv = np.zeros((n, H, dv)) if back else None
+    rc = _load().hstu_oracle_bias_rows(
+        ctypes.c_int32(B), ctypes.c_int32(H), ctypes.c_int32(dqk), ctypes.c_int32(dv),
+        ctypes.c_int32(max_len), ctypes.c_double(alpha), ctypes.c_int32(int(causal)),
+        off.ctypes.data_as(_i32p), ts.ctypes.data_as(_i32p), ctypes.c_int32(len(w)), ctypes.c_int32(f),
+        _p(w), _p(q), _p(k), _p(v), _p(d_o), ctypes.c_int32(n), sel.ctypes.data_as(_i64p),
+        _p(o), _p(dq), _p(dk), _p(dvv))
+    _check(rc, "hstu_oracle_bias_rows")
+    return o, dq, dk, dvv

@@ -120,3 +120,79 @@ int hstu_oracle_bias(int32_t B, int32_t H, int32_t dqk, int32_t dv, int32_t max_
   }
   return 0;
 }
+
+/* The same definition at chosen global rows only (rows do not interact): for row rows[r] of its
+ * sequence, O and dQ of that row as a query, dK and dV of that row as a key; outputs are
+ * [n, H, d].  d_o may be NULL (then only o is written).  Returns -3 if a row lies in no sequence. */
+int hstu_oracle_bias_rows(int32_t B, int32_t H, int32_t dqk, int32_t dv, int32_t max_len,
+                          double alpha, int32_t causal, const int32_t* off, const int32_t* ts,
+                          int32_t nb, int32_t f, const double* w, const double* q, const double* k,
+                          const double* v, const double* d_o, int32_t n, const int64_t* rows,
+                          double* o, double* dq, double* dk, double* dv_out) {
+  if (B < 0 || H < 1 || dqk < 1 || dv < 1 || max_len < 1 || nb < 1 || f < 0 || f > 8 || n < 0) return -1;
+  const double N = (double)max_len;
+  int bad = 0;
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+  for (int r = 0; r < n; ++r)
+    for (int h = 0; h < H; ++h) {
+      int b = -1;
+      for (int c = 0; c < B; ++c)
+        if (off[c] <= rows[r] && rows[r] < off[c + 1]) { b = c; break; }
+      if (b < 0) {
+#pragma omp atomic write
+        bad = 1;
+        continue;
+      }
+      const int64_t s = off[b];
+      const int L = off[b + 1] - off[b];
+      const int me = (int)(rows[r] - s);
+      double* oi = o ? o + ((int64_t)r * H + h) * dv : NULL;
+      double* dqi = (dq && d_o) ? dq + ((int64_t)r * H + h) * dqk : NULL;
+      double* dkj = (dk && d_o) ? dk + ((int64_t)r * H + h) * dqk : NULL;
+      double* dvj = (dv_out && d_o) ? dv_out + ((int64_t)r * H + h) * dv : NULL;
+      if (oi) memset(oi, 0, sizeof(double) * dv);
+      if (dqi) memset(dqi, 0, sizeof(double) * dqk);
+      if (dkj) memset(dkj, 0, sizeof(double) * dqk);
+      if (dvj) memset(dvj, 0, sizeof(double) * dv);
+      /* the row as a query i = me against its visible keys */
+      if (oi || dqi) {
+        const double* qi = q + ((s + me) * (int64_t)H + h) * dqk;
+        const double* doi = d_o ? d_o + ((s + me) * (int64_t)H + h) * dv : NULL;
+        const int jend = causal ? me : L - 1;
+        for (int j = 0; j <= jend; ++j) {
+          const double* kj = k + ((s + j) * (int64_t)H + h) * dqk;
+          const double* vj = v + ((s + j) * (int64_t)H + h) * dv;
+          const double x = alpha * (dot(qi, kj, dqk) + w[hstu_oracle_bias_bucket(ts[s + me], ts[s + j], nb, f)]);
+          const double sg = sigmoid(x);
+          if (oi) {
+            const double p = x * sg / N;
+            for (int t = 0; t < dv; ++t) oi[t] += p * vj[t];
+          }
+          if (dqi) {
+            const double ds = dot(doi, vj, dv) / N * sg * (1.0 + x * (1.0 - sg));
+            for (int t = 0; t < dqk; ++t) dqi[t] += alpha * ds * kj[t];
+          }
+        }
+      }
+      /* the row as a key j = me against the queries that see it */
+      if (dkj || dvj) {
+        const double* kj = k + ((s + me) * (int64_t)H + h) * dqk;
+        const double* vj = v + ((s + me) * (int64_t)H + h) * dv;
+        for (int i = causal ? me : 0; i < L; ++i) {
+          const double* qi = q + ((s + i) * (int64_t)H + h) * dqk;
+          const double* doi = d_o + ((s + i) * (int64_t)H + h) * dv;
+          const double x = alpha * (dot(qi, kj, dqk) + w[hstu_oracle_bias_bucket(ts[s + i], ts[s + me], nb, f)]);
+          const double sg = sigmoid(x);
+          if (dvj) {
+            const double p = x * sg / N;
+            for (int t = 0; t < dv; ++t) dvj[t] += p * doi[t];
+          }
+          if (dkj) {
+            const double ds = dot(doi, vj, dv) / N * sg * (1.0 + x * (1.0 - sg));
+            for (int t = 0; t < dqk; ++t) dkj[t] += alpha * ds * qi[t];
+          }
+        }
+      }
+    }
+  return bad ? -3 : 0;
+}

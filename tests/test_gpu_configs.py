@@ -51,3 +51,42 @@ def test_config5_sampled_rows():
     # properties that hold at any size: finite everywhere, nothing beyond what was asked
     for t in (o, dq, dk, dv):
         assert torch.isfinite(t.float()).all()
+
+
+def test_config5_with_timestamp_bias_sampled_rows():
+    """bench.py's cfg5_bias workload (config 5 with sorted event timestamps, 64 buckets, four
+    groups per octave) at full size: sampled query and key rows against the bias oracle.  The
+    table gradient is a sum over every pair and cannot be sampled; it is checked against the
+    full oracle at the sizes of tests/test_gpu_bias.py and here only for being finite."""
+    import paper_2508_04711_amd as lib
+    w = workloads.config(5)
+    vals = workloads.values(w)
+    dev = _dev(vals)
+    off_np = w.seq_offsets()
+    off = torch.from_numpy(off_np).cuda()
+    ts_np, tab_np = workloads.timestamps(w, "events", 0), workloads.bias_table(64, 0, 1.0)
+    ts, tab = torch.from_numpy(ts_np).cuda(), torch.from_numpy(tab_np).cuda()
+    o = lib.hstu_jagged_attn_bias_fwd(dev["q"], dev["k"], dev["v"], off, ts, tab, 2, w.max_len, w.alpha, True)
+    dq, dk, dv, dw = lib.hstu_jagged_attn_bias_bwd(dev["q"], dev["k"], dev["v"], dev["d_o"], off, ts, tab, 2,
+                                                   w.max_len, w.alpha, True)
+    torch.cuda.synchronize()
+    print("config 5 with bias: gpu done", flush=True)
+    rng = np.random.default_rng(6)
+    sel = []
+    for b, L in enumerate(w.lengths):
+        s = int(off_np[b])
+        local = [0, 1, 127, 128, L - 1, L - 129] + [int(x) for x in rng.integers(0, L, size=4)]
+        sel += [s + x for x in local if 0 <= x < L]
+    sel = sorted(set(sel))
+    f64 = {k: workloads.to_f64(v) for k, v in vals.items()}
+    want = oracle.bias_rows(f64["q"], f64["k"], f64["v"], f64["d_o"], off_np, ts_np,
+                            tab_np.astype(np.float64), 2, w.max_len, w.alpha, True, sel)
+    print("config 5 with bias: oracle done", flush=True)
+    for name, got, ref in zip(("o", "dq", "dk", "dv"), (o, dq, dk, dv), want):
+        g = got[sel].double().cpu().numpy()
+        rms = float(np.sqrt((ref ** 2).mean()))
+        excess = np.abs(g - ref) - (2e-2 * rms + np.abs(ref) * 2.0 ** -8)
+        assert excess.max() <= 0, (name, float(np.abs(g - ref).max() / rms))
+    for t in (o, dq, dk, dv, dw):
+        assert torch.isfinite(t.float()).all()
+    assert (dw != 0).any()

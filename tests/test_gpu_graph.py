@@ -56,3 +56,57 @@ def test_forward_backward_step_replays_from_a_graph(lengths, H, d):
         for name, a, b in zip(("o", "dq", "dk", "dv"), got, (o, dq, dk, dv)):
             assert torch.equal(a, b), (name, it)
             assert torch.isfinite(a.float()).all()
+
+
+def test_step_with_timestamp_bias_replays_from_a_graph():
+    """The calls with bias add one small kernel (the per-row records; it also clears the table
+    gradient, so no memset is recorded) and fp32 atomics for the table gradient: dq, dk, dv and o
+    replay bit for bit, the table gradient to the rounding of its atomics."""
+    import paper_2508_04711_amd as lib
+    lengths, H, d = [700, 130, 1, 519, 0, 64], 2, 64
+    w = workloads.custom("graph_bias", lengths, H, d, d, max_len=max(lengths), dtype="bf16", seed=13)
+    vals = {k: v.cuda() for k, v in workloads.values(w).items()}
+    off = torch.from_numpy(w.seq_offsets()).cuda()
+    ts = torch.from_numpy(workloads.timestamps(w, "events", 2)).cuda()
+    tab = torch.from_numpy(workloads.bias_table(40, 2)).cuda()
+    T = w.total_rows
+    p = (w.batch, H, d, d, w.max_len, w.alpha, True, 0, T)
+    ws = torch.empty(max(lib.hstu_jagged_attn_bias_workspace_bytes(p, 0),
+                         lib.hstu_jagged_attn_bias_workspace_bytes(p, 1)), dtype=torch.uint8, device="cuda")
+    q, k, v, g = (vals[n].clone() for n in ("q", "k", "v", "d_o"))
+    o = torch.empty((T, H, d), dtype=torch.bfloat16, device="cuda")
+    dq, dk, dv = torch.empty_like(o), torch.empty_like(o), torch.empty_like(o)
+    dw = torch.empty_like(tab)
+
+    def step():
+        lib.hstu_jagged_attn_bias_fwd(q, k, v, off, ts, tab, 2, w.max_len, w.alpha, True, out=o, workspace=ws)
+        lib.hstu_jagged_attn_bias_bwd(q, k, v, g, off, ts, tab, 2, w.max_len, w.alpha, True,
+                                      out=(dq, dk, dv, dw), workspace=ws)
+
+    step()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    gen = torch.Generator(device="cpu").manual_seed(7)
+    for it in range(3):
+        print("graph replay with bias", it, flush=True)
+        for t in (q, k, v, g):
+            t.copy_((torch.randn(t.shape, generator=gen) * 0.5).to(torch.bfloat16).cuda())
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [x.clone() for x in (o, dq, dk, dv, dw)]
+        for t in (o, dq, dk, dv, dw):
+            t.zero_()
+        step()
+        torch.cuda.synchronize()
+        for name, a, b in zip(("o", "dq", "dk", "dv"), got, (o, dq, dk, dv)):
+            assert torch.equal(a, b), (name, it)
+        scale = dw.abs().max().item()
+        assert (got[4] - dw).abs().max().item() <= 1e-5 * scale

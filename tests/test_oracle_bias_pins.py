@@ -128,3 +128,20 @@ def test_constant_table_shifts_every_score():
     o = oracle.bias_attention(q, k, v, None, off, np.array([5], dtype=np.int32), np.full(8, c), 1, 1, 0.3)[0]
     x = 0.3 * (2.0 * 0.5 - 3.0 + c)
     assert abs(o[0, 0, 0] - x / (1 + np.exp(-x))) < 1e-15
+
+
+@pytest.mark.parametrize("causal", [True, False])
+def test_sampled_rows_equal_the_full_computation(causal):
+    """bias_rows (used where the full oracle is too slow) against bias_attention, which the
+    tests above pin: every row of a small problem, in shuffled order."""
+    off, q, k, v, g, ts, w, f = _problem(11, [9, 1, 23, 0, 14], 2, 5, 3)
+    full = oracle.bias_attention(q, k, v, g, off, ts, w, f, 23, 0.37, causal)
+    sel = np.random.default_rng(2).permutation(int(off[-1]))
+    got = oracle.bias_rows(q, k, v, g, off, ts, w, f, 23, 0.37, causal, sel)
+    for name, a, b in zip(("o", "dq", "dk", "dv"), got, full[:4]):
+        np.testing.assert_allclose(a, b[sel], rtol=1e-12, atol=1e-14, err_msg=name)
+    only_o = oracle.bias_rows(q, k, v, None, off, ts, w, f, 23, 0.37, causal, sel[:5])
+    np.testing.assert_allclose(only_o[0], full[0][sel[:5]], rtol=1e-12, atol=1e-14)
+    assert only_o[1] is None
+    with pytest.raises(Exception):
+        oracle.bias_rows(q, k, v, g, off, ts, w, f, 23, 0.37, causal, [int(off[-1])])   # no such row
