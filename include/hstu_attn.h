@@ -158,7 +158,8 @@ typedef struct {
   int32_t groups_log2;        /* f: 0..8                                                        */
 } hstu_ts_bias;
 
-/* Workspace of the two calls below (which: HSTU_WS_FWD or HSTU_WS_BWD; 0 for invalid input). */
+/* Workspace of the calls with bias (which: HSTU_WS_FWD, HSTU_WS_BWD, or HSTU_WS_CP for
+ * hstu_jagged_attn_cp_partial_bias; 0 for invalid input). */
 size_t hstu_jagged_attn_bias_workspace_bytes(const hstu_attn_params* params, int which);
 
 /* hstu_jagged_attn_fwd / hstu_jagged_attn_bwd with the bias above; same arguments, layouts and
@@ -174,6 +175,18 @@ int hstu_jagged_attn_bias_bwd(const hstu_attn_params* params, const hstu_ts_bias
                               const void* q, const void* k, const void* v, const void* d_o,
                               const int32_t* seq_offsets, void* dq, void* dk, void* dv,
                               void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* The timestamp bias for one context-parallel step: the two sides' timestamps in the layouts of
+ * their buffers (see hstu_jagged_attn_cp_partial_bias). */
+typedef struct {
+  const int32_t* q_timestamps;   /* device, [q_rows]: the rows of q_local                          */
+  const int32_t* kv_timestamps;  /* device, [kv_rows]: the rows of k_part / v_part                 */
+  const float* ts_weights;       /* device, [num_buckets] fp32                                     */
+  float* d_ts_weights;           /* device, [num_buckets] fp32; backward only (NULL otherwise):
+                                    overwritten when cp->accumulate is 0, added to when it is 1    */
+  int32_t num_buckets;           /* 1..512                                                         */
+  int32_t groups_log2;           /* 0..8                                                           */
+} hstu_cp_ts_bias;
 
 /* One context-parallel rank's partial (section 2.3): the query rows of
  * `q_rank` against the keys of `kv_rank` (or all keys), masked on positions
@@ -193,6 +206,18 @@ int hstu_jagged_attn_cp_partial(const hstu_attn_params* params, const hstu_cp_de
                                 const void* d_o_local, const int32_t* seq_offsets_global,
                                 void* o_local, void* dq_local, void* dk_part, void* dv_part,
                                 void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* hstu_jagged_attn_cp_partial with the timestamp bias (same reading as hstu_jagged_attn_bias_fwd:
+ * the bucket of |timestamp of the query row - timestamp of the key row|).  Same arguments and
+ * errors, plus those of the calls with bias (bf16, d_qk == d_v).  Workspace:
+ * hstu_jagged_attn_bias_workspace_bytes(params, HSTU_WS_CP).  The partial table gradients of the
+ * (query rank, key rank) pairs add up to the whole batch's. */
+int hstu_jagged_attn_cp_partial_bias(const hstu_attn_params* params, const hstu_cp_desc* cp,
+                                     const hstu_cp_ts_bias* bias, const void* q_local,
+                                     const void* k_part, const void* v_part, const void* d_o_local,
+                                     const int32_t* seq_offsets_global, void* o_local, void* dq_local,
+                                     void* dk_part, void* dv_part, void* workspace,
+                                     size_t workspace_bytes, void* hip_stream);
 
 /* One rank's whole context-parallel pass as a ring of cp_size steps (section 3 names ring
  * attention as the variant for longer sequences; the partials are the ones of section 2.3).

@@ -15,6 +15,7 @@ from .binding import (  # noqa: F401
     hstu_jagged_attn_bias_workspace_bytes,
     hstu_jagged_attn_bwd,
     hstu_jagged_attn_cp_partial,
+    hstu_jagged_attn_cp_partial_bias,
     hstu_jagged_attn_fwd,
     hstu_jagged_attn_workspace_bytes,
     hstu_schedule_tile_rows,

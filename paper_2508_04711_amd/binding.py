@@ -52,6 +52,14 @@ class _TsBias(ctypes.Structure):
     ]
 
 
+class _CpTsBias(ctypes.Structure):
+    _fields_ = [
+        ("q_timestamps", ctypes.c_void_p), ("kv_timestamps", ctypes.c_void_p),
+        ("ts_weights", ctypes.c_void_p), ("d_ts_weights", ctypes.c_void_p),
+        ("num_buckets", ctypes.c_int32), ("groups_log2", ctypes.c_int32),
+    ]
+
+
 class _RingDesc(ctypes.Structure):
     _fields_ = [
         ("cp_size", ctypes.c_int32), ("q_rank", ctypes.c_int32), ("accumulate_dkv", ctypes.c_int32),
@@ -113,6 +121,10 @@ def load_library():
     lib.hstu_jagged_attn_bias_bwd.restype = ctypes.c_int
     lib.hstu_jagged_attn_bias_bwd.argtypes = [pp, bp, vp, vp, vp, vp, i32p, vp, vp, vp, vp,
                                               ctypes.c_size_t, vp]
+    lib.hstu_jagged_attn_cp_partial_bias.restype = ctypes.c_int
+    lib.hstu_jagged_attn_cp_partial_bias.argtypes = [pp, ctypes.POINTER(_CpDesc), ctypes.POINTER(_CpTsBias),
+                                                     vp, vp, vp, vp, i32p, vp, vp, vp, vp, vp,
+                                                     ctypes.c_size_t, vp]
     lib.hstu_schedule_tile_rows.restype = ctypes.c_int
     lib.hstu_schedule_tile_rows.argtypes = [pp, ctypes.c_int]
     _lib = lib
@@ -396,6 +408,69 @@ def hstu_jagged_attn_cp_partial(q_local: torch.Tensor, k_part: torch.Tensor, v_p
     if rc != 0:
         raise HstuError(rc, "hstu_jagged_attn_cp_partial")
     return o, dq, dk, dvv
+
+
+def hstu_jagged_attn_cp_partial_bias(q_local: torch.Tensor, k_part: torch.Tensor, v_part: torch.Tensor,
+                                     d_o_local: Optional[torch.Tensor], seq_offsets_global: torch.Tensor,
+                                     total_rows: int, q_timestamps: torch.Tensor,
+                                     kv_timestamps: torch.Tensor, ts_weights: torch.Tensor,
+                                     groups_log2: int, max_len: int, alpha: float, causal: bool,
+                                     cp_size: int, q_rank: int, kv_rank: int, accumulate: bool = False,
+                                     out: Optional[tuple] = None, want_o: bool = True,
+                                     workspace: Optional[torch.Tensor] = None, stream=None,
+                                     out_dtype: Optional[torch.dtype] = None):
+    """hstu_jagged_attn_cp_partial with the timestamp bias: returns (o_local, dq_local, dk_part,
+    dv_part, d_ts_weights); the timestamps are those of the rows of q_local and of k_part.
+    `out` may pass the five output tensors (required when accumulate is set)."""
+    nq, H, dqk = q_local.shape
+    nk, _, dv = v_part.shape
+    dt = q_local.dtype
+    _check_tensor(q_local, "q_local", nq, H, dqk, dt); _check_tensor(k_part, "k_part", nk, H, dqk, dt)
+    _check_tensor(v_part, "v_part", nk, H, dv, dt)
+    if d_o_local is not None:
+        _check_tensor(d_o_local, "d_o_local", nq, H, dv, dt)
+    so = seq_offsets_global
+    if so.dtype != torch.int32 or not so.is_cuda or not so.is_contiguous():
+        raise ValueError("seq_offsets_global must be a contiguous int32 device tensor")
+    B = so.numel() - 1
+    odt = _out_dtype(dt, out_dtype)
+    if out is not None:
+        o, dq, dk, dvv, dw = out
+        first = next(t for t in out[:4] if t is not None)
+        odt = first.dtype
+        for t, name, rows, dim in ((o, "o_local", nq, dv), (dq, "dq_local", nq, dqk),
+                                   (dk, "dk_part", nk, dqk), (dvv, "dv_part", nk, dv)):
+            if t is not None:
+                _check_tensor(t, name, rows, H, dim, odt)
+    else:
+        if accumulate:
+            raise ValueError("accumulate needs the outputs to add to")
+        o = torch.empty((nq, H, dv), dtype=odt, device=q_local.device) if want_o else None
+        if d_o_local is not None:
+            dq = torch.empty_like(q_local, dtype=odt); dk = torch.empty_like(k_part, dtype=odt)
+            dvv = torch.empty_like(v_part, dtype=odt)
+            dw = torch.empty_like(ts_weights)
+        else:
+            dq = dk = dvv = dw = None
+    for name, t, rows in (("q_timestamps", q_timestamps, nq), ("kv_timestamps", kv_timestamps, nk)):
+        if t.dtype != torch.int32 or not t.is_cuda or not t.is_contiguous() or tuple(t.shape) != (rows,):
+            raise ValueError("%s must be a contiguous int32 device tensor of one entry per row" % name)
+    for name, t in (("ts_weights", ts_weights), ("d_ts_weights", dw)):
+        if t is not None and (t.dtype != torch.float32 or not t.is_cuda or not t.is_contiguous()
+                              or t.dim() != 1 or t.numel() != ts_weights.numel()):
+            raise ValueError("%s must be a contiguous 1-d fp32 device tensor of one entry per bucket" % name)
+    p = _params(B, H, dqk, dv, max_len, alpha, causal, _dtype_code(q_local), total_rows, _code(odt))
+    desc = _CpDesc(int(cp_size), int(q_rank), int(kv_rank), int(bool(accumulate)), int(nq), int(nk))
+    bias = _CpTsBias(q_timestamps.data_ptr(), kv_timestamps.data_ptr(), ts_weights.data_ptr(),
+                     dw.data_ptr() if dw is not None else None, int(ts_weights.numel()), int(groups_log2))
+    ws = _bias_workspace(p, HSTU_WS_CP, workspace, q_local.device)
+    rc = load_library().hstu_jagged_attn_cp_partial_bias(
+        ctypes.byref(p), ctypes.byref(desc), ctypes.byref(bias), _ptr(q_local), _ptr(k_part), _ptr(v_part),
+        _ptr(d_o_local), _ptr(so), _ptr(o), _ptr(dq), _ptr(dk), _ptr(dvv), _ptr(ws), ws.numel(),
+        _stream(stream))
+    if rc != 0:
+        raise HstuError(rc, "hstu_jagged_attn_cp_partial_bias")
+    return o, dq, dk, dvv, dw
 
 
 def hstu_schedule_tile_rows(dtype_code: int, d_qk: int, d_v: int, side: int, total_rows: int = 1,

@@ -388,6 +388,7 @@ int build_ts_records(const hstu_attn_params* p, const hstu_ts_bias* b, const int
 }
 void set_bias(AttnArgs& a, const hstu_ts_bias* b, const char* ws) {
   a.ts_rec = reinterpret_cast<const TsRecord*>(ws);
+  a.ts_rec_own = a.ts_rec;
   a.ts_w = b->ts_weights;
   a.d_ts_w = b->d_ts_weights;
   a.nb = b->num_buckets;
@@ -482,9 +483,11 @@ size_t hstu_jagged_attn_workspace_bytes(const hstu_attn_params* params, int whic
 }
 
 size_t hstu_jagged_attn_bias_workspace_bytes(const hstu_attn_params* params, int which) {
-  if (which != HSTU_WS_FWD && which != HSTU_WS_BWD) return 0;
+  if (which != HSTU_WS_FWD && which != HSTU_WS_BWD && which != HSTU_WS_CP) return 0;
   const size_t plain = hstu_jagged_attn_workspace_bytes(params, which);
-  return plain ? plain + ts_record_bytes(params) : 0;
+  if (!plain) return 0;
+  // one array of records, or one per side (neither side holds more rows than the whole batch)
+  return plain + (which == HSTU_WS_CP ? 2 : 1) * ts_record_bytes(params);
 }
 
 // Forward over the whole batch, with the timestamp bias if `bias` is not null.
@@ -622,6 +625,7 @@ int hstu_jagged_attn_bias_bwd(const hstu_attn_params* params, const hstu_ts_bias
 // acc_kv: add to dk_part / dv_part (the two differ in a ring: a rank's own accumulators run
 // over the steps, the key-side gradients belong to the part that is visiting).
 static int cp_partial_impl(const hstu_attn_params* params, const hstu_cp_desc* cp,
+                           const hstu_cp_ts_bias* bias,
                            const void* q_local, const void* k_part, const void* v_part,
                            const void* d_o_local, const int32_t* seq_offsets_global,
                            void* o_local, void* dq_local, void* dk_part, void* dv_part,
@@ -639,7 +643,17 @@ static int cp_partial_impl(const hstu_attn_params* params, const hstu_cp_desc* c
   const void* ptrs[] = {q_local, k_part, v_part, d_o_local, o_local, dq_local, dk_part, dv_part, workspace};
   for (const void* ptr : ptrs)
     if (ptr && !aligned16(ptr)) return HSTU_ERR_MISALIGNED;
-  if (workspace_bytes < hstu_jagged_attn_workspace_bytes(params, HSTU_WS_CP))
+  if (bias) {
+    if (params->dtype != HSTU_BF16 || params->d_qk != params->d_v) return HSTU_ERR_UNSUPPORTED;
+    if (bias->num_buckets < 1 || bias->num_buckets > MAX_TS_BUCKETS || bias->groups_log2 < 0 ||
+        bias->groups_log2 > 8)
+      return HSTU_ERR_BAD_SHAPE;
+    if (!bias->q_timestamps || !bias->kv_timestamps || !bias->ts_weights ||
+        (backward && !bias->d_ts_weights))
+      return HSTU_ERR_NULL_PTR;
+  }
+  if (workspace_bytes < (bias ? hstu_jagged_attn_bias_workspace_bytes(params, HSTU_WS_CP)
+                              : hstu_jagged_attn_workspace_bytes(params, HSTU_WS_CP)))
     return HSTU_ERR_WORKSPACE_TOO_SMALL;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   char* ws = (char*)workspace;
@@ -650,6 +664,32 @@ static int cp_partial_impl(const hstu_attn_params* params, const hstu_cp_desc* c
   BuiltPlan pf, pk, pq;
   int np = 0;
   size_t base = 0, tbase = 0, qbase = 0;
+  // with bias: the records of the query side's rows, then of the key side's, come first
+  const TsRecord *q_rec = nullptr, *kv_rec = nullptr;
+  if (bias) {
+    const int64_t qr = clamp_rows(cp->q_rows, params->total_rows), kr = clamp_rows(cp->kv_rows, params->total_rows);
+    q_rec = reinterpret_cast<const TsRecord*>(ws);
+    kv_rec = reinterpret_cast<const TsRecord*>(ws + ts_record_bytes(params));
+    base = 2 * ts_record_bytes(params);
+    TimedLaunch timed(7, stream);
+    // the first launch also clears the table gradient unless the step adds to it
+    float* clear = (backward && !acc_q) ? bias->d_ts_weights : nullptr;
+    if (launch_ts_records(bias->q_timestamps, nullptr, 0, qr, const_cast<TsRecord*>(q_rec), clear,
+                          bias->num_buckets, stream) != hipSuccess ||
+        launch_ts_records(bias->kv_timestamps, cp->kv_rank < 0 ? seq_offsets_global : nullptr,
+                          params->batch, kr, const_cast<TsRecord*>(kv_rec), nullptr, bias->num_buckets,
+                          stream) != hipSuccess)
+      return HSTU_ERR_HIP;
+  }
+  auto with_bias = [&](AttnArgs& a, bool owners_are_queries) {
+    if (!bias) return;
+    a.ts_rec = owners_are_queries ? kv_rec : q_rec;
+    a.ts_rec_own = owners_are_queries ? q_rec : kv_rec;
+    a.ts_w = bias->ts_weights;
+    a.d_ts_w = bias->d_ts_weights;
+    a.nb = bias->num_buckets;
+    a.fbits = bias->groups_log2;
+  };
   const SideSpec sf = cp_side(params, cp, 0, PASS_FWD), sq = cp_side(params, cp, 0, PASS_DQ);
   if (do_f) {
     rc = prepare_plan(params, cp->cp_size, sf, seq_offsets_global, ws, workspace_bytes, base, &pa[np++], &pf);
@@ -675,6 +715,7 @@ static int cp_partial_impl(const hstu_attn_params* params, const hstu_cp_desc* c
   if (do_f) {
     AttnArgs a = base_args(params, pf, acc_q);
     a.q = q_local; a.k = k_part; a.v = v_part; a.o = o_local;
+    with_bias(a, true);
     rc = make_tcopy(params, sf, pf, v_part, params->d_v, ws, workspace_bytes, &tbase, stream, &a.vt);
     if (rc != HSTU_OK) return rc;
     rc = run_query_pass(params, PASS_FWD, a, pf, sf, o_local, params->d_v, ws, workspace_bytes, &tbase, stream);
@@ -683,12 +724,14 @@ static int cp_partial_impl(const hstu_attn_params* params, const hstu_cp_desc* c
   if (do_k) {
     AttnArgs a = base_args(params, pk, acc_kv);
     a.q = q_local; a.k = k_part; a.v = v_part; a.d_o = d_o_local; a.dk = dk_part; a.dv = dv_part;
+    with_bias(a, false);
     rc = run_pass(params, PASS_DKDV, a, stream);
     if (rc != HSTU_OK) return rc;
   }
   if (do_q) {
     AttnArgs b = base_args(params, pq, acc_q);
     b.q = q_local; b.k = k_part; b.v = v_part; b.d_o = d_o_local; b.dq = dq_local;
+    with_bias(b, true);
     rc = run_query_pass(params, PASS_DQ, b, pq, sq, dq_local, params->d_qk, ws, workspace_bytes, &qbase, stream);
     if (rc != HSTU_OK) return rc;
   }
@@ -701,8 +744,22 @@ int hstu_jagged_attn_cp_partial(const hstu_attn_params* params, const hstu_cp_de
                                 void* o_local, void* dq_local, void* dk_part, void* dv_part,
                                 void* workspace, size_t workspace_bytes, void* hip_stream) {
   const int acc = (cp && cp->accumulate) ? 1 : 0;
-  return cp_partial_impl(params, cp, q_local, k_part, v_part, d_o_local, seq_offsets_global, o_local,
-                         dq_local, dk_part, dv_part, acc, acc, workspace, workspace_bytes, hip_stream);
+  return cp_partial_impl(params, cp, nullptr, q_local, k_part, v_part, d_o_local, seq_offsets_global,
+                         o_local, dq_local, dk_part, dv_part, acc, acc, workspace, workspace_bytes,
+                         hip_stream);
+}
+
+int hstu_jagged_attn_cp_partial_bias(const hstu_attn_params* params, const hstu_cp_desc* cp,
+                                     const hstu_cp_ts_bias* bias, const void* q_local,
+                                     const void* k_part, const void* v_part, const void* d_o_local,
+                                     const int32_t* seq_offsets_global, void* o_local, void* dq_local,
+                                     void* dk_part, void* dv_part, void* workspace,
+                                     size_t workspace_bytes, void* hip_stream) {
+  if (!bias) return HSTU_ERR_NULL_PTR;
+  const int acc = (cp && cp->accumulate) ? 1 : 0;
+  return cp_partial_impl(params, cp, bias, q_local, k_part, v_part, d_o_local, seq_offsets_global,
+                         o_local, dq_local, dk_part, dv_part, acc, acc, workspace, workspace_bytes,
+                         hip_stream);
 }
 
 int hstu_cp_ring_pass(const hstu_attn_params* params, const hstu_cp_ring_desc* ring,
@@ -790,7 +847,7 @@ int hstu_cp_ring_pass(const hstu_attn_params* params, const hstu_cp_ring_desc* r
       // (pointers of an empty part are never dereferenced; any valid one satisfies the checks)
       void* dkp = backward ? (ring->dk_parts[r] ? ring->dk_parts[r] : dq_local) : nullptr;
       void* dvp = backward ? (ring->dv_parts[r] ? ring->dv_parts[r] : dq_local) : nullptr;
-      rc = cp_partial_impl(params, &d, q_local, kp ? kp : q_local, vp ? vp : q_local, d_o_local,
+      rc = cp_partial_impl(params, &d, nullptr, q_local, kp ? kp : q_local, vp ? vp : q_local, d_o_local,
                            seq_offsets_global, o_local, dq_local, dkp, dvp, s > 0 ? 1 : 0,
                            ring->accumulate_dkv ? 1 : 0, workspace, workspace_bytes, cs);
       if (rc != HSTU_OK) return cleanup(rc);

@@ -110,8 +110,11 @@ struct TsRecord {
 static_assert(sizeof(TsRecord) == 16, "one 16-byte record per row");
 constexpr int MAX_TS_BUCKETS = 512;
 
-// Builds the records of all rows (rec has total_rows + 64 entries; the surplus is cleared) and,
-// if d_w is not null, clears the nb entries of the table gradient.
+// Builds the records of `total_rows` rows (rec has total_rows + 64 entries; the surplus is
+// cleared) and, if d_w is not null, clears the nb entries of the table gradient.  off: the
+// offsets of the whole-batch layout (a row's range stops at the end of its sequence), or null for
+// any other layout of rows (the range covers the next 32 rows whatever they belong to: a superset,
+// which only makes the one-bucket test of a block more cautious).
 hipError_t launch_ts_records(const int32_t* ts, const int32_t* off, int batch, int64_t total_rows,
                              TsRecord* rec, float* d_w, int nb, hipStream_t stream);
 
@@ -150,8 +153,9 @@ struct AttnArgs {
   float* partial;   // partial results of split tiles: [slot][head][tile row][d] fp32 (or null)
   float alpha;
   float inv_n;
-  // Timestamp bias (bf16 kernels, whole-batch layout only; ts_rec == null: no bias).
-  const TsRecord* ts_rec;  // per row, built by launch_ts_records
+  // Timestamp bias (bf16 kernels; ts_rec == null: no bias).
+  const TsRecord* ts_rec;      // per row of the streamed side's buffers, built by launch_ts_records
+  const TsRecord* ts_rec_own;  // per row of the owner side's buffers (the same array for whole batches)
   const float* ts_w;       // bucket table, nb entries
   float* d_ts_w;           // its gradient (dq pass: added with atomics), or null
   int32_t nb;              // buckets

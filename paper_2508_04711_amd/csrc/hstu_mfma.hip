@@ -593,7 +593,7 @@ __device__ __forceinline__ BiasCtx bias_setup(const AttnArgs& a, float* wtab, co
   c.rec = a.ts_rec;
   c.nb = a.nb; c.f = a.fbits; c.hh = hh;
   const bool ok = orow < it.nrows;
-  c.t_own = ok ? a.ts_rec[it.row0 + orow].ts : 0;
+  c.t_own = ok ? a.ts_rec_own[it.row0 + orow].ts : 0;
   c.o_lo = wave_min(ok ? c.t_own : 0x7fffffff);
   c.o_hi = wave_max(ok ? c.t_own : (int)0x80000000);
   __syncthreads();
@@ -1441,7 +1441,7 @@ int waves_bf16(int pass, int64_t owner_rows, int heads) {
 #define HSTU_DISPATCH_BIAS(KERNEL, NW, ...)                                             \
   do {                                                                                  \
     const dim3 grid((unsigned)((int64_t)a.max_items * a.num_heads)), block(NW * 64);    \
-    if (a.nb < 1 || a.nb > MAX_TS_BUCKETS || !a.ts_w) return hipErrorInvalidValue;      \
+    if (a.nb < 1 || a.nb > MAX_TS_BUCKETS || !a.ts_w || !a.ts_rec_own) return hipErrorInvalidValue; \
     if (d_qk == 128 && d_v == 128) hipLaunchKernelGGL((KERNEL<128, 128, __VA_ARGS__>), grid, block, 0, stream, a); \
     else if (d_qk == 64 && d_v == 64) hipLaunchKernelGGL((KERNEL<64, 64, __VA_ARGS__>), grid, block, 0, stream, a); \
     else if (d_qk == 32 && d_v == 32) hipLaunchKernelGGL((KERNEL<32, 32, __VA_ARGS__>), grid, block, 0, stream, a); \

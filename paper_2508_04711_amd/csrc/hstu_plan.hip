@@ -522,7 +522,8 @@ namespace {
 
 // Timestamp records (see TsRecord): one thread per row.  The sequence of a row is found by
 // bisection of the offsets; rows outside every sequence (offsets that do not end at the row
-// count) get a range of their own timestamp only.
+// count) get a range of their own timestamp only.  Without offsets a row's range covers the
+// next 32 rows of the array.
 __global__ void __launch_bounds__(256) ts_records_kernel(const int32_t* __restrict__ ts,
                                                          const int32_t* __restrict__ off, int batch,
                                                          int total, TsRecord* __restrict__ rec,
@@ -533,13 +534,16 @@ __global__ void __launch_bounds__(256) ts_records_kernel(const int32_t* __restri
   if (r >= total + 64) return;
   TsRecord x = {0, 0, 0, 0};
   if (r < total) {
-    int lo = 0, hi = batch;  // off[lo] <= r < off[hi] when the offsets are well-formed
-    while (hi - lo > 1) {
-      const int mid = (lo + hi) >> 1;
-      if (off[mid] <= r) lo = mid; else hi = mid;
+    int end = total;
+    if (off) {
+      int lo = 0, hi = batch;  // off[lo] <= r < off[hi] when the offsets are well-formed
+      while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (off[mid] <= r) lo = mid; else hi = mid;
+      }
+      end = off[hi];
+      end = end < total ? end : total;
     }
-    int end = off[hi];
-    end = end < total ? end : total;
     const int last = r + 32 < end ? r + 32 : end;
     x.ts = x.lo = x.hi = ts[r];
     for (int i = r + 1; i < last; ++i) {
@@ -555,7 +559,7 @@ __global__ void __launch_bounds__(256) ts_records_kernel(const int32_t* __restri
 
 hipError_t launch_ts_records(const int32_t* ts, const int32_t* off, int batch, int64_t total_rows,
                              TsRecord* rec, float* d_w, int nb, hipStream_t stream) {
-  if (batch < 1 || total_rows < 1 || total_rows + 64 >= (1ll << 31)) return hipErrorInvalidValue;
+  if ((off && batch < 1) || total_rows < 0 || total_rows + 64 >= (1ll << 31)) return hipErrorInvalidValue;
   const unsigned blocks = (unsigned)((total_rows + 64 + 255) / 256);
   hipLaunchKernelGGL(ts_records_kernel, dim3(blocks), dim3(256), 0, stream, ts, off, batch,
                      (int)total_rows, rec, d_w, nb);

@@ -116,7 +116,28 @@ def test_bias_calls_reject_bad_arguments_on_the_host(lib):
         plain = lib.hstu_jagged_attn_workspace_bytes(ctypes.byref(ok), which)
         with_bias = lib.hstu_jagged_attn_bias_workspace_bytes(ctypes.byref(ok), which)
         assert with_bias == plain + 16 * (10 + 64) + (-16 * (10 + 64)) % 256
-    assert lib.hstu_jagged_attn_bias_workspace_bytes(ctypes.byref(ok), 2) == 0
+    # the context-parallel call with bias: records for both sides' rows
+    rec = 16 * (10 + 64) + (-16 * (10 + 64)) % 256
+    assert lib.hstu_jagged_attn_bias_workspace_bytes(ctypes.byref(ok), 2) == \
+        lib.hstu_jagged_attn_workspace_bytes(ctypes.byref(ok), 2) + 2 * rec
+    assert lib.hstu_jagged_attn_bias_workspace_bytes(ctypes.byref(ok), 3) == 0
+    # hstu_jagged_attn_cp_partial_bias: the descriptor's checks come before any device work
+    cpd = binding._CpDesc(2, 0, 1, 0, 5, 5)
+
+    def cpb(p, b, ws_bytes=1 << 20, d_o=fake):
+        return lib.hstu_jagged_attn_cp_partial_bias(ctypes.byref(p), ctypes.byref(cpd),
+                                                    ctypes.byref(b) if b is not None else None, fake, fake,
+                                                    fake, d_o, fake, fake, fake, fake, fake, fake, ws_bytes, None)
+
+    def cdesc(tq=0x1000, tk=0x1000, w=0x1000, dw=0x1000, nb=16, f=2):
+        return binding._CpTsBias(tq, tk, w, dw, nb, f)
+
+    assert cpb(ok, None) == -1
+    assert cpb(ok, cdesc(tq=None)) == -1 and cpb(ok, cdesc(tk=None)) == -1 and cpb(ok, cdesc(w=None)) == -1
+    assert cpb(ok, cdesc(dw=None)) == -1                 # backward (d_o given) needs the gradient buffer
+    assert cpb(ok, cdesc(nb=600)) == -2 and cpb(ok, cdesc(f=12)) == -2
+    assert cpb(_params(binding, dtype=1, out_dtype=1), cdesc()) == -3
+    assert cpb(ok, cdesc(), ws_bytes=128) == -4
     assert lib.hstu_jagged_attn_bias_workspace_bytes(ctypes.byref(_params(binding, d_qk=48)), 0) == 0
 
 
