@@ -276,7 +276,9 @@ int hstu_cp_reorder(int32_t batch, int64_t total_rows, int32_t cp_size, int32_t 
 /* Bytes of workspace the given entry point needs for `params` (an upper bound
  * that depends on batch, total_rows, num_heads, d_v and dtype only; 0 on invalid params).
  * Schedules, plus for bf16 forward passes over batches whose mean sequence length
- * total_rows / batch exceeds 1024 a transposed copy of V.
+ * total_rows / batch exceeds 1024 a transposed copy of V, plus fp32 partial results where heavy
+ * query tiles may be cut along the keys, plus 8 bytes per row for packed tiles.  The
+ * environment variables above change the answer: set them before asking.
  * `which` is a hstu_ws_kind. */
 size_t hstu_jagged_attn_workspace_bytes(const hstu_attn_params* params, int which);
 
@@ -288,8 +290,10 @@ int hstu_validate_offsets_host(const int32_t* host_offsets, int32_t batch, int64
 const char* hstu_attn_status_string(int status);
 
 /* ---- schedule inspection (for tests of the tile table, section 2.2 / 2.3) -------------------
- * Builds on the device, exactly as the attention entry points do, the table of work items for
- * one side of a problem and copies it to host memory (this call synchronises the stream).
+ * Builds on the device, exactly as the attention entry points do (when they tile per sequence:
+ * packed tiles have a schedule of their own, 128 consecutive rows per item in row order, which this
+ * call does not show), the table of work items for one side of a problem and copies it to host
+ * memory (this call synchronises the stream).
  *   side: 0 = items are query tiles streaming over key segments (forward, dq pass)
  *         1 = items are key tiles streaming over query segments (dk/dv pass)
  *   cp == NULL: whole-batch attention; else the context-parallel problem it describes
