@@ -263,8 +263,10 @@ int hstu_cp_ring_pass(const hstu_attn_params* params, const hstu_cp_ring_desc* r
  *   scatter == 0 (gather):  dst[t][r] = src[t][g(r)]   dst: local [local_rows, ...], src: global
  *   scatter == 1:           dst[t][g(r)] = src[t][r]   dst: global, src: local (only the rank's
  *                           rows of dst are written; the gradient path back to the global layout)
- * where g(r) is the global row of local row r.  row_bytes[t] must be a multiple of 16; pointers
- * 16-byte aligned.  Bit-exact copy; rows beyond local_rows / total_rows are never touched.
+ * where g(r) is the global row of local row r.  row_bytes[t] must be a multiple of 4 (multiples
+ * of 16 move at full memory width; narrower rows, e.g. one int32 timestamp per row, word by
+ * word); pointers 16-byte aligned.  Bit-exact copy; rows beyond local_rows / total_rows are never
+ * touched.
  * One kernel launch on hip_stream; needs no workspace and allocates nothing.  seq_offsets is a
  * device pointer to batch + 1 int32 (the global offsets), read by the kernel only.
  */

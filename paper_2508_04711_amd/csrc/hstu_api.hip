@@ -874,7 +874,7 @@ int hstu_cp_reorder(int32_t batch, int64_t total_rows, int32_t cp_size, int32_t 
   ReorderArgs ra = {};
   for (int t = 0; t < num_tensors; ++t) {
     if (!src[t] || !dst[t]) return HSTU_ERR_NULL_PTR;
-    if (row_bytes[t] < 16 || row_bytes[t] % 16 != 0) return HSTU_ERR_BAD_SHAPE;
+    if (row_bytes[t] < 4 || row_bytes[t] % 4 != 0) return HSTU_ERR_BAD_SHAPE;
     if (!aligned16(src[t]) || !aligned16(dst[t])) return HSTU_ERR_MISALIGNED;
     ra.src[t] = (const char*)src[t];
     ra.dst[t] = (char*)dst[t];

@@ -443,9 +443,14 @@ __global__ void __launch_bounds__(REORDER_THREADS) reorder_kernel(ReorderArgs a)
   const int64_t rb = a.row_bytes[blockIdx.y];
   const char* src = a.src[blockIdx.y] + (a.scatter ? local_row : global_row) * rb;
   char* dst = a.dst[blockIdx.y] + (a.scatter ? global_row : local_row) * rb;
+  constexpr int N = REORDER_THREADS;
+  if (rb % 16 != 0) {  // narrow rows (a multiple of 4 bytes, e.g. one timestamp per row): word copies
+    const int64_t words = nrows * rb / 4;
+    for (int64_t c = tid; c < words; c += N) ((uint32_t*)dst)[c] = ((const uint32_t*)src)[c];
+    return;
+  }
   const int64_t chunks = nrows * rb / 16;
   typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
-  constexpr int N = REORDER_THREADS;
   // plain loads and stores: non-temporal ones gain 5 % on copies larger than the last-level
   // cache and lose 15 % on the smaller ones that the batches here produce
   constexpr int U = 4;

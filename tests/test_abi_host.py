@@ -154,7 +154,7 @@ def test_reorder_rejects_bad_arguments_on_the_host(lib):
     assert call(cp=0) == -5 and call(rank=2) == -5 and call(rank=-1) == -5
     assert call(total=-1) == -2 and call(total=1 << 31) == -2 and call(local=-1) == -2
     assert call(n=0) == -2 and call(n=5) == -2
-    assert call(rb=(24,)) == -2 and call(rb=(0,)) == -2
+    assert call(rb=(26,)) == -2 and call(rb=(0,)) == -2 and call(rb=(2,)) == -2   # multiples of 4 only
     assert call(src=(None,)) == -1 and call(dst=(None,)) == -1
     assert call(src=(0x1008,)) == -7
     assert call(off=None) == -1

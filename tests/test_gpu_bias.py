@@ -170,7 +170,9 @@ def test_context_parallel_partials_with_bias(cp):
     dw_sum = torch.zeros(40, **f32)
     for rq in range(cp):
         print("cp bias", cp, rq, "all keys", flush=True)
-        ql, gl, tq = dev["q"][trow[rq]].contiguous(), dev["d_o"][trow[rq]].contiguous(), ts[trow[rq]].contiguous()
+        # the rank's rows and their timestamps, moved by the reorder kernel in one launch
+        ql, gl, tq = lib.hstu_cp_reorder([dev["q"], dev["d_o"], ts], off, T, cp, rq, len(rows[rq]))
+        assert torch.equal(tq, ts[trow[rq]])
         o, dq, dk, dv, dw = lib.hstu_jagged_attn_cp_partial_bias(
             ql, dev["k"], dev["v"], gl, off, T, tq, ts, tab, 2, w.max_len, w.alpha, True, cp, rq, -1,
             out_dtype=torch.float32)

@@ -28,8 +28,8 @@ def _bytes(t):
 def _tensors(T, seed):
     g = torch.Generator().manual_seed(seed)
     a = torch.randn((T, 2, 64), generator=g).to(torch.bfloat16)          # 256 B rows
-    b = torch.randn((T, 3, 32), generator=g)                             # fp32, 384 B rows
-    c = torch.randint(0, 255, (T, 16), generator=g, dtype=torch.uint8)   # 16 B rows: the minimum
+    b = torch.randn((T, 5), generator=g)                                 # fp32, 20 B rows: moved word by word
+    c = torch.randint(-2 ** 31, 2 ** 31 - 1, (T,), generator=g, dtype=torch.int32)   # 4 B rows (timestamps)
     d = torch.randn((T, 4, 128), generator=g).to(torch.bfloat16)         # 1 KiB rows
     return [a, b, c, d]
 
@@ -127,7 +127,8 @@ def test_argument_errors():
     off = torch.tensor([0, 64], dtype=torch.int32, device="cuda")
     good = torch.zeros((64, 8), dtype=torch.bfloat16, device="cuda")       # 16-byte rows
     with pytest.raises(lib.HstuError) as e:
-        lib.hstu_cp_reorder([torch.zeros((64, 6), dtype=torch.bfloat16, device="cuda")], off, 64, 2, 0, 32)
+        # 6-byte rows: not a multiple of 4
+        lib.hstu_cp_reorder([torch.zeros((64, 3), dtype=torch.bfloat16, device="cuda")], off, 64, 2, 0, 32)
     assert e.value.status == -2
     with pytest.raises(lib.HstuError) as e:
         lib.hstu_cp_reorder([good], off, 64, 2, 2, 32)
