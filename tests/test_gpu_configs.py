@@ -90,3 +90,49 @@ def test_config5_with_timestamp_bias_sampled_rows():
     for t in (o, dq, dk, dv, dw):
         assert torch.isfinite(t.float()).all()
     assert (dw != 0).any()
+
+
+@pytest.mark.parametrize("with_bias", [False, True])
+def test_one_very_long_sequence(with_bias):
+    """70 000 rows in one sequence (beyond any benchmark configuration): 1094 streamed tiles per
+    pass, heavy query tiles cut along the keys, and with the bias 35 refills of the per-lane block
+    table.  Sampled rows against the oracles."""
+    import paper_2508_04711_amd as lib
+    L = 70000
+    w = workloads.custom("very_long", [L, 300], 2, 64, 64, L, dtype="bf16", seed=21)
+    vals = workloads.values(w)
+    dev = _dev(vals)
+    off_np = w.seq_offsets()
+    off = torch.from_numpy(off_np).cuda()
+    f64 = {k: workloads.to_f64(v) for k, v in vals.items()}
+    rng = np.random.default_rng(7)
+    sel = sorted(set([0, 1, 63, 64, 4095, 4096, L - 1, L - 129, L, L + 299] + [int(x) for x in rng.integers(0, L, size=10)]))
+    if with_bias:
+        ts_np, tab_np = workloads.timestamps(w, "events", 3), workloads.bias_table(96, 3)
+        ts, tab = torch.from_numpy(ts_np).cuda(), torch.from_numpy(tab_np).cuda()
+        o = lib.hstu_jagged_attn_bias_fwd(dev["q"], dev["k"], dev["v"], off, ts, tab, 2, w.max_len, w.alpha, True,
+                                          out_dtype=torch.float32)
+        dq, dk, dv, dw = lib.hstu_jagged_attn_bias_bwd(dev["q"], dev["k"], dev["v"], dev["d_o"], off, ts, tab, 2,
+                                                       w.max_len, w.alpha, True, out_dtype=torch.float32)
+        torch.cuda.synchronize()
+        assert torch.isfinite(dw).all()
+        want = oracle.bias_rows(f64["q"], f64["k"], f64["v"], f64["d_o"], off_np, ts_np,
+                                tab_np.astype(np.float64), 2, w.max_len, w.alpha, True, sel)
+    else:
+        o = lib.hstu_jagged_attn_fwd(dev["q"], dev["k"], dev["v"], off, w.max_len, w.alpha, True,
+                                     out_dtype=torch.float32)
+        dq, dk, dv = lib.hstu_jagged_attn_bwd(dev["q"], dev["k"], dev["v"], dev["d_o"], off, w.max_len, w.alpha,
+                                              True, out_dtype=torch.float32)
+        torch.cuda.synchronize()
+        want = oracle.rows(f64["q"], f64["k"], f64["v"], f64["d_o"], off_np, w.max_len, w.alpha, True, sel)
+    print("very long: gpu and oracle done", with_bias, flush=True)
+    # the bar is relative to the RMS of the whole tensor; the sampled rows' RMS stands in for it,
+    # taken over the long sequence's rows (the short one's outputs are far larger: few terms / N)
+    for name, got, ref in zip(("o", "dq", "dk", "dv"), (o, dq, dk, dv), want):
+        g = got[sel].double().cpu().numpy()
+        err = np.abs(g - ref)
+        for rows_idx in ([i for i, r in enumerate(sel) if r < L], [i for i, r in enumerate(sel) if r >= L]):
+            rms = float(np.sqrt((ref[rows_idx] ** 2).mean()))
+            assert err[rows_idx].max() <= 2e-2 * rms, (name, float(err[rows_idx].max() / rms))
+    for t in (o, dq, dk, dv):
+        assert torch.isfinite(t).all()
