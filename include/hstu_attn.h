@@ -256,6 +256,26 @@ int hstu_cp_ring_pass(const hstu_attn_params* params, const hstu_cp_ring_desc* r
                       void* o_local, void* dq_local, void* workspace, size_t workspace_bytes,
                       void* compute_stream, void* copy_stream);
 
+/* The ring pass with the timestamp bias (hstu_jagged_attn_cp_partial_bias at every step): the
+ * timestamps of a part's rows travel with its K and V.  Workspace:
+ * hstu_jagged_attn_bias_workspace_bytes(params, HSTU_WS_CP).  d_ts_weights receives the rank's sum
+ * over all its steps (overwritten). */
+typedef struct hstu_cp_ring_ts_bias {
+  const int32_t* q_timestamps;       /* [q_rows]: the rows of q_local                          */
+  const int32_t* const* ts_parts;    /* per rank: [part_rows[r]] timestamps of its rows        */
+  int32_t* ts_recv[2];               /* [recv_rows] each                                       */
+  const float* ts_weights;           /* [num_buckets] fp32                                     */
+  float* d_ts_weights;               /* [num_buckets] fp32, backward only (NULL otherwise)     */
+  int32_t num_buckets;               /* 1..512                                                 */
+  int32_t groups_log2;               /* 0..8                                                   */
+} hstu_cp_ring_ts_bias;
+
+int hstu_cp_ring_pass_bias(const hstu_attn_params* params, const hstu_cp_ring_desc* ring,
+                           const hstu_cp_ring_ts_bias* bias, const void* q_local,
+                           const void* d_o_local, const int32_t* seq_offsets_global, void* o_local,
+                           void* dq_local, void* workspace, size_t workspace_bytes,
+                           void* compute_stream, void* copy_stream);
+
 /* Memory reorder for the load-balanced split (section 2.3: the "data shuffling ... memory
  * reordering" kernels that replace chunk + concatenate; section 3 credits them with +37 % QPS).
  * Moves whole rows between the global jagged layout and `rank`'s local layout (see hstu_cp_desc),

@@ -7,6 +7,7 @@ from .binding import (  # noqa: F401
     hstu_attn_status_string,
     hstu_cp_reorder,
     hstu_cp_ring_pass,
+    hstu_cp_ring_pass_bias,
     hstu_debug_dump_schedule,
     hstu_debug_timing_begin,
     hstu_debug_timing_end,

@@ -60,6 +60,14 @@ class _CpTsBias(ctypes.Structure):
     ]
 
 
+class _RingTsBias(ctypes.Structure):
+    _fields_ = [
+        ("q_timestamps", ctypes.c_void_p), ("ts_parts", ctypes.c_void_p), ("ts_recv", ctypes.c_void_p * 2),
+        ("ts_weights", ctypes.c_void_p), ("d_ts_weights", ctypes.c_void_p),
+        ("num_buckets", ctypes.c_int32), ("groups_log2", ctypes.c_int32),
+    ]
+
+
 class _RingDesc(ctypes.Structure):
     _fields_ = [
         ("cp_size", ctypes.c_int32), ("q_rank", ctypes.c_int32), ("accumulate_dkv", ctypes.c_int32),
@@ -109,6 +117,9 @@ def load_library():
     lib.hstu_cp_ring_pass.restype = ctypes.c_int
     lib.hstu_cp_ring_pass.argtypes = [pp, ctypes.POINTER(_RingDesc), vp, vp, i32p, vp, vp, vp,
                                       ctypes.c_size_t, vp, vp]
+    lib.hstu_cp_ring_pass_bias.restype = ctypes.c_int
+    lib.hstu_cp_ring_pass_bias.argtypes = [pp, ctypes.POINTER(_RingDesc), ctypes.POINTER(_RingTsBias), vp, vp,
+                                           i32p, vp, vp, vp, ctypes.c_size_t, vp, vp]
     lib.hstu_cp_reorder.restype = ctypes.c_int
     lib.hstu_cp_reorder.argtypes = [ctypes.c_int32, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32,
                                     ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p,
@@ -574,7 +585,8 @@ def hstu_cp_ring_pass(q_local: torch.Tensor, d_o_local: Optional[torch.Tensor], 
                       seq_offsets_global: torch.Tensor, total_rows: int, max_len: int, alpha: float,
                       causal: bool, cp_size: int, q_rank: int, out_dtype: torch.dtype = torch.float32,
                       accumulate_dkv: bool = False, out: Optional[tuple] = None, recv=None,
-                      workspace: Optional[torch.Tensor] = None, stream=None, copy_stream=None):
+                      workspace: Optional[torch.Tensor] = None, stream=None, copy_stream=None,
+                      _bias=None):
     """One rank's context-parallel pass as a ring over the K/V parts of all ranks.
 
     k_parts / v_parts: one tensor per rank (its rows of K and V in its local layout), standing
@@ -642,6 +654,32 @@ def hstu_cp_ring_pass(q_local: torch.Tensor, d_o_local: Optional[torch.Tensor], 
                      (ctypes.c_void_p * 2)(recv[2].data_ptr(), recv[3].data_ptr()),
                      ctypes.cast(dkp, ctypes.c_void_p) if backward else None,
                      ctypes.cast(dvp, ctypes.c_void_p) if backward else None)
+    if _bias is not None:
+        q_ts, ts_parts, ts_weights, groups_log2, dw = _bias
+        if len(ts_parts) != cp_size:
+            raise ValueError("one timestamp tensor per rank")
+        for name, t, n in [("q_timestamps", q_ts, nq)] + [("ts_parts[%d]" % r, ts_parts[r], rows[r])
+                                                         for r in range(cp_size)]:
+            if t.dtype != torch.int32 or not t.is_cuda or not t.is_contiguous() or tuple(t.shape) != (n,):
+                raise ValueError("%s must be a contiguous int32 device tensor of one entry per row" % name)
+        if backward and dw is None:
+            dw = torch.empty_like(ts_weights)
+        ts_recv = [torch.empty(max(recv_rows, 1), dtype=torch.int32, device=dev) for _ in range(2)]
+        tsp = arr(ts_parts)
+        bias = _RingTsBias(q_ts.data_ptr(), ctypes.cast(tsp, ctypes.c_void_p),
+                           (ctypes.c_void_p * 2)(ts_recv[0].data_ptr(), ts_recv[1].data_ptr()),
+                           ts_weights.data_ptr(), dw.data_ptr() if dw is not None else None,
+                           int(ts_weights.numel()), int(groups_log2))
+        ws = _bias_workspace(p, HSTU_WS_CP, workspace, dev)
+        rc = load_library().hstu_cp_ring_pass_bias(
+            ctypes.byref(p), ctypes.byref(desc), ctypes.byref(bias), _ptr(q_local), _ptr(d_o_local), _ptr(so),
+            _ptr(o), _ptr(dq), _ptr(ws), ws.numel(), ctypes.c_void_p(stream.cuda_stream),
+            ctypes.c_void_p(copy_stream.cuda_stream))
+        if rc != 0:
+            raise HstuError(rc, "hstu_cp_ring_pass_bias")
+        for t in list(recv) + list(k_parts) + list(v_parts) + ts_recv + list(ts_parts):
+            t.record_stream(copy_stream)
+        return o, dq, dks, dvs, dw
     ws = _workspace(p, HSTU_WS_CP, workspace, dev)
     rc = load_library().hstu_cp_ring_pass(
         ctypes.byref(p), ctypes.byref(desc), _ptr(q_local), _ptr(d_o_local), _ptr(so), _ptr(o), _ptr(dq),
@@ -652,3 +690,22 @@ def hstu_cp_ring_pass(q_local: torch.Tensor, d_o_local: Optional[torch.Tensor], 
     for t in list(recv) + list(k_parts) + list(v_parts):
         t.record_stream(copy_stream)
     return o, dq, dks, dvs
+
+
+def hstu_cp_ring_pass_bias(q_local: torch.Tensor, d_o_local: Optional[torch.Tensor], k_parts, v_parts,
+                           seq_offsets_global: torch.Tensor, total_rows: int, q_timestamps: torch.Tensor,
+                           ts_parts, ts_weights: torch.Tensor, groups_log2: int, max_len: int, alpha: float,
+                           causal: bool, cp_size: int, q_rank: int, out_dtype: torch.dtype = torch.float32,
+                           accumulate_dkv: bool = False, out: Optional[tuple] = None, recv=None,
+                           workspace: Optional[torch.Tensor] = None, stream=None, copy_stream=None):
+    """hstu_cp_ring_pass with the timestamp bias: ts_parts[r] holds the timestamps of rank r's rows,
+    q_timestamps those of q_local.  Returns (o_local, dq_local, dk_parts, dv_parts, d_ts_weights);
+    `out` may pass the five (d_ts_weights is overwritten with the rank's sum over its steps)."""
+    dw = None
+    if out is not None:
+        out, dw = tuple(out[:4]), out[4]
+    return hstu_cp_ring_pass(q_local, d_o_local, k_parts, v_parts, seq_offsets_global, total_rows, max_len,
+                             alpha, causal, cp_size, q_rank, out_dtype=out_dtype,
+                             accumulate_dkv=accumulate_dkv, out=out, recv=recv, workspace=workspace,
+                             stream=stream, copy_stream=copy_stream,
+                             _bias=(q_timestamps, ts_parts, ts_weights, groups_log2, dw))

@@ -762,10 +762,11 @@ int hstu_jagged_attn_cp_partial_bias(const hstu_attn_params* params, const hstu_
                          hip_stream);
 }
 
-int hstu_cp_ring_pass(const hstu_attn_params* params, const hstu_cp_ring_desc* ring,
-                      const void* q_local, const void* d_o_local, const int32_t* seq_offsets_global,
-                      void* o_local, void* dq_local, void* workspace, size_t workspace_bytes,
-                      void* compute_stream, void* copy_stream) {
+// The ring pass, with the timestamp bias if `bias` is not null.
+static int ring_impl(const hstu_attn_params* params, const hstu_cp_ring_desc* ring,
+                     const hstu_cp_ring_ts_bias* bias, const void* q_local, const void* d_o_local,
+                     const int32_t* seq_offsets_global, void* o_local, void* dq_local, void* workspace,
+                     size_t workspace_bytes, void* compute_stream, void* copy_stream) {
   int rc = check_params(params);
   if (rc != HSTU_OK) return rc;
   if (!ring) return HSTU_ERR_NULL_PTR;
@@ -787,10 +788,11 @@ int hstu_cp_ring_pass(const hstu_attn_params* params, const hstu_cp_ring_desc* r
     if (backward && ring->part_rows[r] > 0 && (!ring->dk_parts[r] || !ring->dv_parts[r]))
       return HSTU_ERR_NULL_PTR;
     if (r != me && ring->part_rows[r] > ring->recv_rows) return HSTU_ERR_BAD_CP;
+    if (bias && ring->part_rows[r] > 0 && (!bias->ts_parts || !bias->ts_parts[r])) return HSTU_ERR_NULL_PTR;
   }
   if (cp > 1 && ring->recv_rows > 0)
     for (int b = 0; b < 2; ++b)
-      if (!ring->k_recv[b] || !ring->v_recv[b]) return HSTU_ERR_NULL_PTR;
+      if (!ring->k_recv[b] || !ring->v_recv[b] || (bias && !bias->ts_recv[b])) return HSTU_ERR_NULL_PTR;
   if (params->batch == 0 || params->total_rows == 0) return HSTU_OK;
 
   hipStream_t cs = static_cast<hipStream_t>(compute_stream), xs = static_cast<hipStream_t>(copy_stream);
@@ -827,6 +829,9 @@ int hstu_cp_ring_pass(const hstu_attn_params* params, const hstu_cp_ring_desc* r
       if (hipMemcpyAsync(ring->k_recv[b], ring->k_parts[r], rows * krow, hipMemcpyDeviceToDevice, xs) != hipSuccess ||
           hipMemcpyAsync(ring->v_recv[b], ring->v_parts[r], rows * vrow, hipMemcpyDeviceToDevice, xs) != hipSuccess)
         return HSTU_ERR_HIP;
+      if (bias && hipMemcpyAsync(bias->ts_recv[b], bias->ts_parts[r], rows * sizeof(int32_t),
+                                 hipMemcpyDeviceToDevice, xs) != hipSuccess)
+        return HSTU_ERR_HIP;
     }
     return hipEventRecord(landed[b], xs) == hipSuccess ? HSTU_OK : HSTU_ERR_HIP;
   };
@@ -847,7 +852,17 @@ int hstu_cp_ring_pass(const hstu_attn_params* params, const hstu_cp_ring_desc* r
       // (pointers of an empty part are never dereferenced; any valid one satisfies the checks)
       void* dkp = backward ? (ring->dk_parts[r] ? ring->dk_parts[r] : dq_local) : nullptr;
       void* dvp = backward ? (ring->dv_parts[r] ? ring->dv_parts[r] : dq_local) : nullptr;
-      rc = cp_partial_impl(params, &d, nullptr, q_local, kp ? kp : q_local, vp ? vp : q_local, d_o_local,
+      hstu_cp_ts_bias step_bias = {};
+      if (bias) {
+        const int32_t* kt = s == 0 ? bias->ts_parts[r] : bias->ts_recv[b];
+        step_bias.q_timestamps = bias->q_timestamps;
+        step_bias.kv_timestamps = kt ? kt : bias->q_timestamps;  // (an empty part is never read)
+        step_bias.ts_weights = bias->ts_weights;
+        step_bias.d_ts_weights = bias->d_ts_weights;
+        step_bias.num_buckets = bias->num_buckets;
+        step_bias.groups_log2 = bias->groups_log2;
+      }
+      rc = cp_partial_impl(params, &d, bias ? &step_bias : nullptr, q_local, kp ? kp : q_local, vp ? vp : q_local, d_o_local,
                            seq_offsets_global, o_local, dq_local, dkp, dvp, s > 0 ? 1 : 0,
                            ring->accumulate_dkv ? 1 : 0, workspace, workspace_bytes, cs);
       if (rc != HSTU_OK) return cleanup(rc);
@@ -859,6 +874,25 @@ int hstu_cp_ring_pass(const hstu_attn_params* params, const hstu_cp_ring_desc* r
     }
   }
   return cleanup(HSTU_OK);
+}
+
+int hstu_cp_ring_pass(const hstu_attn_params* params, const hstu_cp_ring_desc* ring,
+                      const void* q_local, const void* d_o_local, const int32_t* seq_offsets_global,
+                      void* o_local, void* dq_local, void* workspace, size_t workspace_bytes,
+                      void* compute_stream, void* copy_stream) {
+  return ring_impl(params, ring, nullptr, q_local, d_o_local, seq_offsets_global, o_local, dq_local,
+                   workspace, workspace_bytes, compute_stream, copy_stream);
+}
+
+int hstu_cp_ring_pass_bias(const hstu_attn_params* params, const hstu_cp_ring_desc* ring,
+                           const hstu_cp_ring_ts_bias* bias, const void* q_local,
+                           const void* d_o_local, const int32_t* seq_offsets_global, void* o_local,
+                           void* dq_local, void* workspace, size_t workspace_bytes,
+                           void* compute_stream, void* copy_stream) {
+  if (!bias) return HSTU_ERR_NULL_PTR;
+  if (!bias->q_timestamps || !bias->ts_weights) return HSTU_ERR_NULL_PTR;
+  return ring_impl(params, ring, bias, q_local, d_o_local, seq_offsets_global, o_local, dq_local,
+                   workspace, workspace_bytes, compute_stream, copy_stream);
 }
 
 int hstu_cp_reorder(int32_t batch, int64_t total_rows, int32_t cp_size, int32_t rank, int32_t scatter,

@@ -212,3 +212,51 @@ def test_context_parallel_partials_with_bias(cp):
     _check("dk sum", dk_sum, want[2], "bf16", "cp%d" % cp)
     _check("dv sum", dv_sum, want[3], "bf16", "cp%d" % cp)
     _check_dw(dw_acc, want[4], "cp%d pairs" % cp)
+
+
+@pytest.mark.parametrize("cp", [1, 2, 4])
+def test_ring_pass_with_bias(cp):
+    """Every rank's ring pass with the bias: the parts' timestamps travel with their K and V; o and
+    dq per rank equal the oracle's rows, the key-side gradients (added to travelling buffers) and
+    the ranks' table gradients add up to the whole batch's."""
+    import paper_2508_04711_amd as lib
+    lengths = [160, 5, 233, 1, 0, 384, 77, 900]
+    w = workloads.custom("ring_bias", lengths, 2, 64, 64, 900, dtype="bf16", seed=40 + cp)
+    vals = workloads.values(w)
+    dev = _dev(vals)
+    f64 = {k: workloads.to_f64(v) for k, v in vals.items()}
+    off_np = w.seq_offsets()
+    off = torch.from_numpy(off_np).cuda()
+    T = w.total_rows
+    ts_np, tab_np = workloads.timestamps(w, "events", cp), workloads.bias_table(48, cp)
+    ts, tab = torch.from_numpy(ts_np).cuda(), torch.from_numpy(tab_np).cuda()
+    want = oracle.bias_attention(f64["q"], f64["k"], f64["v"], f64["d_o"], off_np, ts_np,
+                                 tab_np.astype(np.float64), 2, w.max_len, w.alpha, True)
+    rows = [oracle.cp_global_rows(off_np, cp, r) for r in range(cp)]
+    parts = [lib.hstu_cp_reorder([dev["k"], dev["v"], ts], off, T, cp, r, len(rows[r])) for r in range(cp)]
+    kp, vp, tp = [p[0] for p in parts], [p[1] for p in parts], [p[2] for p in parts]
+    f32 = dict(dtype=torch.float32, device="cuda")
+    dks = [torch.zeros((len(rows[r]), 2, 64), **f32) for r in range(cp)]
+    dvs = [torch.zeros((len(rows[r]), 2, 64), **f32) for r in range(cp)]
+    dw_sum = torch.zeros(48, **f32)
+    for rq in range(cp):
+        print("ring with bias", cp, rq, flush=True)
+        ql, gl, tq = lib.hstu_cp_reorder([dev["q"], dev["d_o"], ts], off, T, cp, rq, len(rows[rq]))
+        nq = len(rows[rq])
+        o, dq = torch.empty((nq, 2, 64), **f32), torch.empty((nq, 2, 64), **f32)
+        dw = torch.full((48,), float("nan"), **f32)          # overwritten, whatever it held
+        lib.hstu_cp_ring_pass_bias(ql, gl, kp, vp, off, T, tq, tp, tab, 2, w.max_len, w.alpha, True, cp, rq,
+                                   accumulate_dkv=True, out=(o, dq, dks, dvs, dw))
+        torch.cuda.synchronize()
+        _check("o", o, want[0][rows[rq]], "bf16", "ring bias cp%d q%d" % (cp, rq))
+        _check("dq", dq, want[1][rows[rq]], "bf16", "ring bias cp%d q%d" % (cp, rq))
+        dw_sum += dw
+        o2 = lib.hstu_cp_ring_pass_bias(ql, None, kp, vp, off, T, tq, tp, tab, 2, w.max_len, w.alpha, True,
+                                        cp, rq)[0]
+        torch.cuda.synchronize()
+        assert torch.equal(o2, o)
+    for r in range(cp):
+        if len(rows[r]):
+            _check("dk", dks[r], want[2][rows[r]], "bf16", "ring bias cp%d part %d" % (cp, r))
+            _check("dv", dvs[r], want[3][rows[r]], "bf16", "ring bias cp%d part %d" % (cp, r))
+    _check_dw(dw_sum, want[4], "ring bias cp%d" % cp)
