@@ -138,6 +138,14 @@ def test_bias_calls_reject_bad_arguments_on_the_host(lib):
     assert cpb(ok, cdesc(nb=600)) == -2 and cpb(ok, cdesc(f=12)) == -2
     assert cpb(_params(binding, dtype=1, out_dtype=1), cdesc()) == -3
     assert cpb(ok, cdesc(), ws_bytes=128) == -4
+    # hstu_cp_ring_pass_bias: no descriptor, or one without the query timestamps or the table
+    ring = binding._RingDesc()
+    def rpb(b):
+        return lib.hstu_cp_ring_pass_bias(ctypes.byref(ok), ctypes.byref(ring),
+                                          ctypes.byref(b) if b is not None else None, fake, None, fake, fake,
+                                          None, fake, 1 << 20, ctypes.c_void_p(1), ctypes.c_void_p(2))
+    assert rpb(None) == -1
+    assert rpb(binding._RingTsBias()) == -1
     assert lib.hstu_jagged_attn_bias_workspace_bytes(ctypes.byref(_params(binding, d_qk=48)), 0) == 0
 
 
