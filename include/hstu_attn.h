@@ -163,7 +163,8 @@ typedef struct {
 size_t hstu_jagged_attn_bias_workspace_bytes(const hstu_attn_params* params, int which);
 
 /* hstu_jagged_attn_fwd / hstu_jagged_attn_bwd with the bias above; same arguments, layouts and
- * errors, plus: bf16 inputs only and d_qk == d_v (otherwise HSTU_ERR_UNSUPPORTED),
+ * errors, plus: bf16 inputs need d_qk == d_v (otherwise HSTU_ERR_UNSUPPORTED; fp32 inputs take
+ * any supported pair and are computed in fp32 throughout, table and its gradient included),
  * num_buckets or groups_log2 out of range HSTU_ERR_BAD_SHAPE, a NULL field of `bias` (other
  * than d_ts_weights in the forward call) HSTU_ERR_NULL_PTR.  dq, dk, dv are deterministic as in
  * hstu_jagged_attn_bwd; d_ts_weights is not (see above). */
@@ -209,7 +210,7 @@ int hstu_jagged_attn_cp_partial(const hstu_attn_params* params, const hstu_cp_de
 
 /* hstu_jagged_attn_cp_partial with the timestamp bias (same reading as hstu_jagged_attn_bias_fwd:
  * the bucket of |timestamp of the query row - timestamp of the key row|).  Same arguments and
- * errors, plus those of the calls with bias (bf16, d_qk == d_v).  Workspace:
+ * errors, plus those of the calls with bias.  Workspace:
  * hstu_jagged_attn_bias_workspace_bytes(params, HSTU_WS_CP).  The partial table gradients of the
  * (query rank, key rank) pairs add up to the whole batch's. */
 int hstu_jagged_attn_cp_partial_bias(const hstu_attn_params* params, const hstu_cp_desc* cp,

@@ -110,6 +110,22 @@ struct TsRecord {
 static_assert(sizeof(TsRecord) == 16, "one 16-byte record per row");
 constexpr int MAX_TS_BUCKETS = 512;
 
+// The bucket of a timestamp difference (the library's reading of section 2.1's sketch of the
+// bias; see include/hstu_attn.h): 0 for delta <= 1, else min(nb - 1, e * 2^f + m) with
+// e = floor(log2 delta) and m the f bits below delta's leading one.  Integer arithmetic only.
+__device__ __forceinline__ int bias_bucket(uint32_t delta, int nb, int f) {
+  const uint32_t d = delta > 2u ? delta : 2u;  // (no branch: the result for delta <= 1 is selected below)
+  const int e = 31 - __builtin_clz(d);
+  const uint32_t top = e >= f ? d >> (e - f) : d << (f - e);
+  int b = (e << f) + (int)top - (1 << f);
+  b = b < nb - 1 ? b : nb - 1;
+  return delta <= 1u ? 0 : b;
+}
+// |a - b| of two int32 values, exact up to 2^32 - 1.
+__device__ __forceinline__ uint32_t abs_diff(int a, int b) {
+  return a > b ? (uint32_t)a - (uint32_t)b : (uint32_t)b - (uint32_t)a;
+}
+
 // Builds the records of `total_rows` rows (rec has total_rows + 64 entries; the surplus is
 // cleared) and, if d_w is not null, clears the nb entries of the table gradient.  off: the
 // offsets of the whole-batch layout (a row's range stops at the end of its sequence), or null for
@@ -153,7 +169,7 @@ struct AttnArgs {
   float* partial;   // partial results of split tiles: [slot][head][tile row][d] fp32 (or null)
   float alpha;
   float inv_n;
-  // Timestamp bias (bf16 kernels; ts_rec == null: no bias).
+  // Timestamp bias (ts_rec == null: no bias).
   const TsRecord* ts_rec;      // per row of the streamed side's buffers, built by launch_ts_records
   const TsRecord* ts_rec_own;  // per row of the owner side's buffers (the same array for whole batches)
   const float* ts_w;       // bucket table, nb entries

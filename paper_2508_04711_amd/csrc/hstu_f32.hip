@@ -90,6 +90,18 @@ __device__ __forceinline__ void store_part(float* row, const float (&acc)[D / 4]
 
 __device__ __forceinline__ float sigmoid_precise(float x) { return 1.0f / (1.0f + expf(-x)); }
 
+// Timestamp bias of one pair (0 without bias): the table entry of the bucket of the two rows'
+// timestamp difference; `bucket` receives the bucket.
+__device__ __forceinline__ float pair_bias(const AttnArgs& a, int t_own, int64_t streamed_row, int& bucket) {
+  bucket = 0;
+  if (!a.ts_rec) return 0.f;
+  bucket = bias_bucket(abs_diff(t_own, a.ts_rec[streamed_row].ts), a.nb, a.fbits);
+  return a.ts_w[bucket];
+}
+__device__ __forceinline__ int own_timestamp(const AttnArgs& a, int64_t row, bool on) {
+  return (a.ts_rec && on) ? a.ts_rec_own[row].ts : 0;
+}
+
 // ---------------------------------------------------------------------------------------------
 template <int DQK, int DV>
 __global__ void __launch_bounds__(THREADS) hstu_fwd_f32(AttnArgs a) {
@@ -107,6 +119,7 @@ __global__ void __launch_bounds__(THREADS) hstu_fwd_f32(AttnArgs a) {
 #pragma unroll
   for (int i = 0; i < DV / 4; ++i) op[i] = 0.f;
   const int qpos = it.pos0 + r;
+  const int t_own = own_timestamp(a, (int64_t)it.row0 + r, on);
 
   for (int g = 0; g < it.nseg; ++g) {
     int beg, end;
@@ -118,7 +131,9 @@ __global__ void __launch_bounds__(THREADS) hstu_fwd_f32(AttnArgs a) {
       stage<DV>(vt, (const float*)a.v + ((int64_t)it.seg_row0[g] + t0) * sv + h * DV, sv, valid, tid);
       __syncthreads();
       for (int j = 0; j < valid; ++j) {
-        const float s = row_sum(dot_part<DQK>(qp, kt + j * DQK, c));
+        int bucket;
+        const float s = row_sum(dot_part<DQK>(qp, kt + j * DQK, c)) +
+                        pair_bias(a, t_own, (int64_t)it.seg_row0[g] + t0 + j, bucket);
         const float x = a.alpha * s;
         float p = x * sigmoid_precise(x);
         const int kpos = it.seg_pos0[g] + t0 + j;
@@ -151,6 +166,7 @@ __global__ void __launch_bounds__(THREADS) hstu_dkdv_f32(AttnArgs a) {
 #pragma unroll
   for (int i = 0; i < DV / 4; ++i) dvp[i] = 0.f;
   const int kpos = it.pos0 + r;
+  const int t_own = own_timestamp(a, (int64_t)it.row0 + r, on);
 
   for (int g = 0; g < it.nseg; ++g) {
     int beg, end;
@@ -162,7 +178,9 @@ __global__ void __launch_bounds__(THREADS) hstu_dkdv_f32(AttnArgs a) {
       stage<DV>(gt, (const float*)a.d_o + ((int64_t)it.seg_row0[g] + t0) * sv + h * DV, sv, valid, tid);
       __syncthreads();
       for (int i = 0; i < valid; ++i) {
-        const float s = row_sum(dot_part<DQK>(kp, qt + i * DQK, c));
+        int bucket;
+        const float s = row_sum(dot_part<DQK>(kp, qt + i * DQK, c)) +
+                        pair_bias(a, t_own, (int64_t)it.seg_row0[g] + t0 + i, bucket);
         const float dp = row_sum(dot_part<DV>(vp, gt + i * DV, c));
         const float x = a.alpha * s;
         const float sg = sigmoid_precise(x);
@@ -187,6 +205,7 @@ template <int DQK, int DV>
 __global__ void __launch_bounds__(THREADS) hstu_dq_f32(AttnArgs a) {
   __shared__ __attribute__((aligned(16))) float kt[ST * DQK];
   __shared__ __attribute__((aligned(16))) float vt[ST * DV];
+  __shared__ float dwl[MAX_TS_BUCKETS];  // the workgroup's share of the bias table's gradient
   const int H = a.num_heads;
   const int slot = blockIdx.x / H, h = blockIdx.x % H;
   Item it;
@@ -194,12 +213,16 @@ __global__ void __launch_bounds__(THREADS) hstu_dq_f32(AttnArgs a) {
   const int tid = threadIdx.x, r = tid >> 2, c = tid & 3;
   const int64_t sq = (int64_t)H * DQK, sv = (int64_t)H * DV;
   const bool on = r < it.nrows;
+  const bool want_dw = a.ts_rec && a.d_ts_w;
+  if (want_dw)
+    for (int i = tid; i < a.nb; i += THREADS) dwl[i] = 0.f;  // (the loop's first barrier orders this)
   float qp[DQK / 4], gp[DV / 4], dqp[DQK / 4];
   load_part<DQK>(qp, (const float*)a.q + ((int64_t)it.row0 + r) * sq + h * DQK, on, c);
   load_part<DV>(gp, (const float*)a.d_o + ((int64_t)it.row0 + r) * sv + h * DV, on, c);
 #pragma unroll
   for (int i = 0; i < DQK / 4; ++i) dqp[i] = 0.f;
   const int qpos = it.pos0 + r;
+  const int t_own = own_timestamp(a, (int64_t)it.row0 + r, on);
 
   for (int g = 0; g < it.nseg; ++g) {
     int beg, end;
@@ -211,7 +234,9 @@ __global__ void __launch_bounds__(THREADS) hstu_dq_f32(AttnArgs a) {
       stage<DV>(vt, (const float*)a.v + ((int64_t)it.seg_row0[g] + t0) * sv + h * DV, sv, valid, tid);
       __syncthreads();
       for (int j = 0; j < valid; ++j) {
-        const float s = row_sum(dot_part<DQK>(qp, kt + j * DQK, c));
+        int bucket;
+        const float s = row_sum(dot_part<DQK>(qp, kt + j * DQK, c)) +
+                        pair_bias(a, t_own, (int64_t)it.seg_row0[g] + t0 + j, bucket);
         const float dp = row_sum(dot_part<DV>(gp, vt + j * DV, c));
         const float x = a.alpha * s;
         const float sg = sigmoid_precise(x);
@@ -219,8 +244,16 @@ __global__ void __launch_bounds__(THREADS) hstu_dq_f32(AttnArgs a) {
         const int kpos = it.seg_pos0[g] + t0 + j;
         if (a.causal && kpos > qpos) ds = 0.f;
         axpy_part<DQK>(dqp, ds, kt + j * DQK, c);
+        // one of the row's four lanes adds the pair's dS to its bucket (rows without an owner
+        // have dS = 0: their q and d_o parts are zero)
+        if (want_dw && c == 0 && ds != 0.f) atomicAdd(dwl + bucket, ds);
       }
     }
+  }
+  if (want_dw) {
+    __syncthreads();
+    for (int i = tid; i < a.nb; i += THREADS)
+      if (dwl[i] != 0.f) atomicAdd(a.d_ts_w + i, dwl[i] * a.alpha * a.inv_n);
   }
   if (on)
     store_part<DQK>((float*)a.dq + ((int64_t)it.row0 + r) * sq + h * DQK, dqp, a.alpha * a.inv_n,

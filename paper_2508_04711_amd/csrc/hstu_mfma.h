@@ -450,19 +450,6 @@ __device__ __forceinline__ void rec_copy_async(char* tile, const TsRecord* rec, 
   __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, HSTU_LDS(void, tile), 16, lane * 16, 0, 0, 0);
 }
 
-__device__ __forceinline__ int bias_bucket(uint32_t delta, int nb, int f) {
-  const uint32_t d = delta > 2u ? delta : 2u;  // (no branch: the result for delta <= 1 is selected below)
-  const int e = 31 - __builtin_clz(d);
-  const uint32_t top = e >= f ? d >> (e - f) : d << (f - e);
-  int b = (e << f) + (int)top - (1 << f);
-  b = b < nb - 1 ? b : nb - 1;
-  return delta <= 1u ? 0 : b;
-}
-
-__device__ __forceinline__ uint32_t abs_diff(int a, int b) {
-  return a > b ? (uint32_t)a - (uint32_t)b : (uint32_t)b - (uint32_t)a;
-}
-
 __device__ __forceinline__ int wave_min(int x) {
 #pragma unroll
   for (int m = 32; m >= 1; m >>= 1) { const int y = __shfl_xor(x, m); x = y < x ? y : x; }

@@ -44,7 +44,11 @@ def _run(w, kind, nb, f, causal=True, wscale=1.0, out_dtype=torch.float32, seed=
     rms = float(np.sqrt(np.mean(want[4] ** 2)))
     err = float(np.abs(got - want[4]).max())
     print("   dw: max|err|/rms = %.2e" % (err / max(rms, 1e-300)), flush=True)
-    assert err <= 2e-3 * rms + 1e-30, "%s dw: max|err|/rms = %.3e" % (tag, err / max(rms, 1e-300))
+    # fp32 inputs: a bucket's entry is an fp32 sum of up to ~1e5 terms of either sign, added in an
+    # order the atomics decide; its rounding error grows with the sum of the magnitudes, not with
+    # the (cancelling) result: 1e-4 x RMS leaves an order of magnitude over the ~1e-5 measured
+    bar = 2e-3 if w.dtype == "bf16" else 1e-4
+    assert err <= bar * rms + 1e-30, "%s dw: max|err|/rms = %.3e" % (tag, err / max(rms, 1e-300))
     # buckets no pair falls into stay exactly zero
     assert (got[want[4] == 0.0] == 0.0).all()
     return dw
@@ -122,9 +126,9 @@ def test_bias_argument_errors():
     with pytest.raises(lib.HstuError) as e:      # too many buckets
         lib.hstu_jagged_attn_bias_fwd(dev["q"], dev["k"], dev["v"], off, ts, big, 2, 64, w.alpha, True)
     assert e.value.status == -2
-    f32 = {k: v.float() for k, v in dev.items()}
-    with pytest.raises(lib.HstuError) as e:      # fp32 inputs are not supported with bias
-        lib.hstu_jagged_attn_bias_fwd(f32["q"], f32["k"], f32["v"], off, ts, tab, 2, 64, w.alpha, True)
+    wide_v = torch.zeros((128, 1, 64), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(lib.HstuError) as e:      # bf16 inputs with bias need d_qk == d_v
+        lib.hstu_jagged_attn_bias_fwd(dev["q"], dev["k"], wide_v, off, ts, tab, 2, 64, w.alpha, True)
     assert e.value.status == -3
     small = torch.empty(256, dtype=torch.uint8, device="cuda")
     with pytest.raises(lib.HstuError) as e:
@@ -260,3 +264,45 @@ def test_ring_pass_with_bias(cp):
             _check("dk", dks[r], want[2][rows[r]], "bf16", "ring bias cp%d part %d" % (cp, r))
             _check("dv", dvs[r], want[3][rows[r]], "bf16", "ring bias cp%d part %d" % (cp, r))
     _check_dw(dw_sum, want[4], "ring bias cp%d" % cp)
+
+
+@pytest.mark.parametrize("kind", ["events", "shuffled", "wide"])
+@pytest.mark.parametrize("causal", [True, False])
+def test_bias_fp32_inputs(kind, causal):
+    """All-fp32 arithmetic: o, dq, dk, dv within 1e-5 x RMS of the oracle (which no misplaced pair
+    would survive), the table gradient within 1e-4.  Unequal head dimensions are allowed here."""
+    w = workloads.custom("bias_f32", [150, 1, 0, 77, 260, 33], 2, 64, 32, 260, dtype="f32", scale=1.0, seed=50)
+    _run(w, kind, nb=40, f=2, causal=causal, wscale=0.5, seed=7)
+
+
+def test_bias_fp32_context_parallel_partial():
+    import paper_2508_04711_amd as lib
+    cp = 2
+    w = workloads.custom("cp_bias_f32", [200, 61, 0, 130], 2, 32, 32, 200, dtype="f32", scale=1.0, seed=51)
+    vals = workloads.values(w)
+    dev = _dev(vals)
+    f64 = {k: workloads.to_f64(v) for k, v in vals.items()}
+    off_np = w.seq_offsets()
+    off = torch.from_numpy(off_np).cuda()
+    T = w.total_rows
+    ts_np, tab_np = workloads.timestamps(w, "events", 9), workloads.bias_table(24, 9, 0.5)
+    ts, tab = torch.from_numpy(ts_np).cuda(), torch.from_numpy(tab_np).cuda()
+    want = oracle.bias_attention(f64["q"], f64["k"], f64["v"], f64["d_o"], off_np, ts_np,
+                                 tab_np.astype(np.float64), 1, w.max_len, w.alpha, True)
+    rows = [oracle.cp_global_rows(off_np, cp, r) for r in range(cp)]
+    dk_sum = torch.zeros((T, 2, 32), dtype=torch.float32, device="cuda")
+    dv_sum = torch.zeros_like(dk_sum)
+    dw_sum = torch.zeros(24, dtype=torch.float32, device="cuda")
+    for rq in range(cp):
+        ql, gl, tq = lib.hstu_cp_reorder([dev["q"], dev["d_o"], ts], off, T, cp, rq, len(rows[rq]))
+        o, dq, dk, dv, dw = lib.hstu_jagged_attn_cp_partial_bias(ql, dev["k"], dev["v"], gl, off, T, tq, ts, tab, 1,
+                                                                 w.max_len, w.alpha, True, cp, rq, -1)
+        torch.cuda.synchronize()
+        _check("o", o, want[0][rows[rq]], "f32", "cp f32 q%d" % rq)
+        _check("dq", dq, want[1][rows[rq]], "f32", "cp f32 q%d" % rq)
+        dk_sum += dk; dv_sum += dv; dw_sum += dw
+    _check("dk", dk_sum, want[2], "f32", "cp f32")
+    _check("dv", dv_sum, want[3], "f32", "cp f32")
+    g = dw_sum.double().cpu().numpy()
+    rms = float(np.sqrt(np.mean(want[4] ** 2)))
+    assert np.abs(g - want[4]).max() <= 1e-4 * rms
