@@ -31,3 +31,25 @@ def test_values_are_seeded_and_rounded_once():
     w2 = workloads.custom("t", [3, 4], 2, 32, 32, 8, dtype="bf16")
     x = workloads.values(w2)["q"]
     assert np.array_equal(workloads.to_f64(x), x.float().double().numpy())
+
+
+def test_timestamps_and_tables_are_seeded_and_shaped():
+    w = workloads.custom("t", [40, 0, 7, 300], 1, 32, 32, 300)
+    off = w.seq_offsets()
+    for kind in ("events", "shuffled", "equal", "wide"):
+        ts = workloads.timestamps(w, kind, 3)
+        assert ts.dtype == np.int32 and ts.shape == (w.total_rows,)
+        assert np.array_equal(ts, workloads.timestamps(w, kind, 3))          # seeded
+        assert not np.array_equal(ts, workloads.timestamps(w, kind, 4)) or kind == "never"
+        for b in range(w.batch):
+            seg = ts[off[b]:off[b + 1]].astype(np.int64)
+            if kind in ("events", "wide"):
+                assert (np.diff(seg) >= 0).all()                               # a history is sorted
+            if kind == "equal":
+                assert (seg == seg[:1]).all()
+    sh = workloads.timestamps(w, "shuffled", 3).astype(np.int64)
+    assert (np.diff(sh[off[3]:off[4]]) < 0).any()                              # not sorted
+    span = workloads.timestamps(w, "wide", 3).astype(np.int64)
+    assert span.max() - span.min() > 2 ** 31                                   # differences beyond int32
+    tab = workloads.bias_table(24, 1, 0.5)
+    assert tab.dtype == np.float32 and tab.shape == (24,) and np.array_equal(tab, workloads.bias_table(24, 1, 0.5))

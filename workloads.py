@@ -141,8 +141,8 @@ def timestamps(w: Workload, kind: str = "events", seed: int = 0) -> np.ndarray:
 
     "events": per sequence a random start plus cumulative heavy-tailed gaps (log-normal seconds
     with a median of a minute: bursts of activity separated by idle hours), non-decreasing
-    inside a sequence, as a user's interaction history is; "shuffled": the same values in random
-    order inside each sequence (nothing sorted: every block of pairs spans many buckets);
+    inside a sequence, as a user's interaction history is; "shuffled": values drawn the same way
+    but in random order inside each sequence (nothing sorted: every block of pairs spans many buckets);
     "equal": one value per sequence (every difference zero); "wide": differences up to the
     whole int32 range.
     """
