@@ -163,8 +163,7 @@ typedef struct {
 size_t hstu_jagged_attn_bias_workspace_bytes(const hstu_attn_params* params, int which);
 
 /* hstu_jagged_attn_fwd / hstu_jagged_attn_bwd with the bias above; same arguments, layouts and
- * errors, plus: bf16 inputs need d_qk == d_v (otherwise HSTU_ERR_UNSUPPORTED; fp32 inputs take
- * any supported pair and are computed in fp32 throughout, table and its gradient included),
+ * errors (fp32 inputs are computed in fp32 throughout, table and its gradient included), plus:
  * num_buckets or groups_log2 out of range HSTU_ERR_BAD_SHAPE, a NULL field of `bias` (other
  * than d_ts_weights in the forward call) HSTU_ERR_NULL_PTR.  dq, dk, dv are deterministic as in
  * hstu_jagged_attn_bwd; d_ts_weights is not (see above). */

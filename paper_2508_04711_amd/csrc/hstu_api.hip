@@ -369,7 +369,6 @@ int run_query_pass(const hstu_attn_params* p, int pass, AttnArgs& a, const Built
 // Timestamp bias: argument checks and the per-row records at the start of the workspace.
 int check_bias(const hstu_attn_params* p, const hstu_ts_bias* b, bool backward) {
   if (!b) return HSTU_ERR_NULL_PTR;
-  if (p->dtype == HSTU_BF16 && p->d_qk != p->d_v) return HSTU_ERR_UNSUPPORTED;
   if (b->num_buckets < 1 || b->num_buckets > MAX_TS_BUCKETS || b->groups_log2 < 0 || b->groups_log2 > 8)
     return HSTU_ERR_BAD_SHAPE;
   if (!b->timestamps || !b->ts_weights || (backward && !b->d_ts_weights)) return HSTU_ERR_NULL_PTR;
@@ -644,7 +643,6 @@ static int cp_partial_impl(const hstu_attn_params* params, const hstu_cp_desc* c
   for (const void* ptr : ptrs)
     if (ptr && !aligned16(ptr)) return HSTU_ERR_MISALIGNED;
   if (bias) {
-    if (params->dtype == HSTU_BF16 && params->d_qk != params->d_v) return HSTU_ERR_UNSUPPORTED;
     if (bias->num_buckets < 1 || bias->num_buckets > MAX_TS_BUCKETS || bias->groups_log2 < 0 ||
         bias->groups_log2 > 8)
       return HSTU_ERR_BAD_SHAPE;

@@ -613,16 +613,11 @@ __device__ __forceinline__ void bwd_elem(float s, float dp, float c1, float alph
     return hipGetLastError();                                                           \
   } while (0)
 
-// The kernels with the timestamp bias exist for equal head dimensions of Q/K and V only.
+// The kernels with the timestamp bias: the same dispatch after a check of the bias arguments.
 #define HSTU_DISPATCH_BIAS(KERNEL, NW, ...)                                             \
   do {                                                                                  \
-    const dim3 grid((unsigned)((int64_t)a.max_items * a.num_heads)), block(NW * 64);    \
     if (a.nb < 1 || a.nb > MAX_TS_BUCKETS || !a.ts_w || !a.ts_rec_own) return hipErrorInvalidValue; \
-    if (d_qk == 128 && d_v == 128) hipLaunchKernelGGL((KERNEL<128, 128, __VA_ARGS__>), grid, block, 0, stream, a); \
-    else if (d_qk == 64 && d_v == 64) hipLaunchKernelGGL((KERNEL<64, 64, __VA_ARGS__>), grid, block, 0, stream, a); \
-    else if (d_qk == 32 && d_v == 32) hipLaunchKernelGGL((KERNEL<32, 32, __VA_ARGS__>), grid, block, 0, stream, a); \
-    else return hipErrorInvalidValue;                                                   \
-    return hipGetLastError();                                                           \
+    HSTU_DISPATCH_D(KERNEL, NW, __VA_ARGS__);                                           \
   } while (0)
 
 }  // namespace
