@@ -152,8 +152,9 @@ typedef struct {
   const float* ts_weights;    /* device, [num_buckets] fp32: the table                          */
   float* d_ts_weights;        /* device, [num_buckets] fp32: backward output (overwritten: the
                                  sum over all visible pairs and heads of alpha * dS); NULL is
-                                 allowed in the forward call.  Summed with fp32 atomics: the
-                                 last bits vary from run to run                                 */
+                                 allowed in the forward call.  Summed in 64-bit fixed point
+                                 inside a workgroup (terms below 2^-32 of the unscaled dS are
+                                 lost) and in double precision across workgroups             */
   int32_t num_buckets;        /* 1..512                                                         */
   int32_t groups_log2;        /* f: 0..8                                                        */
 } hstu_ts_bias;
@@ -166,7 +167,7 @@ size_t hstu_jagged_attn_bias_workspace_bytes(const hstu_attn_params* params, int
  * errors (fp32 inputs are computed in fp32 throughout, table and its gradient included), plus:
  * num_buckets or groups_log2 out of range HSTU_ERR_BAD_SHAPE, a NULL field of `bias` (other
  * than d_ts_weights in the forward call) HSTU_ERR_NULL_PTR.  dq, dk, dv are deterministic as in
- * hstu_jagged_attn_bwd; d_ts_weights is not (see above). */
+ * hstu_jagged_attn_bwd; d_ts_weights is, up to the order of its double-precision additions. */
 int hstu_jagged_attn_bias_fwd(const hstu_attn_params* params, const hstu_ts_bias* bias,
                               const void* q, const void* k, const void* v,
                               const int32_t* seq_offsets, void* o, void* workspace,
@@ -334,8 +335,8 @@ int hstu_debug_dump_schedule(const hstu_attn_params* params, const hstu_cp_desc*
  *   begin: max_records in [1, 65536]; launches beyond it are not recorded.
  *   end:   waits for the recorded launches, writes per launch, in launch order, its kind
  *          (0 forward, 1 dk/dv pass, 2 dq pass, 3 schedule build, 4 transposed copy,
- *          5 reorder, 6 sum of the partial results of split tiles, 7 timestamp records)
- *          and its duration in milliseconds; returns the number written (<= capacity) or a status < 0.
+ *          5 reorder, 6 sum of the partial results of split tiles, 7 timestamp records,
+ *          8 scaling of the bias table's gradient) and its duration in milliseconds; returns the number written (<= capacity) or a status < 0.
  */
 int hstu_debug_timing_begin(int max_records);
 int hstu_debug_timing_end(int32_t* kinds, float* milliseconds, int capacity);

@@ -518,7 +518,7 @@ def hstu_debug_dump_schedule(seq_offsets: torch.Tensor, total_rows: int, num_hea
 
 
 KERNEL_KINDS = {0: "fwd", 1: "dkdv", 2: "dq", 3: "plan", 4: "transpose", 5: "reorder", 6: "reduce",
-                7: "ts_records"}
+                7: "ts_records", 8: "dw_finish"}
 
 
 def hstu_debug_timing_begin(max_records: int = 4096) -> None:

@@ -374,24 +374,40 @@ int check_bias(const hstu_attn_params* p, const hstu_ts_bias* b, bool backward) 
   if (!b->timestamps || !b->ts_weights || (backward && !b->d_ts_weights)) return HSTU_ERR_NULL_PTR;
   return HSTU_OK;
 }
+// The workspace of a call with bias starts with the call's table of sums for the table gradient
+// (one double per bucket), then one array of records per layout of rows.
+constexpr size_t DW_ACC_BYTES = MAX_TS_BUCKETS * sizeof(double);
 size_t ts_record_bytes(const hstu_attn_params* p) {
   return align_up((size_t)(p->total_rows + 64) * sizeof(TsRecord), 256);
 }
-// Builds the records at the start of the workspace (and clears the table gradient).
+size_t bias_front_bytes(const hstu_attn_params* p, int arrays) {
+  return DW_ACC_BYTES + arrays * ts_record_bytes(p);
+}
+// Builds the records (and clears the table of sums for a backward call).
 int build_ts_records(const hstu_attn_params* p, const hstu_ts_bias* b, const int32_t* off, char* ws,
                      bool backward, hipStream_t stream) {
   TimedLaunch timed(7, stream);
-  return launch_ts_records(b->timestamps, off, p->batch, p->total_rows, reinterpret_cast<TsRecord*>(ws),
-                           backward ? b->d_ts_weights : nullptr, b->num_buckets, stream) == hipSuccess
+  return launch_ts_records(b->timestamps, off, p->batch, p->total_rows,
+                           reinterpret_cast<TsRecord*>(ws + DW_ACC_BYTES),
+                           backward ? reinterpret_cast<double*>(ws) : nullptr, b->num_buckets,
+                           stream) == hipSuccess
              ? HSTU_OK : HSTU_ERR_HIP;
 }
-void set_bias(AttnArgs& a, const hstu_ts_bias* b, const char* ws) {
-  a.ts_rec = reinterpret_cast<const TsRecord*>(ws);
+void set_bias(AttnArgs& a, const hstu_ts_bias* b, char* ws, bool backward) {
+  a.ts_rec = reinterpret_cast<const TsRecord*>(ws + DW_ACC_BYTES);
   a.ts_rec_own = a.ts_rec;
   a.ts_w = b->ts_weights;
-  a.d_ts_w = b->d_ts_weights;
+  a.d_ts_acc = backward ? reinterpret_cast<double*>(ws) : nullptr;
   a.nb = b->num_buckets;
   a.fbits = b->groups_log2;
+}
+// Scales the call's sums into the caller's table gradient.
+int finish_dw(const hstu_attn_params* p, const char* ws, float* d_w, int nb, int accumulate,
+              hipStream_t stream) {
+  TimedLaunch timed(8, stream);
+  return launch_dw_finish(reinterpret_cast<const double*>(ws), d_w, nb,
+                          (double)p->alpha / (double)p->max_len, accumulate, stream) == hipSuccess
+             ? HSTU_OK : HSTU_ERR_HIP;
 }
 
 SideSpec full_side(const hstu_attn_params* p, int side, int pass) {
@@ -486,7 +502,7 @@ size_t hstu_jagged_attn_bias_workspace_bytes(const hstu_attn_params* params, int
   const size_t plain = hstu_jagged_attn_workspace_bytes(params, which);
   if (!plain) return 0;
   // one array of records, or one per side (neither side holds more rows than the whole batch)
-  return plain + (which == HSTU_WS_CP ? 2 : 1) * ts_record_bytes(params);
+  return plain + bias_front_bytes(params, which == HSTU_WS_CP ? 2 : 1);
 }
 
 // Forward over the whole batch, with the timestamp bias if `bias` is not null.
@@ -504,7 +520,7 @@ static int fwd_impl(const hstu_attn_params* params, const hstu_ts_bias* bias, co
                               : hstu_jagged_attn_workspace_bytes(params, HSTU_WS_FWD)))
     return HSTU_ERR_WORKSPACE_TOO_SMALL;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  const size_t first = bias ? ts_record_bytes(params) : 0;  // the records come first
+  const size_t first = bias ? bias_front_bytes(params, 1) : 0;  // the records come first
   if (bias && (rc = build_ts_records(params, bias, seq_offsets, (char*)workspace, false, stream)) != HSTU_OK)
     return rc;
   if (!bias && packed_tiles(params)) {
@@ -523,7 +539,7 @@ static int fwd_impl(const hstu_attn_params* params, const hstu_ts_bias* bias, co
   size_t base = bp.end;
   AttnArgs a = base_args(params, bp, 0);
   a.q = q; a.k = k; a.v = v; a.o = o;
-  if (bias) set_bias(a, bias, (const char*)workspace);
+  if (bias) set_bias(a, bias, (char*)workspace, false);
   rc = make_tcopy(params, full_side(params, 0, PASS_FWD), bp, v, params->d_v, (char*)workspace,
                   workspace_bytes, &base, stream, &a.vt);
   if (rc != HSTU_OK) return rc;
@@ -563,7 +579,7 @@ static int bwd_impl(const hstu_attn_params* params, const hstu_ts_bias* bias, co
                               : hstu_jagged_attn_workspace_bytes(params, HSTU_WS_BWD)))
     return HSTU_ERR_WORKSPACE_TOO_SMALL;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  const size_t first = bias ? ts_record_bytes(params) : 0;  // the records come first
+  const size_t first = bias ? bias_front_bytes(params, 1) : 0;  // the records come first
   if (bias && (rc = build_ts_records(params, bias, seq_offsets, (char*)workspace, true, stream)) != HSTU_OK)
     return rc;
   if (!bias && packed_tiles(params)) {
@@ -592,15 +608,17 @@ static int bwd_impl(const hstu_attn_params* params, const hstu_ts_bias* bias, co
   if (rc != HSTU_OK) return rc;
   AttnArgs a = base_args(params, pk, 0);
   a.q = q; a.k = k; a.v = v; a.d_o = d_o; a.dk = dk; a.dv = dv;
-  if (bias) set_bias(a, bias, (const char*)workspace);
+  if (bias) set_bias(a, bias, (char*)workspace, true);
   rc = run_pass(params, PASS_DKDV, a, stream);
   if (rc != HSTU_OK) return rc;
   AttnArgs b = base_args(params, pq, 0);
   b.q = q; b.k = k; b.v = v; b.d_o = d_o; b.dq = dq;
-  if (bias) set_bias(b, bias, (const char*)workspace);
+  if (bias) set_bias(b, bias, (char*)workspace, true);
   size_t base = pq.end;
-  return run_query_pass(params, PASS_DQ, b, pq, full_side(params, 0, PASS_DQ), dq, params->d_qk,
-                        (char*)workspace, workspace_bytes, &base, stream);
+  rc = run_query_pass(params, PASS_DQ, b, pq, full_side(params, 0, PASS_DQ), dq, params->d_qk,
+                      (char*)workspace, workspace_bytes, &base, stream);
+  if (rc != HSTU_OK || !bias) return rc;
+  return finish_dw(params, (const char*)workspace, bias->d_ts_weights, bias->num_buckets, 0, stream);
 }
 
 int hstu_jagged_attn_bwd(const hstu_attn_params* params, const void* q, const void* k,
@@ -666,12 +684,12 @@ static int cp_partial_impl(const hstu_attn_params* params, const hstu_cp_desc* c
   const TsRecord *q_rec = nullptr, *kv_rec = nullptr;
   if (bias) {
     const int64_t qr = clamp_rows(cp->q_rows, params->total_rows), kr = clamp_rows(cp->kv_rows, params->total_rows);
-    q_rec = reinterpret_cast<const TsRecord*>(ws);
-    kv_rec = reinterpret_cast<const TsRecord*>(ws + ts_record_bytes(params));
-    base = 2 * ts_record_bytes(params);
+    q_rec = reinterpret_cast<const TsRecord*>(ws + DW_ACC_BYTES);
+    kv_rec = reinterpret_cast<const TsRecord*>(ws + DW_ACC_BYTES + ts_record_bytes(params));
+    base = bias_front_bytes(params, 2);
     TimedLaunch timed(7, stream);
-    // the first launch also clears the table gradient unless the step adds to it
-    float* clear = (backward && !acc_q) ? bias->d_ts_weights : nullptr;
+    // the first launch also clears the call's table of sums
+    double* clear = backward ? reinterpret_cast<double*>(ws) : nullptr;
     if (launch_ts_records(bias->q_timestamps, nullptr, 0, qr, const_cast<TsRecord*>(q_rec), clear,
                           bias->num_buckets, stream) != hipSuccess ||
         launch_ts_records(bias->kv_timestamps, cp->kv_rank < 0 ? seq_offsets_global : nullptr,
@@ -684,7 +702,7 @@ static int cp_partial_impl(const hstu_attn_params* params, const hstu_cp_desc* c
     a.ts_rec = owners_are_queries ? kv_rec : q_rec;
     a.ts_rec_own = owners_are_queries ? q_rec : kv_rec;
     a.ts_w = bias->ts_weights;
-    a.d_ts_w = bias->d_ts_weights;
+    a.d_ts_acc = backward ? reinterpret_cast<double*>(ws) : nullptr;
     a.nb = bias->num_buckets;
     a.fbits = bias->groups_log2;
   };
@@ -707,7 +725,12 @@ static int cp_partial_impl(const hstu_attn_params* params, const hstu_cp_desc* c
     if (rc != HSTU_OK) return rc;
     qbase = pq.end;
   }
-  if (np == 0) return HSTU_OK;
+  // with bias, a backward call ends by scaling its sums into the caller's table gradient
+  auto finish = [&]() -> int {
+    if (!bias || !backward) return HSTU_OK;
+    return finish_dw(params, ws, bias->d_ts_weights, bias->num_buckets, acc_q, stream);
+  };
+  if (np == 0) return finish();
   rc = launch_built(pa, np, stream);
   if (rc != HSTU_OK) return rc;
   if (do_f) {
@@ -733,7 +756,7 @@ static int cp_partial_impl(const hstu_attn_params* params, const hstu_cp_desc* c
     rc = run_query_pass(params, PASS_DQ, b, pq, sq, dq_local, params->d_qk, ws, workspace_bytes, &qbase, stream);
     if (rc != HSTU_OK) return rc;
   }
-  return HSTU_OK;
+  return finish();
 }
 
 int hstu_jagged_attn_cp_partial(const hstu_attn_params* params, const hstu_cp_desc* cp,

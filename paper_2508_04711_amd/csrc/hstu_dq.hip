@@ -22,27 +22,26 @@ namespace {
 // Sum of dS per bucket for the gradient of the bias table (dq pass only: it visits every pair once).
 // A run of blocks that fall into one bucket adds up in a register per lane and goes to the
 // workgroup's LDS table when the bucket changes; the pairs of a block that spans several
-// buckets go there one by one.  The LDS table holds 2^shift copies of every bucket, a lane adds
-// to copy (lane mod 2^shift): lanes that hit the same bucket at once then mostly hit different
-// addresses (same-address LDS atomics are served one after the other).
-constexpr int DW_LDS = 2048;  // floats of the workgroup's table
+// buckets go there one by one.  The LDS table is 64-bit fixed point (see dw_to_fixed) and holds
+// 2^shift copies of every bucket, a lane adds to copy (lane mod 2^shift).
+constexpr int DW_LDS = 1024;  // entries of the workgroup's table
 __host__ __device__ constexpr int dw_shift(int nb) {
   int s = 0;
   while (s < 5 && (nb << (s + 1)) <= DW_LDS) ++s;
   return s;
 }
 struct DwAcc {
-  float* dwl;   // LDS, 2^shift entries per bucket
-  float sum;    // per lane: dS of the current run
-  int cur;      // bucket of the current run (uniform; -1: none)
+  unsigned long long* dwl;  // LDS, 2^shift entries per bucket
+  float sum;                // per lane: dS of the current run
+  int cur;                  // bucket of the current run (uniform; -1: none)
   int shift;
   __device__ __forceinline__ void add(int bucket, int lane, float x) {
-    atomicAdd(dwl + (bucket << shift) + (lane & ((1 << shift) - 1)), x);
+    atomicAdd(dwl + (bucket << shift) + (lane & ((1 << shift) - 1)), dw_to_fixed(x));
   }
   __device__ __forceinline__ void flush(int lane) {
     if (cur >= 0) {
       const float t = wave_sum(sum);
-      if (lane == 0) atomicAdd(dwl + (cur << shift), t);
+      if (lane == 0) atomicAdd(dwl + (cur << shift), dw_to_fixed(t));
     }
     sum = 0.f;
   }
@@ -110,7 +109,7 @@ __global__ void __launch_bounds__(NW * 64, 2) hstu_dq_bf16(AttnArgs a) {
   __shared__ __attribute__((aligned(1024))) char tmem0[BIAS ? REC_TILE : 16];
   __shared__ __attribute__((aligned(1024))) char tmem1[BIAS ? REC_TILE : 16];
   __shared__ float wtab[BIAS ? MAX_TS_BUCKETS : 1];
-  __shared__ float dwl[BIAS ? DW_LDS : 1];
+  __shared__ unsigned long long dwl[BIAS ? DW_LDS : 1];
   auto kbuf = [&](int b) { return b ? smem1 : smem0; };
   auto vbuf = [&](int b) { return (b ? smem1 : smem0) + KB; };
   auto tbuf = [&](int b) { return b ? tmem1 : tmem0; };
@@ -137,7 +136,7 @@ __global__ void __launch_bounds__(NW * 64, 2) hstu_dq_bf16(AttnArgs a) {
   DwAcc dwa = {dwl, 0.f, -1, 0};
   if constexpr (BIAS) {
     dwa.shift = dw_shift(a.nb);
-    for (int i = tid; i < (a.nb << dwa.shift); i += NW * 64) dwl[i] = 0.f;
+    for (int i = tid; i < (a.nb << dwa.shift); i += NW * 64) dwl[i] = 0ull;
     bias = bias_setup<NW * 64>(a, wtab, it, orow, tid, hh);
   }
 
@@ -208,16 +207,15 @@ __global__ void __launch_bounds__(NW * 64, 2) hstu_dq_bf16(AttnArgs a) {
   }
 
   if constexpr (BIAS) {
-    // the workgroup's sums go to the table gradient (fp32 atomics: the order of the additions,
-    // and with it the last bits of the result, varies from run to run)
+    // the workgroup's sums go to the call's table (double precision atomics: their order can
+    // change the result by a unit of the 53rd bit, far below the fp32 it is rounded to)
     dwa.flush(lane);
     __syncthreads();
-    const float scale = a.alpha * a.inv_n;
     for (int i = tid; i < a.nb; i += NW * 64) {
-      float t = 0.f;
+      unsigned long long t = 0ull;
       const int cm = (1 << dwa.shift) - 1;  // (rotated by i: neighbouring threads read different banks)
       for (int c = 0; c <= cm; ++c) t += dwl[(i << dwa.shift) + ((c + i) & cm)];
-      if (t != 0.f) atomicAdd(a.d_ts_w + i, t * scale);
+      if (t != 0ull) atomicAdd(a.d_ts_acc + i, dw_from_fixed(t));
     }
   }
 
@@ -238,7 +236,7 @@ hipError_t launch_dq_bf16(const AttnArgs& a, int d_qk, int d_v, hipStream_t stre
   if (a.waves != 4 || (a.row_seq && a.ts_rec)) return hipErrorInvalidValue;
   if (a.row_seq) HSTU_DISPATCH_D(hstu_dq_bf16, 4, 4, false, true);
   if (a.ts_rec) {
-    if (!a.d_ts_w) return hipErrorInvalidValue;
+    if (!a.d_ts_acc) return hipErrorInvalidValue;
     HSTU_DISPATCH_BIAS(hstu_dq_bf16, 4, 4, true, false);
   }
   HSTU_DISPATCH_D(hstu_dq_bf16, 4, 4, false, false);

@@ -205,7 +205,7 @@ template <int DQK, int DV>
 __global__ void __launch_bounds__(THREADS) hstu_dq_f32(AttnArgs a) {
   __shared__ __attribute__((aligned(16))) float kt[ST * DQK];
   __shared__ __attribute__((aligned(16))) float vt[ST * DV];
-  __shared__ float dwl[MAX_TS_BUCKETS];  // the workgroup's share of the bias table's gradient
+  __shared__ unsigned long long dwl[MAX_TS_BUCKETS];  // the workgroup's sums of dS per bucket (fixed point)
   const int H = a.num_heads;
   const int slot = blockIdx.x / H, h = blockIdx.x % H;
   Item it;
@@ -213,9 +213,9 @@ __global__ void __launch_bounds__(THREADS) hstu_dq_f32(AttnArgs a) {
   const int tid = threadIdx.x, r = tid >> 2, c = tid & 3;
   const int64_t sq = (int64_t)H * DQK, sv = (int64_t)H * DV;
   const bool on = r < it.nrows;
-  const bool want_dw = a.ts_rec && a.d_ts_w;
+  const bool want_dw = a.ts_rec && a.d_ts_acc;
   if (want_dw)
-    for (int i = tid; i < a.nb; i += THREADS) dwl[i] = 0.f;  // (the loop's first barrier orders this)
+    for (int i = tid; i < a.nb; i += THREADS) dwl[i] = 0ull;  // (the loop's first barrier orders this)
   float qp[DQK / 4], gp[DV / 4], dqp[DQK / 4];
   load_part<DQK>(qp, (const float*)a.q + ((int64_t)it.row0 + r) * sq + h * DQK, on, c);
   load_part<DV>(gp, (const float*)a.d_o + ((int64_t)it.row0 + r) * sv + h * DV, on, c);
@@ -246,14 +246,14 @@ __global__ void __launch_bounds__(THREADS) hstu_dq_f32(AttnArgs a) {
         axpy_part<DQK>(dqp, ds, kt + j * DQK, c);
         // one of the row's four lanes adds the pair's dS to its bucket (rows without an owner
         // have dS = 0: their q and d_o parts are zero)
-        if (want_dw && c == 0 && ds != 0.f) atomicAdd(dwl + bucket, ds);
+        if (want_dw && c == 0 && ds != 0.f) atomicAdd(dwl + bucket, dw_to_fixed(ds));
       }
     }
   }
   if (want_dw) {
     __syncthreads();
     for (int i = tid; i < a.nb; i += THREADS)
-      if (dwl[i] != 0.f) atomicAdd(a.d_ts_w + i, dwl[i] * a.alpha * a.inv_n);
+      if (dwl[i] != 0ull) atomicAdd(a.d_ts_acc + i, dw_from_fixed(dwl[i]));
   }
   if (on)
     store_part<DQK>((float*)a.dq + ((int64_t)it.row0 + r) * sq + h * DQK, dqp, a.alpha * a.inv_n,

@@ -532,10 +532,10 @@ namespace {
 __global__ void __launch_bounds__(256) ts_records_kernel(const int32_t* __restrict__ ts,
                                                          const int32_t* __restrict__ off, int batch,
                                                          int total, TsRecord* __restrict__ rec,
-                                                         float* __restrict__ d_w, int nb) {
+                                                         double* __restrict__ acc, int nb) {
   const int r = blockIdx.x * 256 + threadIdx.x;
-  if (d_w)
-    for (int i = r; i < nb; i += gridDim.x * 256) d_w[i] = 0.f;
+  if (acc)
+    for (int i = r; i < nb; i += gridDim.x * 256) acc[i] = 0.0;
   if (r >= total + 64) return;
   TsRecord x = {0, 0, 0, 0};
   if (r < total) {
@@ -562,12 +562,32 @@ __global__ void __launch_bounds__(256) ts_records_kernel(const int32_t* __restri
 
 }  // namespace
 
+namespace {
+
+__global__ void __launch_bounds__(256) dw_finish_kernel(const double* __restrict__ acc,
+                                                        float* __restrict__ d_w, int nb, double scale,
+                                                        int accumulate) {
+  for (int i = threadIdx.x; i < nb; i += 256) {
+    const float x = (float)(acc[i] * scale);
+    d_w[i] = accumulate ? d_w[i] + x : x;
+  }
+}
+
+}  // namespace
+
+hipError_t launch_dw_finish(const double* acc, float* d_w, int nb, double scale, int accumulate,
+                            hipStream_t stream) {
+  if (!acc || !d_w || nb < 1) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(dw_finish_kernel, dim3(1), dim3(256), 0, stream, acc, d_w, nb, scale, accumulate);
+  return hipGetLastError();
+}
+
 hipError_t launch_ts_records(const int32_t* ts, const int32_t* off, int batch, int64_t total_rows,
-                             TsRecord* rec, float* d_w, int nb, hipStream_t stream) {
+                             TsRecord* rec, double* acc, int nb, hipStream_t stream) {
   if ((off && batch < 1) || total_rows < 0 || total_rows + 64 >= (1ll << 31)) return hipErrorInvalidValue;
   const unsigned blocks = (unsigned)((total_rows + 64 + 255) / 256);
   hipLaunchKernelGGL(ts_records_kernel, dim3(blocks), dim3(256), 0, stream, ts, off, batch,
-                     (int)total_rows, rec, d_w, nb);
+                     (int)total_rows, rec, acc, nb);
   return hipGetLastError();
 }
 

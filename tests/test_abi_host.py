@@ -113,11 +113,11 @@ def test_bias_calls_reject_bad_arguments_on_the_host(lib):
     for which in (0, 1):
         plain = lib.hstu_jagged_attn_workspace_bytes(ctypes.byref(ok), which)
         with_bias = lib.hstu_jagged_attn_bias_workspace_bytes(ctypes.byref(ok), which)
-        assert with_bias == plain + 16 * (10 + 64) + (-16 * (10 + 64)) % 256
+        assert with_bias == plain + 512 * 8 + 16 * (10 + 64) + (-16 * (10 + 64)) % 256   # sums, then records
     # the context-parallel call with bias: records for both sides' rows
     rec = 16 * (10 + 64) + (-16 * (10 + 64)) % 256
     assert lib.hstu_jagged_attn_bias_workspace_bytes(ctypes.byref(ok), 2) == \
-        lib.hstu_jagged_attn_workspace_bytes(ctypes.byref(ok), 2) + 2 * rec
+        lib.hstu_jagged_attn_workspace_bytes(ctypes.byref(ok), 2) + 512 * 8 + 2 * rec
     assert lib.hstu_jagged_attn_bias_workspace_bytes(ctypes.byref(ok), 3) == 0
     # hstu_jagged_attn_cp_partial_bias: the descriptor's checks come before any device work
     cpd = binding._CpDesc(2, 0, 1, 0, 5, 5)
