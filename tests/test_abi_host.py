@@ -34,6 +34,20 @@ def test_every_declared_symbol_is_exported(lib):
         assert hasattr(lib, n), n
 
 
+def test_header_is_plain_c_and_cxx(tmp_path):
+    """The boundary is a C header: it must compile as strict C99 and as C++ with no warnings."""
+    import subprocess
+    src = tmp_path / "use_header.c"
+    src.write_text('#include "hstu_attn.h"\n'
+                   'int main(void) { hstu_attn_params p; hstu_cp_desc c; hstu_ts_bias b; hstu_cp_ring_desc r;\n'
+                   '  (void)p; (void)c; (void)b; (void)r; return hstu_attn_status_string(0) == 0; }\n')
+    inc = os.path.join(ROOT, "include")
+    for cmd in (["gcc", "-std=c99", "-x", "c"], ["g++", "-std=c++11", "-x", "c++"]):
+        res = subprocess.run(cmd + ["-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-I", inc, str(src)],
+                             capture_output=True, text=True)
+        assert res.returncode == 0, res.stderr
+
+
 def _params(binding, **kw):
     base = dict(batch=2, num_heads=2, d_qk=64, d_v=64, max_len=16, alpha=0.125, causal=1, dtype=0,
                 total_rows=10, out_dtype=0, reserved=0)
