@@ -470,6 +470,7 @@ __device__ __forceinline__ float wave_sum(float x) {
 struct BiasCtx {
   const float* wtab;     // LDS copy of the table
   const TsRecord* rec;   // the records of all rows, padded by 64
+  bf16x8 ones;           // A operand with 1.0 in the first two slots of every row (see bias_block)
   int t_own;             // timestamp of the lane's owner row
   int o_lo, o_hi;        // range of the timestamps of the wave's valid owner rows (uniform)
   int nb, f, hh;
@@ -480,7 +481,7 @@ struct BiasCtx {
 struct BlockBias {
   int b0;
   bool uni;
-  float wb;
+  uint32_t wpair;  // the table entry as two bf16 halves, high part in the low 16 bits (see bias_block)
 };
 
 // BlockBias of the stream's blocks, one block per lane: blocks [128k, 128k + 64) in set 0,
@@ -512,7 +513,12 @@ struct BlockTable {
                                           : (s_lo > c.o_hi ? (uint32_t)s_lo - (uint32_t)c.o_hi : 0u);
       const int b0 = bias_bucket(dmin, c.nb, c.f), b1 = bias_bucket(dmax, c.nb, c.f);
       code = b0 | (b0 != b1 ? NONUNIFORM : 0);
-      w = *HSTU_LDS(float, c.wtab + b0);
+      // the entry as hi + lo, both bf16: exact to 2^-16 of its value
+      const float wv = *HSTU_LDS(float, c.wtab + b0);
+      const __bf16 hi = (__bf16)wv;
+      const __bf16 lo = (__bf16)(wv - (float)hi);
+      w = __builtin_bit_cast(float, (uint32_t)__builtin_bit_cast(uint16_t, hi) |
+                                        ((uint32_t)__builtin_bit_cast(uint16_t, lo) << 16));
     }
     const bool odd = (first >> 6) & 1;
     code0 = odd ? code0 : code; w0 = odd ? w0 : w;
@@ -530,7 +536,7 @@ struct BlockTable {
     BlockBias b;
     b.b0 = c & (NONUNIFORM - 1);
     b.uni = (c & NONUNIFORM) == 0;
-    b.wb = __builtin_bit_cast(float, odd ? x1 : x0);
+    b.wpair = (uint32_t)(odd ? x1 : x0);
     return b;
   }
 };
@@ -541,8 +547,14 @@ struct BlockTable {
 __device__ __forceinline__ void bias_block(f32x16& s, const char* trec, int blk, const BiasCtx& c,
                                            const BlockBias& bb, int (&bk)[16]) {
   if (bb.uni) {
-#pragma unroll
-    for (int r = 0; r < 16; ++r) { s[r] = bb.wb; bk[r] = bb.b0; }
+    // One matrix instruction writes the entry into all 32x32 accumulator elements: every row of A has
+    // ones in its first two slots, every column of B the entry's two bf16 halves there, so that
+    // D = 1*hi + 1*lo.  (Sixteen register moves cost the vector pipe four times what this costs
+    // the matrix pipe, and the vector pipe is the fuller one.)  bk stays unset: only blocks of
+    // several buckets use it.
+    const u32x4 bq = {c.hh == 0 ? bb.wpair : 0u, 0u, 0u, 0u};
+    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    s = mfma(c.ones, __builtin_bit_cast(bf16x8, bq), zero);
   } else {
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
@@ -582,6 +594,10 @@ __device__ __forceinline__ BiasCtx bias_setup(const AttnArgs& a, float* wtab, co
   c.wtab = wtab;
   c.rec = a.ts_rec;
   c.nb = a.nb; c.f = a.fbits; c.hh = hh;
+  {
+    const u32x4 o = {hh == 0 ? 0x3f803f80u : 0u, 0u, 0u, 0u};
+    c.ones = __builtin_bit_cast(bf16x8, o);
+  }
   const bool ok = orow < it.nrows;
   c.t_own = ok ? a.ts_rec_own[it.row0 + orow].ts : 0;
   c.o_lo = wave_min(ok ? c.t_own : 0x7fffffff);
