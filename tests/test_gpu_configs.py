@@ -136,3 +136,60 @@ def test_one_very_long_sequence(with_bias):
             assert err[rows_idx].max() <= 2e-2 * rms, (name, float(err[rows_idx].max() / rms))
     for t in (o, dq, dk, dv):
         assert torch.isfinite(t).all()
+
+
+@pytest.mark.parametrize("with_bias", [False, True])
+def test_tensors_beyond_four_gib(with_bias):
+    """1024 sequences of 4200 rows, H = 4, d = 128: every tensor is 4.4e9 bytes, so byte offsets
+    of the rows of the last 25 sequences do not fit 32 bits.  The inputs are drawn on the device;
+    the oracle gets the sequences the sampled rows lie in (rows of different sequences do not
+    interact): the first, the one that contains byte offset 2^32, its successor, and the last."""
+    import paper_2508_04711_amd as lib
+    L, B, H, d = 4200, 1024, 4, 128
+    w = workloads.custom("beyond_4gib", [L] * B, H, d, d, L, dtype="bf16", seed=31)
+    assert w.total_rows * H * d * 2 > 2 ** 32
+    dev = workloads.device_values(w)
+    off_np = w.seq_offsets()
+    off = torch.from_numpy(off_np).cuda()
+    straddle = (2 ** 32 // (H * d * 2)) // L
+    seqs = [0, straddle, straddle + 1, B - 1]
+    assert int(off_np[straddle]) * H * d * 2 < 2 ** 32 < int(off_np[straddle + 1]) * H * d * 2
+    print("beyond 4 GiB: inputs drawn", with_bias, flush=True)
+    if with_bias:
+        ts_np, tab_np = workloads.timestamps(w, "events", 5), workloads.bias_table(64, 5)
+        ts, tab = torch.from_numpy(ts_np).cuda(), torch.from_numpy(tab_np).cuda()
+        o = lib.hstu_jagged_attn_bias_fwd(dev["q"], dev["k"], dev["v"], off, ts, tab, 2, w.max_len, w.alpha, True)
+        dq, dk, dv, dw = lib.hstu_jagged_attn_bias_bwd(dev["q"], dev["k"], dev["v"], dev["d_o"], off, ts, tab, 2,
+                                                       w.max_len, w.alpha, True)
+        torch.cuda.synchronize()
+        assert torch.isfinite(dw).all() and (dw != 0).any()
+    else:
+        o = lib.hstu_jagged_attn_fwd(dev["q"], dev["k"], dev["v"], off, w.max_len, w.alpha, True)
+        dq, dk, dv = lib.hstu_jagged_attn_bwd(dev["q"], dev["k"], dev["v"], dev["d_o"], off, w.max_len, w.alpha, True)
+        torch.cuda.synchronize()
+    print("beyond 4 GiB: gpu done", flush=True)
+    # the sub-problem of the chosen sequences, with offsets of its own
+    rows = np.concatenate([np.arange(off_np[b], off_np[b + 1]) for b in seqs])
+    rows_t = torch.from_numpy(rows).cuda()
+    sub = {k: workloads.to_f64(v[rows_t]) for k, v in dev.items()}
+    sub_off = (np.arange(len(seqs) + 1) * L).astype(np.int32)
+    rng = np.random.default_rng(9)
+    local = sorted(set([0, 1, 63, 64, 127, 128, L - 1, L - 2, L - 65] + [int(x) for x in rng.integers(0, L, size=6)]))
+    sel = [i * L + x for i in range(len(seqs)) for x in local]
+    if with_bias:
+        want = oracle.bias_rows(sub["q"], sub["k"], sub["v"], sub["d_o"], sub_off, ts_np[rows],
+                                tab_np.astype(np.float64), 2, w.max_len, w.alpha, True, sel)
+    else:
+        want = oracle.rows(sub["q"], sub["k"], sub["v"], sub["d_o"], sub_off, w.max_len, w.alpha, True, sel)
+    print("beyond 4 GiB: oracle done", flush=True)
+    glob = torch.from_numpy(rows[sel]).cuda()
+    for name, got, ref in zip(("o", "dq", "dk", "dv"), (o, dq, dk, dv), want):
+        g = got[glob].double().cpu().numpy()
+        rms = float(np.sqrt((ref ** 2).mean()))
+        excess = np.abs(g - ref) - (2e-2 * rms + np.abs(ref) * 2.0 ** -8)
+        assert excess.max() <= 0, (name, float(np.abs(g - ref).max() / rms))
+    # every sequence has the same shape, so outputs beyond 4 GiB are as large as those before it
+    for t in (o, dq, dk, dv):
+        head, tail = t[:L * 8].float(), t[-L * 8:].float()
+        assert torch.isfinite(tail).all()
+        assert 0.8 < float(tail.pow(2).mean().sqrt() / head.pow(2).mean().sqrt()) < 1.25

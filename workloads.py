@@ -131,6 +131,24 @@ def values(w: Workload) -> Dict[str, torch.Tensor]:
     return out
 
 
+def device_values(w: Workload, device: str = "cuda", rows_per_chunk: int = 1 << 19) -> Dict[str, torch.Tensor]:
+    """q, k, v, d_o drawn on the device (seeded device generator, the same distribution as
+    values()), for workloads whose tensors are too large to draw on the host and copy: several
+    GiB each.  The values differ from values(w): a test takes what it gives the oracle from these
+    tensors."""
+    g = torch.Generator(device=device).manual_seed(w.seed)
+    T, H = w.total_rows, w.num_heads
+    out = {}
+    for name, d in (("q", w.d_qk), ("k", w.d_qk), ("v", w.d_v), ("d_o", w.d_v)):
+        x = torch.empty((T, H, d), dtype=torch_dtype(w), device=device)
+        for r0 in range(0, T, rows_per_chunk):
+            r1 = min(T, r0 + rows_per_chunk)
+            x[r0:r1] = (torch.randn((r1 - r0, H, d), generator=g, dtype=torch.float32, device=device)
+                        * w.scale).to(x.dtype)
+        out[name] = x
+    return out
+
+
 def to_f64(t: torch.Tensor) -> np.ndarray:
     """Exact widening of stored values (bf16 or fp32) to float64 for the oracle."""
     return t.detach().cpu().to(torch.float64).numpy()
