@@ -75,7 +75,7 @@ bool short_sequences(const hstu_attn_params* p) {
 // sequence, i.e. more 64-row tiles per item than per-sequence tiles do, and in this regime every
 // streamed tile costs a memory round trip.
 constexpr int PACKED_TILE = 128;
-constexpr int64_t PACKED_MEAN_LEN = 96;
+constexpr int64_t PACKED_MEAN_LEN = 256;
 bool packed_tiles(const hstu_attn_params* p) {
   if (p->dtype != HSTU_BF16 || !short_sequences(p) || getenv("HSTU_ATTN_NO_PACK")) return false;
   int64_t limit = PACKED_MEAN_LEN;
@@ -212,12 +212,23 @@ int prepare_plan(const hstu_attn_params* p, int cp_size, const SideSpec& s, cons
   int shift = 0;
   while (((longest / 32 + 4) >> shift) >= 2048) ++shift;
   // When even the heaviest possible item is a small fraction of what one workgroup slot gets
-  // to do in total (batches of many short sequences), the order cannot unbalance the tail, and
-  // the natural order keeps the items of a sequence, which share their streamed rows, together:
-  // one bin.  (Measured on 4096 sequences of 32..256 rows: forward 654 us in natural order, 716
-  // us sorted.)
-  const int64_t per_slot = s.owner_rows * p->num_heads / 32 / 512;
-  if ((longest / 32 + 4) * 8 < per_slot) shift = 30;
+  // to do in total (large batches), the order cannot unbalance the tail, and the natural order
+  // keeps the items of a sequence, which share their streamed rows, together in time: one bin.
+  // Both sides of the comparison in (owner row, streamed row) pairs: the heaviest item has at
+  // most tile x longest; all items together at least batch x mean owner rows x mean streamed
+  // rows (half of it under the causal mask), the sum of products being smallest when every
+  // sequence has the mean length.
+  // Measured, H = 4, d = 128, sorted -> natural: 1536 sequences of 300..600 rows forward 1.18 ->
+  // 0.86 ms, dQ 1.32 -> 1.07, dK/dV 1.94 -> 2.06; 768 of 600..1200 forward 1.68 -> 1.15, dQ 1.83 ->
+  // 1.53, dK/dV 2.68 -> 2.94; 512 of 1000..2000 forward 2.17 -> 2.10, dQ 2.91 -> 2.29, dK/dV 4.25
+  // -> 3.96: the passes whose owners are queries always gain, the dK/dV pass only beyond the
+  // short-sequence form, so there it stays sorted.
+  const int64_t batch = p->batch > 0 ? p->batch : 1;
+  const int64_t all_pairs = s.owner_rows / batch * (s.streamed_rows / batch) / (p->causal ? 2 : 1) * batch;
+  const int64_t per_slot = all_pairs / 512 * p->num_heads;
+  if ((int64_t)tile_rows(p, s.pass, s.owner_rows) * longest * 8 < per_slot &&
+      (s.side == 0 || !short_sequences(p)))
+    shift = 30;
   a.cost_shift = shift;
   a.split_max = split;
   a.split_blocks = SPLIT_BLOCKS;

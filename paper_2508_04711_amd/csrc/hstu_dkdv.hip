@@ -9,8 +9,11 @@ namespace {
 // dk/dv pass: owners are key rows (K and V rows in registers), Q and dO are streamed.
 //   S  = Q K^T   (A = Q tile rows,  B = K registers)   lane: key n, query rows in registers
 //   dP = dO V^T  (A = dO tile rows, B = V registers)
-//   dV += P^T dO   (A = P registers,  B = dO tile transposed read)
-//   dK += dS^T Q   (A = dS registers, B = Q tile transposed read)
+//   dV^T += dO^T P   (A = dO tile transposed read, B = P registers)   lane: key n, columns in registers
+//   dK^T += Q^T dS   (A = Q tile transposed read,  B = dS registers)
+// (The transposes of dV and dK are what is accumulated, so that a lane ends up with four
+// consecutive elements of its key row per accumulator group and the epilogue writes 8 bytes per
+// lane and instruction; with the operands the other way round it wrote single elements.)
 // Each key tile belongs to exactly one workgroup, so dk and dv need no atomics.
 // =============================================================================================
 
@@ -67,8 +70,8 @@ __device__ __forceinline__ void dkdv_step(const Init& init, const char* qn, cons
     if (m < KS) s_out = mfma(op[m], kreg[m], s_out);
     else d_out = mfma(op[m], vreg[m - KS], d_out);
     if (CONTR) {
-      if (m < VS) dvacc[m >> 1] = mfma(pd_prev[m & 1], tp[m], dvacc[m >> 1]);
-      else dkacc[(m - VS) >> 1] = mfma(pd_prev[2 + ((m - VS) & 1)], tp[m], dkacc[(m - VS) >> 1]);
+      if (m < VS) dvacc[m >> 1] = mfma(tp[m], pd_prev[m & 1], dvacc[m >> 1]);
+      else dkacc[(m - VS) >> 1] = mfma(tp[m], pd_prev[2 + ((m - VS) & 1)], dkacc[(m - VS) >> 1]);
     }
     if (m + AHEAD < NS) {
       op[m + AHEAD] = read_rows(m + AHEAD);
@@ -96,8 +99,9 @@ __device__ __forceinline__ void dkdv_step(const Init& init, const char* qn, cons
 // spilled at 64 + 64): measured 1.36x faster than one on long sequences (H = 8, d = 64, the skewed
 // 96 K-row batch: 4.32 -> 3.18 ms) and 1.67x on 4096 short ones.  At d = 128 the two accumulator
 // sets alone take 128 registers and the kernel runs one wave per SIMD with the full register file.
+// One item (owner tile) of one head.
 template <int DQK, int DV, int NW, bool BIAS, bool PACKED>
-__global__ void __launch_bounds__(NW * 64, (DQK + DV <= 128 ? 2 : 1)) hstu_dkdv_bf16(AttnArgs a) {
+__device__ __forceinline__ void dkdv_item(const AttnArgs& a, const Item& it, int h) {
   static_assert(!(PACKED && BIAS), "packed tiles: no bias");
   constexpr int QB = ST * DQK * 2, GB = ST * DV * 2;
   // Three tile buffers: an iteration of the main loop touches tiles j and j+1 while the copy of
@@ -115,10 +119,6 @@ __global__ void __launch_bounds__(NW * 64, (DQK + DV <= 128 ? 2 : 1)) hstu_dkdv_
   auto tbuf = [&](int b) { return b == 0 ? tmem0 : (b == 1 ? tmem1 : tmem2); };
 
   const int H = a.num_heads;
-  const int slot = blockIdx.x / H, h = blockIdx.x % H;
-  Item it;
-  if (!fetch_item(a.plan, slot, it)) return;
-
   const int tid = threadIdx.x, lane = tid & 63, n = lane & 31, hh = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int64_t sq = (int64_t)H * DQK, sv = (int64_t)H * DV;
@@ -129,6 +129,8 @@ __global__ void __launch_bounds__(NW * 64, (DQK + DV <= 128 ? 2 : 1)) hstu_dkdv_
 
   const int orow = wave * 32 + n;
   const bool wave_on = wave * 32 < it.nrows;
+  int2 wsq = {};
+  if constexpr (PACKED) wsq = window_bounds(a.row_seq, it.row0 + orow, orow < it.nrows);
   bf16x8 kreg[DQK / 16], vreg[DV / 16];
   load_owner<DQK>(kreg, kg, sq, orow, it.nrows, hh);
   load_owner<DV>(vreg, vg, sv, orow, it.nrows, hh);
@@ -164,11 +166,16 @@ __global__ void __launch_bounds__(NW * 64, (DQK + DV <= 128 ? 2 : 1)) hstu_dkdv_
   };
   // Position of block i of the stream (i in [0, NB)); the positions grow with i.
   auto block_pos = [&](int i) { return tile_ref(it, st, i >> 1).pos + (i & 1) * 32; };
-  Window win = {};
-  if constexpr (PACKED) win = make_window(a.row_seq, it.row0 + orow, orow < it.nrows, 1, a.causal);
+  Window win = {};  // (packed tiles: set below, once the first tile copies are on their way)
   // Does any query of block i see a key of this wave?  Once true it stays true.
-  // (Packed tiles: the few blocks of a tile's stream all run; the windows do the rest.)
-  auto block_on = [&](int i) { return wave_on && (PACKED || !a.causal || block_pos(i) + 31 >= k_lo); };
+  auto block_on = [&](int i) {
+    if constexpr (PACKED) return wave_on && block_pos(i) + 31 >= win.lo_min;
+    else return wave_on && (!a.causal || block_pos(i) + 31 >= k_lo);
+  };
+  // Packed tiles: block i is not yet beyond the last row that sees a key of the wave (i < 0: no
+  // such block).  Once false it stays false; a step is skipped when the block it would contract
+  // is beyond, and with it every later step.
+  auto not_past = [&](int i) { return !PACKED || i < 0 || block_pos(i) <= win.hi_max; };
   auto mask_of = [&](int pos) { return PACKED ? win.masks(pos) : (a.causal && pos < k_hi); };
   auto vis_of = [&](int pos) {
     if constexpr (PACKED) return win.vis(pos, hh);
@@ -177,6 +184,10 @@ __global__ void __launch_bounds__(NW * 64, (DQK + DV <= 128 ? 2 : 1)) hstu_dkdv_
 
   if (T > 0) copy_tile(0, 0);
   if (T > 1) copy_tile(1, 1);
+  if constexpr (PACKED) {
+    __builtin_amdgcn_sched_barrier(0);
+    win = make_window(wsq, it.row0 + orow, orow < it.nrows, 1, a.causal);
+  }
   tile_copy_wait<0>();
   tile_barrier();
   if (T > 0) {  // (no visible query at all: a context-parallel pair with every query before the keys)
@@ -224,7 +235,7 @@ __global__ void __launch_bounds__(NW * 64, (DQK + DV <= 128 ? 2 : 1)) hstu_dkdv_
     if (j + 2 < T) copy_tile(j + 2, B2);  // every wave left tile j-1 before the last barrier
     {
       const int i = 2 * j + 1;  // scores of (tile j+1, block 0), contraction of (tile j, block 0)
-      if (block_on(i + 1 < NB ? i + 1 : i)) {
+      if (block_on(i + 1 < NB ? i + 1 : i) && not_past(i - 1)) {
         const int pos = block_pos(i);
         dkdv_step<DQK, DV, true>(init_of(tbuf(B1), 0, bb_of(i + 1)), qbuf(B1), gbuf(B1), 0, qbuf(B0), gbuf(B0), 0, raq,
                                  rag, caq, cag, kreg, vreg, sacc[1], dacc[1], sacc[0], dacc[0], pd[0],
@@ -233,7 +244,7 @@ __global__ void __launch_bounds__(NW * 64, (DQK + DV <= 128 ? 2 : 1)) hstu_dkdv_
     }
     if (j + 1 < T) {
       const int i = 2 * j + 2;  // scores of (tile j+1, block 1), contraction of (tile j, block 1)
-      if (block_on(i + 1)) {
+      if (block_on(i + 1) && not_past(i - 1)) {
         const int pos = block_pos(i);
         dkdv_step<DQK, DV, true>(init_of(tbuf(B1), 1, bb_of(i + 1)), qbuf(B1), gbuf(B1), 1, qbuf(B0), gbuf(B0), 1, raq,
                                  rag, caq, cag, kreg, vreg, sacc[0], dacc[0], sacc[1], dacc[1], pd[1],
@@ -249,40 +260,63 @@ __global__ void __launch_bounds__(NW * 64, (DQK + DV <= 128 ? 2 : 1)) hstu_dkdv_
     if (j + 2 < T) iter(j + 2, std::integral_constant<int, 2>{});
   }
 
-  // contraction of the last block (tile T-1, block 1) on its own
-  if (block_on(NB - 1)) {
+  // contraction of the last block (tile T-1, block 1) on its own, if the step before it ran
+  if (block_on(NB - 1) && not_past(NB - 2)) {
     const int lb = (T - 1) % 3;
     const char* qt = qbuf(lb);
     const char* gt = gbuf(lb);
 #pragma unroll
     for (int c = 0; c < DV / 32; ++c) {
-      dvacc[c] = mfma(pd[1][0], cag.read(gt, 2, c), dvacc[c]);
-      dvacc[c] = mfma(pd[1][1], cag.read(gt, 3, c), dvacc[c]);
+      dvacc[c] = mfma(cag.read(gt, 2, c), pd[1][0], dvacc[c]);
+      dvacc[c] = mfma(cag.read(gt, 3, c), pd[1][1], dvacc[c]);
     }
 #pragma unroll
     for (int c = 0; c < DQK / 32; ++c) {
-      dkacc[c] = mfma(pd[1][2], caq.read(qt, 2, c), dkacc[c]);
-      dkacc[c] = mfma(pd[1][3], caq.read(qt, 3, c), dkacc[c]);
+      dkacc[c] = mfma(caq.read(qt, 2, c), pd[1][2], dkacc[c]);
+      dkacc[c] = mfma(caq.read(qt, 3, c), pd[1][3], dkacc[c]);
     }
   }
   }  // T > 0
 
-  // Accumulators: lane holds column c*32 + n of key rows 8*(r/4) + 4*hh + r%4 of its wave.
-  if (wave_on) {
-    const float scale = a.alpha * a.inv_n;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int row = wave * 32 + 8 * (r >> 2) + 4 * hh + (r & 3);
-      if (row >= it.nrows) continue;
-      const int64_t ek = ((int64_t)it.row0 + row) * sq + h * DQK + n;
-      const int64_t ev = ((int64_t)it.row0 + row) * sv + h * DV + n;
-#pragma unroll
-      for (int c = 0; c < DQK / 32; ++c)
-        store_one(a.dk, ek + c * 32, dkacc[c][r] * scale, a.accumulate, a.out_f32);
-#pragma unroll
-      for (int c = 0; c < DV / 32; ++c)
-        store_one(a.dv, ev + c * 32, dvacc[c][r] * scale, a.accumulate, a.out_f32);
+  // dK^T and dV^T accumulators: lane holds key row n, elements c*32 + 8*(r/4) + 4*hh + r%4.
+  // (P is held without its factor alpha / N, like dS.)
+  if (orow < it.nrows) {
+    store_owner_major<DQK>(a.dk, ((int64_t)it.row0 + orow) * sq + h * DQK, dkacc, a.alpha * a.inv_n, hh,
+                           a.accumulate, a.out_f32);
+    store_owner_major<DV>(a.dv, ((int64_t)it.row0 + orow) * sv + h * DV, dvacc, a.alpha * a.inv_n, hh,
+                          a.accumulate, a.out_f32);
+  }
+}
+
+// Plain tiles: one workgroup per (item, head); the hardware hands out workgroups in index order,
+// which is what balances items of very different cost.  Packed tiles (items of about equal cost,
+// each a few memory round trips long): a workgroup walks over every gridDim.x-th (item, head) and
+// fetches the next item's description while it works on the current one, so that the stores of
+// one item overlap the loads of the next and neither a workgroup launch nor the description's
+// round trip lies between them; with one workgroup per CU nothing else would overlap them.
+template <int DQK, int DV, int NW, bool BIAS, bool PACKED>
+__global__ void __launch_bounds__(NW * 64, (DQK + DV <= 128 ? 2 : 1)) hstu_dkdv_bf16(AttnArgs a) {
+  const int H = a.num_heads;
+  Item it;
+  if constexpr (PACKED) {
+    // (the items of packed tiles are in their natural order: no indirection through the schedule)
+    const int units = a.plan.header[0] * H;
+    int u = blockIdx.x;
+    if (u >= units) return;
+    RawItem raw = load_raw_item(a.plan.items + u / H);
+    while (true) {
+      const bool on = decode_item(raw, it);
+      const int h = u % H;
+      u += gridDim.x;
+      const bool more = u < units;
+      if (more) raw = load_raw_item(a.plan.items + u / H);  // in flight while this item is worked on
+      if (on) dkdv_item<DQK, DV, NW, BIAS, PACKED>(a, it, h);
+      if (!more) break;
+      tile_barrier();  // every wave has left the item's tiles before the next item's copies land
     }
+  } else {
+    if (!fetch_item(a.plan, blockIdx.x / H, it)) return;
+    dkdv_item<DQK, DV, NW, BIAS, PACKED>(a, it, blockIdx.x % H);
   }
 }
 
@@ -290,7 +324,12 @@ __global__ void __launch_bounds__(NW * 64, (DQK + DV <= 128 ? 2 : 1)) hstu_dkdv_
 
 hipError_t launch_dkdv_bf16(const AttnArgs& a, int d_qk, int d_v, hipStream_t stream) {
   if (a.waves != 4 || (a.row_seq && a.ts_rec)) return hipErrorInvalidValue;
-  if (a.row_seq) HSTU_DISPATCH_D(hstu_dkdv_bf16, 4, 4, false, true);
+  if (a.row_seq) {
+    // One workgroup per CU is resident at the larger head dimensions: as many workgroups as CUs,
+    // each walking over its share of the items.  Two per CU overlap each other's memory round
+    // trips already, and the hardware's own dispatch serves them better (measured).
+    HSTU_DISPATCH_G(d_qk + d_v > 128 ? 256 : 0, hstu_dkdv_bf16, 4, 4, false, true);
+  }
   if (a.ts_rec) HSTU_DISPATCH_BIAS(hstu_dkdv_bf16, 4, 4, true, false);
   HSTU_DISPATCH_D(hstu_dkdv_bf16, 4, 4, false, false);
 }

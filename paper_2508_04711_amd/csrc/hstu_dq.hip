@@ -117,7 +117,7 @@ __global__ void __launch_bounds__(NW * 64, 2) hstu_dq_bf16(AttnArgs a) {
   const int H = a.num_heads;
   const int slot = blockIdx.x / H, h = blockIdx.x % H;
   Item it;
-  if (!fetch_item(a.plan, slot, it)) return;
+  if (!fetch_item<PACKED>(a.plan, slot, it)) return;
 
   const int tid = threadIdx.x, lane = tid & 63, n = lane & 31, hh = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -129,6 +129,8 @@ __global__ void __launch_bounds__(NW * 64, 2) hstu_dq_bf16(AttnArgs a) {
 
   const int orow = wave * 32 + n;
   const bool wave_on = wave * 32 < it.nrows;
+  int2 wsq = {};
+  if constexpr (PACKED) wsq = window_bounds(a.row_seq, it.row0 + orow, orow < it.nrows);
   bf16x8 qreg[DQK / 16], greg[DV / 16];
   load_owner<DQK>(qreg, qg, sq, orow, it.nrows, hh);
   load_owner<DV>(greg, gg, sv, orow, it.nrows, hh);
@@ -152,14 +154,17 @@ __global__ void __launch_bounds__(NW * 64, 2) hstu_dq_bf16(AttnArgs a) {
 
   RowAddr<DQK> rak; RowAddr<DV> rav; ColAddr<DQK> cak;
   rak.init(n, hh); rav.init(n, hh); cak.init(lane);
-  Window win = {};
-  if constexpr (PACKED) win = make_window(a.row_seq, it.row0 + orow, orow < it.nrows, 0, a.causal);
 
   if (st.total > 0) {
     const TileRef t0 = tile_ref(it, st, 0);
     tile_copy_async<DQK, NW>(kbuf(0), kg + (int64_t)t0.row * sq, sq, t0.valid, wave, lane);
     tile_copy_async<DV, NW>(vbuf(0), vg + (int64_t)t0.row * sv, sv, t0.valid, wave, lane);
     if (BIAS && wave == 0) rec_copy_async(tbuf(0), a.ts_rec + t0.row, t0.valid, lane);
+  }
+  Window win = {};
+  if constexpr (PACKED) {  // (looked at only now that the first tile copies are on their way)
+    __builtin_amdgcn_sched_barrier(0);
+    win = make_window(wsq, it.row0 + orow, orow < it.nrows, 0, a.causal);
   }
   tile_copy_wait<0>();
   tile_barrier();
@@ -187,8 +192,9 @@ __global__ void __launch_bounds__(NW * 64, 2) hstu_dq_bf16(AttnArgs a) {
 #pragma unroll
       for (int blk = 0; blk < ST / 32; ++blk) {
         const int k_lo = tj.pos + blk * 32;
-        // no key of the block is visible (packed tiles: the windows decide)
+        // no key of the block is visible (packed tiles: to no row of the wave)
         if (blk * 32 >= tj.valid || (!PACKED && a.causal && k_lo > q_hi)) continue;
+        if (PACKED && (k_lo > win.hi_max || k_lo + 31 < win.lo_min)) continue;
         const BlockBias bb = BIAS ? tab.get(2 * j + blk) : BlockBias{};
         if constexpr (PACKED)
           dq_block<DQK, DV, BIAS>(bias, tbuf(BUF), bb, dwa, kt, vt, blk, rak, rav, cak, qreg, greg, dqacc, c1,

@@ -100,7 +100,7 @@ __global__ void __launch_bounds__(NW * 64, 2) hstu_fwd_bf16(AttnArgs a) {
   const int H = a.num_heads;
   const int slot = blockIdx.x / H, h = blockIdx.x % H;
   Item it;
-  if (!fetch_item(a.plan, slot, it)) return;
+  if (!fetch_item<PACKED>(a.plan, slot, it)) return;
 
   const int tid = threadIdx.x, lane = tid & 63, n = lane & 31, hh = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -113,6 +113,8 @@ __global__ void __launch_bounds__(NW * 64, 2) hstu_fwd_bf16(AttnArgs a) {
 
   const int orow = wave * 32 + n;  // this lane's owner row inside the tile
   const bool wave_on = wave * 32 < it.nrows;
+  int2 wsq = {};
+  if constexpr (PACKED) wsq = window_bounds(a.row_seq, it.row0 + orow, orow < it.nrows);
   bf16x8 qreg[DQK / 16];
   load_owner<DQK>(qreg, qg, sq, orow, it.nrows, hh);
   BiasCtx bias = {};
@@ -145,13 +147,17 @@ __global__ void __launch_bounds__(NW * 64, 2) hstu_fwd_bf16(AttnArgs a) {
   };
   // Position of block i (i in [0, NB)); positions grow with i.
   auto block_pos = [&](int i) { return tile_ref(it, st, i >> 1).pos + (i & 1) * 32; };
-  Window win = {};
-  if constexpr (PACKED) win = make_window(a.row_seq, it.row0 + orow, orow < it.nrows, 0, a.causal);
+  Window win = {};  // (packed tiles: set below, once the first tile copies are on their way)
   // Does any key of block i precede (or equal) a query of this wave?  Once false it stays false.
-  // (Packed tiles: the few blocks of a tile's stream all run; the windows do the rest.)
+  // (Packed tiles: no block lies beyond the last row that some row of the wave sees.)
   auto block_on = [&](int i) {
-    return wave_on && i < NB && (PACKED || !a.causal || block_pos(i) <= q_hi);
+    if constexpr (PACKED) return wave_on && i < NB && block_pos(i) <= win.hi_max;
+    else return wave_on && i < NB && (!a.causal || block_pos(i) <= q_hi);
   };
+  // Packed tiles: has the stream reached the first row that some row of the wave sees by block i?
+  // Once true it stays true.  A step skipped before that leaves its accumulators at their initial
+  // zeros, from which the first step that runs derives P = 0 for the block before its own.
+  auto started = [&](int i) { return !PACKED || block_pos(i < NB ? i : NB - 1) + 31 >= win.lo_min; };
 
   RowAddr<DQK> ra;
   ra.init(n, hh);
@@ -166,6 +172,10 @@ __global__ void __launch_bounds__(NW * 64, 2) hstu_fwd_bf16(AttnArgs a) {
   if (T > 1) copy_k(1, 1);
   if (PD > 1 && T > 1) copy_v(1, 1);
   if (PD > 1 && T > 2) copy_k(2, 2);
+  if constexpr (PACKED) {
+    __builtin_amdgcn_sched_barrier(0);
+    win = make_window(wsq, it.row0 + orow, orow < it.nrows, 0, a.causal);
+  }
   tile_copy_wait<0>();
   tile_barrier();
 
@@ -196,7 +206,7 @@ __global__ void __launch_bounds__(NW * 64, 2) hstu_fwd_bf16(AttnArgs a) {
     auto bb_of = [&](int i) { return BIAS ? tab.get(i) : BlockBias{}; };
 
     // S of block 0 on its own, then step 0 (nothing to multiply by V yet)
-    if (block_on(0)) {
+    if (block_on(0) && started(1)) {
       init_of(tbuf(0), 0, bb_of(0))(sacc[0]);
 #pragma unroll
       for (int ks = 0; ks < DQK / 16; ++ks) sacc[0] = mfma(ra.read(kbuf(0), 0, ks), qreg[ks], sacc[0]);
@@ -217,13 +227,13 @@ __global__ void __launch_bounds__(NW * 64, 2) hstu_fwd_bf16(AttnArgs a) {
       if (j + PD < T) copy_v(j + PD, (B0 + PD) % NBUF);
       {
         const int i = 2 * j + 1;  // S of (tile j+1, block 0), P V of (tile j, block 0)
-        if (block_on(i - 1))
+        if (block_on(i - 1) && started(i + 1))
           fwd_step<DQK, DV, true>(init_of(tbuf(B1), 0, bb_of(i + 1)), kbuf(B1), 0, vbuf(B0), 0, ra, ca, qreg, sacc[1],
                                   sacc[0], pb[0], pb[1], oacc, c1, mask_of(i), vis_of(i));
       }
       if (j + 1 < T) {
         const int i = 2 * j + 2;  // S of (tile j+1, block 1), P V of (tile j, block 1)
-        if (block_on(i - 1))
+        if (block_on(i - 1) && started(i + 1))
           fwd_step<DQK, DV, true>(init_of(tbuf(B1), 1, bb_of(i + 1)), kbuf(B1), 1, vbuf(B0), 1, ra, ca, qreg, sacc[0],
                                   sacc[1], pb[1], pb[0], oacc, c1, mask_of(i), vis_of(i));
       }

@@ -342,9 +342,34 @@ __device__ __forceinline__ void store_one(void* out, int64_t elem, float x, int 
   }
 }
 
+// An item as it lies in memory, loaded by every lane alike (what a workgroup that walks over items
+// fetches ahead of time) ...
+struct RawItem { u32x4 w[4]; };
+__device__ __forceinline__ RawItem load_raw_item(const Item* src) {
+  RawItem r;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) r.w[i] = ((const u32x4*)src)[i];
+  return r;
+}
+// ... and brought into scalar registers when its turn comes.  False: no owner rows.
+__device__ __forceinline__ bool decode_item(const RawItem& r, Item& it) {
+  auto word = [&](int i) { return (int)__builtin_amdgcn_readfirstlane(r.w[i >> 2][i & 3]); };
+  it.row0 = word(0); it.nrows = word(1); it.pos0 = word(2); it.nseg = word(3);
+#pragma unroll
+  for (int g = 0; g < 2; ++g) {
+    it.seg_row0[g] = word(4 + g); it.seg_len[g] = word(6 + g);
+    it.seg_pos0[g] = word(8 + g); it.seg_tcol0[g] = word(10 + g);
+  }
+  it.cost = 0;
+  it.part = word(13);
+  return it.nrows > 0;
+}
+
+// DIRECT: the items are in schedule order already (packed tiles), no indirection.
+template <bool DIRECT = false>
 __device__ __forceinline__ bool fetch_item(const Plan& plan, int slot, Item& it) {
   if (slot >= plan.header[0]) return false;
-  const Item* src = plan.items + plan.order[slot];
+  const Item* src = plan.items + (DIRECT ? slot : plan.order[slot]);
   // The item is the same for every lane: keep it in scalar registers so that everything derived
   // from it (addresses, buffer resources, loop bounds) is uniform.
   it.row0 = __builtin_amdgcn_readfirstlane(src->row0);
@@ -402,13 +427,18 @@ __device__ __forceinline__ int wave_max(int x);
 
 // side 0: owners are queries, 1: owners are keys.  row_seq[row] = {first row, end row} of the
 // row's sequence.  Lanes without a valid owner row get an empty window.
-__device__ __forceinline__ Window make_window(const int2* row_seq, int row, bool valid, int side, int causal) {
+// The bounds are loaded on their own (window_bounds) so that a kernel can request them first of
+// all and look at them only after it has issued its first tile copies: one memory round trip for
+// both instead of two in a row.
+__device__ __forceinline__ int2 window_bounds(const int2* row_seq, int row, bool valid) {
+  return valid ? row_seq[row] : make_int2(0, 0);
+}
+__device__ __forceinline__ Window make_window(const int2& sq, int row, bool valid, int side, int causal) {
   Window w;
   int hi = -1;
   w.lo = 0x3fffffff;
   w.span = 0;
   if (valid) {
-    const int2 sq = row_seq[row];
     w.lo = (causal && side == 1) ? row : sq.x;
     hi = (causal && side == 0) ? row : sq.y - 1;
     w.span = (uint32_t)(hi - w.lo);
@@ -613,9 +643,12 @@ __device__ __forceinline__ void bwd_elem(float s, float dp, float c1, float alph
   ds = dp * (sg + alpha * p * (1.0f - sg));
 }
 
-#define HSTU_DISPATCH_D(KERNEL, NW, ...)                                                \
+// CAP > 0: at most that many workgroups (for kernels that walk over the (item, head) pairs).
+#define HSTU_DISPATCH_D(KERNEL, NW, ...) HSTU_DISPATCH_G(0, KERNEL, NW, __VA_ARGS__)
+#define HSTU_DISPATCH_G(CAP, KERNEL, NW, ...)                                           \
   do {                                                                                  \
-    const dim3 grid((unsigned)((int64_t)a.max_items * a.num_heads)), block(NW * 64);    \
+    const int64_t units_ = (int64_t)a.max_items * a.num_heads, cap_ = (CAP);            \
+    const dim3 grid((unsigned)(cap_ > 0 && units_ > cap_ ? cap_ : units_)), block(NW * 64); \
     if (d_qk == 128 && d_v == 128) hipLaunchKernelGGL((KERNEL<128, 128, __VA_ARGS__>), grid, block, 0, stream, a); \
     else if (d_qk == 64 && d_v == 64) hipLaunchKernelGGL((KERNEL<64, 64, __VA_ARGS__>), grid, block, 0, stream, a); \
     else if (d_qk == 32 && d_v == 32) hipLaunchKernelGGL((KERNEL<32, 32, __VA_ARGS__>), grid, block, 0, stream, a); \

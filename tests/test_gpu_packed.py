@@ -1,4 +1,4 @@
-"""Packed tiles: batches of very short sequences (bf16; by default a mean length of at most 96,
+"""Packed tiles: batches of very short sequences (bf16; by default a mean length of at most 256,
 here forced for every case with HSTU_ATTN_PACK_LEN) are tiled 128 rows at a time across sequence
 boundaries, each row seeing the window of its own sequence.  Against the oracle, through the C
 ABI, on the shapes that stress the windows: many sequences per tile, sequences spanning tiles,

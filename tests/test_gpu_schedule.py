@@ -82,13 +82,16 @@ def test_full_attention_schedule(lengths, causal, side):
     T = sum(lengths)
     off = torch.tensor(np.concatenate([[0], np.cumsum(lengths)]), dtype=torch.int32, device="cuda")
     tile = lib.hstu_schedule_tile_rows(0, 128, 128, side, T, 2, len(lengths))
-    got = lib.hstu_debug_dump_schedule(off, T, 2, 128, 128, causal, 0, side)
+    got = lib.hstu_debug_dump_schedule(off, T, 2, 128, 128, causal, 0, side, max_len=max(lengths + [1]))
     want = _expected_items(lengths, tile, causal, side)
     assert sorted(map(tuple, got.tolist())) == sorted(want)
-    costs = got[:, 10]
-    # heavy tiles first, unless even the heaviest tile is small against what one of the 512
-    # workgroup slots gets in total: then the library keeps the natural order, and any order is fine
-    if costs.max() * 8 * 512 > costs.sum() * 2:
+    costs = got[:, 10].astype(np.int64)
+    # Heavy tiles first, unless even the heaviest tile is small against what one of the 512
+    # workgroup slots gets in total: then the library may keep the natural order.  It decides from
+    # bounds (max_len for the heaviest tile, the mean length for the total), which this condition,
+    # from the actual costs, implies: a cost of c means more than 32 (c - 1) streamed rows, and a
+    # tile's pairs are at most 32 x tile x cost.
+    if (costs.max() - 1) * 8 * 512 > costs.sum() * 2:
         assert np.all(costs[:-1] >= costs[1:]), "heavy tiles first"
     covered = np.zeros(T, dtype=np.int64)
     for it in got:
