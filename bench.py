@@ -7,7 +7,7 @@ context-parallel workload every rank's reorder into its local layout, its partia
 reorder back, ranks one after the other on the one GPU).
 Inputs are resident in HBM before the timed region starts.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg5|cfg3|cfg2|cfg4|cfg4_ring|cfg5_bias]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg5|cfg3|cfg2|cfg4|cfg4_ring|cfg5_bias|short|mid]
 """
 from __future__ import annotations
 
@@ -69,7 +69,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="cfg5", choices=["cfg2", "cfg3", "cfg4", "cfg4_ring", "cfg5", "cfg5_bias"])
+    ap.add_argument("--workload", default="cfg5", choices=["cfg2", "cfg3", "cfg4", "cfg4_ring", "cfg5", "cfg5_bias", "short", "mid"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-prefix-rows", type=int, default=0, help="rows per sequence in the CPU sample")
     args = ap.parse_args()
@@ -86,8 +86,12 @@ def main() -> int:
 
     ring = args.workload.endswith("_ring")
     with_bias = args.workload.endswith("_bias")  # the same batch with the timestamp bias
-    cfg = int(args.workload[3:4])
-    w = workloads.config(cfg)
+    if args.workload in ("short", "mid"):  # large batches of short sequences
+        cfg = 0
+        w = workloads.large_batch(args.workload)
+    else:
+        cfg = int(args.workload[3:4])
+        w = workloads.config(cfg)
     dev = torch.device("cuda:0")
     vals = {k: v.to(dev) for k, v in workloads.values(w).items()}
     off_np = w.seq_offsets()
@@ -247,12 +251,19 @@ def main() -> int:
         # two tensors of H*d bf16 rows per launch, read once and written once
         moved = 2.0 * (T / w.cp_size) * H * (w.d_qk + w.d_v) * 2
         roofline["kernels"]["reorder"]["algorithmic_gbs"] = moved / (avg_ms["reorder"] * 1e-3) / 1e9
-    if cfg == 2:
-        # below the ridge: report the forward against HBM bandwidth over algorithmic bytes
-        bytes_alg = 2.0 * T * H * (2 * w.d_qk + 2 * w.d_v)
-        gbs = bytes_alg / (avg_ms["fwd"] * 1e-3) / 1e9
+    # Algorithmic bytes per launch: every input row read once, every output row written once.
+    row = 2.0 * T * H
+    bytes_alg = {"fwd": row * (2 * w.d_qk + 2 * w.d_v), "dkdv": row * (3 * w.d_qk + 3 * w.d_v),
+                 "dq": row * (3 * w.d_qk + 2 * w.d_v)}
+    if not w.cp_size and alg[dom] / bytes_alg[dom] < PEAK_BF16_TFLOPS * 1e3 / PEAK_HBM_GBS:
+        # below the ridge (flops per byte under peak flops / peak bandwidth): the dominant kernel
+        # is reported against HBM bandwidth over its algorithmic bytes
+        gbs = bytes_alg[dom] / (dom_ms * 1e-3) / 1e9
         roofline.update({"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                          "frac": gbs / PEAK_HBM_GBS})
+        for k in roofline["kernels"]:
+            if k in bytes_alg:
+                roofline["kernels"][k]["algorithmic_gbs"] = bytes_alg[k] / (avg_ms[k] * 1e-3) / 1e9
 
     out = {
         "metric": "jagged HSTU attn fwd+bwd TFLOP/s (causal-visible, bf16)" if w.backward
@@ -268,7 +279,7 @@ def main() -> int:
         "roofline": roofline,
     }
     if not args.no_cpu_baseline:
-        prefix = args.cpu_prefix_rows or {2: 1024, 3: 4096, 4: 4096, 5: 4096}[cfg]
+        prefix = args.cpu_prefix_rows or {0: 300, 2: 1024, 3: 4096, 4: 4096, 5: 4096}[cfg]
         out["cpu_baseline"] = _cpu_baseline(w, prefix)
     print(json.dumps(out))
     return 0

@@ -17,6 +17,14 @@ def test_config_lengths_and_totals():
     assert workloads.config(5).pairs_per_head == 698506850
 
 
+def test_large_batches_are_pinned():
+    short, mid = workloads.large_batch("short"), workloads.large_batch("mid")
+    assert (short.batch, short.total_rows, short.pairs_per_head) == (8192, 328154, 7548970)
+    assert (mid.batch, mid.total_rows, mid.pairs_per_head) == (1536, 693773, 162709638)
+    assert min(short.lengths) == 16 and max(short.lengths) == 64 == short.max_len
+    assert min(mid.lengths) >= 300 and max(mid.lengths) <= 600 == mid.max_len
+
+
 def test_flop_counts():
     w = workloads.config(3)
     f = w.flops()

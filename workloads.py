@@ -109,6 +109,20 @@ def config(cfg: int) -> Workload:
     return Workload("cfg5_skewed_B8_lognormal", lengths, 8, 128, 128, 32768, "bf16", 0.5, 6, True)
 
 
+def large_batch(kind: str) -> Workload:
+    """Large batches of short sequences (the regime the paper's section 3 contrasts with long
+    sequences), H = 4, d = 128, bf16, forward and backward:
+    "short": 8192 sequences of 16..64 rows; "mid": 1536 sequences of 300..600 rows."""
+    rng = np.random.default_rng(7)
+    if kind == "short":
+        lengths = rng.integers(16, 64, endpoint=True, size=8192)
+        return Workload("short_B8192_L16-64", tuple(int(x) for x in lengths), 4, 128, 128, 64, "bf16", 0.5, 7, True)
+    if kind == "mid":
+        lengths = rng.integers(300, 600, endpoint=True, size=1536)
+        return Workload("mid_B1536_L300-600", tuple(int(x) for x in lengths), 4, 128, 128, 600, "bf16", 0.5, 8, True)
+    raise ValueError("unknown large batch %r" % (kind,))
+
+
 def custom(name: str, lengths, num_heads: int, d_qk: int, d_v: int, max_len: int,
            dtype: str = "bf16", scale: float = 0.5, seed: int = 0, backward: bool = True,
            cp_size: int = 0) -> Workload:
