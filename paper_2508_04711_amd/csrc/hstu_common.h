@@ -198,6 +198,9 @@ struct AttnArgs {
   // Packed tiles (bf16 kernels, whole-batch layout, batches of short sequences; null: not packed):
   // per row the first row and the end row of its sequence, built by launch_packed_plan.
   const int2* row_seq;
+  // Large batch (many items, none of them a large share of the whole): kernels that run one
+  // workgroup per CU may launch as many workgroups as CUs and let each walk over its share.
+  int32_t large_batch;
 };
 
 // Owner rows per item each kernel family expects (pass: 0 forward, 1 dk/dv, 2 dq); the

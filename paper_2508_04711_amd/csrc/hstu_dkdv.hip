@@ -288,35 +288,42 @@ __device__ __forceinline__ void dkdv_item(const AttnArgs& a, const Item& it, int
   }
 }
 
-// Plain tiles: one workgroup per (item, head); the hardware hands out workgroups in index order,
-// which is what balances items of very different cost.  Packed tiles (items of about equal cost,
-// each a few memory round trips long): a workgroup walks over every gridDim.x-th (item, head) and
-// fetches the next item's description while it works on the current one, so that the stores of
-// one item overlap the loads of the next and neither a workgroup launch nor the description's
-// round trip lies between them; with one workgroup per CU nothing else would overlap them.
+// One workgroup per (item, head), handed out by the hardware in index order, which is what
+// balances items of very different cost - unless the grid is smaller than the number of (item,
+// head) pairs: then a workgroup walks over every gridDim.x-th pair and fetches the descriptions of
+// the next ones while it works on the current one, so that the stores of one item overlap the
+// loads of the next and neither a workgroup launch nor the description's round trips lie between
+// them.  With one workgroup per CU nothing else would overlap them; the host asks for it where
+// items are many and of about equal cost (packed tiles, large batches).
 template <int DQK, int DV, int NW, bool BIAS, bool PACKED>
 __global__ void __launch_bounds__(NW * 64, (DQK + DV <= 128 ? 2 : 1)) hstu_dkdv_bf16(AttnArgs a) {
   const int H = a.num_heads;
   Item it;
-  if constexpr (PACKED) {
-    // (the items of packed tiles are in their natural order: no indirection through the schedule)
-    const int units = a.plan.header[0] * H;
-    int u = blockIdx.x;
-    if (u >= units) return;
-    RawItem raw = load_raw_item(a.plan.items + u / H);
-    while (true) {
-      const bool on = decode_item(raw, it);
-      const int h = u % H;
-      u += gridDim.x;
-      const bool more = u < units;
-      if (more) raw = load_raw_item(a.plan.items + u / H);  // in flight while this item is worked on
-      if (on) dkdv_item<DQK, DV, NW, BIAS, PACKED>(a, it, h);
-      if (!more) break;
-      tile_barrier();  // every wave has left the item's tiles before the next item's copies land
-    }
-  } else {
+  if (!PACKED && gridDim.x >= (unsigned)(a.max_items * H)) {
     if (!fetch_item(a.plan, blockIdx.x / H, it)) return;
     dkdv_item<DQK, DV, NW, BIAS, PACKED>(a, it, blockIdx.x % H);
+    return;
+  }
+  // (the items of packed tiles are in schedule order already: no indirection)
+  auto index_of = [&](int unit) { return PACKED ? unit / H : a.plan.order[unit / H]; };
+  const int units = a.plan.header[0] * H;
+  const int stride = (int)gridDim.x;
+  int u = blockIdx.x;
+  if (u >= units) return;
+  RawItem raw = load_raw_item(a.plan.items + index_of(u));
+  int next = (int64_t)u + stride < units ? index_of(u + stride) : 0;
+  while (true) {
+    const bool on = decode_item(raw, it);
+    const int h = u % H;
+    const bool more = (int64_t)u + stride < units;
+    u += more ? stride : 0;
+    if (more) {  // in flight while this item is worked on
+      raw = load_raw_item(a.plan.items + next);
+      next = (int64_t)u + stride < units ? index_of(u + stride) : 0;
+    }
+    if (on) dkdv_item<DQK, DV, NW, BIAS, PACKED>(a, it, h);
+    if (!more) break;
+    tile_barrier();  // every wave has left the item's tiles before the next item's copies land
   }
 }
 
@@ -324,14 +331,16 @@ __global__ void __launch_bounds__(NW * 64, (DQK + DV <= 128 ? 2 : 1)) hstu_dkdv_
 
 hipError_t launch_dkdv_bf16(const AttnArgs& a, int d_qk, int d_v, hipStream_t stream) {
   if (a.waves != 4 || (a.row_seq && a.ts_rec)) return hipErrorInvalidValue;
-  if (a.row_seq) {
-    // One workgroup per CU is resident at the larger head dimensions: as many workgroups as CUs,
-    // each walking over its share of the items.  Two per CU overlap each other's memory round
-    // trips already, and the hardware's own dispatch serves them better (measured).
-    HSTU_DISPATCH_G(d_qk + d_v > 128 ? 256 : 0, hstu_dkdv_bf16, 4, 4, false, true);
+  // One workgroup per CU is resident at the larger head dimensions: as many workgroups as CUs,
+  // each walking over its share of the items.  Two per CU overlap each other's memory round
+  // trips already, and the hardware's own dispatch serves them better (measured).
+  const int64_t cap = a.large_batch && d_qk + d_v > 128 ? 256 : 0;
+  if (a.row_seq) HSTU_DISPATCH_G(d_qk + d_v > 128 ? 256 : 0, hstu_dkdv_bf16, 4, 4, false, true);
+  if (a.ts_rec) {
+    if (a.nb < 1 || a.nb > MAX_TS_BUCKETS || !a.ts_w || !a.ts_rec_own) return hipErrorInvalidValue;
+    HSTU_DISPATCH_G(cap, hstu_dkdv_bf16, 4, 4, true, false);
   }
-  if (a.ts_rec) HSTU_DISPATCH_BIAS(hstu_dkdv_bf16, 4, 4, true, false);
-  HSTU_DISPATCH_D(hstu_dkdv_bf16, 4, 4, false, false);
+  HSTU_DISPATCH_G(cap, hstu_dkdv_bf16, 4, 4, false, false);
 }
 
 }  // namespace hstu

@@ -193,3 +193,53 @@ def test_tensors_beyond_four_gib(with_bias):
         head, tail = t[:L * 8].float(), t[-L * 8:].float()
         assert torch.isfinite(tail).all()
         assert 0.8 < float(tail.pow(2).mean().sqrt() / head.pow(2).mean().sqrt()) < 1.25
+
+
+@pytest.mark.parametrize("mode", ["plain", "bias", "packed"])
+def test_large_batch_of_short_sequences(mode, monkeypatch):
+    """4096 sequences of 32..256 rows, H = 4, d = 128: a batch large enough for the natural item
+    order and for the dK/dV workgroups that walk over items (per-sequence tiles with and without
+    the bias, packed tiles).  Sampled rows of a few sequences against the oracle on those
+    sequences alone (rows of different sequences do not interact)."""
+    import paper_2508_04711_amd as lib
+    if mode == "packed":
+        monkeypatch.setenv("HSTU_ATTN_PACK_LEN", "1024")
+    else:
+        monkeypatch.setenv("HSTU_ATTN_NO_PACK", "1")
+    rng = np.random.default_rng(17)
+    lengths = [int(x) for x in rng.integers(32, 257, size=4096)]
+    w = workloads.custom("large_batch", lengths, 4, 128, 128, 256, dtype="bf16", seed=41)
+    vals = workloads.values(w)
+    dev = _dev(vals)
+    off_np = w.seq_offsets()
+    off = torch.from_numpy(off_np).cuda()
+    print("large batch", mode, w.total_rows, flush=True)
+    if mode == "bias":
+        ts_np, tab_np = workloads.timestamps(w, "events", 6), workloads.bias_table(48, 6)
+        ts, tab = torch.from_numpy(ts_np).cuda(), torch.from_numpy(tab_np).cuda()
+        o = lib.hstu_jagged_attn_bias_fwd(dev["q"], dev["k"], dev["v"], off, ts, tab, 1, w.max_len, w.alpha, True)
+        dq, dk, dv, dw = lib.hstu_jagged_attn_bias_bwd(dev["q"], dev["k"], dev["v"], dev["d_o"], off, ts, tab, 1,
+                                                       w.max_len, w.alpha, True)
+        assert torch.isfinite(dw).all() and (dw != 0).any()
+    else:
+        o = lib.hstu_jagged_attn_fwd(dev["q"], dev["k"], dev["v"], off, w.max_len, w.alpha, True)
+        dq, dk, dv = lib.hstu_jagged_attn_bwd(dev["q"], dev["k"], dev["v"], dev["d_o"], off, w.max_len, w.alpha, True)
+    torch.cuda.synchronize()
+    seqs = [0, 1, 255, 256, 2047, 3000, 4094, 4095]
+    rows = np.concatenate([np.arange(off_np[b], off_np[b + 1]) for b in seqs])
+    sub = {k: workloads.to_f64(v[torch.from_numpy(rows)]) for k, v in vals.items()}
+    sub_off = np.concatenate([[0], np.cumsum([lengths[b] for b in seqs])]).astype(np.int32)
+    sel = np.arange(len(rows))
+    if mode == "bias":
+        want = oracle.bias_rows(sub["q"], sub["k"], sub["v"], sub["d_o"], sub_off, ts_np[rows],
+                                tab_np.astype(np.float64), 1, w.max_len, w.alpha, True, sel)
+    else:
+        want = oracle.rows(sub["q"], sub["k"], sub["v"], sub["d_o"], sub_off, w.max_len, w.alpha, True, sel)
+    glob = torch.from_numpy(rows).cuda()
+    for name, got, ref in zip(("o", "dq", "dk", "dv"), (o, dq, dk, dv), want):
+        g = got[glob].double().cpu().numpy()
+        rms = float(np.sqrt((ref ** 2).mean()))
+        excess = np.abs(g - ref) - (2e-2 * rms + np.abs(ref) * 2.0 ** -7)
+        assert excess.max() <= 0, (mode, name, float(np.abs(g - ref).max() / rms))
+    for t in (o, dq, dk, dv):
+        assert torch.isfinite(t.float()).all()
