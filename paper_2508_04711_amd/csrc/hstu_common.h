@@ -121,9 +121,18 @@ __device__ __forceinline__ int bias_bucket(uint32_t delta, int nb, int f) {
   b = b < nb - 1 ? b : nb - 1;
   return delta <= 1u ? 0 : b;
 }
+// The same bucket for delta < 2^24, where the conversion to float is exact: the float's exponent
+// and its top f mantissa bits are e and m.  (127 + e) * 2^f + m comes out of one shift of the bit
+// pattern; delta = 0 and 1 land at or below zero and are clamped to bucket 0 like the rest.
+constexpr uint32_t BIAS_SMALL_DELTA = 1u << 24;
+__device__ __forceinline__ int bias_bucket_small(uint32_t delta, int nb, int f) {
+  const int b = (int)(__builtin_bit_cast(uint32_t, (float)delta) >> (23 - f)) - (127 << f);
+  const int lo = b > 0 ? b : 0;
+  return lo < nb - 1 ? lo : nb - 1;
+}
 // |a - b| of two int32 values, exact up to 2^32 - 1.
 __device__ __forceinline__ uint32_t abs_diff(int a, int b) {
-  return a > b ? (uint32_t)a - (uint32_t)b : (uint32_t)b - (uint32_t)a;
+  return (uint32_t)(a > b ? a : b) - (uint32_t)(a > b ? b : a);
 }
 
 // The gradient of the bias table is a sum of dS over all visible pairs of a bucket.  A workgroup

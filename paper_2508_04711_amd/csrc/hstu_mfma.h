@@ -511,15 +511,16 @@ struct BiasCtx {
 struct BlockBias {
   int b0;
   bool uni;
+  bool small;      // every difference of the block is below BIAS_SMALL_DELTA
   uint32_t wpair;  // the table entry as two bf16 halves, high part in the low 16 bits (see bias_block)
 };
 
 // BlockBias of the stream's blocks, one block per lane: blocks [128k, 128k + 64) in set 0,
 // [128k + 64, 128k + 128) in set 1; a set is refilled when the stream enters the other one.
 struct BlockTable {
-  int code0, code1;  // bucket | NONUNIFORM
+  int code0, code1;  // bucket | NONUNIFORM | SMALL
   float w0, w1;
-  static constexpr int NONUNIFORM = 1 << 30;
+  static constexpr int NONUNIFORM = 1 << 30, SMALL = 1 << 29;
 
   // Fills the set of blocks [first, first + 64), first a multiple of 64; blocks >= nblocks (past
   // the end of the stream: their scores are computed and discarded) get a zero bias.
@@ -542,7 +543,7 @@ struct BlockTable {
       const uint32_t dmin = c.o_lo > s_hi ? (uint32_t)c.o_lo - (uint32_t)s_hi
                                           : (s_lo > c.o_hi ? (uint32_t)s_lo - (uint32_t)c.o_hi : 0u);
       const int b0 = bias_bucket(dmin, c.nb, c.f), b1 = bias_bucket(dmax, c.nb, c.f);
-      code = b0 | (b0 != b1 ? NONUNIFORM : 0);
+      code = b0 | (b0 != b1 ? NONUNIFORM : 0) | (dmax < BIAS_SMALL_DELTA ? SMALL : 0);
       // the entry as hi + lo, both bf16: exact to 2^-16 of its value
       const float wv = *HSTU_LDS(float, c.wtab + b0);
       const __bf16 hi = (__bf16)wv;
@@ -564,8 +565,9 @@ struct BlockTable {
     const int x1 = __builtin_amdgcn_readlane(__builtin_bit_cast(int, w1), l);
     const int c = odd ? c1 : c0;
     BlockBias b;
-    b.b0 = c & (NONUNIFORM - 1);
+    b.b0 = c & (SMALL - 1);
     b.uni = (c & NONUNIFORM) == 0;
+    b.small = (c & SMALL) != 0;
     b.wpair = (uint32_t)(odd ? x1 : x0);
     return b;
   }
@@ -585,6 +587,14 @@ __device__ __forceinline__ void bias_block(f32x16& s, const char* trec, int blk,
     const u32x4 bq = {c.hh == 0 ? bb.wpair : 0u, 0u, 0u, 0u};
     const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     s = mfma(c.ones, __builtin_bit_cast(bf16x8, bq), zero);
+  } else if (bb.small) {  // (the common case: a third of the instructions of the general one)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int row = blk * 32 + 8 * (r >> 2) + 4 * c.hh + (r & 3);
+      const int t = *HSTU_LDS(int, trec + row * (int)sizeof(TsRecord));
+      bk[r] = bias_bucket_small(abs_diff(c.t_own, t), c.nb, c.f);
+      s[r] = *HSTU_LDS(float, c.wtab + bk[r]);
+    }
   } else {
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
