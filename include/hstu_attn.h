@@ -42,8 +42,8 @@
  *     tiles along the keys when a problem has too few tiles to fill the chip; with it the
  *     result of a query row does not depend on how many other rows the call has (bit for bit).
  *     Batches of very short sequences (bf16, mean length total_rows / batch of at most 256) are
- *     tiled 128 rows at a time across sequence boundaries by the whole-batch calls without bias
- *     ("packed tiles"); HSTU_ATTN_NO_PACK (any value) turns that off, HSTU_ATTN_PACK_LEN=<n>
+ *     tiled 128 rows at a time across sequence boundaries by the whole-batch calls, with or
+ *     without bias ("packed tiles"); HSTU_ATTN_NO_PACK (any value) turns that off, HSTU_ATTN_PACK_LEN=<n>
  *     moves the threshold (at most 1024).  With packed tiles the last bits of a row's result
  *     depend on the sequences that share its tile.  Set either before the workspace query too.
  *   - Return value: HSTU_OK (0) or a negative hstu_status.  Nothing is launched

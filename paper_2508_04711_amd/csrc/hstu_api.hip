@@ -66,14 +66,13 @@ bool short_sequences(const hstu_attn_params* p) {
 }
 
 // Batches of very short sequences (mean length at most PACKED_MEAN_LEN): the whole-batch entry
-// points without bias tile the rows of the batch regardless of sequence boundaries (packed tiles),
-// so that no tile is mostly padding.  HSTU_ATTN_NO_PACK (any value) turns this off,
-// HSTU_ATTN_PACK_LEN=<n> moves the threshold (up to the 1024 of the short-sequence form).
-// Measured, fwd + bwd, H = 4, d = 128: 8192 sequences of 16..64 rows 1.53 ms packed, 2.28 ms tiled
-// per sequence (whose schedule build alone is 0.16 ms); 4096 of 32..256 rows 3.07 against 2.93 ms
-// and 2048 of 200..256 rows 2.52 against 2.48 ms: a packed tile streams from the start of its first
-// sequence, i.e. more 64-row tiles per item than per-sequence tiles do, and in this regime every
-// streamed tile costs a memory round trip.
+// points tile the rows of the batch regardless of sequence boundaries (packed tiles), so that no
+// tile is mostly padding.  HSTU_ATTN_NO_PACK (any value) turns this off, HSTU_ATTN_PACK_LEN=<n>
+// moves the threshold (up to the 1024 of the short-sequence form).
+// Measured, fwd + bwd, H = 4, d = 128, per-sequence tiles -> packed: 8192 sequences of 16..64 rows
+// 1.98 -> 1.35 ms (the per-sequence schedule build alone is 0.16 ms); 4096 of 32..256 rows 2.82 ->
+// 2.65 ms; 2048 of 200..400 rows 3.13 -> 3.06 ms; 1536 of 300..600 rows 3.94 -> 3.92 ms: beyond a mean
+// of ~300 rows the two are within noise of each other.
 constexpr int PACKED_TILE = 128;
 constexpr int64_t PACKED_MEAN_LEN = 256;
 bool packed_tiles(const hstu_attn_params* p) {
@@ -538,15 +537,20 @@ static int fwd_impl(const hstu_attn_params* params, const hstu_ts_bias* bias, co
     return HSTU_ERR_WORKSPACE_TOO_SMALL;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   const size_t first = bias ? bias_front_bytes(params, 1) : 0;  // the records come first
-  if (bias && (rc = build_ts_records(params, bias, seq_offsets, (char*)workspace, false, stream)) != HSTU_OK)
+  // (packed tiles: a block's rows may belong to several sequences, so a record's range covers
+  // the next 32 rows of the batch whatever sequences they belong to)
+  const bool packed = packed_tiles(params);
+  if (bias && (rc = build_ts_records(params, bias, packed ? nullptr : seq_offsets, (char*)workspace, false,
+                                     stream)) != HSTU_OK)
     return rc;
-  if (!bias && packed_tiles(params)) {
+  if (packed) {
     PackedPlans pp;
-    rc = build_packed(params, seq_offsets, (char*)workspace, workspace_bytes, 0, stream, &pp);
+    rc = build_packed(params, seq_offsets, (char*)workspace, workspace_bytes, first, stream, &pp);
     if (rc != HSTU_OK) return rc;
     AttnArgs a = base_args(params, pp.side[0], 0);
     a.q = q; a.k = k; a.v = v; a.o = o;
     a.row_seq = pp.row_seq;
+    if (bias) set_bias(a, bias, (char*)workspace, false);
     return run_pass(params, PASS_FWD, a, stream);
   }
   BuiltPlan bp;
@@ -597,21 +601,27 @@ static int bwd_impl(const hstu_attn_params* params, const hstu_ts_bias* bias, co
     return HSTU_ERR_WORKSPACE_TOO_SMALL;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   const size_t first = bias ? bias_front_bytes(params, 1) : 0;  // the records come first
-  if (bias && (rc = build_ts_records(params, bias, seq_offsets, (char*)workspace, true, stream)) != HSTU_OK)
+  const bool packed = packed_tiles(params);
+  if (bias && (rc = build_ts_records(params, bias, packed ? nullptr : seq_offsets, (char*)workspace, true,
+                                     stream)) != HSTU_OK)
     return rc;
-  if (!bias && packed_tiles(params)) {
+  if (packed) {
     PackedPlans pp;
-    rc = build_packed(params, seq_offsets, (char*)workspace, workspace_bytes, 0, stream, &pp);
+    rc = build_packed(params, seq_offsets, (char*)workspace, workspace_bytes, first, stream, &pp);
     if (rc != HSTU_OK) return rc;
     AttnArgs a = base_args(params, pp.side[1], 0);
     a.q = q; a.k = k; a.v = v; a.d_o = d_o; a.dk = dk; a.dv = dv;
     a.row_seq = pp.row_seq;
+    if (bias) set_bias(a, bias, (char*)workspace, true);
     rc = run_pass(params, PASS_DKDV, a, stream);
     if (rc != HSTU_OK) return rc;
     AttnArgs b = base_args(params, pp.side[0], 0);
     b.q = q; b.k = k; b.v = v; b.d_o = d_o; b.dq = dq;
     b.row_seq = pp.row_seq;
-    return run_pass(params, PASS_DQ, b, stream);
+    if (bias) set_bias(b, bias, (char*)workspace, true);
+    rc = run_pass(params, PASS_DQ, b, stream);
+    if (rc != HSTU_OK || !bias) return rc;
+    return finish_dw(params, (const char*)workspace, bias->d_ts_weights, bias->num_buckets, 0, stream);
   }
   BuiltPlan pk, pq;
   PlanArgs pa[2];

@@ -102,7 +102,6 @@ __device__ __forceinline__ void dkdv_step(const Init& init, const char* qn, cons
 // One item (owner tile) of one head.
 template <int DQK, int DV, int NW, bool BIAS, bool PACKED>
 __device__ __forceinline__ void dkdv_item(const AttnArgs& a, const Item& it, int h) {
-  static_assert(!(PACKED && BIAS), "packed tiles: no bias");
   constexpr int QB = ST * DQK * 2, GB = ST * DV * 2;
   // Three tile buffers: an iteration of the main loop touches tiles j and j+1 while the copy of
   // tile j+2 is in flight.  One array per buffer, so that the compiler can see that a copy into
@@ -330,16 +329,17 @@ __global__ void __launch_bounds__(NW * 64, (DQK + DV <= 128 ? 2 : 1)) hstu_dkdv_
 }  // namespace
 
 hipError_t launch_dkdv_bf16(const AttnArgs& a, int d_qk, int d_v, hipStream_t stream) {
-  if (a.waves != 4 || (a.row_seq && a.ts_rec)) return hipErrorInvalidValue;
+  if (a.waves != 4) return hipErrorInvalidValue;
+  if (a.ts_rec && (a.nb < 1 || a.nb > MAX_TS_BUCKETS || !a.ts_w || !a.ts_rec_own)) return hipErrorInvalidValue;
   // One workgroup per CU is resident at the larger head dimensions: as many workgroups as CUs,
   // each walking over its share of the items.  Two per CU overlap each other's memory round
   // trips already, and the hardware's own dispatch serves them better (measured).
   const int64_t cap = a.large_batch && d_qk + d_v > 128 ? 256 : 0;
-  if (a.row_seq) HSTU_DISPATCH_G(d_qk + d_v > 128 ? 256 : 0, hstu_dkdv_bf16, 4, 4, false, true);
-  if (a.ts_rec) {
-    if (a.nb < 1 || a.nb > MAX_TS_BUCKETS || !a.ts_w || !a.ts_rec_own) return hipErrorInvalidValue;
-    HSTU_DISPATCH_G(cap, hstu_dkdv_bf16, 4, 4, true, false);
+  if (a.row_seq) {  // packed tiles: walking whatever the size of the batch
+    if (a.ts_rec) HSTU_DISPATCH_G(d_qk + d_v > 128 ? 256 : 0, hstu_dkdv_bf16, 4, 4, true, true);
+    HSTU_DISPATCH_G(d_qk + d_v > 128 ? 256 : 0, hstu_dkdv_bf16, 4, 4, false, true);
   }
+  if (a.ts_rec) HSTU_DISPATCH_G(cap, hstu_dkdv_bf16, 4, 4, true, false);
   HSTU_DISPATCH_G(cap, hstu_dkdv_bf16, 4, 4, false, false);
 }
 

@@ -102,7 +102,6 @@ __device__ __forceinline__ void dq_block(const BiasCtx& bias, const char* trec,
 
 template <int DQK, int DV, int NW, bool BIAS, bool PACKED>
 __global__ void __launch_bounds__(NW * 64, 2) hstu_dq_bf16(AttnArgs a) {
-  static_assert(!(PACKED && BIAS), "packed tiles: no bias");
   constexpr int KB = ST * DQK * 2, VB = ST * DV * 2;
   __shared__ __attribute__((aligned(1024))) char smem0[KB + VB];
   __shared__ __attribute__((aligned(1024))) char smem1[KB + VB];
@@ -239,12 +238,12 @@ __global__ void __launch_bounds__(NW * 64, 2) hstu_dq_bf16(AttnArgs a) {
 }  // namespace
 
 hipError_t launch_dq_bf16(const AttnArgs& a, int d_qk, int d_v, hipStream_t stream) {
-  if (a.waves != 4 || (a.row_seq && a.ts_rec)) return hipErrorInvalidValue;
-  if (a.row_seq) HSTU_DISPATCH_D(hstu_dq_bf16, 4, 4, false, true);
-  if (a.ts_rec) {
-    if (!a.d_ts_acc) return hipErrorInvalidValue;
-    HSTU_DISPATCH_BIAS(hstu_dq_bf16, 4, 4, true, false);
+  if (a.waves != 4 || (a.ts_rec && !a.d_ts_acc)) return hipErrorInvalidValue;
+  if (a.row_seq) {
+    if (a.ts_rec) HSTU_DISPATCH_BIAS(hstu_dq_bf16, 4, 4, true, true);
+    HSTU_DISPATCH_D(hstu_dq_bf16, 4, 4, false, true);
   }
+  if (a.ts_rec) HSTU_DISPATCH_BIAS(hstu_dq_bf16, 4, 4, true, false);
   HSTU_DISPATCH_D(hstu_dq_bf16, 4, 4, false, false);
 }
 

@@ -75,7 +75,7 @@ __device__ __forceinline__ void fwd_step(const Init& init, const char* kn, int b
 // PACKED: packed tiles (see Window).
 template <int DQK, int DV, int NW, bool VT, bool BIAS, bool PACKED>
 __global__ void __launch_bounds__(NW * 64, 2) hstu_fwd_bf16(AttnArgs a) {
-  static_assert(!(PACKED && (VT || BIAS)), "packed tiles: row-major V tiles, no bias");
+  static_assert(!(PACKED && VT), "packed tiles: row-major V tiles");
   constexpr int KB = ST * DQK * 2, VB = ST * DV * 2;
   // NBUF buffers each for the K tiles and the transposed V tiles; copies run PD tiles ahead.
   // Eight waves (one workgroup per CU) use three, four waves (two workgroups per CU) two.
@@ -336,7 +336,7 @@ hipError_t launch_fwd_bf16(const AttnArgs& a, int d_qk, int d_v, hipStream_t str
   if (a.vt == nullptr) {  // no transposed copy of V was built
     if (a.waves != 4) return hipErrorInvalidValue;
     if (a.row_seq) {
-      if (a.ts_rec) return hipErrorInvalidValue;
+      if (a.ts_rec) HSTU_DISPATCH_BIAS(hstu_fwd_bf16, 4, 4, false, true, true);
       HSTU_DISPATCH_D(hstu_fwd_bf16, 4, 4, false, false, true);
     }
     if (a.ts_rec) HSTU_DISPATCH_BIAS(hstu_fwd_bf16, 4, 4, false, true, false);

@@ -15,8 +15,12 @@ from test_gpu_parity import _check, _dev
 pytestmark = pytest.mark.gpu
 
 
-def _run(w, kind, nb, f, causal=True, wscale=1.0, out_dtype=torch.float32, seed=0):
+def _run(w, kind, nb, f, causal=True, wscale=1.0, out_dtype=torch.float32, seed=0, check=None):
+    """check(name, got, want, tag): replaces the standard bar for o, dq, dk, dv (batches of very short
+    sequences, whose outputs are sums of a handful of terms, state their own)."""
     import paper_2508_04711_amd as lib
+    if check is None:
+        check = lambda name, got, ref, tag: _check(name, got, ref, w.dtype, tag)
     vals = workloads.values(w)
     dev = _dev(vals)
     f64 = {k: workloads.to_f64(v) for k, v in vals.items()}
@@ -32,13 +36,13 @@ def _run(w, kind, nb, f, causal=True, wscale=1.0, out_dtype=torch.float32, seed=
     o = lib.hstu_jagged_attn_bias_fwd(dev["q"], dev["k"], dev["v"], off, ts, tab, f, w.max_len, w.alpha,
                                       causal, out_dtype=out_dtype)
     torch.cuda.synchronize()
-    _check("o", o, want[0], w.dtype, tag)
+    check("o", o, want[0], tag)
     dq, dk, dv, dw = lib.hstu_jagged_attn_bias_bwd(dev["q"], dev["k"], dev["v"], dev["d_o"], off, ts, tab,
                                                    f, w.max_len, w.alpha, causal, out_dtype=out_dtype)
     torch.cuda.synchronize()
-    _check("dq", dq, want[1], w.dtype, tag)
-    _check("dk", dk, want[2], w.dtype, tag)
-    _check("dv", dv, want[3], w.dtype, tag)
+    check("dq", dq, want[1], tag)
+    check("dk", dk, want[2], tag)
+    check("dv", dv, want[3], tag)
     got = dw.double().cpu().numpy()
     assert np.isfinite(got).all()
     rms = float(np.sqrt(np.mean(want[4] ** 2)))

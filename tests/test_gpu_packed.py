@@ -148,3 +148,62 @@ def test_four_thousand_short_sequences():
         _check("o", o[s:e], want_o, "bf16", "short4096@%d" % first)
         for name, g, ref in zip(("dq", "dk", "dv"), (dq, dk, dv), want):
             _check(name, g[s:e], ref, "bf16", "short4096@%d" % first)
+
+
+# ---- packed tiles with the timestamp bias ---------------------------------------------------
+
+@pytest.mark.parametrize("kind", ["events", "shuffled", "equal", "wide"])
+@pytest.mark.parametrize("d", [32, 64, 128])
+def test_packed_tiles_with_bias_match_oracle(kind, d):
+    """Blocks whose rows belong to several sequences: the ranges a block's one-bucket test uses
+    cover the rows of all of them; hidden pairs contribute neither to the outputs nor to dW."""
+    from test_gpu_bias import _run as run_bias
+    rng = np.random.default_rng(d)
+    lengths = [int(x) for x in rng.integers(0, 90, size=40)] + [300, 1, 129, 64]
+    w = workloads.custom("packed_bias", lengths, 2, d, d, 300, dtype="bf16", seed=30 + d)
+    run_bias(w, kind, nb=40, f=2, causal=True, seed=d, check=_check_few_terms)
+
+
+def test_packed_tiles_with_bias_no_mask_and_bucket_shapes():
+    from test_gpu_bias import _run as run_bias
+    lengths = [5, 70, 33, 0, 128, 17, 250, 1, 1, 64] * 4
+    w = workloads.custom("packed_bias_full", lengths, 3, 64, 64, 250, dtype="bf16", seed=7)
+    run_bias(w, "events", nb=24, f=1, causal=False, seed=1, check=_check_few_terms)
+    run_bias(w, "events", nb=1, f=0, causal=True, seed=2, check=_check_few_terms)
+    run_bias(w, "wide", nb=512, f=4, causal=True, out_dtype=torch.bfloat16, seed=3, check=_check_few_terms)
+
+
+def test_packed_bias_table_gradient_equals_per_sequence_tiles(monkeypatch):
+    """The same call with packed and with per-sequence tiles, 36 K rows in 600 sequences: the
+    outputs agree to operand rounding and the table gradient, a sum over the same visible pairs,
+    to fp32 summation error."""
+    import paper_2508_04711_amd as lib
+    rng = np.random.default_rng(3)
+    lengths = [int(x) for x in rng.integers(1, 120, size=600)]
+    w = workloads.custom("packed_bias_many", lengths, 4, 128, 128, 120, dtype="bf16", seed=12)
+    dev = _dev(workloads.values(w))
+    off = torch.from_numpy(w.seq_offsets()).cuda()
+    ts = torch.from_numpy(workloads.timestamps(w, "events", 4)).cuda()
+    tab = torch.from_numpy(workloads.bias_table(64, 4)).cuda()
+    res = {}
+    for mode in ("packed", "tiled"):
+        if mode == "tiled":
+            monkeypatch.setenv("HSTU_ATTN_NO_PACK", "1")
+        o = lib.hstu_jagged_attn_bias_fwd(dev["q"], dev["k"], dev["v"], off, ts, tab, 2, w.max_len, w.alpha, True,
+                                          out_dtype=torch.float32)
+        g = lib.hstu_jagged_attn_bias_bwd(dev["q"], dev["k"], dev["v"], dev["d_o"], off, ts, tab, 2, w.max_len,
+                                          w.alpha, True, out_dtype=torch.float32)
+        torch.cuda.synchronize()
+        res[mode] = (o,) + tuple(g)
+    # The two forms see a block's table entry as hi + lo bf16 halves or as the fp32 value depending
+    # on which blocks each of them finds to be of one bucket, so scores differ in the 16th bit and
+    # a P or dS operand may round to the other bf16 neighbour: one term of a handful moves by 2^-8
+    # of its value.  The table gradient sums fp32 dS values that are never rounded.
+    for name, a, b in zip(("o", "dq", "dk", "dv", "dw"), res["packed"], res["tiled"]):
+        a, b = a.double(), b.double()
+        rms = float(b.pow(2).mean().sqrt())
+        print("packed vs tiled", name, float((a - b).abs().max()) / rms, flush=True)
+        if name == "dw":
+            assert float((a - b).abs().max()) <= 2e-3 * rms
+        else:
+            assert bool(((a - b).abs() <= 1e-2 * rms + b.abs() * 2.0 ** -7).all()), name
