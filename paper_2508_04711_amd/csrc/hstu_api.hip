@@ -221,13 +221,14 @@ int prepare_plan(const hstu_attn_params* p, int cp_size, const SideSpec& s, cons
   // Measured, H = 4, d = 128, sorted -> natural: 1536 sequences of 300..600 rows forward 1.18 ->
   // 0.86 ms, dQ 1.32 -> 1.07, dK/dV 1.94 -> 2.06; 768 of 600..1200 forward 1.68 -> 1.15, dQ 1.83 ->
   // 1.53, dK/dV 2.68 -> 2.94; 512 of 1000..2000 forward 2.17 -> 2.10, dQ 2.91 -> 2.29, dK/dV 4.25
-  // -> 3.96: the passes whose owners are queries always gain, the dK/dV pass only beyond the
-  // short-sequence form, so there it stays sorted.
+  // -> 3.96: the passes whose owners are queries always gain, the dK/dV pass at one workgroup per
+  // CU (d_qk + d_v > 128) only beyond the short-sequence form, so there it stays sorted (at two
+  // workgroups per CU it gains 4 %: H = 8, d = 64, 1024 sequences of 400..800 rows 1.76 -> 1.69 ms).
   const int64_t batch = p->batch > 0 ? p->batch : 1;
   const int64_t all_pairs = s.owner_rows / batch * (s.streamed_rows / batch) / (p->causal ? 2 : 1) * batch;
   const int64_t per_slot = all_pairs / 512 * p->num_heads;
   const bool large = (int64_t)tile_rows(p, s.pass, s.owner_rows) * longest * 8 < per_slot;
-  if (large && (s.side == 0 || !short_sequences(p))) shift = 30;
+  if (large && (s.side == 0 || !short_sequences(p) || p->d_qk + p->d_v <= 128)) shift = 30;
   // (Walking workgroups take every 256th item: fine for a sorted list of short items, but in the
   // natural order of longer sequences the stride beats against the tiles per sequence: measured
   // 7 % slower on 512 sequences of 1000..2000 rows, 3 to 5 % faster on 200..1200 rows.)

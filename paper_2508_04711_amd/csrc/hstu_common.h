@@ -210,6 +210,13 @@ struct AttnArgs {
   // Large batch (many items, none of them a large share of the whole): kernels that run one
   // workgroup per CU may launch as many workgroups as CUs and let each walk over its share.
   int32_t large_batch;
+  // Schedules in natural order (the items of a sequence are neighbours in the list) with a head
+  // count that divides 8: the hardware hands workgroup i to XCD i % 8, each XCD with an L2 of
+  // its own, so the unit -> (item, head) map gives every XCD one head and one contiguous part
+  // of the list (8 / heads parts) and the tiles of a sequence, which stream the same rows, meet
+  // in one L2.  1: the plain map, unit = item * heads + head (with 8 heads that already is one
+  // head per XCD).
+  int32_t xcd_parts;
 };
 
 // Owner rows per item each kernel family expects (pass: 0 forward, 1 dk/dv, 2 dq); the

@@ -296,29 +296,47 @@ __device__ __forceinline__ void dkdv_item(const AttnArgs& a, const Item& it, int
 // items are many and of about equal cost (packed tiles, large batches).
 template <int DQK, int DV, int NW, bool BIAS, bool PACKED>
 __global__ void __launch_bounds__(NW * 64, (DQK + DV <= 128 ? 2 : 1)) hstu_dkdv_bf16(AttnArgs a) {
-  const int H = a.num_heads;
   Item it;
-  if (!PACKED && gridDim.x >= (unsigned)(a.max_items * H)) {
-    if (!fetch_item(a.plan, blockIdx.x / H, it)) return;
-    dkdv_item<DQK, DV, NW, BIAS, PACKED>(a, it, blockIdx.x % H);
+  const int64_t bound = a.xcd_parts <= 1 ? (int64_t)a.max_items * a.num_heads
+                                         : 8 * (((int64_t)a.max_items + a.xcd_parts - 1) / a.xcd_parts);
+  if (!PACKED && gridDim.x >= bound) {
+    const Unit un = unit_of(a, blockIdx.x);
+    if (!un.on || !fetch_item(a.plan, un.slot, it)) return;
+    dkdv_item<DQK, DV, NW, BIAS, PACKED>(a, it, un.h);
     return;
   }
-  // (the items of packed tiles are in schedule order already: no indirection)
-  auto index_of = [&](int unit) { return PACKED ? unit / H : a.plan.order[unit / H]; };
-  const int units = a.plan.header[0] * H;
+  const int n = a.plan.header[0];
+  const int units = unit_count(a, n);
   const int stride = (int)gridDim.x;
+  // The description of unit u, as loaded (all zeros, i.e. no rows, for a unit that is none).
+  // (The items of packed tiles are in schedule order already: no indirection.)
+  auto index_of = [&](const Unit& un) { return PACKED ? un.slot : a.plan.order[un.slot]; };
+  auto valid = [&](const Unit& un) { return un.on && un.slot < n; };
   int u = blockIdx.x;
   if (u >= units) return;
-  RawItem raw = load_raw_item(a.plan.items + index_of(u));
-  int next = (int64_t)u + stride < units ? index_of(u + stride) : 0;
+  Unit cur = unit_of(a, u);
+  RawItem raw = {};
+  if (valid(cur)) raw = load_raw_item(a.plan.items + index_of(cur));
+  Unit nxt = {};
+  int next = 0;
+  if ((int64_t)u + stride < units) {
+    nxt = unit_of(a, u + stride);
+    if (valid(nxt)) next = index_of(nxt);
+  }
   while (true) {
-    const bool on = decode_item(raw, it);
-    const int h = u % H;
+    const bool on = valid(cur) && decode_item(raw, it);
+    const int h = cur.h;
     const bool more = (int64_t)u + stride < units;
     u += more ? stride : 0;
     if (more) {  // in flight while this item is worked on
-      raw = load_raw_item(a.plan.items + next);
-      next = (int64_t)u + stride < units ? index_of(u + stride) : 0;
+      cur = nxt;
+      raw = RawItem{};
+      if (valid(cur)) raw = load_raw_item(a.plan.items + next);
+      next = 0;
+      if ((int64_t)u + stride < units) {
+        nxt = unit_of(a, u + stride);
+        if (valid(nxt)) next = index_of(nxt);
+      }
     }
     if (on) dkdv_item<DQK, DV, NW, BIAS, PACKED>(a, it, h);
     if (!more) break;

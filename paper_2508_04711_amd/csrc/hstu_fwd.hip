@@ -98,9 +98,10 @@ __global__ void __launch_bounds__(NW * 64, 2) hstu_fwd_bf16(AttnArgs a) {
   auto tbuf = [&](int b) { return b == 0 ? tmem0 : (b == 1 ? tmem1 : tmem2); };
 
   const int H = a.num_heads;
-  const int slot = blockIdx.x / H, h = blockIdx.x % H;
+  const Unit un = unit_of(a, blockIdx.x);
+  const int slot = un.slot, h = un.h;
   Item it;
-  if (!fetch_item<PACKED>(a.plan, slot, it)) return;
+  if (!un.on || !fetch_item<PACKED>(a.plan, slot, it)) return;
 
   const int tid = threadIdx.x, lane = tid & 63, n = lane & 31, hh = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);

@@ -342,6 +342,29 @@ __device__ __forceinline__ void store_one(void* out, int64_t elem, float x, int 
   }
 }
 
+// Which (item of the schedule, head) a workgroup-sized unit of work is (see AttnArgs::xcd_parts).
+// on == false: none (the grid is sized from bounds).
+struct Unit { int slot, h; bool on; };
+__device__ __forceinline__ Unit unit_of(const AttnArgs& a, int u) {
+  const int H = a.num_heads;
+  Unit r;
+  if (a.xcd_parts <= 1) {
+    r.slot = u / H; r.h = u % H; r.on = true;  // (the item fetch checks the slot)
+    return r;
+  }
+  const int n = a.plan.header[0];
+  const int per = (n + a.xcd_parts - 1) / a.xcd_parts;
+  const int x = u & 7, j = u >> 3;
+  r.h = x % H;
+  r.slot = (x / H) * per + j;
+  r.on = j < per && r.slot < n;
+  return r;
+}
+// Units the (item, head) pairs of a schedule of n items are spread over.
+__device__ __forceinline__ int unit_count(const AttnArgs& a, int n) {
+  return a.xcd_parts <= 1 ? n * a.num_heads : 8 * ((n + a.xcd_parts - 1) / a.xcd_parts);
+}
+
 // An item as it lies in memory, loaded by every lane alike (what a workgroup that walks over items
 // fetches ahead of time) ...
 struct RawItem { u32x4 w[4]; };
@@ -657,7 +680,9 @@ __device__ __forceinline__ void bwd_elem(float s, float dp, float c1, float alph
 #define HSTU_DISPATCH_D(KERNEL, NW, ...) HSTU_DISPATCH_G(0, KERNEL, NW, __VA_ARGS__)
 #define HSTU_DISPATCH_G(CAP, KERNEL, NW, ...)                                           \
   do {                                                                                  \
-    const int64_t units_ = (int64_t)a.max_items * a.num_heads, cap_ = (CAP);            \
+    const int64_t units_ = a.xcd_parts <= 1 ? (int64_t)a.max_items * a.num_heads        \
+                               : 8 * (((int64_t)a.max_items + a.xcd_parts - 1) / a.xcd_parts); \
+    const int64_t cap_ = (CAP);                                                         \
     const dim3 grid((unsigned)(cap_ > 0 && units_ > cap_ ? cap_ : units_)), block(NW * 64); \
     if (d_qk == 128 && d_v == 128) hipLaunchKernelGGL((KERNEL<128, 128, __VA_ARGS__>), grid, block, 0, stream, a); \
     else if (d_qk == 64 && d_v == 64) hipLaunchKernelGGL((KERNEL<64, 64, __VA_ARGS__>), grid, block, 0, stream, a); \
