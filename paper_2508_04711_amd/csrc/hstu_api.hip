@@ -114,6 +114,8 @@ struct BuiltPlan {
   size_t end;
   int waves;
   bool large;         // short sequences, and even the heaviest item is a small share of one workgroup slot's work
+  bool natural;       // the items are in their natural order (those of a sequence are neighbours)
+  bool chunks;        // dK/dV workgroups walk over contiguous runs of the list
 };
 
 // Bound on the items of a schedule, taken with the smallest tile any kernel variant uses so that
@@ -221,14 +223,23 @@ int prepare_plan(const hstu_attn_params* p, int cp_size, const SideSpec& s, cons
   // Measured, H = 4, d = 128, sorted -> natural: 1536 sequences of 300..600 rows forward 1.18 ->
   // 0.86 ms, dQ 1.32 -> 1.07, dK/dV 1.94 -> 2.06; 768 of 600..1200 forward 1.68 -> 1.15, dQ 1.83 ->
   // 1.53, dK/dV 2.68 -> 2.94; 512 of 1000..2000 forward 2.17 -> 2.10, dQ 2.91 -> 2.29, dK/dV 4.25
-  // -> 3.96: the passes whose owners are queries always gain, the dK/dV pass at one workgroup per
-  // CU (d_qk + d_v > 128) only beyond the short-sequence form, so there it stays sorted (at two
-  // workgroups per CU it gains 4 %: H = 8, d = 64, 1024 sequences of 400..800 rows 1.76 -> 1.69 ms).
+  // -> 3.96: the passes whose owners are queries always gain; the dK/dV pass at two workgroups per
+  // CU gains 4 % (H = 8, d = 64, 1024 sequences of 400..800 rows 1.76 -> 1.69 ms); at one workgroup
+  // per CU (d_qk + d_v > 128) it gains beyond the short-sequence form, and below it when its
+  // walking workgroups take contiguous runs (2 to 5 %), but loses 4 % when they take every 256th
+  // item, whose stride beats against the tiles per sequence.
   const int64_t batch = p->batch > 0 ? p->batch : 1;
   const int64_t all_pairs = s.owner_rows / batch * (s.streamed_rows / batch) / (p->causal ? 2 : 1) * batch;
   const int64_t per_slot = all_pairs / 512 * p->num_heads;
   const bool large = (int64_t)tile_rows(p, s.pass, s.owner_rows) * longest * 8 < per_slot;
-  if (large && (s.side == 0 || !short_sequences(p) || p->d_qk + p->d_v <= 128)) shift = 30;
+  // The dK/dV pass at one workgroup per CU walks over the list (see launch_dkdv_bf16): in natural
+  // order when its workgroups can take contiguous runs of one XCD's share, which needs a head
+  // count that divides 8; sorted by cost, every 256th item, otherwise.
+  const bool chunks = large && s.side == 1 && short_sequences(p) && p->d_qk + p->d_v > 128 &&
+                      p->dtype == HSTU_BF16 && p->num_heads <= 8 && 8 % p->num_heads == 0;
+  out->chunks = chunks;
+  if (large && (s.side == 0 || !short_sequences(p) || p->d_qk + p->d_v <= 128 || chunks)) shift = 30;
+  out->natural = shift == 30 && split <= 1;
   // (Walking workgroups take every 256th item: fine for a sorted list of short items, but in the
   // natural order of longer sequences the stride beats against the tiles per sequence: measured
   // 7 % slower on 512 sequences of 1000..2000 rows, 3 to 5 % faster on 200..1200 rows.)
@@ -294,6 +305,8 @@ int build_packed(const hstu_attn_params* p, const int32_t* off, char* ws, size_t
     bp.split = 1;
     bp.waves = PACKED_TILE / 32;
     bp.large = false;  // (the packed dK/dV kernel walks whatever the size)
+    bp.natural = true;
+    bp.chunks = false;
     bp.end = at;
   }
   out->row_seq = a.row_seq;
@@ -341,6 +354,9 @@ AttnArgs base_args(const hstu_attn_params* p, const BuiltPlan& bp, int accumulat
   a.max_items = (int32_t)bp.max_items;
   a.waves = bp.waves;
   a.large_batch = bp.large ? 1 : 0;
+  a.walk_chunks = bp.chunks ? 1 : 0;
+  a.xcd_parts = bp.natural && p->dtype == HSTU_BF16 && p->num_heads < 8 && 8 % p->num_heads == 0
+                    ? 8 / p->num_heads : 1;
   a.out_f32 = p->out_dtype == HSTU_F32 ? 1 : 0;
   a.alpha = p->alpha;
   a.inv_n = 1.0f / (float)p->max_len;

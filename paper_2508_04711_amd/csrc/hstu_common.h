@@ -217,6 +217,9 @@ struct AttnArgs {
   // in one L2.  1: the plain map, unit = item * heads + head (with 8 heads that already is one
   // head per XCD).
   int32_t xcd_parts;
+  // Walking workgroups take contiguous runs of their XCD's units instead of every n-th unit
+  // (natural order with a head count that divides 8).
+  int32_t walk_chunks;
 };
 
 // Owner rows per item each kernel family expects (pass: 0 forward, 1 dk/dv, 2 dq); the

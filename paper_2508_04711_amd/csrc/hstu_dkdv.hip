@@ -307,33 +307,44 @@ __global__ void __launch_bounds__(NW * 64, (DQK + DV <= 128 ? 2 : 1)) hstu_dkdv_
   }
   const int n = a.plan.header[0];
   const int units = unit_count(a, n);
-  const int stride = (int)gridDim.x;
+  // Every gridDim.x-th unit from blockIdx.x on - or, for a schedule in natural order (walk_chunks),
+  // one contiguous run of this XCD's units (unit = 8 * j + XCD, see unit_of): whole sequences, whose
+  // tiles then follow each other in time on one CU and find their streamed rows in the caches,
+  // where a stride would beat against the number of tiles per sequence.
+  int u = blockIdx.x, stride = (int)gridDim.x, end = units;
+  if (a.walk_chunks && (gridDim.x & 7) == 0) {
+    const int x = u & 7, m = u >> 3, wgs = (int)(gridDim.x >> 3), per = (units + 7) >> 3;
+    const int c = (per + wgs - 1) / wgs;
+    const int64_t last = (int64_t)8 * (m + 1) * c;
+    u = 8 * m * c + x;
+    stride = 8;
+    end = last < units ? (int)last : units;
+  }
   // The description of unit u, as loaded (all zeros, i.e. no rows, for a unit that is none).
   // (The items of packed tiles are in schedule order already: no indirection.)
   auto index_of = [&](const Unit& un) { return PACKED ? un.slot : a.plan.order[un.slot]; };
   auto valid = [&](const Unit& un) { return un.on && un.slot < n; };
-  int u = blockIdx.x;
-  if (u >= units) return;
+  if (u >= end) return;
   Unit cur = unit_of(a, u);
   RawItem raw = {};
   if (valid(cur)) raw = load_raw_item(a.plan.items + index_of(cur));
   Unit nxt = {};
   int next = 0;
-  if ((int64_t)u + stride < units) {
+  if ((int64_t)u + stride < end) {
     nxt = unit_of(a, u + stride);
     if (valid(nxt)) next = index_of(nxt);
   }
   while (true) {
     const bool on = valid(cur) && decode_item(raw, it);
     const int h = cur.h;
-    const bool more = (int64_t)u + stride < units;
+    const bool more = (int64_t)u + stride < end;
     u += more ? stride : 0;
     if (more) {  // in flight while this item is worked on
       cur = nxt;
       raw = RawItem{};
       if (valid(cur)) raw = load_raw_item(a.plan.items + next);
       next = 0;
-      if ((int64_t)u + stride < units) {
+      if ((int64_t)u + stride < end) {
         nxt = unit_of(a, u + stride);
         if (valid(nxt)) next = index_of(nxt);
       }
@@ -352,7 +363,7 @@ hipError_t launch_dkdv_bf16(const AttnArgs& a, int d_qk, int d_v, hipStream_t st
   // One workgroup per CU is resident at the larger head dimensions: as many workgroups as CUs,
   // each walking over its share of the items.  Two per CU overlap each other's memory round
   // trips already, and the hardware's own dispatch serves them better (measured).
-  const int64_t cap = a.large_batch && d_qk + d_v > 128 ? 256 : 0;
+  const int64_t cap = (a.large_batch || a.walk_chunks) && d_qk + d_v > 128 ? 256 : 0;
   if (a.row_seq) {  // packed tiles: walking whatever the size of the batch
     if (a.ts_rec) HSTU_DISPATCH_G(d_qk + d_v > 128 ? 256 : 0, hstu_dkdv_bf16, 4, 4, true, true);
     HSTU_DISPATCH_G(d_qk + d_v > 128 ? 256 : 0, hstu_dkdv_bf16, 4, 4, false, true);
