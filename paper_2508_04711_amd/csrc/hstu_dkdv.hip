@@ -43,7 +43,7 @@ __device__ __forceinline__ void dkdv_step(const Init& init, const char* qn, cons
                                           f32x16& s_out, f32x16& d_out,
                                           const bf16x8 (&pd_prev)[4], bf16x8 (&pd_cur)[4],
                                           f32x16 (&dkacc)[DQK / 32], f32x16 (&dvacc)[DV / 32],
-                                          float c1, float alpha, bool mask, const Vis& vis) {
+                                          float c1, float alpha, bool mask, const Vis& vis_of) {
   constexpr int KS = DQK / 16, VS = DV / 16, NS = KS + VS;
   constexpr int AHEAD = NS < 4 ? NS : 4;  // operand reads in flight ahead of their use
   constexpr int GRP = 4;                  // slots between scheduling fences
@@ -65,6 +65,13 @@ __device__ __forceinline__ void dkdv_step(const Init& init, const char* qn, cons
   }
   fence();
   float p[16], ds[16];
+  // The elementwise work of a group of four slots is done in four stages over the group's
+  // 64 / NS elements, one stage per slot, so that an instruction's operands were produced a few
+  // instructions earlier and not by its predecessor (a lone wave pays every such dependence, most
+  // of all behind exp and rcp, in stalled cycles and hazard nops).
+  constexpr bool STAGED = NS == 4 || NS == 8 || NS == 16;
+  constexpr int EPG = STAGED ? 64 / NS : 1;
+  float st_t[EPG], st_g[EPG];
 #pragma unroll
   for (int m = 0; m < NS; ++m) {
     if (m < KS) s_out = mfma(op[m], kreg[m], s_out);
@@ -77,12 +84,38 @@ __device__ __forceinline__ void dkdv_step(const Init& init, const char* qn, cons
       op[m + AHEAD] = read_rows(m + AHEAD);
       if (CONTR) tp[m + AHEAD] = read_cols(m + AHEAD);
     }
+    if constexpr (STAGED) {
+      const int e0 = (m / 4) * EPG, ph = m % 4;
+      if (ph == 0) {
 #pragma unroll
-    for (int e = m * 16 / NS; e < (m + 1) * 16 / NS; ++e) bwd_elem(s_in[e], d_in[e], c1, alpha, p[e], ds[e]);
+        for (int j = 0; j < EPG; ++j) st_t[j] = s_in[e0 + j] * c1;
+#pragma unroll
+        for (int j = 0; j < EPG; ++j) st_t[j] = __builtin_amdgcn_exp2f(st_t[j]);
+      } else if (ph == 1) {
+#pragma unroll
+        for (int j = 0; j < EPG; ++j) st_t[j] = 1.0f + st_t[j];
+#pragma unroll
+        for (int j = 0; j < EPG; ++j) st_g[j] = __builtin_amdgcn_rcpf(st_t[j]);
+      } else if (ph == 2) {  // p' = s * sg, 1 - sg
+#pragma unroll
+        for (int j = 0; j < EPG; ++j) p[e0 + j] = s_in[e0 + j] * st_g[j];
+#pragma unroll
+        for (int j = 0; j < EPG; ++j) st_t[j] = 1.0f - st_g[j];
+      } else {               // ds' = dp * (sg + alpha * p' * (1 - sg))
+#pragma unroll
+        for (int j = 0; j < EPG; ++j) st_t[j] = alpha * p[e0 + j] * st_t[j];
+#pragma unroll
+        for (int j = 0; j < EPG; ++j) ds[e0 + j] = d_in[e0 + j] * (st_g[j] + st_t[j]);
+      }
+    } else {
+#pragma unroll
+      for (int e = m * 16 / NS; e < (m + 1) * 16 / NS; ++e) bwd_elem(s_in[e], d_in[e], c1, alpha, p[e], ds[e]);
+    }
     if (m % GRP == GRP - 1) fence();
   }
   if (mask) {
     asm volatile("" ::: "memory");  // not speculable: keeps the selects off the unmasked path
+    const auto vis = vis_of();      // (the block's position is worked out on this path only)
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const bool on = vis(r);
@@ -166,19 +199,47 @@ __device__ __forceinline__ void dkdv_item(const AttnArgs& a, const Item& it, int
   // Position of block i of the stream (i in [0, NB)); the positions grow with i.
   auto block_pos = [&](int i) { return tile_ref(it, st, i >> 1).pos + (i & 1) * 32; };
   Window win = {};  // (packed tiles: set below, once the first tile copies are on their way)
+  // Plain tiles: the block positions grow by 32 inside a segment, so the first block any query of
+  // which sees a key of this wave (first_on) and the last block the diagonal touches (last_masked:
+  // position < k_hi) have closed forms, worked out once; a step then costs two comparisons instead
+  // of the scalar arithmetic of a block position.
+  int first_on = 0, last_masked = -1;
+  if (!PACKED && a.causal) {
+    first_on = NB;
+#pragma unroll
+    for (int g = 1; g >= 0; --g) {
+      const int i0 = g ? 2 * st.n[0] : 0, nb = 2 * st.n[g];     // the segment's blocks [i0, i0 + nb)
+      const int p0 = it.seg_pos0[g] + st.beg[g];                 // position of its first block
+      if (nb > 0) {
+        const int q = (k_lo - 31 - p0 + 31) >> 5;                // first block with pos + 31 >= k_lo
+        const int f = q < 0 ? 0 : q;
+        if (f < nb) first_on = i0 + f;
+        const int m = (k_hi - 1 - p0) >> 5;                      // last block with pos < k_hi
+        if (m >= 0 && last_masked < 0) last_masked = i0 + (m < nb - 1 ? m : nb - 1);
+      }
+    }
+  }
   // Does any query of block i see a key of this wave?  Once true it stays true.
   auto block_on = [&](int i) {
     if constexpr (PACKED) return wave_on && block_pos(i) + 31 >= win.lo_min;
-    else return wave_on && (!a.causal || block_pos(i) + 31 >= k_lo);
+    else return wave_on && i >= first_on;
   };
   // Packed tiles: block i is not yet beyond the last row that sees a key of the wave (i < 0: no
   // such block).  Once false it stays false; a step is skipped when the block it would contract
   // is beyond, and with it every later step.
   auto not_past = [&](int i) { return !PACKED || i < 0 || block_pos(i) <= win.hi_max; };
-  auto mask_of = [&](int pos) { return PACKED ? win.masks(pos) : (a.causal && pos < k_hi); };
-  auto vis_of = [&](int pos) {
-    if constexpr (PACKED) return win.vis(pos, hh);
-    else return VisAfter{k_lo + n - pos, hh};
+  // Block i may hold pairs the mask hides ...
+  auto mask_of = [&](int i) {
+    if constexpr (PACKED) return win.masks(block_pos(i));
+    else return i <= last_masked;
+  };
+  // ... and which of its rows the lane's key sees (made on the masked path only).
+  auto vis_of = [&](int i) {
+    return [&, i] {
+      const int pos = block_pos(i);
+      if constexpr (PACKED) return win.vis(pos, hh);
+      else return VisAfter{k_lo + n - pos, hh};
+    };
   };
 
   if (T > 0) copy_tile(0, 0);
@@ -220,10 +281,9 @@ __device__ __forceinline__ void dkdv_item(const AttnArgs& a, const Item& it, int
   }
   // step 0: scores of block 1, elementwise of block 0, nothing to contract yet
   if (block_on(1)) {
-    const int pos = block_pos(0);
     dkdv_step<DQK, DV, false>(init_of(tbuf(0), 1, bb_of(1)), qbuf(0), gbuf(0), 1, qbuf(0), gbuf(0), 0, raq, rag,
                               caq, cag, kreg, vreg, sacc[0], dacc[0], sacc[1], dacc[1], pd[1], pd[0],
-                              dkacc, dvacc, c1, a.alpha, mask_of(pos), vis_of(pos));
+                              dkacc, dvacc, c1, a.alpha, mask_of(0), vis_of(0));
   }
 
   // Iteration j: steps 2j+1 and 2j+2, which touch tiles j and j+1 only.
@@ -235,19 +295,17 @@ __device__ __forceinline__ void dkdv_item(const AttnArgs& a, const Item& it, int
     {
       const int i = 2 * j + 1;  // scores of (tile j+1, block 0), contraction of (tile j, block 0)
       if (block_on(i + 1 < NB ? i + 1 : i) && not_past(i - 1)) {
-        const int pos = block_pos(i);
         dkdv_step<DQK, DV, true>(init_of(tbuf(B1), 0, bb_of(i + 1)), qbuf(B1), gbuf(B1), 0, qbuf(B0), gbuf(B0), 0, raq,
                                  rag, caq, cag, kreg, vreg, sacc[1], dacc[1], sacc[0], dacc[0], pd[0],
-                                 pd[1], dkacc, dvacc, c1, a.alpha, mask_of(pos), vis_of(pos));
+                                 pd[1], dkacc, dvacc, c1, a.alpha, mask_of(i), vis_of(i));
       }
     }
     if (j + 1 < T) {
       const int i = 2 * j + 2;  // scores of (tile j+1, block 1), contraction of (tile j, block 1)
       if (block_on(i + 1) && not_past(i - 1)) {
-        const int pos = block_pos(i);
         dkdv_step<DQK, DV, true>(init_of(tbuf(B1), 1, bb_of(i + 1)), qbuf(B1), gbuf(B1), 1, qbuf(B0), gbuf(B0), 1, raq,
                                  rag, caq, cag, kreg, vreg, sacc[0], dacc[0], sacc[1], dacc[1], pd[1],
-                                 pd[0], dkacc, dvacc, c1, a.alpha, mask_of(pos), vis_of(pos));
+                                 pd[0], dkacc, dvacc, c1, a.alpha, mask_of(i), vis_of(i));
       }
     }
     tile_copy_wait<0>();

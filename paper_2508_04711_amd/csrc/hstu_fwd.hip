@@ -31,7 +31,7 @@ __device__ __forceinline__ void fwd_step(const Init& init, const char* kn, int b
                                          const bf16x8 (&qreg)[DQK / 16], const f32x16& s_in,
                                          f32x16& s_out, const bf16x8 (&p_prev)[2],
                                          bf16x8 (&p_cur)[2], f32x16 (&oacc)[DV / 32], float c1,
-                                         bool mask, const Vis& vis) {
+                                         bool mask, const Vis& vis_of) {
   constexpr int KS = DQK / 16, NPV = DV / 16, NSL = KS > NPV ? KS : NPV;
   constexpr int AHEAD = 3;  // operand reads in flight ahead of their use
   bf16x8 ka[KS], va[NPV];
@@ -60,6 +60,7 @@ __device__ __forceinline__ void fwd_step(const Init& init, const char* kn, int b
   }
   if (mask) {
     asm volatile("" ::: "memory");  // not speculable: keeps the selects off the unmasked path
+    const auto vis = vis_of();      // (the block's position is worked out on this path only)
 #pragma unroll
     for (int r = 0; r < 16; ++r) p[r] = vis(r) ? p[r] : 0.f;
   }
@@ -151,9 +152,29 @@ __global__ void __launch_bounds__(NW * 64, 2) hstu_fwd_bf16(AttnArgs a) {
   Window win = {};  // (packed tiles: set below, once the first tile copies are on their way)
   // Does any key of block i precede (or equal) a query of this wave?  Once false it stays false.
   // (Packed tiles: no block lies beyond the last row that some row of the wave sees.)
+  // Plain tiles: the block positions grow by 32 inside a segment, so the last block with a key
+  // some query of the wave sees (last_on: position <= q_hi) and the first block the diagonal touches
+  // (first_masked: position + 31 > q_lo) have closed forms, worked out once; a step then costs two
+  // comparisons instead of the scalar arithmetic of a block position.
+  int last_on = NB - 1, first_masked = NB;
+  if (!PACKED && a.causal) {
+    last_on = -1;
+#pragma unroll
+    for (int g = 1; g >= 0; --g) {
+      const int i0 = g ? 2 * st.n[0] : 0, nb = 2 * st.n[g];  // the segment's blocks [i0, i0 + nb)
+      const int p0 = it.seg_pos0[g] + st.beg[g];              // position of its first block
+      if (nb > 0) {
+        const int m = (q_hi - p0) >> 5;                       // last block with pos <= q_hi
+        if (m >= 0 && last_on < 0) last_on = i0 + (m < nb - 1 ? m : nb - 1);
+        const int f0 = ((q_lo - 31 - p0) >> 5) + 1;           // first block with pos + 31 > q_lo
+        const int f = f0 < 0 ? 0 : f0;
+        if (f < nb) first_masked = i0 + f;
+      }
+    }
+  }
   auto block_on = [&](int i) {
     if constexpr (PACKED) return wave_on && i < NB && block_pos(i) <= win.hi_max;
-    else return wave_on && i < NB && (!a.causal || block_pos(i) <= q_hi);
+    else return wave_on && i <= last_on;
   };
   // Packed tiles: has the stream reached the first row that some row of the wave sees by block i?
   // Once true it stays true.  A step skipped before that leaves its accumulators at their initial
@@ -193,11 +214,15 @@ __global__ void __launch_bounds__(NW * 64, 2) hstu_fwd_bf16(AttnArgs a) {
         for (int e = 0; e < 8; ++e) pb[x][y][e] = (__bf16)0.f;
     }
     auto mask_of = [&](int i) {
-      return PACKED ? win.masks(block_pos(i)) : (a.causal && block_pos(i) + 31 > q_lo);
+      if constexpr (PACKED) return win.masks(block_pos(i));
+      else return i >= first_masked;
     };
-    auto vis_of = [&](int i) {
-      if constexpr (PACKED) return win.vis(block_pos(i), hh);
-      else return VisBefore{q_lo + n - block_pos(i), hh};
+    auto vis_of = [&](int i) {  // (made on the masked path only)
+      return [&, i] {
+        const int pos = block_pos(i);
+        if constexpr (PACKED) return win.vis(pos, hh);
+        else return VisBefore{q_lo + n - pos, hh};
+      };
     };
     BlockTable tab = {};
     if constexpr (BIAS) {
