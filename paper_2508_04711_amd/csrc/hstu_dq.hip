@@ -67,11 +67,27 @@ __device__ __forceinline__ void dq_block(const BiasCtx& bias, const char* trec,
   for (int ks = 0; ks < DQK / 16; ++ks) s = mfma(rak.read(kt, blk, ks), qreg[ks], s);
 #pragma unroll
   for (int ks = 0; ks < DV / 16; ++ks) dp = mfma(rav.read(vt, blk, ks), greg[ks], dp);
+  // Stage by stage over eight elements at a time, so that no instruction consumes the result of
+  // its predecessor (exp and rcp results are late: a dependent successor costs a hazard nop and
+  // stalled cycles).  p' = s * sg; ds' = dp * (sg + alpha * p' * (1 - sg)).
   float ds[16];
 #pragma unroll
-  for (int r = 0; r < 16; ++r) {
-    float p;
-    bwd_elem(s[r], dp[r], c1, alpha, p, ds[r]);
+  for (int h = 0; h < 16; h += 8) {
+    float t[8], g[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) t[j] = s[h + j] * c1;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) t[j] = __builtin_amdgcn_exp2f(t[j]);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) t[j] = 1.0f + t[j];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) g[j] = __builtin_amdgcn_rcpf(t[j]);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) t[j] = alpha * (s[h + j] * g[j]);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) t[j] = t[j] * (1.0f - g[j]) + g[j];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) ds[h + j] = dp[h + j] * t[j];
   }
   if (mask) {
 #pragma unroll
