@@ -69,7 +69,9 @@ __device__ __forceinline__ void dkdv_step(const Init& init, const char* qn, cons
   // 64 / NS elements, one stage per slot, so that an instruction's operands were produced a few
   // instructions earlier and not by its predecessor (a lone wave pays every such dependence, most
   // of all behind exp and rcp, in stalled cycles and hazard nops).
-  constexpr bool STAGED = NS == 4 || NS == 8 || NS == 16;
+  // (Only where a wave has the whole register file: the variants built for two workgroups per CU
+  // are at their limit of 256, and the values in flight would spill.)
+  constexpr bool STAGED = DQK + DV > 128 && (NS == 8 || NS == 16);
   constexpr int EPG = STAGED ? 64 / NS : 1;
   float st_t[EPG], st_g[EPG];
 #pragma unroll
@@ -357,12 +359,17 @@ __global__ void __launch_bounds__(NW * 64, (DQK + DV <= 128 ? 2 : 1)) hstu_dkdv_
   Item it;
   const int64_t bound = a.xcd_parts <= 1 ? (int64_t)a.max_items * a.num_heads
                                          : 8 * (((int64_t)a.max_items + a.xcd_parts - 1) / a.xcd_parts);
-  if (!PACKED && gridDim.x >= bound) {
+  // (The variants built for two workgroups per CU never walk - the host launches them on the whole
+  // grid - and are compiled without that path, whose prefetched descriptions would cost them
+  // registers they do not have.)
+  constexpr bool CAN_WALK = DQK + DV > 128;
+  if (!CAN_WALK || (!PACKED && gridDim.x >= bound)) {
     const Unit un = unit_of(a, blockIdx.x);
-    if (!un.on || !fetch_item(a.plan, un.slot, it)) return;
+    if (!un.on || !fetch_item<PACKED>(a.plan, un.slot, it)) return;
     dkdv_item<DQK, DV, NW, BIAS, PACKED>(a, it, un.h);
     return;
   }
+  if constexpr (CAN_WALK) {
   const int n = a.plan.header[0];
   const int units = unit_count(a, n);
   // Every gridDim.x-th unit from blockIdx.x on - or, for a schedule in natural order (walk_chunks),
@@ -411,6 +418,7 @@ __global__ void __launch_bounds__(NW * 64, (DQK + DV <= 128 ? 2 : 1)) hstu_dkdv_
     if (!more) break;
     tile_barrier();  // every wave has left the item's tiles before the next item's copies land
   }
+  }  // CAN_WALK
 }
 
 }  // namespace

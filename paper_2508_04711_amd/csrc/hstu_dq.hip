@@ -70,7 +70,16 @@ __device__ __forceinline__ void dq_block(const BiasCtx& bias, const char* trec,
   // Stage by stage over eight elements at a time, so that no instruction consumes the result of
   // its predecessor (exp and rcp results are late: a dependent successor costs a hazard nop and
   // stalled cycles).  p' = s * sg; ds' = dp * (sg + alpha * p' * (1 - sg)).
+  // (Not with the bias: its variants are at the register limit, and the sixteen values in flight
+  // would spill.)
   float ds[16];
+  if constexpr (BIAS) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      float p;
+      bwd_elem(s[r], dp[r], c1, alpha, p, ds[r]);
+    }
+  } else {
 #pragma unroll
   for (int h = 0; h < 16; h += 8) {
     float t[8], g[8];
@@ -88,6 +97,7 @@ __device__ __forceinline__ void dq_block(const BiasCtx& bias, const char* trec,
     for (int j = 0; j < 8; ++j) t[j] = t[j] * (1.0f - g[j]) + g[j];
 #pragma unroll
     for (int j = 0; j < 8; ++j) ds[h + j] = dp[h + j] * t[j];
+  }
   }
   if (mask) {
 #pragma unroll
