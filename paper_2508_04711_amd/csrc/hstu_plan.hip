@@ -280,6 +280,10 @@ __device__ __forceinline__ void plan_body(const PlanArgs& a) {
     pvis[0] = von[0] ? vvis[0] : (first1 ? vvis[1] : 0);
     pvis[1] = second ? vvis[1] : 0;
     }
+    if (a.split_max <= 1 && a.cost_shift >= 30) {  // natural order: nothing to sort
+      if (active) { a.items[i] = it; a.order[i] = i; }
+      continue;
+    }
     if (a.split_max <= 1) {
       if (active) a.items[i] = it;
       bin = it.cost >> a.cost_shift;
@@ -346,8 +350,9 @@ __device__ __forceinline__ void plan_body(const PlanArgs& a) {
   const int items_final = a.split_max > 1 ? (carry_sub < a.max_items ? carry_sub : a.max_items) : num_items;
   __syncthreads();
 
+  const bool sorted = !(a.split_max <= 1 && a.cost_shift >= 30);
   // ---- pass 3: bin start positions (exclusive scan over the reversed histogram) ----------
-  {
+  if (sorted) {
     const int h0 = hist[2 * tid], h1 = hist[2 * tid + 1];
     int tot;
     const int inc = block_scan(h0 + h1, scan_buf, &tot);
@@ -357,7 +362,7 @@ __device__ __forceinline__ void plan_body(const PlanArgs& a) {
   __syncthreads();
 
   // ---- pass 4: scatter item indices into schedule order ----------------------------------
-  for (int i0 = 0; i0 < items_final; i0 += PLAN_THREADS) {
+  for (int i0 = 0; sorted && i0 < items_final; i0 += PLAN_THREADS) {
     const int i = i0 + tid;
     const bool active = i < items_final;
     int bin = active ? a.items[i].cost >> a.cost_shift : 0;
