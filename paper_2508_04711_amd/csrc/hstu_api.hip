@@ -254,6 +254,8 @@ int prepare_plan(const hstu_attn_params* p, int cp_size, const SideSpec& s, cons
   a.tile_base = reinterpret_cast<int32_t*>(ws + l.tile_base);
   a.stile_base = reinterpret_cast<int32_t*>(ws + l.stile_base);
   a.ttile = reinterpret_cast<int32_t*>(ws + l.ttile);
+  // only the forward pass with a transposed copy of V reads it (see make_tcopy)
+  a.want_ttile = s.pass == PASS_FWD && p->dtype == HSTU_BF16 && !short_sequences(p) ? 1 : 0;
   a.order = reinterpret_cast<int32_t*>(ws + l.order);
   a.items = reinterpret_cast<Item*>(ws + l.items);
   *args = a;

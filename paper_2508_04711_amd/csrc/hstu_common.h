@@ -94,6 +94,7 @@ struct PlanArgs {
   int32_t* tile_base;
   int32_t* stile_base;
   int32_t* ttile;
+  int32_t want_ttile;     // the streamed side's tile table is needed (a transposed copy will be built from it)
   int32_t* order;
   Item* items;
 };

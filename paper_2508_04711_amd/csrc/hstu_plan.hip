@@ -185,7 +185,7 @@ __device__ __forceinline__ void plan_body(const PlanArgs& a) {
   const int num_stiles = num_stiles_s;
 
   // ---- pass 1b: the 64-row tiles of the streamed side (what the transposed copies are cut into)
-  for (int i = tid; i < num_stiles; i += PLAN_THREADS) {
+  for (int i = tid; a.want_ttile && i < num_stiles; i += PLAN_THREADS) {
     int lo = 0, hi = a.batch;
     while (hi - lo > 1) {
       const int mid = (lo + hi) >> 1;
