@@ -75,3 +75,12 @@ def test_occupancy_and_lds_match_the_launch_configuration():
             assert waves_per_simd >= 2 and lds <= 80 * 1024, (dqk, dv, flags, waves_per_simd, lds)
         else:
             assert waves_per_simd >= 1 and lds <= 160 * 1024, (dqk, dv, flags, waves_per_simd, lds)
+
+
+def test_helper_kernels_use_no_scratch():
+    """The schedule, reorder, transpose, reduce and record kernels: no spills, no scratch memory."""
+    k = _kernels()
+    helpers = {sym: v for sym, v in k.items() if "_bf16I" not in sym and "_f32I" not in sym}
+    assert len(helpers) >= 6, sorted(helpers)
+    for sym, v in helpers.items():
+        assert int(v["VGPRs_Spill"]) == 0 and int(v["ScratchSize_[bytes/lane]"]) == 0, (sym, v)
