@@ -146,3 +146,49 @@ def test_config4_every_rank_sampled():
     ek = np.abs(dk_sum[sel].double().cpu().numpy() - sdk).max() / float(np.sqrt((sdk ** 2).mean()))
     ev = np.abs(dv_sum[sel].double().cpu().numpy() - sdv).max() / float(np.sqrt((sdv ** 2).mean()))
     assert ek <= 2e-2 and ev <= 2e-2, (ek, ev)
+
+
+@pytest.mark.parametrize("cp", [2, 4])
+def test_large_batch_rank_partials_against_all_keys(cp):
+    """4096 sequences of 64..512 rows, H = 4, d = 128: a batch large enough for the natural item
+    order, the XCD-aware workgroup map and the dK/dV workgroups that walk over items, here with the
+    two-segment items of a context-parallel rank.  Every rank's partial against all keys (as the
+    benchmark runs them), scattered back; sampled sequences against the oracle's full attention."""
+    import paper_2508_04711_amd as lib
+    rng = np.random.default_rng(31 + cp)
+    B, H, d = 4096, 4, 128
+    lengths = [int(x) for x in rng.integers(64, 513, size=B)]
+    w = workloads.custom("cp_large_batch", lengths, H, d, d, 512, dtype="bf16", seed=60 + cp)
+    dev = workloads.device_values(w)
+    off_np = w.seq_offsets()
+    off = torch.from_numpy(off_np).cuda()
+    T = w.total_rows
+    o = torch.zeros((T, H, d), dtype=torch.bfloat16, device="cuda")
+    dq = torch.zeros_like(o)
+    dk = torch.zeros((T, H, d), dtype=torch.float32, device="cuda")
+    dv = torch.zeros_like(dk)
+    for r in range(cp):
+        n = len(oracle.cp_global_rows(off_np, cp, r))
+        print("cp large batch", cp, r, n, flush=True)
+        ql, gl = lib.hstu_cp_reorder([dev["q"], dev["d_o"]], off, T, cp, r, n)
+        ol, dql, dkp, dvp = lib.hstu_jagged_attn_cp_partial(ql, dev["k"], dev["v"], gl, off, T, w.max_len, w.alpha,
+                                                            True, cp, r, -1)
+        lib.hstu_cp_reorder([ol, dql], off, T, cp, r, n, scatter=True, out=[o, dq])
+        dk += dkp.float()
+        dv += dvp.float()
+    torch.cuda.synchronize()
+    seqs = [0, 1, B // 2 - 1, B // 2, B - 2, B - 1]
+    rows = np.concatenate([np.arange(off_np[b], off_np[b + 1]) for b in seqs])
+    rows_t = torch.from_numpy(rows).cuda()
+    sub = {k: workloads.to_f64(v[rows_t]) for k, v in dev.items()}
+    sub_off = np.concatenate([[0], np.cumsum([lengths[b] for b in seqs])]).astype(np.int32)
+    want = oracle.rows(sub["q"], sub["k"], sub["v"], sub["d_o"], sub_off, w.max_len, w.alpha, True,
+                       np.arange(len(rows)))
+    for name, got, ref in zip(("o", "dq", "dk", "dv"), (o, dq, dk, dv), want):
+        g = got[rows_t].double().cpu().numpy()
+        rms = float(np.sqrt((ref ** 2).mean()))
+        # dk and dv are sums of cp bf16 partial results: cp roundings instead of one
+        excess = np.abs(g - ref) - (2e-2 * rms + np.abs(ref) * 2.0 ** -7)
+        assert excess.max() <= 0, (cp, name, float(np.abs(g - ref).max() / rms))
+    for t in (o, dq, dk, dv):
+        assert torch.isfinite(t.float()).all()
