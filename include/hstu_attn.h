@@ -70,7 +70,9 @@ typedef enum {
   HSTU_ERR_WORKSPACE_TOO_SMALL = -4, /* workspace_bytes below the query function's answer   */
   HSTU_ERR_BAD_CP = -5,              /* cp_size < 1, a rank out of range, negative rows     */
   HSTU_ERR_HIP = -6,                 /* a HIP call failed; hipGetLastError() is left intact */
-  HSTU_ERR_MISALIGNED = -7           /* a data pointer is not 16-byte aligned               */
+  HSTU_ERR_MISALIGNED = -7,          /* a data pointer is not 16-byte aligned               */
+  HSTU_ERR_STATIC_SCRATCH = -8       /* hstu_jagged_attn_fwd_static: the problem needs more
+                                        scratch than HSTU_STATIC_SCRATCH_BYTES                */
 } hstu_status;
 
 typedef enum { HSTU_BF16 = 0, HSTU_F32 = 1 } hstu_dtype;
@@ -120,6 +122,26 @@ typedef struct {
 int hstu_jagged_attn_fwd(const hstu_attn_params* params, const void* q, const void* k,
                          const void* v, const int32_t* seq_offsets, void* o, void* workspace,
                          size_t workspace_bytes, void* hip_stream);
+
+/* hstu_jagged_attn_fwd for callers that cannot allocate device memory or hand over a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, layouts, results (bit for bit) and errors, without the workspace: the schedule, the
+ * transposed copy of V and the partial results of split tiles live in a static device array of
+ * HSTU_STATIC_SCRATCH_BYTES inside the library, which every GPU the library runs on holds until
+ * the process ends.  A problem whose hstu_jagged_attn_workspace_bytes(params, HSTU_WS_FWD) exceeds
+ * that size is refused with HSTU_ERR_STATIC_SCRATCH and nothing is launched (batches whose mean
+ * sequence length is at most 1024 need a few hundred bytes per sequence and 64 per 128 rows;
+ * longer sequences add a copy of V and, from max_len 4096 on, up to
+ * (rows / 128 + batch + 1024 / num_heads + 2) * num_heads * 128 * d_v * 4 bytes of partial results).
+ * The call allocates nothing: no hipMalloc, hipFree or allocating library routine.  The device of
+ * `hip_stream` must be the current device; the array's address on that device is looked up at the
+ * first call there.  All calls on one GPU share that GPU's array: calls that overlap in time on
+ * one GPU (different streams, or threads) race, and must be serialised by the caller.  Nothing
+ * in the array has to survive between calls, and nothing in it is assumed to be zero. */
+#define HSTU_STATIC_SCRATCH_BYTES (16u << 20)
+size_t hstu_static_scratch_bytes(void);
+int hstu_jagged_attn_fwd_static(const hstu_attn_params* params, const void* q, const void* k,
+                                const void* v, const int32_t* seq_offsets, void* o, void* hip_stream);
 
 /* Backward: exact gradients of sum(O * d_o) with respect to q, k, v.  S is
  * recomputed from q and k; no forward output or statistic is needed because the

@@ -18,8 +18,10 @@ from .binding import (  # noqa: F401
     hstu_jagged_attn_cp_partial,
     hstu_jagged_attn_cp_partial_bias,
     hstu_jagged_attn_fwd,
+    hstu_jagged_attn_fwd_static,
     hstu_jagged_attn_workspace_bytes,
     hstu_schedule_tile_rows,
+    hstu_static_scratch_bytes,
     hstu_validate_offsets_host,
     library_path,
     load_library,

@@ -96,6 +96,10 @@ def load_library():
     pp = ctypes.POINTER(_Params)
     lib.hstu_jagged_attn_fwd.restype = ctypes.c_int
     lib.hstu_jagged_attn_fwd.argtypes = [pp, vp, vp, vp, i32p, vp, vp, ctypes.c_size_t, vp]
+    lib.hstu_jagged_attn_fwd_static.restype = ctypes.c_int
+    lib.hstu_jagged_attn_fwd_static.argtypes = [pp, vp, vp, vp, i32p, vp, vp]
+    lib.hstu_static_scratch_bytes.restype = ctypes.c_size_t
+    lib.hstu_static_scratch_bytes.argtypes = []
     lib.hstu_jagged_attn_bwd.restype = ctypes.c_int
     lib.hstu_jagged_attn_bwd.argtypes = [pp, vp, vp, vp, vp, i32p, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.hstu_jagged_attn_cp_partial.restype = ctypes.c_int
@@ -239,6 +243,30 @@ def hstu_jagged_attn_fwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor,
                                              _stream(stream))
     if rc != 0:
         raise HstuError(rc, "hstu_jagged_attn_fwd")
+    return out
+
+
+def hstu_static_scratch_bytes() -> int:
+    """Size of the static device array hstu_jagged_attn_fwd_static works in."""
+    return int(load_library().hstu_static_scratch_bytes())
+
+
+def hstu_jagged_attn_fwd_static(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor,
+                                seq_offsets: torch.Tensor, max_len: int, alpha: float,
+                                causal: bool, out: torch.Tensor, stream=None) -> torch.Tensor:
+    """hstu_jagged_attn_fwd without a workspace and without any allocation: `out` is the caller's."""
+    T, H, dqk = q.shape
+    dv = v.shape[2]
+    _check_tensor(q, "q", T, H, dqk, q.dtype); _check_tensor(k, "k", T, H, dqk, q.dtype)
+    _check_tensor(v, "v", T, H, dv, q.dtype); _check_tensor(out, "out", T, H, dv, out.dtype)
+    if seq_offsets.dtype != torch.int32 or not seq_offsets.is_cuda or not seq_offsets.is_contiguous():
+        raise ValueError("seq_offsets must be a contiguous int32 device tensor")
+    p = _params(seq_offsets.numel() - 1, H, dqk, dv, max_len, alpha, causal, _dtype_code(q), T,
+                _code(out.dtype))
+    rc = load_library().hstu_jagged_attn_fwd_static(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v),
+                                                    _ptr(seq_offsets), _ptr(out), _stream(stream))
+    if rc != 0:
+        raise HstuError(rc, "hstu_jagged_attn_fwd_static")
     return out
 
 

@@ -1,7 +1,9 @@
 // C ABI of the jagged HSTU attention library: argument checks, workspace carving, launches.
 // See include/hstu_attn.h for the contract of every entry point.
+#include <atomic>
 #include <cmath>
 #include <cstdlib>
+#include <mutex>
 #include <vector>
 
 #include "../../include/hstu_attn.h"
@@ -481,6 +483,7 @@ const char* hstu_attn_status_string(int status) {
     case HSTU_ERR_BAD_CP: return "bad context-parallel descriptor";
     case HSTU_ERR_HIP: return "a HIP call failed";
     case HSTU_ERR_MISALIGNED: return "a data pointer is not 16-byte aligned";
+    case HSTU_ERR_STATIC_SCRATCH: return "the problem needs more scratch than the library's static buffer holds";
     default: return "unknown status";
   }
 }
@@ -599,6 +602,49 @@ int hstu_jagged_attn_bias_fwd(const hstu_attn_params* params, const hstu_ts_bias
                               size_t workspace_bytes, void* hip_stream) {
   if (!bias) return HSTU_ERR_NULL_PTR;
   return fwd_impl(params, bias, q, k, v, seq_offsets, o, workspace, workspace_bytes, hip_stream);
+}
+
+// ---- forward for callers that cannot allocate -----------------------------------------------
+// The same forward with its scratch (schedule, transposed copy of V, partial results) in a static
+// device array instead of a caller's workspace.  Host code never uses the array's name as an
+// address: the device address is looked up once per device and kept.
+constexpr size_t STATIC_SCRATCH_BYTES = (size_t)HSTU_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+constexpr int STATIC_MAX_DEVICES = 64;
+static std::atomic<void*> g_scratch_ptr[STATIC_MAX_DEVICES];
+static std::mutex g_scratch_mutex;
+
+// Address of the current device's copy of the array (looked up at the first call on that device).
+static int static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= STATIC_MAX_DEVICES) return HSTU_ERR_HIP;
+  void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!p) {
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    p = g_scratch_ptr[dev].load(std::memory_order_relaxed);
+    if (!p) {
+      if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return HSTU_ERR_HIP;
+      g_scratch_ptr[dev].store(p, std::memory_order_release);
+    }
+  }
+  *out = p;
+  return HSTU_OK;
+}
+
+size_t hstu_static_scratch_bytes(void) { return STATIC_SCRATCH_BYTES; }
+
+int hstu_jagged_attn_fwd_static(const hstu_attn_params* params, const void* q, const void* k,
+                                const void* v, const int32_t* seq_offsets, void* o, void* hip_stream) {
+  const int rc = check_params(params);
+  if (rc != HSTU_OK) return rc;
+  if (params->batch == 0 || params->total_rows == 0) return HSTU_OK;
+  if (!q || !k || !v || !o || !seq_offsets) return HSTU_ERR_NULL_PTR;
+  const size_t need = hstu_jagged_attn_workspace_bytes(params, HSTU_WS_FWD);
+  if (need == 0 || need > STATIC_SCRATCH_BYTES) return HSTU_ERR_STATIC_SCRATCH;
+  void* ws = nullptr;
+  const int rs = static_scratch(&ws);
+  if (rs != HSTU_OK) return rs;
+  return fwd_impl(params, nullptr, q, k, v, seq_offsets, o, ws, STATIC_SCRATCH_BYTES, hip_stream);
 }
 
 // Backward over the whole batch, with the timestamp bias if `bias` is not null.

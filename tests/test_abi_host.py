@@ -228,3 +228,19 @@ def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(binding, "_LIB_PATH", "/nonexistent/libhstu_attn.so")
     with pytest.raises(RuntimeError):
         binding.load_library()
+
+
+def test_static_scratch_forward_refuses_large_problems_on_the_host(lib):
+    """The forward without workspace checks the size before any device call: a problem whose
+    workspace exceeds the static array is refused with its own status, and the limit is exported."""
+    from paper_2508_04711_amd import binding
+    assert lib.hstu_static_scratch_bytes() == 16 << 20
+    big = _params(binding, batch=8, num_heads=8, d_qk=128, d_v=128, max_len=32768, total_rows=96016)
+    assert lib.hstu_jagged_attn_workspace_bytes(ctypes.byref(big), 0) > (16 << 20)
+    one = ctypes.c_void_p(4096)  # never dereferenced: the size check comes first
+    assert lib.hstu_jagged_attn_fwd_static(ctypes.byref(big), one, one, one, one, one, None) == -8
+    assert b"static" in lib.hstu_attn_status_string(-8)
+    bad = _params(binding, d_qk=48)
+    assert lib.hstu_jagged_attn_fwd_static(ctypes.byref(bad), one, one, one, one, one, None) == -3
+    empty = _params(binding, batch=0, total_rows=0)
+    assert lib.hstu_jagged_attn_fwd_static(ctypes.byref(empty), None, None, None, None, None, None) == 0
