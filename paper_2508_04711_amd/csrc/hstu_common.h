@@ -261,6 +261,9 @@ hipError_t launch_reduce_partials(const Plan& plan, int64_t max_tiles, const flo
 
 hipError_t launch_fwd_bf16(const AttnArgs& a, int d_qk, int d_v, hipStream_t stream);
 hipError_t launch_dkdv_bf16(const AttnArgs& a, int d_qk, int d_v, hipStream_t stream);
+// The dk/dv pass with two waves per 32 keys (plain per-sequence schedules at d_qk = d_v = 128).
+bool dkdv_pair_supported(const AttnArgs& a, int d_qk, int d_v);
+hipError_t launch_dkdv_pair_bf16(const AttnArgs& a, int d_qk, int d_v, hipStream_t stream);
 hipError_t launch_dq_bf16(const AttnArgs& a, int d_qk, int d_v, hipStream_t stream);
 hipError_t launch_fwd_f32(const AttnArgs& a, int d_qk, int d_v, hipStream_t stream);
 hipError_t launch_dkdv_f32(const AttnArgs& a, int d_qk, int d_v, hipStream_t stream);
