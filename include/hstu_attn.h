@@ -31,21 +31,20 @@
  *     out_dtype is fp32); fp32 inputs are computed in fp32 throughout.
  *   - `workspace` is caller-owned device scratch of at least
  *     hstu_jagged_attn_workspace_bytes() bytes, 256-byte aligned.  The library
- *     allocates nothing and keeps no state between calls; calls are
+ *     allocates no device memory and keeps no state between calls (the two
+ *     exceptions are named where they are declared: the static scratch array of
+ *     hstu_jagged_attn_fwd_static and the timing recorder); calls are
  *     asynchronous on `hip_stream` (a hipStream_t, NULL = the default stream)
  *     and calls on different streams with different workspaces may overlap.
- *   - Environment: HSTU_ATTN_FWD_TILE=128 or 256 overrides the query-tile height the bf16
- *     forward pass picks from the problem size, and makes it use the transposed copy of V
- *     whatever the mean sequence length (testing and tuning only; results are the same to
- *     rounding; set it before the workspace query too, which it affects).
- *     HSTU_ATTN_NO_SPLIT (any value) keeps the forward and dQ passes from cutting heavy query
- *     tiles along the keys when a problem has too few tiles to fill the chip; with it the
- *     result of a query row does not depend on how many other rows the call has (bit for bit).
- *     Batches of very short sequences (bf16, mean length total_rows / batch of at most 256) are
- *     tiled 128 rows at a time across sequence boundaries by the whole-batch calls, with or
- *     without bias ("packed tiles"); HSTU_ATTN_NO_PACK (any value) turns that off, HSTU_ATTN_PACK_LEN=<n>
- *     moves the threshold (at most 1024).  With packed tiles the last bits of a row's result
- *     depend on the sequences that share its tile.  Set either before the workspace query too.
+ *   - Sizes: total_rows < 2^31; (rows / 128 + 2 * batch + 1) * num_heads < 2^31; and
+ *     where a bf16 forward pass builds its transposed copy of V (mean sequence
+ *     length total_rows / batch above 1024, or a forced tile height) the key
+ *     side may hold at most 131071 tiles of 64 rows, sequences' last tiles
+ *     included (about 8.3 million rows).  Beyond: HSTU_ERR_BAD_SHAPE, and the
+ *     workspace query returns 0.
+ *   - Nothing in the process environment changes what a call does: the choices a caller (or a
+ *     test) may want to force are bits of `params->flags` (hstu_flags below), and the same flags
+ *     must be given to the workspace query and to the call.
  *   - Return value: HSTU_OK (0) or a negative hstu_status.  Nothing is launched
  *     when an error is returned.  batch == 0 or total_rows == 0 is HSTU_OK and
  *     launches nothing.  No exception or abort crosses this boundary.
@@ -66,7 +65,7 @@ typedef enum {
   HSTU_ERR_BAD_SHAPE = -2,           /* batch < 0, num_heads < 1, total_rows < 0 or
                                         >= 2^31, max_len < 1, alpha not finite              */
   HSTU_ERR_UNSUPPORTED = -3,         /* head dim not in {32,64,128}, unknown dtype, out_dtype
-                                        neither dtype nor fp32, reserved != 0               */
+                                        neither dtype nor fp32, unknown bits in flags       */
   HSTU_ERR_WORKSPACE_TOO_SMALL = -4, /* workspace_bytes below the query function's answer   */
   HSTU_ERR_BAD_CP = -5,              /* cp_size < 1, a rank out of range, negative rows     */
   HSTU_ERR_HIP = -6,                 /* a HIP call failed; hipGetLastError() is left intact */
@@ -78,6 +77,28 @@ typedef enum {
 typedef enum { HSTU_BF16 = 0, HSTU_F32 = 1 } hstu_dtype;
 
 typedef enum { HSTU_WS_FWD = 0, HSTU_WS_BWD = 1, HSTU_WS_CP = 2 } hstu_ws_kind;
+
+/* Bits of hstu_attn_params.flags.  0 is the normal choice everywhere; the bits force one of the
+ * library's forms where it would otherwise pick by problem size (testing, tuning, bit-for-bit
+ * reproducibility).  Results are the same to rounding whatever the flags. */
+typedef enum {
+  HSTU_FLAG_NO_SPLIT = 1,       /* the forward and dQ passes never cut heavy query tiles along the keys
+                                   (done when a problem has too few tiles to fill the chip); with it
+                                   and HSTU_FLAG_NO_PACK a query row's result does not depend, bit for
+                                   bit, on how many other rows the call has                        */
+  HSTU_FLAG_NO_PACK = 2,        /* never tile across sequence boundaries ("packed tiles": bf16
+                                   whole-batch calls whose mean length total_rows / batch is at
+                                   most 256 tile the batch 128 rows at a time whatever sequences
+                                   the rows belong to; the last bits of a row's result then depend
+                                   on the sequences that share its tile)                          */
+  HSTU_FLAG_PACK_SHORT = 4,     /* packed tiles up to a mean length of 1024 instead of 256         */
+  HSTU_FLAG_FWD_TILE_128 = 8,   /* bf16 forward: 128-row query tiles with the transposed copy of V,
+                                   whatever the problem size and the mean sequence length         */
+  HSTU_FLAG_FWD_TILE_256 = 16,  /* ... 256-row query tiles                                         */
+  HSTU_FLAG_DKDV_ONE_WAVE = 32  /* dk/dv pass at d_qk = d_v = 128: the kernel with one wave per 32
+                                   keys instead of the one that splits the work over two          */
+} hstu_flags;
+#define HSTU_FLAGS_ALL 63
 
 /* Problem description (section 2.1 for alpha and the mask, section 2.2 for the
  * jagged batch).  `total_rows` is passed by value so that grids and workspaces
@@ -96,7 +117,7 @@ typedef struct {
   int32_t out_dtype;   /* hstu_dtype of the outputs o, dq, dk, dv: equal to dtype, or
                           HSTU_F32 to receive the fp32 accumulators unrounded (also the
                           precise choice for accumulate = 1 over several ring steps)      */
-  int32_t reserved;    /* must be 0                                                        */
+  int32_t flags;       /* 0, or an OR of hstu_flags; other bits HSTU_ERR_UNSUPPORTED            */
 } hstu_attn_params;
 
 /* One context-parallel step (section 2.3).  Local layout of rank r: for every
@@ -143,9 +164,11 @@ size_t hstu_static_scratch_bytes(void);
 int hstu_jagged_attn_fwd_static(const hstu_attn_params* params, const void* q, const void* k,
                                 const void* v, const int32_t* seq_offsets, void* o, void* hip_stream);
 
-/* Backward: exact gradients of sum(O * d_o) with respect to q, k, v.  S is
- * recomputed from q and k; no forward output or statistic is needed because the
- * SiLU is pointwise.  dk and dv are accumulated per key tile without atomics;
+/* Backward of the section 2.1 equation (the paper trains with it but does not print it; derived:
+ * with x = alpha*<q_i,k_j>, sg = sigmoid(x), p = x*sg/N, dp = <d_o_i, v_j>/N, ds = dp*sg*(1+x*(1-sg)):
+ * dv_j += p*d_o_i, dq_i += alpha*ds*k_j, dk_j += alpha*ds*q_i over the visible pairs): exact
+ * gradients of sum(O * d_o) with respect to q, k, v.  S is recomputed from q and k; no forward
+ * output or statistic is needed because the SiLU is pointwise.  dk and dv are accumulated per key tile without atomics;
  * dq is produced by a second pass over key tiles, so results are deterministic.
  *   d_o : [T, H, d_v] (input)    dq, dk : [T, H, d_qk]   dv : [T, H, d_v] (outputs)
  */
@@ -253,6 +276,9 @@ int hstu_jagged_attn_cp_partial_bias(const hstu_attn_params* params, const hstu_
  * rounding between steps is acceptable.  The rank's contribution to the key-side gradients of
  * each part goes to dk_parts[r] / dv_parts[r] (added to them when accumulate_dkv != 0, as the
  * gradient buffer that travels with a part would be).
+ * The call creates five HIP events (host objects, no device memory) for the ordering between the
+ * two streams and destroys them before it returns; it is therefore not a call to make under
+ * stream capture.
  * All arrays of the descriptor are host arrays of cp_size entries; the pointers in them are
  * device pointers.  Both streams must be distinct; on return everything is enqueued, the
  * compute stream carries the results, and the copy stream has been made to wait for the work
@@ -322,8 +348,8 @@ int hstu_cp_reorder(int32_t batch, int64_t total_rows, int32_t cp_size, int32_t 
  * that depends on batch, total_rows, num_heads, d_v and dtype only; 0 on invalid params).
  * Schedules, plus for bf16 forward passes over batches whose mean sequence length
  * total_rows / batch exceeds 1024 a transposed copy of V, plus fp32 partial results where heavy
- * query tiles may be cut along the keys, plus 8 bytes per row for packed tiles.  The
- * environment variables above change the answer: set them before asking.
+ * query tiles may be cut along the keys, plus 8 bytes per row for packed tiles.  The flags
+ * change the answer: ask with the flags of the call.
  * `which` is a hstu_ws_kind. */
 size_t hstu_jagged_attn_workspace_bytes(const hstu_attn_params* params, int which);
 
@@ -358,10 +384,30 @@ int hstu_debug_dump_schedule(const hstu_attn_params* params, const hstu_cp_desc*
  *   end:   waits for the recorded launches, writes per launch, in launch order, its kind
  *          (0 forward, 1 dk/dv pass, 2 dq pass, 3 schedule build, 4 transposed copy,
  *          5 reorder, 6 sum of the partial results of split tiles, 7 timestamp records,
- *          8 scaling of the bias table's gradient) and its duration in milliseconds; returns the number written (<= capacity) or a status < 0.
+ *          8 scaling of the bias table's gradient, 9 matrix-instruction loop, 10 atomic-rate kernel) and its duration in milliseconds; returns the number written (<= capacity) or a status < 0.
  */
 int hstu_debug_timing_begin(int max_records);
 int hstu_debug_timing_end(int32_t* kinds, float* milliseconds, int capacity);
+
+/* ---- measurement kernels (the measurement section: what the attention kernels' rates are read
+ * against) -----------------------------------------------------------------------------------
+ * hstu_debug_mfma_loop: one launch of a kernel that issues nothing but v_mfma_f32_32x32x16_bf16 in
+ * its loop (two workgroups of four waves per CU, four independent accumulators per wave,
+ * `iterations` x 4 instructions per wave), with the same operand values in every lane
+ * (random_operands = 0) or different ones (1: the chip's power limit, and with it the clock it
+ * holds, depends on the data).  *flops_per_launch receives the flops of the launch (host pointer);
+ * the caller times it (kind 9 of the timing recorder).  sink: device, 64 floats, never written in
+ * practice.  This is the rate the matrix cores sustain on this machine; the published peak assumes
+ * the 2.4 GHz clock.
+ * hstu_debug_dq_atomic_rate: one launch of 256 workgroups (one per CU) that add 1.0 with fp32
+ * atomics (no return value) to dq_f32 [rows, num_heads, 128] in the pattern a dk/dv pass would need
+ * to produce dq itself: per 32-row block 16 KB per workgroup, each instruction covering two rows
+ * of 128 contiguous bytes; head_per_xcd != 0 keeps every head's rows to one XCD (num_heads = 8).
+ * *payload_bytes_per_launch receives the bytes added (host pointer); kind 10 of the recorder. */
+int hstu_debug_mfma_loop(int random_operands, int iterations, float* sink, double* flops_per_launch,
+                         void* hip_stream);
+int hstu_debug_dq_atomic_rate(float* dq_f32, int64_t rows, int32_t num_heads, int32_t blocks,
+                              int32_t head_per_xcd, double* payload_bytes_per_launch, void* hip_stream);
 
 /* Rows per work item on the given side for a whole-batch problem described by `params` (the
  * tile height depends on the problem size: large problems use taller query tiles). */

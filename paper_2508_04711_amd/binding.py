@@ -7,6 +7,7 @@ There is no fallback path: if the HIP library is missing, loading raises.
 from __future__ import annotations
 
 import ctypes
+import functools
 import os
 from typing import Optional, Tuple
 
@@ -20,6 +21,31 @@ _lib = None
 
 HSTU_BF16, HSTU_F32 = 0, 1
 HSTU_WS_FWD, HSTU_WS_BWD, HSTU_WS_CP = 0, 1, 2
+# hstu_flags (include/hstu_attn.h)
+HSTU_FLAG_NO_SPLIT, HSTU_FLAG_NO_PACK, HSTU_FLAG_PACK_SHORT = 1, 2, 4
+HSTU_FLAG_FWD_TILE_128, HSTU_FLAG_FWD_TILE_256, HSTU_FLAG_DKDV_ONE_WAVE = 8, 16, 32
+
+# The flags every call of this module passes in hstu_attn_params.flags (0: the library's own
+# choices).  Tests and benchmarks set it, preferably through the `flags` context manager.
+default_flags = 0
+
+
+class flags:
+    """with flags(HSTU_FLAG_NO_PACK | ...): calls inside pass these hstu_flags."""
+
+    def __init__(self, value: int):
+        self.value = int(value)
+
+    def __enter__(self):
+        global default_flags
+        self.saved = default_flags
+        default_flags = self.value
+        return self
+
+    def __exit__(self, *exc):
+        global default_flags
+        default_flags = self.saved
+        return False
 
 
 class HstuError(RuntimeError):
@@ -33,7 +59,7 @@ class _Params(ctypes.Structure):
         ("batch", ctypes.c_int32), ("num_heads", ctypes.c_int32), ("d_qk", ctypes.c_int32),
         ("d_v", ctypes.c_int32), ("max_len", ctypes.c_int32), ("alpha", ctypes.c_float),
         ("causal", ctypes.c_int32), ("dtype", ctypes.c_int32), ("total_rows", ctypes.c_int64),
-        ("out_dtype", ctypes.c_int32), ("reserved", ctypes.c_int32),
+        ("out_dtype", ctypes.c_int32), ("flags", ctypes.c_int32),
     ]
 
 
@@ -140,6 +166,11 @@ def load_library():
     lib.hstu_jagged_attn_cp_partial_bias.argtypes = [pp, ctypes.POINTER(_CpDesc), ctypes.POINTER(_CpTsBias),
                                                      vp, vp, vp, vp, i32p, vp, vp, vp, vp, vp,
                                                      ctypes.c_size_t, vp]
+    lib.hstu_debug_mfma_loop.restype = ctypes.c_int
+    lib.hstu_debug_mfma_loop.argtypes = [ctypes.c_int, ctypes.c_int, vp, ctypes.POINTER(ctypes.c_double), vp]
+    lib.hstu_debug_dq_atomic_rate.restype = ctypes.c_int
+    lib.hstu_debug_dq_atomic_rate.argtypes = [vp, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                              ctypes.POINTER(ctypes.c_double), vp]
     lib.hstu_schedule_tile_rows.restype = ctypes.c_int
     lib.hstu_schedule_tile_rows.argtypes = [pp, ctypes.c_int]
     _lib = lib
@@ -162,7 +193,7 @@ def _params(batch, num_heads, d_qk, d_v, max_len, alpha, causal, dtype_code, tot
             out_dtype_code=None) -> _Params:
     return _Params(int(batch), int(num_heads), int(d_qk), int(d_v), int(max_len), float(alpha),
                    int(bool(causal)), int(dtype_code), int(total_rows),
-                   int(dtype_code if out_dtype_code is None else out_dtype_code), 0)
+                   int(dtype_code if out_dtype_code is None else out_dtype_code), int(default_flags))
 
 
 def _out_dtype(in_dtype: torch.dtype, out_dtype: Optional[torch.dtype]) -> torch.dtype:
@@ -185,6 +216,20 @@ def _stream(stream) -> ctypes.c_void_p:
     if stream is None:
         stream = torch.cuda.current_stream()
     return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _allocates_on_its_stream(fn):
+    """Runs `fn` with its `stream=` argument as torch's current stream, so that whatever the function
+    allocates (outputs, workspace) belongs to the stream its kernels are queued on: the caching
+    allocator then cannot hand that memory to another stream's allocation while they still run."""
+    @functools.wraps(fn)
+    def wrapped(*args, **kwargs):
+        stream = kwargs.get("stream")
+        if stream is None or stream == torch.cuda.current_stream():
+            return fn(*args, **kwargs)
+        with torch.cuda.stream(stream):
+            return fn(*args, **kwargs)
+    return wrapped
 
 
 def _check_tensor(t: torch.Tensor, name: str, rows: int, heads: int, dim: int, dtype) -> None:
@@ -216,6 +261,7 @@ def hstu_validate_offsets_host(host_offsets, total_rows: int) -> int:
         off.ctypes.data_as(ctypes.c_void_p), len(off) - 1, int(total_rows)))
 
 
+@_allocates_on_its_stream
 def hstu_jagged_attn_fwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor,
                          seq_offsets: torch.Tensor, max_len: int, alpha: float, causal: bool = True,
                          out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
@@ -270,6 +316,7 @@ def hstu_jagged_attn_fwd_static(q: torch.Tensor, k: torch.Tensor, v: torch.Tenso
     return out
 
 
+@_allocates_on_its_stream
 def hstu_jagged_attn_bwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, d_o: torch.Tensor,
                          seq_offsets: torch.Tensor, max_len: int, alpha: float, causal: bool = True,
                          out: Optional[Tuple[torch.Tensor, torch.Tensor, torch.Tensor]] = None,
@@ -331,6 +378,7 @@ def _bias_workspace(params: _Params, which: int, workspace, device) -> torch.Ten
     return workspace
 
 
+@_allocates_on_its_stream
 def hstu_jagged_attn_bias_fwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor,
                               seq_offsets: torch.Tensor, timestamps: torch.Tensor,
                               ts_weights: torch.Tensor, groups_log2: int, max_len: int, alpha: float,
@@ -361,6 +409,7 @@ def hstu_jagged_attn_bias_fwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor,
     return out
 
 
+@_allocates_on_its_stream
 def hstu_jagged_attn_bias_bwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, d_o: torch.Tensor,
                               seq_offsets: torch.Tensor, timestamps: torch.Tensor,
                               ts_weights: torch.Tensor, groups_log2: int, max_len: int, alpha: float,
@@ -396,6 +445,7 @@ def hstu_jagged_attn_bias_bwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor,
     return dq, dk, dvv, dw
 
 
+@_allocates_on_its_stream
 def hstu_jagged_attn_cp_partial(q_local: torch.Tensor, k_part: torch.Tensor, v_part: torch.Tensor,
                                 d_o_local: Optional[torch.Tensor], seq_offsets_global: torch.Tensor,
                                 total_rows: int, max_len: int, alpha: float, causal: bool,
@@ -449,6 +499,7 @@ def hstu_jagged_attn_cp_partial(q_local: torch.Tensor, k_part: torch.Tensor, v_p
     return o, dq, dk, dvv
 
 
+@_allocates_on_its_stream
 def hstu_jagged_attn_cp_partial_bias(q_local: torch.Tensor, k_part: torch.Tensor, v_part: torch.Tensor,
                                      d_o_local: Optional[torch.Tensor], seq_offsets_global: torch.Tensor,
                                      total_rows: int, q_timestamps: torch.Tensor,
@@ -519,6 +570,7 @@ def hstu_schedule_tile_rows(dtype_code: int, d_qk: int, d_v: int, side: int, tot
     return int(load_library().hstu_schedule_tile_rows(ctypes.byref(p), int(side)))
 
 
+@_allocates_on_its_stream
 def hstu_debug_dump_schedule(seq_offsets: torch.Tensor, total_rows: int, num_heads: int, d_qk: int,
                              d_v: int, causal: bool, dtype_code: int, side: int,
                              cp: Optional[Tuple[int, int, int, int, int]] = None,
@@ -546,7 +598,31 @@ def hstu_debug_dump_schedule(seq_offsets: torch.Tensor, total_rows: int, num_hea
 
 
 KERNEL_KINDS = {0: "fwd", 1: "dkdv", 2: "dq", 3: "plan", 4: "transpose", 5: "reorder", 6: "reduce",
-                7: "ts_records", 8: "dw_finish"}
+                7: "ts_records", 8: "dw_finish", 9: "mfma_loop", 10: "dq_atomic"}
+
+
+def hstu_debug_mfma_loop(random_operands: bool, iterations: int, sink: torch.Tensor, stream=None) -> float:
+    """Queues one launch of the matrix-instruction loop; returns its flops (the caller times it)."""
+    flops = ctypes.c_double(0.0)
+    rc = load_library().hstu_debug_mfma_loop(int(bool(random_operands)), int(iterations), _ptr(sink),
+                                             ctypes.byref(flops), _stream(stream))
+    if rc != 0:
+        raise HstuError(rc, "hstu_debug_mfma_loop")
+    return flops.value
+
+
+def hstu_debug_dq_atomic_rate(dq_f32: torch.Tensor, blocks: int, head_per_xcd: bool, stream=None) -> float:
+    """Queues one launch of the atomic-rate kernel on dq_f32 [rows, heads, 128] fp32; returns the
+    bytes it adds (the caller times it)."""
+    rows, heads, d = dq_f32.shape
+    if d != 128 or dq_f32.dtype != torch.float32 or not dq_f32.is_contiguous() or not dq_f32.is_cuda:
+        raise ValueError("dq_f32 must be a contiguous fp32 device tensor [rows, heads, 128]")
+    nbytes = ctypes.c_double(0.0)
+    rc = load_library().hstu_debug_dq_atomic_rate(_ptr(dq_f32), int(rows), int(heads), int(blocks),
+                                                  int(bool(head_per_xcd)), ctypes.byref(nbytes), _stream(stream))
+    if rc != 0:
+        raise HstuError(rc, "hstu_debug_dq_atomic_rate")
+    return nbytes.value
 
 
 def hstu_debug_timing_begin(max_records: int = 4096) -> None:
@@ -566,6 +642,7 @@ def hstu_debug_timing_end(capacity: int = 4096):
     return [(KERNEL_KINDS.get(int(kinds[i]), "?"), float(ms[i])) for i in range(n)]
 
 
+@_allocates_on_its_stream
 def hstu_cp_reorder(tensors, seq_offsets: torch.Tensor, total_rows: int, cp_size: int, rank: int,
                     local_rows: int, scatter: bool = False, out=None, stream=None):
     """Moves rows between the global jagged layout and `rank`'s local layout (up to 4 tensors).

@@ -8,7 +8,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libhstu_attn.so")
-SOURCES = ["hstu_api.hip", "hstu_plan.hip", "hstu_fwd.hip", "hstu_dkdv.hip", "hstu_dkdv2.hip", "hstu_dq.hip", "hstu_f32.hip"]
+SOURCES = ["hstu_api.hip", "hstu_plan.hip", "hstu_fwd.hip", "hstu_dkdv.hip", "hstu_dkdv2.hip", "hstu_dq.hip", "hstu_f32.hip", "hstu_probe.hip"]
 FLAGS = [
     "-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC",
     # packed fp32 VALU forms are kept out of the generated code
@@ -55,7 +55,7 @@ def _resource_lines(stderr: str):
 
 def build(verbose: bool = False) -> str:
     """Compiles every source for gfx950 and links the shared library; returns its path."""
-    with ThreadPoolExecutor(max_workers=7) as ex:
+    with ThreadPoolExecutor(max_workers=8) as ex:
         done = list(ex.map(_compile, SOURCES))
     objs = [d[0] for d in done]
     with open(RESOURCES, "w") as f:

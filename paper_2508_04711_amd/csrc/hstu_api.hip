@@ -52,7 +52,8 @@ int check_params(const hstu_attn_params* p) {
   if (!dim_ok(p->d_qk) || !dim_ok(p->d_v)) return HSTU_ERR_UNSUPPORTED;
   if (p->dtype != HSTU_BF16 && p->dtype != HSTU_F32) return HSTU_ERR_UNSUPPORTED;
   if (p->out_dtype != p->dtype && p->out_dtype != HSTU_F32) return HSTU_ERR_UNSUPPORTED;
-  if (p->reserved != 0) return HSTU_ERR_UNSUPPORTED;
+  if (p->flags & ~HSTU_FLAGS_ALL) return HSTU_ERR_UNSUPPORTED;
+  if ((p->flags & HSTU_FLAG_FWD_TILE_128) && (p->flags & HSTU_FLAG_FWD_TILE_256)) return HSTU_ERR_UNSUPPORTED;
   return HSTU_OK;
 }
 
@@ -63,14 +64,15 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 // transposed copy of V first, which would cost as much memory traffic as the pass itself,
 // and keeps to 128-row tiles.
 bool short_sequences(const hstu_attn_params* p) {
-  if (getenv("HSTU_ATTN_FWD_TILE")) return false;  // a forced tile height means the transposed-copy form
+  // a forced tile height means the transposed-copy form
+  if (p->flags & (HSTU_FLAG_FWD_TILE_128 | HSTU_FLAG_FWD_TILE_256)) return false;
   return p->batch > 0 && p->total_rows / p->batch <= 1024;
 }
 
 // Batches of very short sequences (mean length at most PACKED_MEAN_LEN): the whole-batch entry
 // points tile the rows of the batch regardless of sequence boundaries (packed tiles), so that no
-// tile is mostly padding.  HSTU_ATTN_NO_PACK (any value) turns this off, HSTU_ATTN_PACK_LEN=<n>
-// moves the threshold (up to the 1024 of the short-sequence form).
+// tile is mostly padding.  HSTU_FLAG_NO_PACK turns this off, HSTU_FLAG_PACK_SHORT moves the
+// threshold up to the 1024 of the short-sequence form.
 // Measured, fwd + bwd, H = 4, d = 128, per-sequence tiles -> packed: 8192 sequences of 16..64 rows
 // 1.98 -> 1.35 ms (the per-sequence schedule build alone is 0.16 ms); 4096 of 32..256 rows 2.82 ->
 // 2.65 ms; 2048 of 200..400 rows 3.13 -> 3.06 ms; 1536 of 300..600 rows 3.94 -> 3.92 ms: beyond a mean
@@ -78,9 +80,8 @@ bool short_sequences(const hstu_attn_params* p) {
 constexpr int PACKED_TILE = 128;
 constexpr int64_t PACKED_MEAN_LEN = 256;
 bool packed_tiles(const hstu_attn_params* p) {
-  if (p->dtype != HSTU_BF16 || !short_sequences(p) || getenv("HSTU_ATTN_NO_PACK")) return false;
-  int64_t limit = PACKED_MEAN_LEN;
-  if (const char* e = getenv("HSTU_ATTN_PACK_LEN")) limit = atoll(e);
+  if (p->dtype != HSTU_BF16 || !short_sequences(p) || (p->flags & HSTU_FLAG_NO_PACK)) return false;
+  const int64_t limit = (p->flags & HSTU_FLAG_PACK_SHORT) ? 1024 : PACKED_MEAN_LEN;
   return p->total_rows / p->batch <= limit;
 }
 size_t packed_bytes(const hstu_attn_params* p) {
@@ -92,6 +93,8 @@ size_t packed_bytes(const hstu_attn_params* p) {
 // Wavefronts per workgroup and owner rows per item of a pass on a problem of the given size.
 int pass_waves(const hstu_attn_params* p, int pass, int64_t owner_rows) {
   if (p->dtype != HSTU_BF16 || short_sequences(p)) return 4;
+  if (pass == PASS_FWD && (p->flags & HSTU_FLAG_FWD_TILE_128)) return 4;
+  if (pass == PASS_FWD && (p->flags & HSTU_FLAG_FWD_TILE_256)) return 8;
   return waves_bf16(pass, owner_rows, p->num_heads);
 }
 int tile_rows(const hstu_attn_params* p, int pass, int64_t owner_rows) {
@@ -140,7 +143,7 @@ int64_t stiles_bound(const hstu_attn_params* p, const SideSpec& s) {
 // and small batches of long sequences are such problems).
 constexpr int SPLIT_BLOCKS = 64;  // a part covers at least this many visible 32-row blocks
 int split_of(const hstu_attn_params* p, const SideSpec& s) {
-  if (p->dtype != HSTU_BF16 || s.side != 0 || getenv("HSTU_ATTN_NO_SPLIT")) return 1;
+  if (p->dtype != HSTU_BF16 || s.side != 0 || (p->flags & HSTU_FLAG_NO_SPLIT)) return 1;
   // no sequence is long enough for two parts (when the lengths respect max_len)
   if ((int64_t)p->max_len < 2 * SPLIT_BLOCKS * 32) return 1;
   const int64_t wgs = items_bound(p, s) * p->num_heads;
@@ -157,7 +160,7 @@ int split_of(const hstu_attn_params* p, const SideSpec& s) {
 // tiles * split <= tiles + 2 * slots / heads + 1 because split <= 2 * slots / (tiles * heads) + 1.
 int64_t split_items_bound(const hstu_attn_params* p, const SideSpec& s) {
   const int64_t tiles = items_bound(p, s);
-  if (p->dtype != HSTU_BF16 || s.side != 0 || getenv("HSTU_ATTN_NO_SPLIT") ||
+  if (p->dtype != HSTU_BF16 || s.side != 0 || (p->flags & HSTU_FLAG_NO_SPLIT) ||
       (int64_t)p->max_len < 2 * SPLIT_BLOCKS * 32)
     return tiles;
   return tiles + 2 * 512 / p->num_heads + 1;
@@ -191,8 +194,11 @@ int prepare_plan(const hstu_attn_params* p, int cp_size, const SideSpec& s, cons
                  char* ws, size_t ws_bytes, size_t base, PlanArgs* args, BuiltPlan* out) {
   const int split = split_of(p, s);
   const int64_t max_tiles = items_bound(p, s), max_items = max_tiles * split, max_stiles = stiles_bound(p, s);
+  // only the forward pass with a transposed copy of V reads the streamed side's tile table (see make_tcopy)
+  const bool want_ttile = s.pass == PASS_FWD && p->dtype == HSTU_BF16 && !short_sequences(p);
   if (max_items * p->num_heads >= (1ll << 31) || max_stiles * p->num_heads >= (1ll << 31) ||
-      max_stiles * 64 * 2 * 128 >= (1ll << 31))  // transposed rows are addressed with 32-bit byte offsets
+      // (the rows of the transposed copy are addressed with 32-bit byte offsets)
+      (want_ttile && max_stiles * 64 * 2 * 128 >= (1ll << 31)))
     return HSTU_ERR_BAD_SHAPE;
   const PlanLayout l = plan_layout(base, p->batch, max_items, max_stiles, max_tiles);
   if (l.end > ws_bytes) return HSTU_ERR_WORKSPACE_TOO_SMALL;
@@ -256,8 +262,7 @@ int prepare_plan(const hstu_attn_params* p, int cp_size, const SideSpec& s, cons
   a.tile_base = reinterpret_cast<int32_t*>(ws + l.tile_base);
   a.stile_base = reinterpret_cast<int32_t*>(ws + l.stile_base);
   a.ttile = reinterpret_cast<int32_t*>(ws + l.ttile);
-  // only the forward pass with a transposed copy of V reads it (see make_tcopy)
-  a.want_ttile = s.pass == PASS_FWD && p->dtype == HSTU_BF16 && !short_sequences(p) ? 1 : 0;
+  a.want_ttile = want_ttile ? 1 : 0;
   a.order = reinterpret_cast<int32_t*>(ws + l.order);
   a.items = reinterpret_cast<Item*>(ws + l.items);
   *args = a;
@@ -362,6 +367,7 @@ AttnArgs base_args(const hstu_attn_params* p, const BuiltPlan& bp, int accumulat
   a.xcd_parts = bp.natural && p->dtype == HSTU_BF16 && p->num_heads < 8 && 8 % p->num_heads == 0
                     ? 8 / p->num_heads : 1;
   a.out_f32 = p->out_dtype == HSTU_F32 ? 1 : 0;
+  a.dkdv_one_wave = (p->flags & HSTU_FLAG_DKDV_ONE_WAVE) ? 1 : 0;
   a.alpha = p->alpha;
   a.inv_n = 1.0f / (float)p->max_len;
   return a;
@@ -508,9 +514,14 @@ size_t hstu_jagged_attn_workspace_bytes(const hstu_attn_params* params, int whic
   if (check_params(params) != HSTU_OK) return 0;
   const hstu_attn_params* p = params;
   size_t end = 0;
+  bool too_large = false;
   // Each pass: its schedule, then the transposed copies of the tensors it streams (bf16 only).
   // d_t: head dimension of the transposed copy, d_p: of the partial results (0: none)
   auto pass_bytes = [&](const SideSpec& s, int d_t, int d_p) {
+    // the limits of prepare_plan (with the largest split: the query holds for every share of the rows)
+    if (split_items_bound(p, s) * p->num_heads >= (1ll << 31) || stiles_bound(p, s) * p->num_heads >= (1ll << 31) ||
+        (d_t && tcopy_bytes(p, s, d_t) && stiles_bound(p, s) * 64 * 2 * 128 >= (1ll << 31)))
+      too_large = true;
     end = plan_bytes(p, s, end);
     if (d_t) end = align_up(end, 256) + tcopy_bytes(p, s, d_t);
     if (d_p) end = align_up(end, 256) + partial_bytes_bound(p, s, d_p);
@@ -531,6 +542,7 @@ size_t hstu_jagged_attn_workspace_bytes(const hstu_attn_params* params, int whic
   } else {
     return 0;
   }
+  if (too_large) return 0;
   if (which != HSTU_WS_CP && packed_tiles(p)) end = align_up(end, 256) + packed_bytes(p);
   return end + 4096;  // slack for the 256-byte alignment of each piece
 }
@@ -1042,6 +1054,27 @@ int hstu_cp_reorder(int32_t batch, int64_t total_rows, int32_t cp_size, int32_t 
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   TimedLaunch timed(5, stream);
   return launch_reorder(ra, max_tiles, stream) == hipSuccess ? HSTU_OK : HSTU_ERR_HIP;
+}
+
+int hstu_debug_mfma_loop(int random_operands, int iterations, float* sink, double* flops_per_launch,
+                         void* hip_stream) {
+  if (!sink || !flops_per_launch) return HSTU_ERR_NULL_PTR;
+  if (iterations < 1 || iterations > (1 << 24)) return HSTU_ERR_BAD_SHAPE;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  TimedLaunch timed(9, stream);
+  return launch_mfma_loop(iterations, random_operands ? 1 : 0, sink, flops_per_launch, stream) == hipSuccess
+             ? HSTU_OK : HSTU_ERR_HIP;
+}
+
+int hstu_debug_dq_atomic_rate(float* dq_f32, int64_t rows, int32_t num_heads, int32_t blocks,
+                              int32_t head_per_xcd, double* payload_bytes_per_launch, void* hip_stream) {
+  if (!dq_f32 || !payload_bytes_per_launch) return HSTU_ERR_NULL_PTR;
+  if (rows < 64 || rows >= (1ll << 31) || num_heads < 1 || blocks < 1 || blocks > (1 << 20))
+    return HSTU_ERR_BAD_SHAPE;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  TimedLaunch timed(10, stream);
+  return launch_dq_atomic(dq_f32, rows, num_heads, blocks, head_per_xcd ? 1 : 0, payload_bytes_per_launch,
+                          stream) == hipSuccess ? HSTU_OK : HSTU_ERR_HIP;
 }
 
 int hstu_debug_timing_begin(int max_records) {

@@ -221,6 +221,8 @@ struct AttnArgs {
   // Walking workgroups take contiguous runs of their XCD's units instead of every n-th unit
   // (natural order with a head count that divides 8).
   int32_t walk_chunks;
+  // dk/dv pass: keep to the kernel with one wave per 32 keys where the two-wave kernel would serve.
+  int32_t dkdv_one_wave;
 };
 
 // Owner rows per item each kernel family expects (pass: 0 forward, 1 dk/dv, 2 dq); the
@@ -268,5 +270,12 @@ hipError_t launch_dq_bf16(const AttnArgs& a, int d_qk, int d_v, hipStream_t stre
 hipError_t launch_fwd_f32(const AttnArgs& a, int d_qk, int d_v, hipStream_t stream);
 hipError_t launch_dkdv_f32(const AttnArgs& a, int d_qk, int d_v, hipStream_t stream);
 hipError_t launch_dq_f32(const AttnArgs& a, int d_qk, int d_v, hipStream_t stream);
+
+// Measurement kernels (hstu_probe.hip): a loop of matrix instructions only (flops per launch
+// returned), and fp32 atomic adds in the pattern of a dq produced by the dk/dv pass (payload
+// bytes per launch returned).
+hipError_t launch_mfma_loop(int iters, int random, float* sink, double* flops, hipStream_t stream);
+hipError_t launch_dq_atomic(float* buf, int64_t rows, int heads, int nblk, int local, double* bytes,
+                            hipStream_t stream);
 
 }  // namespace hstu

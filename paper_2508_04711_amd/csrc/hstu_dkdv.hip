@@ -425,7 +425,7 @@ __global__ void __launch_bounds__(NW * 64, (DQK + DV <= 128 ? 2 : 1)) hstu_dkdv_
 
 hipError_t launch_dkdv_bf16(const AttnArgs& a, int d_qk, int d_v, hipStream_t stream) {
   if (a.waves != 4) return hipErrorInvalidValue;
-  if (dkdv_pair_supported(a, d_qk, d_v) && !getenv("HSTU_ATTN_DKDV_SINGLE"))
+  if (dkdv_pair_supported(a, d_qk, d_v) && !a.dkdv_one_wave)
     return launch_dkdv_pair_bf16(a, d_qk, d_v, stream);
   if (a.ts_rec && (a.nb < 1 || a.nb > MAX_TS_BUCKETS || !a.ts_w || !a.ts_rec_own)) return hipErrorInvalidValue;
   // One workgroup per CU is resident at the larger head dimensions: as many workgroups as CUs,

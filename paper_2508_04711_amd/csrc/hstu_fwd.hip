@@ -336,11 +336,6 @@ __global__ void __launch_bounds__(256) hstu_transpose_bf16(const uint16_t* __res
 
 int waves_bf16(int pass, int64_t owner_rows, int heads) {
   if (pass == PASS_FWD) {
-    // HSTU_ATTN_FWD_TILE=128|256 overrides the choice (testing and tuning)
-    if (const char* e = getenv("HSTU_ATTN_FWD_TILE")) {
-      if (e[0] == '1') return 4;
-      if (e[0] == '2') return 8;
-    }
     return (owner_rows / 256) * heads >= 2048 ? 8 : 4;
   }
   return 4;

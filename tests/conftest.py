@@ -25,3 +25,13 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+def set_flags(monkeypatch, add: str = "", remove: str = "") -> None:
+    """For the rest of the test, every call through the binding passes the hstu_flags named in
+    `add` as well (e.g. "NO_PACK"), and no longer the one named in `remove`."""
+    from paper_2508_04711_amd import binding
+
+    def bit(name):
+        return getattr(binding, "HSTU_FLAG_" + name) if name else 0
+    monkeypatch.setattr(binding, "default_flags", (binding.default_flags | bit(add)) & ~bit(remove))

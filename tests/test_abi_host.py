@@ -50,11 +50,11 @@ def test_header_is_plain_c_and_cxx(tmp_path):
 
 def _params(binding, **kw):
     base = dict(batch=2, num_heads=2, d_qk=64, d_v=64, max_len=16, alpha=0.125, causal=1, dtype=0,
-                total_rows=10, out_dtype=0, reserved=0)
+                total_rows=10, out_dtype=0, flags=0)
     base.update(kw)
     return binding._Params(base["batch"], base["num_heads"], base["d_qk"], base["d_v"],
                            base["max_len"], base["alpha"], base["causal"], base["dtype"],
-                           base["total_rows"], base["out_dtype"], base["reserved"])
+                           base["total_rows"], base["out_dtype"], base["flags"])
 
 
 def test_status_strings(lib):
@@ -73,7 +73,8 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     assert fwd(_params(binding, d_qk=48)) == -3
     assert fwd(_params(binding, dtype=7)) == -3
     assert fwd(_params(binding, out_dtype=0, dtype=1)) == -3       # fp32 in, bf16 out
-    assert fwd(_params(binding, reserved=1)) == -3
+    assert fwd(_params(binding, flags=64)) == -3      # an unknown bit
+    assert fwd(_params(binding, flags=8 | 16)) == -3  # two forward tile heights at once
     assert fwd(_params(binding, num_heads=0)) == -2
     assert fwd(_params(binding, max_len=0)) == -2
     assert fwd(_params(binding, total_rows=-1)) == -2
@@ -244,3 +245,21 @@ def test_static_scratch_forward_refuses_large_problems_on_the_host(lib):
     assert lib.hstu_jagged_attn_fwd_static(ctypes.byref(bad), one, one, one, one, one, None) == -3
     empty = _params(binding, batch=0, total_rows=0)
     assert lib.hstu_jagged_attn_fwd_static(ctypes.byref(empty), None, None, None, None, None, None) == 0
+
+
+def test_size_limits_are_those_of_the_pass_that_has_them(lib):
+    """Only a forward pass that builds the transposed copy of V is limited to 131071 key tiles; the
+    other passes, and batches of short sequences, take any size below 2^31 rows."""
+    from paper_2508_04711_amd import binding
+    ws = lambda p, which: lib.hstu_jagged_attn_workspace_bytes(ctypes.byref(p), which)
+    # 131072 sequences of 40 rows: short sequences, no transposed copy anywhere
+    many = _params(binding, batch=131072, num_heads=4, d_qk=128, d_v=128, max_len=64, total_rows=131072 * 40)
+    assert ws(many, 0) > 0 and ws(many, 1) > 0
+    # 9 million rows in 1000 long sequences: the forward's transposed copy is out of range, the backward is not
+    long = _params(binding, batch=1000, num_heads=1, d_qk=128, d_v=128, max_len=9000, total_rows=9_000_000)
+    assert ws(long, 0) == 0 and ws(long, 1) > 0
+    # just inside: (rows / 64 + batch + 1) tiles < 131072
+    edge = _params(binding, batch=1000, num_heads=1, d_qk=128, d_v=128, max_len=9000, total_rows=64 * (131071 - 1001))
+    assert ws(edge, 0) > 0
+    over = _params(binding, batch=1000, num_heads=1, d_qk=128, d_v=128, max_len=9000, total_rows=64 * (131072 - 1001))
+    assert ws(over, 0) == 0

@@ -8,6 +8,7 @@ import numpy as np
 import pytest
 import torch
 
+from conftest import set_flags
 import oracle
 import workloads
 from test_gpu_parity import _check, _dev
@@ -104,7 +105,7 @@ def test_bias_many_short_sequences():
 
 def test_zero_table_equals_the_call_without_bias(monkeypatch):
     import paper_2508_04711_amd as lib
-    monkeypatch.setenv("HSTU_ATTN_NO_PACK", "1")   # the calls with bias tile per sequence: so must the other
+    set_flags(monkeypatch, add="NO_PACK")   # the calls with bias tile per sequence: so must the other
     w = workloads.custom("bias_zero", [700, 130, 519], 2, 64, 64, 700, dtype="bf16", seed=11)
     dev = _dev(workloads.values(w))
     off = torch.from_numpy(w.seq_offsets()).cuda()

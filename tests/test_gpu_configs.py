@@ -3,6 +3,7 @@ import numpy as np
 import pytest
 import torch
 
+from conftest import set_flags
 import oracle
 import workloads
 from test_gpu_parity import _dev, _run_full
@@ -203,9 +204,9 @@ def test_large_batch_of_short_sequences(mode, monkeypatch):
     sequences alone (rows of different sequences do not interact)."""
     import paper_2508_04711_amd as lib
     if mode == "packed":
-        monkeypatch.setenv("HSTU_ATTN_PACK_LEN", "1024")
+        set_flags(monkeypatch, add="PACK_SHORT")
     else:
-        monkeypatch.setenv("HSTU_ATTN_NO_PACK", "1")
+        set_flags(monkeypatch, add="NO_PACK")
     rng = np.random.default_rng(17)
     lengths = [int(x) for x in rng.integers(32, 257, size=4096)]
     w = workloads.custom("large_batch", lengths, 4, 128, 128, 256, dtype="bf16", seed=41)
@@ -252,7 +253,7 @@ def test_large_batch_head_counts(H, B, monkeypatch):
     plain map with the dK/dV workgroups walking over the sorted list.  Sampled sequences against
     the oracle on those sequences alone."""
     import paper_2508_04711_amd as lib
-    monkeypatch.setenv("HSTU_ATTN_NO_PACK", "1")
+    set_flags(monkeypatch, add="NO_PACK")
     rng = np.random.default_rng(23 + H)
     lengths = [int(x) for x in rng.integers(32, 257, size=B)]
     w = workloads.custom("large_batch_h%d" % H, lengths, H, 128, 128, 256, dtype="bf16", seed=50 + H)

@@ -3,6 +3,7 @@ import numpy as np
 import pytest
 import torch
 
+from conftest import set_flags
 import oracle
 import workloads
 from test_gpu_parity import _check, _dev
@@ -76,8 +77,8 @@ def test_all_keys_partial_is_bitwise_the_full_pass(monkeypatch):
     # on the number of query rows of the call, and the parts are summed in another order; and with
     # the whole-batch call tiled per sequence like the partial, not with packed tiles.)
     import paper_2508_04711_amd as lib
-    monkeypatch.setenv("HSTU_ATTN_NO_SPLIT", "1")
-    monkeypatch.setenv("HSTU_ATTN_NO_PACK", "1")
+    set_flags(monkeypatch, add="NO_SPLIT")
+    set_flags(monkeypatch, add="NO_PACK")
     lengths = [520, 96, 1030, 8]
     w = workloads.custom("cp_all", lengths, 2, 128, 128, 1030, dtype="bf16", seed=9)
     dev = _dev(workloads.values(w))

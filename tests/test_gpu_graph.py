@@ -5,6 +5,7 @@ against the eager result for the data then in the input buffers."""
 import pytest
 import torch
 
+from conftest import set_flags
 import workloads
 
 pytestmark = pytest.mark.gpu
@@ -121,9 +122,9 @@ def test_large_batch_step_replays_from_a_graph(mode, monkeypatch):
     import numpy as np
     import paper_2508_04711_amd as lib
     if mode == "packed":
-        monkeypatch.setenv("HSTU_ATTN_PACK_LEN", "1024")
+        set_flags(monkeypatch, add="PACK_SHORT")
     else:
-        monkeypatch.setenv("HSTU_ATTN_NO_PACK", "1")
+        set_flags(monkeypatch, add="NO_PACK")
     rng = np.random.default_rng(31)
     lengths = [int(x) for x in rng.integers(32, 257, size=4096)]
     H, d = 4, 128

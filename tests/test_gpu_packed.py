@@ -1,5 +1,5 @@
 """Packed tiles: batches of very short sequences (bf16; by default a mean length of at most 256,
-here forced for every case with HSTU_ATTN_PACK_LEN) are tiled 128 rows at a time across sequence
+here forced for every case with HSTU_FLAG_PACK_SHORT) are tiled 128 rows at a time across sequence
 boundaries, each row seeing the window of its own sequence.  Against the oracle, through the C
 ABI, on the shapes that stress the windows: many sequences per tile, sequences spanning tiles,
 empty sequences, one long sequence among short ones, no mask."""
@@ -7,6 +7,7 @@ import numpy as np
 import pytest
 import torch
 
+from conftest import set_flags
 import oracle
 import workloads
 from test_gpu_parity import _check, _dev
@@ -16,8 +17,8 @@ pytestmark = pytest.mark.gpu
 
 @pytest.fixture(autouse=True)
 def _packed(monkeypatch):
-    monkeypatch.delenv("HSTU_ATTN_NO_PACK", raising=False)
-    monkeypatch.setenv("HSTU_ATTN_PACK_LEN", "1024")
+    set_flags(monkeypatch, remove="NO_PACK")
+    set_flags(monkeypatch, add="PACK_SHORT")
 
 
 def _check_few_terms(name, got, want, tag):
@@ -95,9 +96,9 @@ def test_packed_equals_per_sequence_tiling_closely(monkeypatch):
         torch.cuda.synchronize()
         return (o,) + tuple(g)
 
-    monkeypatch.delenv("HSTU_ATTN_NO_PACK", raising=False)
+    set_flags(monkeypatch, remove="NO_PACK")
     packed = run()
-    monkeypatch.setenv("HSTU_ATTN_NO_PACK", "1")
+    set_flags(monkeypatch, add="NO_PACK")
     plain = run()
     for name, a, b in zip(("o", "dq", "dk", "dv"), packed, plain):
         scale = b.abs().max().item()
@@ -188,7 +189,7 @@ def test_packed_bias_table_gradient_equals_per_sequence_tiles(monkeypatch):
     res = {}
     for mode in ("packed", "tiled"):
         if mode == "tiled":
-            monkeypatch.setenv("HSTU_ATTN_NO_PACK", "1")
+            set_flags(monkeypatch, add="NO_PACK")
         o = lib.hstu_jagged_attn_bias_fwd(dev["q"], dev["k"], dev["v"], off, ts, tab, 2, w.max_len, w.alpha, True,
                                           out_dtype=torch.float32)
         g = lib.hstu_jagged_attn_bias_bwd(dev["q"], dev["k"], dev["v"], dev["d_o"], off, ts, tab, 2, w.max_len,

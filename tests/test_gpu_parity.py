@@ -15,6 +15,7 @@ import numpy as np
 import pytest
 import torch
 
+from conftest import set_flags
 import oracle
 import workloads
 
@@ -108,13 +109,13 @@ SMALL = [
 
 def _tiling(monkeypatch, tiling):
     """Batches of very short sequences take packed tiles (rows tiled across sequence boundaries);
-    HSTU_ATTN_NO_PACK switches that off and HSTU_ATTN_PACK_LEN moves the threshold on the mean
+    HSTU_FLAG_NO_PACK switches that off and HSTU_FLAG_PACK_SHORT moves the threshold on the mean
     length.  The small cases run both ways."""
     if tiling == "per_sequence":
-        monkeypatch.setenv("HSTU_ATTN_NO_PACK", "1")
+        set_flags(monkeypatch, add="NO_PACK")
     else:
-        monkeypatch.delenv("HSTU_ATTN_NO_PACK", raising=False)
-        monkeypatch.setenv("HSTU_ATTN_PACK_LEN", "1024")
+        set_flags(monkeypatch, remove="NO_PACK")
+        set_flags(monkeypatch, add="PACK_SHORT")
 
 
 @pytest.mark.parametrize("tiling", ["packed", "per_sequence"])
@@ -184,7 +185,7 @@ def test_batch_composition_invariance_bit_exact(monkeypatch):
     # the schedule is a function of lengths only and nothing is accumulated across workgroups.
     # (Tiled per sequence: with packed tiles the 32-key blocks a row's sum is grouped into start
     # at the first sequence of its tile, so the last bits depend on the neighbours.)
-    monkeypatch.setenv("HSTU_ATTN_NO_PACK", "1")
+    set_flags(monkeypatch, add="NO_PACK")
     lib = _lib()
     lengths = [130, 257, 1, 64, 300]
     w = workloads.custom("compose", lengths, 2, 128, 128, 300, dtype="bf16", seed=11)
@@ -261,7 +262,7 @@ def test_heavy_tiles_cut_along_the_keys(causal, monkeypatch):
                                         accumulate=True, out=(o2, None, None, None))
         tol = 1e-5 if odt == torch.float32 else 2.0 ** -7
         assert (o2.float() - 1.5 * o).abs().max().item() <= tol * o.abs().max().item() * 1.5
-    monkeypatch.setenv("HSTU_ATTN_NO_SPLIT", "1")
+    set_flags(monkeypatch, add="NO_SPLIT")
     o_ref = lib.hstu_jagged_attn_fwd(*args, off, w.max_len, w.alpha, causal, out_dtype=torch.float32)
     dq_ref, dk_ref, dv_ref = lib.hstu_jagged_attn_bwd(*args, d["d_o"], off, w.max_len, w.alpha, causal,
                                                       out_dtype=torch.float32)
@@ -292,7 +293,7 @@ def test_accumulate_adds_to_existing_outputs():
 
 
 def test_cp_partial_equals_full_pass_for_cp1(monkeypatch):
-    monkeypatch.setenv("HSTU_ATTN_NO_PACK", "1")   # bit for bit: both tiled per sequence
+    set_flags(monkeypatch, add="NO_PACK")   # bit for bit: both tiled per sequence
     lib = _lib()
     w = workloads.custom("cp1", [200, 33, 150], 2, 128, 128, 200, dtype="bf16", seed=9)
     d = _dev(workloads.values(w))
@@ -333,7 +334,7 @@ def test_binding_rejects_bad_tensors():
 def test_wide_forward_tiles(name, lengths, H, dqk, dv, causal, monkeypatch):
     # the 256-row forward tiles (eight wavefronts, three tile buffers) are chosen for large
     # problems only; force them here so that small cases with ragged tails exercise them too
-    monkeypatch.setenv("HSTU_ATTN_FWD_TILE", "256")
+    set_flags(monkeypatch, add="FWD_TILE_256", remove="FWD_TILE_128")
     w = workloads.custom(name, lengths, H, dqk, dv, max_len=max(lengths), dtype="bf16", seed=21)
     print("wide", name, causal, flush=True)
     _run_full(w, causal=causal, backward=False)
@@ -342,7 +343,7 @@ def test_wide_forward_tiles(name, lengths, H, dqk, dv, causal, monkeypatch):
     off = torch.from_numpy(w.seq_offsets()).cuda()
     wide = lib.hstu_jagged_attn_fwd(vals["q"], vals["k"], vals["v"], off, w.max_len, w.alpha, causal,
                                     out_dtype=torch.float32)
-    monkeypatch.setenv("HSTU_ATTN_FWD_TILE", "128")
+    set_flags(monkeypatch, add="FWD_TILE_128", remove="FWD_TILE_256")
     narrow = lib.hstu_jagged_attn_fwd(vals["q"], vals["k"], vals["v"], off, w.max_len, w.alpha, causal,
                                       out_dtype=torch.float32)
     scale = narrow.abs().max().item()

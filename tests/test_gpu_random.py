@@ -5,6 +5,7 @@ import numpy as np
 import pytest
 import torch
 
+from conftest import set_flags
 import oracle
 import workloads
 from test_gpu_parity import _check, _dev
@@ -33,11 +34,11 @@ def _case(seed):
 def test_random_problem(seed, tiling, monkeypatch):
     import paper_2508_04711_amd as lib
     lengths, H, dqk, dv, causal, cp = _case(seed)
-    monkeypatch.delenv("HSTU_ATTN_NO_PACK", raising=False)
+    set_flags(monkeypatch, remove="NO_PACK")
     if tiling == "packed":   # packed tiles forced for every batch they can serve
         if cp or sum(lengths) // len(lengths) > 1024:
             pytest.skip("tiled per sequence whatever the threshold")
-        monkeypatch.setenv("HSTU_ATTN_PACK_LEN", "1024")
+        set_flags(monkeypatch, add="PACK_SHORT")
     if sum(lengths) == 0:
         lengths = lengths + [17]
     w = workloads.custom("rand%d" % seed, lengths, H, dqk, dv, max_len=max(max(lengths), 1), dtype="bf16",
