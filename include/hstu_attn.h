@@ -95,10 +95,14 @@ typedef enum {
   HSTU_FLAG_FWD_TILE_128 = 8,   /* bf16 forward: 128-row query tiles with the transposed copy of V,
                                    whatever the problem size and the mean sequence length         */
   HSTU_FLAG_FWD_TILE_256 = 16,  /* ... 256-row query tiles                                         */
-  HSTU_FLAG_DKDV_ONE_WAVE = 32  /* dk/dv pass at d_qk = d_v = 128: the kernel with one wave per 32
+  HSTU_FLAG_DKDV_ONE_WAVE = 32, /* dk/dv pass at d_qk = d_v = 128: the kernel with one wave per 32
                                    keys instead of the one that splits the work over two          */
+  HSTU_FLAG_BIAS_PER_PAIR = 64  /* calls with the timestamp bias (bf16): every block of pairs looks
+                                   up the fp32 table entry of each pair; without it a block whose
+                                   pairs share a bucket takes the entry as two bf16 halves (exact
+                                   to 2^-16 of its value) through one matrix instruction          */
 } hstu_flags;
-#define HSTU_FLAGS_ALL 63
+#define HSTU_FLAGS_ALL 127
 
 /* Problem description (section 2.1 for alpha and the mask, section 2.2 for the
  * jagged batch).  `total_rows` is passed by value so that grids and workspaces

@@ -4,6 +4,7 @@ Everything is computed by the HIP kernels in csrc/; this package only marshals a
 """
 from . import binding  # noqa: F401
 from .binding import (  # noqa: F401
+    HSTU_FLAG_BIAS_PER_PAIR,
     HSTU_FLAG_DKDV_ONE_WAVE,
     HSTU_FLAG_FWD_TILE_128,
     HSTU_FLAG_FWD_TILE_256,

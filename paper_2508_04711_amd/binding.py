@@ -24,6 +24,7 @@ HSTU_WS_FWD, HSTU_WS_BWD, HSTU_WS_CP = 0, 1, 2
 # hstu_flags (include/hstu_attn.h)
 HSTU_FLAG_NO_SPLIT, HSTU_FLAG_NO_PACK, HSTU_FLAG_PACK_SHORT = 1, 2, 4
 HSTU_FLAG_FWD_TILE_128, HSTU_FLAG_FWD_TILE_256, HSTU_FLAG_DKDV_ONE_WAVE = 8, 16, 32
+HSTU_FLAG_BIAS_PER_PAIR = 64
 
 # The flags every call of this module passes in hstu_attn_params.flags (0: the library's own
 # choices).  Tests and benchmarks set it, preferably through the `flags` context manager.

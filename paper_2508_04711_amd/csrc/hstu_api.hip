@@ -368,6 +368,7 @@ AttnArgs base_args(const hstu_attn_params* p, const BuiltPlan& bp, int accumulat
                     ? 8 / p->num_heads : 1;
   a.out_f32 = p->out_dtype == HSTU_F32 ? 1 : 0;
   a.dkdv_one_wave = (p->flags & HSTU_FLAG_DKDV_ONE_WAVE) ? 1 : 0;
+  a.bias_per_pair = (p->flags & HSTU_FLAG_BIAS_PER_PAIR) ? 1 : 0;
   a.alpha = p->alpha;
   a.inv_n = 1.0f / (float)p->max_len;
   return a;

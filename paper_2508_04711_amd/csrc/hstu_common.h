@@ -205,6 +205,7 @@ struct AttnArgs {
   double* d_ts_acc;        // the call's sums of dS per bucket (dq pass: added with atomics), or null
   int32_t nb;              // buckets
   int32_t fbits;           // log2 of the groups per octave
+  int32_t bias_per_pair;   // no block takes the one-bucket path (HSTU_FLAG_BIAS_PER_PAIR)
   // Packed tiles (bf16 kernels, whole-batch layout, batches of short sequences; null: not packed):
   // per row the first row and the end row of its sequence, built by launch_packed_plan.
   const int2* row_seq;

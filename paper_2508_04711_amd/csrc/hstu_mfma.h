@@ -557,6 +557,7 @@ struct BiasCtx {
   int t_own;             // timestamp of the lane's owner row
   int o_lo, o_hi;        // range of the timestamps of the wave's valid owner rows (uniform)
   int nb, f, hh;
+  int per_pair;          // every block works out its pairs' buckets one by one (AttnArgs::bias_per_pair)
 };
 
 // The uniform part of a block's bias: whether all its pairs fall into one bucket, that bucket
@@ -596,7 +597,7 @@ struct BlockTable {
       const uint32_t dmin = c.o_lo > s_hi ? (uint32_t)c.o_lo - (uint32_t)s_hi
                                           : (s_lo > c.o_hi ? (uint32_t)s_lo - (uint32_t)c.o_hi : 0u);
       const int b0 = bias_bucket(dmin, c.nb, c.f), b1 = bias_bucket(dmax, c.nb, c.f);
-      code = b0 | (b0 != b1 ? NONUNIFORM : 0) | (dmax < BIAS_SMALL_DELTA ? SMALL : 0);
+      code = b0 | (b0 != b1 || c.per_pair ? NONUNIFORM : 0) | (dmax < BIAS_SMALL_DELTA ? SMALL : 0);
       // the entry as hi + lo, both bf16: exact to 2^-16 of its value
       const float wv = *HSTU_LDS(float, c.wtab + b0);
       const __bf16 hi = (__bf16)wv;
@@ -687,6 +688,7 @@ __device__ __forceinline__ BiasCtx bias_setup(const AttnArgs& a, float* wtab, co
   c.wtab = wtab;
   c.rec = a.ts_rec;
   c.nb = a.nb; c.f = a.fbits; c.hh = hh;
+  c.per_pair = a.bias_per_pair;
   {
     const u32x4 o = {hh == 0 ? 0x3f803f80u : 0u, 0u, 0u, 0u};
     c.ones = __builtin_bit_cast(bf16x8, o);

@@ -73,7 +73,7 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     assert fwd(_params(binding, d_qk=48)) == -3
     assert fwd(_params(binding, dtype=7)) == -3
     assert fwd(_params(binding, out_dtype=0, dtype=1)) == -3       # fp32 in, bf16 out
-    assert fwd(_params(binding, flags=64)) == -3      # an unknown bit
+    assert fwd(_params(binding, flags=128)) == -3     # an unknown bit
     assert fwd(_params(binding, flags=8 | 16)) == -3  # two forward tile heights at once
     assert fwd(_params(binding, num_heads=0)) == -2
     assert fwd(_params(binding, max_len=0)) == -2

@@ -6,7 +6,7 @@ import torch
 from conftest import set_flags
 import oracle
 import workloads
-from test_gpu_parity import _dev, _run_full
+from test_gpu_parity import _check, _dev, _run_full
 
 pytestmark = pytest.mark.gpu
 
@@ -27,9 +27,11 @@ def test_config5_sampled_rows():
     dev = _dev(vals)
     off_np = w.seq_offsets()
     off = torch.from_numpy(off_np).cuda()
-    o = lib.hstu_jagged_attn_fwd(dev["q"], dev["k"], dev["v"], off, w.max_len, w.alpha, True)
-    dq, dk, dv = lib.hstu_jagged_attn_bwd(dev["q"], dev["k"], dev["v"], dev["d_o"], off, w.max_len,
-                                          w.alpha, True)
+    outs = {}
+    for odt in (torch.bfloat16, torch.float32):  # as bench.py runs it, and the accumulators unrounded
+        o = lib.hstu_jagged_attn_fwd(dev["q"], dev["k"], dev["v"], off, w.max_len, w.alpha, True, out_dtype=odt)
+        outs[odt] = (o,) + tuple(lib.hstu_jagged_attn_bwd(dev["q"], dev["k"], dev["v"], dev["d_o"], off, w.max_len,
+                                                          w.alpha, True, out_dtype=odt))
     torch.cuda.synchronize()
     print("config 5 gpu done", flush=True)
     rng = np.random.default_rng(5)
@@ -40,18 +42,14 @@ def test_config5_sampled_rows():
         sel += [s + x for x in local if 0 <= x < L]
     sel = sorted(set(sel))
     f64 = {k: workloads.to_f64(v) for k, v in vals.items()}
-    so, sdq, sdk, sdv = oracle.rows(f64["q"], f64["k"], f64["v"], f64["d_o"], off_np, w.max_len,
-                                    w.alpha, True, sel)
+    want = oracle.rows(f64["q"], f64["k"], f64["v"], f64["d_o"], off_np, w.max_len, w.alpha, True, sel)
     print("config 5 oracle done", flush=True)
-    for name, got, ref in (("o", o, so), ("dq", dq, sdq), ("dk", dk, sdk), ("dv", dv, sdv)):
-        g = got[sel].double().cpu().numpy()
-        rms = float(np.sqrt((ref ** 2).mean()))
-        # bf16 outputs: the bar plus the storage rounding of the exact value
-        excess = np.abs(g - ref) - (2e-2 * rms + np.abs(ref) * 2.0 ** -8)
-        assert excess.max() <= 0, (name, float(np.abs(g - ref).max() / rms))
-    # properties that hold at any size: finite everywhere, nothing beyond what was asked
-    for t in (o, dq, dk, dv):
-        assert torch.isfinite(t.float()).all()
+    # fp32 outputs: the stated bar; bf16 outputs: plus the storage rounding of the exact value
+    for odt, got4 in outs.items():
+        for name, got, ref in zip(("o", "dq", "dk", "dv"), got4, want):
+            _check(name, got[sel], ref, "bf16", "config 5")
+            # properties that hold at any size: finite everywhere
+            assert torch.isfinite(got.float()).all()
 
 
 def test_config5_with_timestamp_bias_sampled_rows():
@@ -67,9 +65,12 @@ def test_config5_with_timestamp_bias_sampled_rows():
     off = torch.from_numpy(off_np).cuda()
     ts_np, tab_np = workloads.timestamps(w, "events", 0), workloads.bias_table(64, 0, 1.0)
     ts, tab = torch.from_numpy(ts_np).cuda(), torch.from_numpy(tab_np).cuda()
-    o = lib.hstu_jagged_attn_bias_fwd(dev["q"], dev["k"], dev["v"], off, ts, tab, 2, w.max_len, w.alpha, True)
-    dq, dk, dv, dw = lib.hstu_jagged_attn_bias_bwd(dev["q"], dev["k"], dev["v"], dev["d_o"], off, ts, tab, 2,
-                                                   w.max_len, w.alpha, True)
+    outs = {}
+    for odt in (torch.bfloat16, torch.float32):
+        o = lib.hstu_jagged_attn_bias_fwd(dev["q"], dev["k"], dev["v"], off, ts, tab, 2, w.max_len, w.alpha, True,
+                                          out_dtype=odt)
+        outs[odt] = (o,) + tuple(lib.hstu_jagged_attn_bias_bwd(dev["q"], dev["k"], dev["v"], dev["d_o"], off, ts, tab,
+                                                               2, w.max_len, w.alpha, True, out_dtype=odt))
     torch.cuda.synchronize()
     print("config 5 with bias: gpu done", flush=True)
     rng = np.random.default_rng(6)
@@ -83,14 +84,12 @@ def test_config5_with_timestamp_bias_sampled_rows():
     want = oracle.bias_rows(f64["q"], f64["k"], f64["v"], f64["d_o"], off_np, ts_np,
                             tab_np.astype(np.float64), 2, w.max_len, w.alpha, True, sel)
     print("config 5 with bias: oracle done", flush=True)
-    for name, got, ref in zip(("o", "dq", "dk", "dv"), (o, dq, dk, dv), want):
-        g = got[sel].double().cpu().numpy()
-        rms = float(np.sqrt((ref ** 2).mean()))
-        excess = np.abs(g - ref) - (2e-2 * rms + np.abs(ref) * 2.0 ** -8)
-        assert excess.max() <= 0, (name, float(np.abs(g - ref).max() / rms))
-    for t in (o, dq, dk, dv, dw):
-        assert torch.isfinite(t.float()).all()
-    assert (dw != 0).any()
+    for odt, got5 in outs.items():
+        for name, got, ref in zip(("o", "dq", "dk", "dv"), got5, want):
+            _check(name, got[sel], ref, "bf16", "config 5 with bias")
+        for t in got5:
+            assert torch.isfinite(t.float()).all()
+        assert (got5[4] != 0).any()
 
 
 @pytest.mark.parametrize("with_bias", [False, True])
@@ -156,19 +155,25 @@ def test_tensors_beyond_four_gib(with_bias):
     seqs = [0, straddle, straddle + 1, B - 1]
     assert int(off_np[straddle]) * H * d * 2 < 2 ** 32 < int(off_np[straddle + 1]) * H * d * 2
     print("beyond 4 GiB: inputs drawn", with_bias, flush=True)
+    ts = tab = None
     if with_bias:
         ts_np, tab_np = workloads.timestamps(w, "events", 5), workloads.bias_table(64, 5)
         ts, tab = torch.from_numpy(ts_np).cuda(), torch.from_numpy(tab_np).cuda()
-        o = lib.hstu_jagged_attn_bias_fwd(dev["q"], dev["k"], dev["v"], off, ts, tab, 2, w.max_len, w.alpha, True)
-        dq, dk, dv, dw = lib.hstu_jagged_attn_bias_bwd(dev["q"], dev["k"], dev["v"], dev["d_o"], off, ts, tab, 2,
-                                                       w.max_len, w.alpha, True)
-        torch.cuda.synchronize()
-        assert torch.isfinite(dw).all() and (dw != 0).any()
-    else:
-        o = lib.hstu_jagged_attn_fwd(dev["q"], dev["k"], dev["v"], off, w.max_len, w.alpha, True)
-        dq, dk, dv = lib.hstu_jagged_attn_bwd(dev["q"], dev["k"], dev["v"], dev["d_o"], off, w.max_len, w.alpha, True)
-        torch.cuda.synchronize()
-    print("beyond 4 GiB: gpu done", flush=True)
+
+    def run(odt):
+        if with_bias:
+            o = lib.hstu_jagged_attn_bias_fwd(dev["q"], dev["k"], dev["v"], off, ts, tab, 2, w.max_len, w.alpha, True,
+                                              out_dtype=odt)
+            dq, dk, dv, dw = lib.hstu_jagged_attn_bias_bwd(dev["q"], dev["k"], dev["v"], dev["d_o"], off, ts, tab, 2,
+                                                           w.max_len, w.alpha, True, out_dtype=odt)
+            torch.cuda.synchronize()
+            assert torch.isfinite(dw).all() and (dw != 0).any()
+        else:
+            o = lib.hstu_jagged_attn_fwd(dev["q"], dev["k"], dev["v"], off, w.max_len, w.alpha, True, out_dtype=odt)
+            dq, dk, dv = lib.hstu_jagged_attn_bwd(dev["q"], dev["k"], dev["v"], dev["d_o"], off, w.max_len, w.alpha,
+                                                  True, out_dtype=odt)
+            torch.cuda.synchronize()
+        return o, dq, dk, dv
     # the sub-problem of the chosen sequences, with offsets of its own
     rows = np.concatenate([np.arange(off_np[b], off_np[b + 1]) for b in seqs])
     rows_t = torch.from_numpy(rows).cuda()
@@ -184,16 +189,16 @@ def test_tensors_beyond_four_gib(with_bias):
         want = oracle.rows(sub["q"], sub["k"], sub["v"], sub["d_o"], sub_off, w.max_len, w.alpha, True, sel)
     print("beyond 4 GiB: oracle done", flush=True)
     glob = torch.from_numpy(rows[sel]).cuda()
-    for name, got, ref in zip(("o", "dq", "dk", "dv"), (o, dq, dk, dv), want):
-        g = got[glob].double().cpu().numpy()
-        rms = float(np.sqrt((ref ** 2).mean()))
-        excess = np.abs(g - ref) - (2e-2 * rms + np.abs(ref) * 2.0 ** -8)
-        assert excess.max() <= 0, (name, float(np.abs(g - ref).max() / rms))
-    # every sequence has the same shape, so outputs beyond 4 GiB are as large as those before it
-    for t in (o, dq, dk, dv):
-        head, tail = t[:L * 8].float(), t[-L * 8:].float()
-        assert torch.isfinite(tail).all()
-        assert 0.8 < float(tail.pow(2).mean().sqrt() / head.pow(2).mean().sqrt()) < 1.25
+    for odt in (torch.bfloat16, torch.float32):  # fp32: the stated bar; bf16: plus the storage rounding
+        outs = run(odt)
+        for name, got, ref in zip(("o", "dq", "dk", "dv"), outs, want):
+            _check(name, got[glob], ref, "bf16", "beyond 4 GiB")
+        # every sequence has the same shape, so outputs beyond 4 GiB are as large as those before it
+        for t in outs:
+            head, tail = t[:L * 8].float(), t[-L * 8:].float()
+            assert torch.isfinite(tail).all()
+            assert 0.8 < float(tail.pow(2).mean().sqrt() / head.pow(2).mean().sqrt()) < 1.25
+        del outs
 
 
 @pytest.mark.parametrize("mode", ["plain", "bias", "packed"])
@@ -215,17 +220,24 @@ def test_large_batch_of_short_sequences(mode, monkeypatch):
     off_np = w.seq_offsets()
     off = torch.from_numpy(off_np).cuda()
     print("large batch", mode, w.total_rows, flush=True)
+    ts = tab = None
     if mode == "bias":
         ts_np, tab_np = workloads.timestamps(w, "events", 6), workloads.bias_table(48, 6)
         ts, tab = torch.from_numpy(ts_np).cuda(), torch.from_numpy(tab_np).cuda()
-        o = lib.hstu_jagged_attn_bias_fwd(dev["q"], dev["k"], dev["v"], off, ts, tab, 1, w.max_len, w.alpha, True)
-        dq, dk, dv, dw = lib.hstu_jagged_attn_bias_bwd(dev["q"], dev["k"], dev["v"], dev["d_o"], off, ts, tab, 1,
-                                                       w.max_len, w.alpha, True)
-        assert torch.isfinite(dw).all() and (dw != 0).any()
-    else:
-        o = lib.hstu_jagged_attn_fwd(dev["q"], dev["k"], dev["v"], off, w.max_len, w.alpha, True)
-        dq, dk, dv = lib.hstu_jagged_attn_bwd(dev["q"], dev["k"], dev["v"], dev["d_o"], off, w.max_len, w.alpha, True)
-    torch.cuda.synchronize()
+
+    def run(odt):
+        if mode == "bias":
+            o = lib.hstu_jagged_attn_bias_fwd(dev["q"], dev["k"], dev["v"], off, ts, tab, 1, w.max_len, w.alpha, True,
+                                              out_dtype=odt)
+            dq, dk, dv, dw = lib.hstu_jagged_attn_bias_bwd(dev["q"], dev["k"], dev["v"], dev["d_o"], off, ts, tab, 1,
+                                                           w.max_len, w.alpha, True, out_dtype=odt)
+            assert torch.isfinite(dw).all() and (dw != 0).any()
+        else:
+            o = lib.hstu_jagged_attn_fwd(dev["q"], dev["k"], dev["v"], off, w.max_len, w.alpha, True, out_dtype=odt)
+            dq, dk, dv = lib.hstu_jagged_attn_bwd(dev["q"], dev["k"], dev["v"], dev["d_o"], off, w.max_len, w.alpha,
+                                                  True, out_dtype=odt)
+        torch.cuda.synchronize()
+        return o, dq, dk, dv
     seqs = [0, 1, 255, 256, 2047, 3000, 4094, 4095]
     rows = np.concatenate([np.arange(off_np[b], off_np[b + 1]) for b in seqs])
     sub = {k: workloads.to_f64(v[torch.from_numpy(rows)]) for k, v in vals.items()}
@@ -237,13 +249,13 @@ def test_large_batch_of_short_sequences(mode, monkeypatch):
     else:
         want = oracle.rows(sub["q"], sub["k"], sub["v"], sub["d_o"], sub_off, w.max_len, w.alpha, True, sel)
     glob = torch.from_numpy(rows).cuda()
-    for name, got, ref in zip(("o", "dq", "dk", "dv"), (o, dq, dk, dv), want):
-        g = got[glob].double().cpu().numpy()
-        rms = float(np.sqrt((ref ** 2).mean()))
-        excess = np.abs(g - ref) - (2e-2 * rms + np.abs(ref) * 2.0 ** -7)
-        assert excess.max() <= 0, (mode, name, float(np.abs(g - ref).max() / rms))
-    for t in (o, dq, dk, dv):
-        assert torch.isfinite(t.float()).all()
+    # the stated bar on the fp32 accumulators (measured 1.1e-2 .. 1.3e-2), the storage rounding on top for bf16
+    for odt in (torch.float32, torch.bfloat16):
+        outs = run(odt)
+        for name, got, ref in zip(("o", "dq", "dk", "dv"), outs, want):
+            _check(name, got[glob], ref, "bf16", "large batch %s" % mode)
+        for t in outs:
+            assert torch.isfinite(t.float()).all()
 
 
 @pytest.mark.parametrize("H,B", [(1, 16384), (2, 8192), (3, 8192)])
@@ -261,9 +273,6 @@ def test_large_batch_head_counts(H, B, monkeypatch):
     off_np = w.seq_offsets()
     off = torch.from_numpy(off_np).cuda()
     print("large batch heads", H, B, w.total_rows, flush=True)
-    o = lib.hstu_jagged_attn_fwd(dev["q"], dev["k"], dev["v"], off, w.max_len, w.alpha, True)
-    dq, dk, dv = lib.hstu_jagged_attn_bwd(dev["q"], dev["k"], dev["v"], dev["d_o"], off, w.max_len, w.alpha, True)
-    torch.cuda.synchronize()
     seqs = [0, 1, B // 8 - 1, B // 8, B // 2, B - 2, B - 1]
     rows = np.concatenate([np.arange(off_np[b], off_np[b + 1]) for b in seqs])
     rows_t = torch.from_numpy(rows).cuda()
@@ -271,14 +280,16 @@ def test_large_batch_head_counts(H, B, monkeypatch):
     sub_off = np.concatenate([[0], np.cumsum([lengths[b] for b in seqs])]).astype(np.int32)
     want = oracle.rows(sub["q"], sub["k"], sub["v"], sub["d_o"], sub_off, w.max_len, w.alpha, True,
                        np.arange(len(rows)))
-    for name, got, ref in zip(("o", "dq", "dk", "dv"), (o, dq, dk, dv), want):
-        g = got[rows_t].double().cpu().numpy()
-        rms = float(np.sqrt((ref ** 2).mean()))
-        excess = np.abs(g - ref) - (2e-2 * rms + np.abs(ref) * 2.0 ** -7)
-        assert excess.max() <= 0, (H, name, float(np.abs(g - ref).max() / rms))
-    # every row was written: the outputs of all sequences are of one scale
-    for t in (o, dq, dk, dv):
-        assert torch.isfinite(t.float()).all()
-        a = t[: w.total_rows // 2].float().pow(2).mean().sqrt()
-        b = t[w.total_rows // 2:].float().pow(2).mean().sqrt()
-        assert 0.8 < float(a / b) < 1.25
+    for odt in (torch.float32, torch.bfloat16):  # fp32: the stated bar; bf16: plus the storage rounding
+        o = lib.hstu_jagged_attn_fwd(dev["q"], dev["k"], dev["v"], off, w.max_len, w.alpha, True, out_dtype=odt)
+        dq, dk, dv = lib.hstu_jagged_attn_bwd(dev["q"], dev["k"], dev["v"], dev["d_o"], off, w.max_len, w.alpha, True,
+                                              out_dtype=odt)
+        torch.cuda.synchronize()
+        for name, got, ref in zip(("o", "dq", "dk", "dv"), (o, dq, dk, dv), want):
+            _check(name, got[rows_t], ref, "bf16", "large batch, %d heads" % H)
+        # every row was written: the outputs of all sequences are of one scale
+        for t in (o, dq, dk, dv):
+            assert torch.isfinite(t.float()).all()
+            a = t[: w.total_rows // 2].float().pow(2).mean().sqrt()
+            b = t[w.total_rows // 2:].float().pow(2).mean().sqrt()
+            assert 0.8 < float(a / b) < 1.25

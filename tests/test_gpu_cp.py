@@ -164,19 +164,21 @@ def test_large_batch_rank_partials_against_all_keys(cp):
     off_np = w.seq_offsets()
     off = torch.from_numpy(off_np).cuda()
     T = w.total_rows
-    o = torch.zeros((T, H, d), dtype=torch.bfloat16, device="cuda")
+    # fp32 outputs: the sums of the ranks' partial results then carry no rounding between ranks, and
+    # the stated bar applies as it is
+    o = torch.zeros((T, H, d), dtype=torch.float32, device="cuda")
     dq = torch.zeros_like(o)
-    dk = torch.zeros((T, H, d), dtype=torch.float32, device="cuda")
-    dv = torch.zeros_like(dk)
+    dk = torch.zeros_like(o)
+    dv = torch.zeros_like(o)
     for r in range(cp):
         n = len(oracle.cp_global_rows(off_np, cp, r))
         print("cp large batch", cp, r, n, flush=True)
         ql, gl = lib.hstu_cp_reorder([dev["q"], dev["d_o"]], off, T, cp, r, n)
         ol, dql, dkp, dvp = lib.hstu_jagged_attn_cp_partial(ql, dev["k"], dev["v"], gl, off, T, w.max_len, w.alpha,
-                                                            True, cp, r, -1)
+                                                            True, cp, r, -1, out_dtype=torch.float32)
         lib.hstu_cp_reorder([ol, dql], off, T, cp, r, n, scatter=True, out=[o, dq])
-        dk += dkp.float()
-        dv += dvp.float()
+        dk += dkp
+        dv += dvp
     torch.cuda.synchronize()
     seqs = [0, 1, B // 2 - 1, B // 2, B - 2, B - 1]
     rows = np.concatenate([np.arange(off_np[b], off_np[b + 1]) for b in seqs])
@@ -186,10 +188,6 @@ def test_large_batch_rank_partials_against_all_keys(cp):
     want = oracle.rows(sub["q"], sub["k"], sub["v"], sub["d_o"], sub_off, w.max_len, w.alpha, True,
                        np.arange(len(rows)))
     for name, got, ref in zip(("o", "dq", "dk", "dv"), (o, dq, dk, dv), want):
-        g = got[rows_t].double().cpu().numpy()
-        rms = float(np.sqrt((ref ** 2).mean()))
-        # dk and dv are sums of cp bf16 partial results: cp roundings instead of one
-        excess = np.abs(g - ref) - (2e-2 * rms + np.abs(ref) * 2.0 ** -7)
-        assert excess.max() <= 0, (cp, name, float(np.abs(g - ref).max() / rms))
+        _check(name, got[rows_t], ref, "bf16", "cp large batch, cp=%d" % cp)
     for t in (o, dq, dk, dv):
-        assert torch.isfinite(t.float()).all()
+        assert torch.isfinite(t).all()

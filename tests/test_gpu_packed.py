@@ -10,7 +10,7 @@ import torch
 from conftest import set_flags
 import oracle
 import workloads
-from test_gpu_parity import _check, _dev
+from test_gpu_parity import _check, _check_few_terms, _dev
 
 pytestmark = pytest.mark.gpu
 
@@ -19,17 +19,6 @@ pytestmark = pytest.mark.gpu
 def _packed(monkeypatch):
     set_flags(monkeypatch, remove="NO_PACK")
     set_flags(monkeypatch, add="PACK_SHORT")
-
-
-def _check_few_terms(name, got, want, tag):
-    """Outputs that are sums of a handful of terms are heavy-tailed (largest value > 10x the tensor
-    RMS), so the rounding of a single bf16 P or dS operand (relative 2^-9 of the value) can exceed
-    2e-2 x RMS on its own; such cases add a per-element relative allowance of 2^-7 (the same bar
-    as the many-short-sequences case of test_gpu_parity.py)."""
-    g = got.double().cpu().numpy()
-    assert np.isfinite(g).all(), (tag, name)
-    rms = float(np.sqrt(np.mean(want ** 2)))
-    assert (np.abs(g - want) <= 2e-2 * rms + np.abs(want) * 2.0 ** -7).all(), (tag, name)
 
 
 def _run(w, causal=True, out_dtype=torch.float32, few_terms=False):
@@ -162,6 +151,8 @@ def test_packed_tiles_with_bias_match_oracle(kind, d):
     rng = np.random.default_rng(d)
     lengths = [int(x) for x in rng.integers(0, 90, size=40)] + [300, 1, 129, 64]
     w = workloads.custom("packed_bias", lengths, 2, d, d, 300, dtype="bf16", seed=30 + d)
+    # (40 of the 44 sequences are shorter than 90 rows: the few-terms bar, see _check_few_terms;
+    # measured against the standard bar: 2.03e-2 at d = 128, wide timestamps)
     run_bias(w, kind, nb=40, f=2, causal=True, seed=d, check=_check_few_terms)
 
 
@@ -169,9 +160,9 @@ def test_packed_tiles_with_bias_no_mask_and_bucket_shapes():
     from test_gpu_bias import _run as run_bias
     lengths = [5, 70, 33, 0, 128, 17, 250, 1, 1, 64] * 4
     w = workloads.custom("packed_bias_full", lengths, 3, 64, 64, 250, dtype="bf16", seed=7)
-    run_bias(w, "events", nb=24, f=1, causal=False, seed=1, check=_check_few_terms)
-    run_bias(w, "events", nb=1, f=0, causal=True, seed=2, check=_check_few_terms)
-    run_bias(w, "wide", nb=512, f=4, causal=True, out_dtype=torch.bfloat16, seed=3, check=_check_few_terms)
+    run_bias(w, "events", nb=24, f=1, causal=False, seed=1)
+    run_bias(w, "events", nb=1, f=0, causal=True, seed=2)
+    run_bias(w, "wide", nb=512, f=4, causal=True, out_dtype=torch.bfloat16, seed=3)
 
 
 def test_packed_bias_table_gradient_equals_per_sequence_tiles(monkeypatch):
@@ -186,21 +177,22 @@ def test_packed_bias_table_gradient_equals_per_sequence_tiles(monkeypatch):
     off = torch.from_numpy(w.seq_offsets()).cuda()
     ts = torch.from_numpy(workloads.timestamps(w, "events", 4)).cuda()
     tab = torch.from_numpy(workloads.bias_table(64, 4)).cuda()
-    res = {}
-    for mode in ("packed", "tiled"):
-        if mode == "tiled":
-            set_flags(monkeypatch, add="NO_PACK")
+    def run(packed, per_pair):
+        set_flags(monkeypatch, remove="NO_PACK" if packed else "", add="" if packed else "NO_PACK")
+        set_flags(monkeypatch, add="BIAS_PER_PAIR" if per_pair else "", remove="" if per_pair else "BIAS_PER_PAIR")
         o = lib.hstu_jagged_attn_bias_fwd(dev["q"], dev["k"], dev["v"], off, ts, tab, 2, w.max_len, w.alpha, True,
                                           out_dtype=torch.float32)
         g = lib.hstu_jagged_attn_bias_bwd(dev["q"], dev["k"], dev["v"], dev["d_o"], off, ts, tab, 2, w.max_len,
                                           w.alpha, True, out_dtype=torch.float32)
         torch.cuda.synchronize()
-        res[mode] = (o,) + tuple(g)
-    # The two forms see a block's table entry as hi + lo bf16 halves or as the fp32 value depending
-    # on which blocks each of them finds to be of one bucket, so scores differ in the 16th bit and
-    # a P or dS operand may round to the other bf16 neighbour: one term of a handful moves by 2^-8
-    # of its value.  The table gradient sums fp32 dS values that are never rounded.
-    for name, a, b in zip(("o", "dq", "dk", "dv", "dw"), res["packed"], res["tiled"]):
+        return (o,) + tuple(g)
+    # As the calls run by default, the two forms see a block's table entry as hi + lo bf16 halves or
+    # as the fp32 value depending on which blocks each of them finds to be of one bucket, so scores
+    # differ in the 16th bit and a P or dS operand may round to the other bf16 neighbour: one term
+    # of a handful moves by 2^-8 of its value.  The table gradient sums fp32 dS values that are
+    # never rounded.
+    a4, b4 = run(True, False), run(False, False)
+    for name, a, b in zip(("o", "dq", "dk", "dv", "dw"), a4, b4):
         a, b = a.double(), b.double()
         rms = float(b.pow(2).mean().sqrt())
         print("packed vs tiled", name, float((a - b).abs().max()) / rms, flush=True)
@@ -208,3 +200,12 @@ def test_packed_bias_table_gradient_equals_per_sequence_tiles(monkeypatch):
             assert float((a - b).abs().max()) <= 2e-3 * rms
         else:
             assert bool(((a - b).abs() <= 1e-2 * rms + b.abs() * 2.0 ** -7).all()), name
+    # That this is the whole difference: with every block on the per-pair path both forms see the
+    # same fp32 entries, hence the same scores and the same bf16 operands, and what remains is the
+    # order of fp32 additions.
+    a4, b4 = run(True, True), run(False, True)
+    for name, a, b in zip(("o", "dq", "dk", "dv", "dw"), a4, b4):
+        a, b = a.double(), b.double()
+        rms = float(b.pow(2).mean().sqrt())
+        print("packed vs tiled, per-pair entries", name, float((a - b).abs().max()) / rms, flush=True)
+        assert float((a - b).abs().max()) <= (1e-4 if name == "dw" else 1e-5) * rms, name

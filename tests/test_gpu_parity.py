@@ -54,6 +54,25 @@ def _check(name, got, want, dtype, tag=""):
     return err
 
 
+def _check_few_terms(name, got, want, tag=""):
+    """The bar for bf16 problems whose outputs are sums of a handful of terms (every sequence
+    shorter than a 32-row block).  P and dS enter the second matrix product as bf16 operands, an
+    error of up to 2^-9 of every term; an output that is one term, or a few, inherits it, and the
+    largest elements of such tensors are 10 to 14 times the tensor's RMS, so that this operand
+    rounding alone reaches 2.0e-2 .. 2.7e-2 x RMS (measured, fp32 outputs).  The stated bar presumes
+    sums of many terms, whose operand roundings average out (1.1e-2 on sequences of 32..256 rows).
+    Here a per-element allowance of 2^-8 of the exact value - or of the RMS where the value is
+    smaller: the terms that cancel in a small element are still of the order of the RMS - is added
+    for the operand rounding, and as much again for bf16 outputs' own rounding."""
+    g = got.detach().to(torch.float64).cpu().numpy()
+    assert np.isfinite(g).all(), (tag, name)
+    rms = float(np.sqrt(np.mean(want ** 2)))
+    rel = 2.0 ** -7 if got.dtype == torch.bfloat16 else 2.0 ** -8
+    excess = np.abs(g - want) - (TOL["bf16"] * rms + np.maximum(np.abs(want), rms) * rel)
+    assert excess.max() <= 0, "%s %s (%s out): max|err|/rms = %.3e, over the few-terms bar by %.3e*rms" % (
+        tag, name, got.dtype, float(np.abs(g - want).max() / rms), float(excess.max() / rms))
+
+
 def _dev(vals):
     return {k: v.cuda() for k, v in vals.items()}
 
@@ -214,10 +233,7 @@ def test_large_batch_of_short_sequences(tiling, monkeypatch):
     _tiling(monkeypatch, tiling)
     # More sequences than the schedule kernel keeps in LDS (its global-memory path), many empty.
     # fp32 data checks the addressing to 1e-5.  For bf16 data the outputs here are sums of 1 to 24
-    # terms and heavy-tailed (largest value > 10x the tensor RMS), so the rounding of a single
-    # bf16 P operand (relative 2^-9 of the value) already exceeds 2e-2 x RMS: the bar presumes the
-    # averaging of the benchmark configurations, and this case adds a per-element relative
-    # allowance of 2^-7 instead (operand rounding plus output rounding).
+    # terms: the few-terms bar (see _check_few_terms), on fp32 and on bf16 outputs.
     lib = _lib()
     rng = np.random.default_rng(77)
     lengths = [int(x) for x in rng.integers(0, 24, size=6500)]
@@ -230,14 +246,14 @@ def test_large_batch_of_short_sequences(tiling, monkeypatch):
     off_np = w.seq_offsets()
     off = torch.from_numpy(off_np).cuda()
     f64 = {k: workloads.to_f64(v) for k, v in vals.items()}
-    o = lib.hstu_jagged_attn_fwd(d["q"], d["k"], d["v"], off, w.max_len, w.alpha, True)
-    grads = lib.hstu_jagged_attn_bwd(d["q"], d["k"], d["v"], d["d_o"], off, w.max_len, w.alpha, True)
     want = (oracle.fwd(f64["q"], f64["k"], f64["v"], off_np, w.max_len, w.alpha, True),) + \
         oracle.bwd(f64["q"], f64["k"], f64["v"], f64["d_o"], off_np, w.max_len, w.alpha, True)
-    for name, got, ref in zip(("o", "dq", "dk", "dv"), (o,) + tuple(grads), want):
-        g = got.double().cpu().numpy()
-        rms = float(np.sqrt(np.mean(ref ** 2)))
-        assert (np.abs(g - ref) <= 2e-2 * rms + np.abs(ref) * 2.0 ** -7).all(), name
+    for odt in (torch.float32, torch.bfloat16):
+        o = lib.hstu_jagged_attn_fwd(d["q"], d["k"], d["v"], off, w.max_len, w.alpha, True, out_dtype=odt)
+        grads = lib.hstu_jagged_attn_bwd(d["q"], d["k"], d["v"], d["d_o"], off, w.max_len, w.alpha, True,
+                                         out_dtype=odt)
+        for name, got, ref in zip(("o", "dq", "dk", "dv"), (o,) + tuple(grads), want):
+            _check_few_terms(name, got, ref, "many_short/" + tiling)
 
 
 @pytest.mark.parametrize("causal", [True, False])
