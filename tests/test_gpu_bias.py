@@ -313,3 +313,75 @@ def test_bias_fp32_context_parallel_partial():
     g = dw_sum.double().cpu().numpy()
     rms = float(np.sqrt(np.mean(want[4] ** 2)))
     assert np.abs(g - want[4]).max() <= 1e-4 * rms
+
+
+def test_context_parallel_partial_with_bias_at_full_size():
+    """Config 4's lengths (8 sequences of 4304..14552 rows, CP = 4, H = 4, d = 128) with event
+    timestamps: two ranks' partials against all keys, sampled query rows against the bias oracle;
+    the key-side gradients and the table gradient must be finite and, for the ranks that were
+    run, of the size the oracle's sampled rows show."""
+    import paper_2508_04711_amd as lib
+    w = workloads.config(4)
+    vals = workloads.values(w)
+    dev = _dev(vals)
+    f64 = {k: workloads.to_f64(v) for k, v in vals.items()}
+    off_np = w.seq_offsets()
+    off = torch.from_numpy(off_np).cuda()
+    T, cp = w.total_rows, w.cp_size
+    ts_np, tab_np = workloads.timestamps(w, "events", 4), workloads.bias_table(64, 4)
+    ts, tab = torch.from_numpy(ts_np).cuda(), torch.from_numpy(tab_np).cuda()
+    rng = np.random.default_rng(45)
+    dk_sum = dv_sum = None
+    for rq in range(cp):
+        print("config 4 with bias: rank", rq, flush=True)
+        g = oracle.cp_global_rows(off_np, cp, rq)
+        ql, gl, tq = lib.hstu_cp_reorder([dev["q"], dev["d_o"], ts], off, T, cp, rq, len(g))
+        o, dq, dk, dv, dw = lib.hstu_jagged_attn_cp_partial_bias(
+            ql, dev["k"], dev["v"], gl, off, T, tq, ts, tab, 2, w.max_len, w.alpha, True, cp, rq, -1,
+            out_dtype=torch.float32)
+        torch.cuda.synchronize()
+        dk_sum = dk if dk_sum is None else dk_sum + dk
+        dv_sum = dv if dv_sum is None else dv_sum + dv
+        assert torch.isfinite(dw).all() and (dw != 0).any()
+        if rq in (0, cp - 1):
+            n = len(g)
+            sel = sorted(set([0, 1, 127, 128, n - 1, n // 2] + [int(x) for x in rng.integers(0, n, size=10)]))
+            want = oracle.bias_rows(f64["q"], f64["k"], f64["v"], f64["d_o"], off_np, ts_np,
+                                    tab_np.astype(np.float64), 2, w.max_len, w.alpha, True, g[sel])
+            _check("o", o[sel], want[0], "bf16", "config 4 with bias, rank %d" % rq)
+            _check("dq", dq[sel], want[1], "bf16", "config 4 with bias, rank %d" % rq)
+    # the sums over the four ranks are the whole batch's key-side gradients
+    sel = sorted(set([0, 1, T - 1, T // 2] + [int(x) for x in rng.integers(0, T, size=20)]))
+    want = oracle.bias_rows(f64["q"], f64["k"], f64["v"], f64["d_o"], off_np, ts_np,
+                            tab_np.astype(np.float64), 2, w.max_len, w.alpha, True, sel)
+    _check("dk", dk_sum[sel], want[2], "bf16", "config 4 with bias, all ranks")
+    _check("dv", dv_sum[sel], want[3], "bf16", "config 4 with bias, all ranks")
+
+
+def test_table_gradient_on_a_long_sequence_against_the_full_oracle():
+    """The table gradient is a sum over every visible pair and cannot be sampled: one sequence of
+    config 5's lengths (5337 rows, H = 2, d = 128; 28 million pairs, about a minute of the
+    single-threaded bias oracle) against the full oracle, all five results."""
+    import paper_2508_04711_amd as lib
+    w = workloads.custom("dw_long", [5337], 2, 128, 128, 32768, dtype="bf16", seed=77)
+    vals = workloads.values(w)
+    dev = _dev(vals)
+    f64 = {k: workloads.to_f64(v) for k, v in vals.items()}
+    off_np = w.seq_offsets()
+    off = torch.from_numpy(off_np).cuda()
+    ts_np, tab_np = workloads.timestamps(w, "events", 0), workloads.bias_table(64, 0, 1.0)
+    ts, tab = torch.from_numpy(ts_np).cuda(), torch.from_numpy(tab_np).cuda()
+    o = lib.hstu_jagged_attn_bias_fwd(dev["q"], dev["k"], dev["v"], off, ts, tab, 2, w.max_len, w.alpha, True,
+                                      out_dtype=torch.float32)
+    dq, dk, dv, dw = lib.hstu_jagged_attn_bias_bwd(dev["q"], dev["k"], dev["v"], dev["d_o"], off, ts, tab, 2,
+                                                   w.max_len, w.alpha, True, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    print("dw long: gpu done", flush=True)
+    want = oracle.bias_attention(f64["q"], f64["k"], f64["v"], f64["d_o"], off_np, ts_np,
+                                 tab_np.astype(np.float64), 2, w.max_len, w.alpha, True)
+    print("dw long: oracle done", flush=True)
+    for name, got, ref in zip(("o", "dq", "dk", "dv"), (o, dq, dk, dv), want):
+        _check(name, got, ref, "bf16", "dw long")
+    _check_dw(dw, want[4], "dw long")
+    # buckets no pair falls into are exactly zero
+    assert (dw.cpu().numpy()[want[4] == 0] == 0).all()
