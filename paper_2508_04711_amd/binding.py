@@ -575,7 +575,7 @@ def hstu_schedule_tile_rows(dtype_code: int, d_qk: int, d_v: int, side: int, tot
 def hstu_debug_dump_schedule(seq_offsets: torch.Tensor, total_rows: int, num_heads: int, d_qk: int,
                              d_v: int, causal: bool, dtype_code: int, side: int,
                              cp: Optional[Tuple[int, int, int, int, int]] = None,
-                             max_len: int = 1) -> np.ndarray:
+                             max_len: int = 1, workspace: Optional[torch.Tensor] = None) -> np.ndarray:
     """The device-built schedule as an int32 array [n_items, 12] in schedule order.
 
     cp = (cp_size, q_rank, kv_rank, q_rows, kv_rows) for a context-parallel problem.  The last
@@ -586,7 +586,7 @@ def hstu_debug_dump_schedule(seq_offsets: torch.Tensor, total_rows: int, num_hea
     desc = None
     if cp is not None:
         desc = _CpDesc(int(cp[0]), int(cp[1]), int(cp[2]), 0, int(cp[3]), int(cp[4]))
-    ws = _workspace(p, HSTU_WS_CP if cp is not None else HSTU_WS_FWD, None, seq_offsets.device)
+    ws = _workspace(p, HSTU_WS_CP if cp is not None else HSTU_WS_FWD, workspace, seq_offsets.device)
     max_items = int(total_rows) // 32 + 2 * B + 8 + 2048
     buf = np.zeros((max_items, 12), dtype=np.int32)
     n = load_library().hstu_debug_dump_schedule(
