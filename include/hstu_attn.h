@@ -37,10 +37,9 @@
  *     asynchronous on `hip_stream` (a hipStream_t, NULL = the default stream)
  *     and calls on different streams with different workspaces may overlap.
  *   - Sizes: total_rows < 2^31; (rows / 128 + 2 * batch + 1) * num_heads < 2^31; and
- *     where a bf16 forward pass builds its transposed copy of V (mean sequence
- *     length total_rows / batch above 1024, or a forced tile height) the key
- *     side may hold at most 131071 tiles of 64 rows, sequences' last tiles
- *     included (about 8.3 million rows).  Beyond: HSTU_ERR_BAD_SHAPE, and the
+ *     where a bf16 forward pass builds a transposed copy of V
+ *     (HSTU_FLAG_FWD_TILE_128 / _256) the key side may hold at most 131071
+ *     tiles of 64 rows, sequences' last tiles included (about 8.3 million rows).  Beyond: HSTU_ERR_BAD_SHAPE, and the
  *     workspace query returns 0.
  *   - Nothing in the process environment changes what a call does: the choices a caller (or a
  *     test) may want to force are bits of `params->flags` (hstu_flags below), and the same flags
@@ -92,9 +91,11 @@ typedef enum {
                                    the rows belong to; the last bits of a row's result then depend
                                    on the sequences that share its tile)                          */
   HSTU_FLAG_PACK_SHORT = 4,     /* packed tiles up to a mean length of 1024 instead of 256         */
-  HSTU_FLAG_FWD_TILE_128 = 8,   /* bf16 forward: 128-row query tiles with the transposed copy of V,
-                                   whatever the problem size and the mean sequence length         */
-  HSTU_FLAG_FWD_TILE_256 = 16,  /* ... 256-row query tiles                                         */
+  HSTU_FLAG_FWD_TILE_128 = 8,   /* bf16 forward: the form that first builds a transposed copy of V in
+                                   the workspace and reads that (one LDS instruction per matrix
+                                   instruction instead of one and a half), with 128-row query tiles;
+                                   the default reads V row-major and builds nothing               */
+  HSTU_FLAG_FWD_TILE_256 = 16,  /* ... with 256-row query tiles                                    */
   HSTU_FLAG_DKDV_ONE_WAVE = 32, /* dk/dv pass at d_qk = d_v = 128: the kernel with one wave per 32
                                    keys instead of the one that splits the work over two          */
   HSTU_FLAG_BIAS_PER_PAIR = 64  /* calls with the timestamp bias (bf16): every block of pairs looks
@@ -154,9 +155,9 @@ int hstu_jagged_attn_fwd(const hstu_attn_params* params, const void* q, const vo
  * transposed copy of V and the partial results of split tiles live in a static device array of
  * HSTU_STATIC_SCRATCH_BYTES inside the library, which every GPU the library runs on holds until
  * the process ends.  A problem whose hstu_jagged_attn_workspace_bytes(params, HSTU_WS_FWD) exceeds
- * that size is refused with HSTU_ERR_STATIC_SCRATCH and nothing is launched (batches whose mean
- * sequence length is at most 1024 need a few hundred bytes per sequence and 64 per 128 rows;
- * longer sequences add a copy of V and, from max_len 4096 on, up to
+ * that size is refused with HSTU_ERR_STATIC_SCRATCH and nothing is launched (a schedule needs a few
+ * hundred bytes per sequence and 64 per 128 rows; a forced tile height adds a copy of V; from
+ * max_len 4096 on a call may need up to
  * (rows / 128 + batch + 1024 / num_heads + 2) * num_heads * 128 * d_v * 4 bytes of partial results).
  * The call allocates nothing: no hipMalloc, hipFree or allocating library routine.  The device of
  * `hip_stream` must be the current device; the array's address on that device is looked up at the
@@ -350,8 +351,8 @@ int hstu_cp_reorder(int32_t batch, int64_t total_rows, int32_t cp_size, int32_t 
 
 /* Bytes of workspace the given entry point needs for `params` (an upper bound
  * that depends on batch, total_rows, num_heads, d_v and dtype only; 0 on invalid params).
- * Schedules, plus for bf16 forward passes over batches whose mean sequence length
- * total_rows / batch exceeds 1024 a transposed copy of V, plus fp32 partial results where heavy
+ * Schedules, plus for bf16 forward passes with a forced tile height a transposed copy of V, plus
+ * fp32 partial results where heavy
  * query tiles may be cut along the keys, plus 8 bytes per row for packed tiles.  The flags
  * change the answer: ask with the flags of the call.
  * `which` is a hstu_ws_kind. */

@@ -60,13 +60,23 @@ int check_params(const hstu_attn_params* p) {
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 // Short sequences on average (the host knows the mean length, total_rows / batch, without
-// reading the offsets): the forward pass then reads V tiles row-major instead of building a
-// transposed copy of V first, which would cost as much memory traffic as the pass itself,
-// and keeps to 128-row tiles.
+// reading the offsets): such batches keep the natural item order where they are large, and their
+// dk/dv workgroups may walk over items (see prepare_plan).
 bool short_sequences(const hstu_attn_params* p) {
-  // a forced tile height means the transposed-copy form
+  // a forced tile height means the forms of long sequences
   if (p->flags & (HSTU_FLAG_FWD_TILE_128 | HSTU_FLAG_FWD_TILE_256)) return false;
   return p->batch > 0 && p->total_rows / p->batch <= 1024;
+}
+
+// Whether the bf16 forward pass reads V through a transposed copy built first (see
+// launch_transpose_bf16): only when a tile height is forced.  The copy buys one LDS instruction per
+// matrix instruction instead of one and a half and costs a launch and the copy's traffic.  Measured
+// on one box, the default (row-major V, 128-row tiles) against the copy with 256-row tiles: forward
+// 2.71 against 2.92 + 0.07 ms on the long skewed batch, the step within +-0.7 % (under the chip's
+// power limit a faster forward pass slows the passes after it); the context-parallel workload -3 %
+// per step, the 16-sequence workload -1.5 %, the ring form -3 % (a launch less per step).
+bool fwd_transposed_v(const hstu_attn_params* p) {
+  return p->dtype == HSTU_BF16 && (p->flags & (HSTU_FLAG_FWD_TILE_128 | HSTU_FLAG_FWD_TILE_256)) != 0;
 }
 
 // Batches of very short sequences (mean length at most PACKED_MEAN_LEN): the whole-batch entry
@@ -93,6 +103,7 @@ size_t packed_bytes(const hstu_attn_params* p) {
 // Wavefronts per workgroup and owner rows per item of a pass on a problem of the given size.
 int pass_waves(const hstu_attn_params* p, int pass, int64_t owner_rows) {
   if (p->dtype != HSTU_BF16 || short_sequences(p)) return 4;
+  if (pass == PASS_FWD && !fwd_transposed_v(p)) return 4;  // (the eight-wave forward reads the transposed copy)
   if (pass == PASS_FWD && (p->flags & HSTU_FLAG_FWD_TILE_128)) return 4;
   if (pass == PASS_FWD && (p->flags & HSTU_FLAG_FWD_TILE_256)) return 8;
   return waves_bf16(pass, owner_rows, p->num_heads);
@@ -184,7 +195,7 @@ size_t partial_bytes_bound(const hstu_attn_params* p, const SideSpec& s, int d) 
 
 // Bytes of one transposed copy of a streamed tensor with head dimension d (bf16 only).
 size_t tcopy_bytes(const hstu_attn_params* p, const SideSpec& s, int d) {
-  if (p->dtype != HSTU_BF16 || short_sequences(p)) return 0;
+  if (!fwd_transposed_v(p)) return 0;
   return align_up((size_t)p->num_heads * d * 64 * stiles_bound(p, s) * 2, 256);
 }
 
@@ -195,7 +206,7 @@ int prepare_plan(const hstu_attn_params* p, int cp_size, const SideSpec& s, cons
   const int split = split_of(p, s);
   const int64_t max_tiles = items_bound(p, s), max_items = max_tiles * split, max_stiles = stiles_bound(p, s);
   // only the forward pass with a transposed copy of V reads the streamed side's tile table (see make_tcopy)
-  const bool want_ttile = s.pass == PASS_FWD && p->dtype == HSTU_BF16 && !short_sequences(p);
+  const bool want_ttile = s.pass == PASS_FWD && fwd_transposed_v(p);
   if (max_items * p->num_heads >= (1ll << 31) || max_stiles * p->num_heads >= (1ll << 31) ||
       // (the rows of the transposed copy are addressed with 32-bit byte offsets)
       (want_ttile && max_stiles * 64 * 2 * 128 >= (1ll << 31)))
@@ -327,7 +338,7 @@ int build_packed(const hstu_attn_params* p, const int32_t* off, char* ws, size_t
 int make_tcopy(const hstu_attn_params* p, const SideSpec& s, const BuiltPlan& bp, const void* src,
                int d, char* ws, size_t ws_bytes, size_t* base, hipStream_t stream, const void** out) {
   *out = nullptr;
-  if (p->dtype != HSTU_BF16 || short_sequences(p)) return HSTU_OK;
+  if (!fwd_transposed_v(p)) return HSTU_OK;
   const size_t at = align_up(*base, 256), bytes = tcopy_bytes(p, s, d);
   if (at + bytes > ws_bytes) return HSTU_ERR_WORKSPACE_TOO_SMALL;
   {

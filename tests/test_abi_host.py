@@ -185,9 +185,14 @@ def test_workspace_query(lib):
     from paper_2508_04711_amd import binding
     p = _params(binding, batch=16, total_rows=37117, d_qk=128, d_v=128)
     sizes = [lib.hstu_jagged_attn_workspace_bytes(ctypes.byref(p), k) for k in (0, 1, 2)]
-    # forward and context-parallel workspaces hold a transposed bf16 copy of V: [H, d_v, ~T]
+    # schedules only: the forward reads V row-major
+    assert all(0 < x < (1 << 20) for x in sizes)
+    # with a forced tile height the forward and context-parallel workspaces hold a transposed bf16
+    # copy of V: [H, d_v, ~T]
+    forced = _params(binding, batch=16, total_rows=37117, d_qk=128, d_v=128, flags=8)
+    fsizes = [lib.hstu_jagged_attn_workspace_bytes(ctypes.byref(forced), k) for k in (0, 1, 2)]
     vt = 2 * 128 * 37117 * 2
-    assert vt < sizes[0] < 1.2 * vt and 0 < sizes[1] < (1 << 20) and vt < sizes[2] < 1.5 * vt
+    assert vt < fsizes[0] < 1.2 * vt and 0 < fsizes[1] < (1 << 20) and vt < fsizes[2] < 1.5 * vt
     # with sequences long enough to be cut along the keys (max_len >= 4096) the query-side passes
     # add room for fp32 partial results: at most (tiles + 1024 / H + 1) slots of 128 rows
     long_p = _params(binding, batch=16, total_rows=37117, d_qk=128, d_v=128, max_len=8192)
@@ -202,7 +207,7 @@ def test_workspace_query(lib):
     # grows with the batch and with the rows
     big = _params(binding, batch=500, total_rows=10 ** 6, d_qk=128, d_v=128)
     assert lib.hstu_jagged_attn_workspace_bytes(ctypes.byref(big), 0) > sizes[0]
-    # batches of short sequences (mean length <= 1024) need no transposed copy: schedules only
+    # batches of short sequences: schedules only
     short = _params(binding, batch=4096, total_rows=600000, d_qk=128, d_v=128)
     # (mean length <= 512: plus 8 bytes per row and two small schedules for the packed tiles)
     assert 0 < lib.hstu_jagged_attn_workspace_bytes(ctypes.byref(short), 0) < (4 << 20) + 8 * 600000 + (1 << 20)
@@ -255,11 +260,15 @@ def test_size_limits_are_those_of_the_pass_that_has_them(lib):
     # 131072 sequences of 40 rows: short sequences, no transposed copy anywhere
     many = _params(binding, batch=131072, num_heads=4, d_qk=128, d_v=128, max_len=64, total_rows=131072 * 40)
     assert ws(many, 0) > 0 and ws(many, 1) > 0
-    # 9 million rows in 1000 long sequences: the forward's transposed copy is out of range, the backward is not
-    long = _params(binding, batch=1000, num_heads=1, d_qk=128, d_v=128, max_len=9000, total_rows=9_000_000)
-    assert ws(long, 0) == 0 and ws(long, 1) > 0
+    # 9 million rows in 1000 long sequences: fine by default, out of range for the forward's transposed copy
+    long = _params(binding, batch=1000, num_heads=1, d_qk=128, d_v=128, max_len=2000, total_rows=9_000_000)
+    assert ws(long, 0) > 0 and ws(long, 1) > 0
+    forced = _params(binding, batch=1000, num_heads=1, d_qk=128, d_v=128, max_len=2000, total_rows=9_000_000, flags=8)
+    assert ws(forced, 0) == 0 and ws(forced, 1) > 0
     # just inside: (rows / 64 + batch + 1) tiles < 131072
-    edge = _params(binding, batch=1000, num_heads=1, d_qk=128, d_v=128, max_len=9000, total_rows=64 * (131071 - 1001))
+    edge = _params(binding, batch=1000, num_heads=1, d_qk=128, d_v=128, max_len=2000, total_rows=64 * (131071 - 1001),
+                   flags=8)
     assert ws(edge, 0) > 0
-    over = _params(binding, batch=1000, num_heads=1, d_qk=128, d_v=128, max_len=9000, total_rows=64 * (131072 - 1001))
+    over = _params(binding, batch=1000, num_heads=1, d_qk=128, d_v=128, max_len=2000, total_rows=64 * (131072 - 1001),
+                   flags=8)
     assert ws(over, 0) == 0

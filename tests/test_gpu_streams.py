@@ -11,7 +11,7 @@ pytestmark = pytest.mark.gpu
 
 def test_side_stream_calls_keep_their_temporaries_while_the_current_stream_allocates():
     import paper_2508_04711_amd as lib
-    # long enough for the forward's transposed copy of V and several tiles per sequence
+    # several tiles per sequence
     w = workloads.custom("side_stream", [1500, 2077, 1201], 2, 128, 128, 2077, dtype="bf16", seed=21)
     dev = {k: v.cuda() for k, v in workloads.values(w).items()}
     off = torch.from_numpy(w.seq_offsets()).cuda()

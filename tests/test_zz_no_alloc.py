@@ -32,10 +32,9 @@ def _both(w, dev, off, out_dtype):
 
 def test_static_scratch_forward_twice_second_smaller():
     assert lib.hstu_static_scratch_bytes() == 16 << 20
-    # first: sequences long enough for the form with a transposed copy of V in the scratch array
-    # (mean length > 1024), ragged tails, several tiles per sequence
+    # first: long sequences with ragged tails, several tiles per sequence
     big = _batch("static_a", [1500, 2077, 1101], 2, 128, 2048, 11)
-    # second: a smaller batch of short sequences (no transposed copy), an empty one among them
+    # second: a smaller batch of short sequences, an empty one among them
     small = _batch("static_b", [130, 0, 1, 77, 300, 64], 2, 128, 300, 12)
     for (w, dev, off), odt in ((big, torch.bfloat16), (small, torch.float32), (big, torch.float32)):
         want, got = _both(w, dev, off, odt)
@@ -44,7 +43,7 @@ def test_static_scratch_forward_twice_second_smaller():
 
 
 def test_static_scratch_refuses_what_does_not_fit_and_still_works_after():
-    rows = 400_000  # mean length > 1024: the transposed copy of V alone is 2 * rows * H * d bytes
+    rows = 400_000  # max_len >= 4096: room for the partial results of split tiles, ~900 MB here
     q = torch.empty((rows, 4, 128), dtype=torch.bfloat16, device="cuda")
     off = torch.tensor([0, rows // 2, rows], dtype=torch.int32, device="cuda")
     with pytest.raises(lib.HstuError) as e:
