@@ -239,6 +239,18 @@ __device__ __forceinline__ void pair_body(const AttnArgs& a, const Item& it, int
     block_copy_async<D>(buf + QB, cur.g, rs, cur.valid, wave, voff);
     cur.next(a, it, st, h);
   };
+  // The copy issued in every step: block cur.b while the stream lasts, afterwards a copy of no rows
+  // (zeros arrive; the buffer is one that no later step reads for anything that counts).  Every
+  // step thus issues the same two loads and waits with the same count, with no branch around
+  // either: the compiler's own bookkeeping of copies in flight follows that, whereas with a
+  // condition evaluated at both places it assumed older copies pending and put a wait for
+  // everything in front of some steps' first operand reads, i.e. right behind the copy just issued.
+  auto copy_step = [&](char* buf, bool live) {
+    const int valid = live ? cur.valid : 0;
+    block_copy_async<D>(buf, cur.q, rs, valid, wave, voff);
+    block_copy_async<D>(buf + QB, cur.g, rs, valid, wave, voff);
+    if (live) cur.next(a, it, st, h);
+  };
   auto block_pos = [&](int b) { return tile_ref(it, st, b >> 1).pos + (b & 1) * BR; };
 
   // Ring buffers 4 and 5 stand for the two blocks before the first one (the contractions of the
@@ -310,8 +322,7 @@ __device__ __forceinline__ void pair_body(const AttnArgs& a, const Item& it, int
 
     auto step = [&](int t, auto tag) {
       constexpr int S = decltype(tag)::value;  // t mod 6; S & 1 is the parity of t
-      const bool copying = t + AHEAD_COPY < NBLK;
-      if (copying) copy_next(ring((S + AHEAD_COPY) % NSLOT));
+      copy_step(ring((S + AHEAD_COPY) % NSLOT), t + AHEAD_COPY < NBLK);
       if constexpr (ROLE == 0) {
         if (t <= NBLK + 1) {  // (nothing left to contract in the last step)
           // block t-1: masked when the diagonal touches it or when it lies beyond the stream
@@ -331,8 +342,7 @@ __device__ __forceinline__ void pair_body(const AttnArgs& a, const Item& it, int
                          sd[(S + 1) & 1], pk[(S + 1) & 1], pk[S & 1], acc, S & 1 ? xa1 : xa0);
       }
       // block t+1 must have landed; the copies of the later blocks may stay in flight
-      if (copying) tile_copy_wait<2 * (AHEAD_COPY - 1)>();
-      else tile_copy_wait<0>();
+      tile_copy_wait<2 * (AHEAD_COPY - 1)>();
       tile_barrier();
     };
     for (int t = 0; t < nsteps; t += NSLOT) {
@@ -343,6 +353,7 @@ __device__ __forceinline__ void pair_body(const AttnArgs& a, const Item& it, int
       if (t + 4 < nsteps) step(t + 4, std::integral_constant<int, 4>{});
       if (t + 5 < nsteps) step(t + 5, std::integral_constant<int, 5>{});
     }
+    tile_copy_wait<0>();  // (the last steps' empty copies: nothing may be in flight when the workgroup's LDS is released)
   }
 
   // Accumulators: lane holds key row n, elements c*32 + 8*(r/4) + 4*hh + r%4 (P and dS are held
