@@ -85,6 +85,20 @@ __device__ __forceinline__ void block_copy_async(char* buf, const __bf16* base, 
   __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, HSTU_LDS(void, buf + wave * 1024), 16, voff, 0, 0, 0);
 }
 
+// The same copy issued by the four waves of role B alone (two wave-wide loads per wave): inside the
+// loop role A, whose vector work makes it the longer of the two, issues no copies, keeps no
+// cursor and waits for no memory.
+template <int D>
+__device__ __forceinline__ void block_copy_async_half(char* buf, const __bf16* base, int rs, int valid,
+                                                      int w, const int (&voff2)[2]) {
+  static_assert(BR / (64 / (D / 8)) == PW, "two loads per wave of one role");
+  const int rows = valid < 0 ? 0 : (valid < BR ? valid : BR);
+  const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      (void*)base, 0, __builtin_amdgcn_readfirstlane(rows * rs), 0x00020000);
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, HSTU_LDS(void, buf + (2 * w) * 1024), 16, voff2[0], 0, 0, 0);
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, HSTU_LDS(void, buf + (2 * w + 1) * 1024), 16, voff2[1], 0, 0, 0);
+}
+
 __device__ __forceinline__ void lds_writes_done() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
 
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
@@ -239,16 +253,24 @@ __device__ __forceinline__ void pair_body(const AttnArgs& a, const Item& it, int
     block_copy_async<D>(buf + QB, cur.g, rs, cur.valid, wave, voff);
     cur.next(a, it, st, h);
   };
-  // The copy issued in every step: block cur.b while the stream lasts, afterwards a copy of no rows
-  // (zeros arrive; the buffer is one that no later step reads for anything that counts).  Every
-  // step thus issues the same two loads and waits with the same count, with no branch around
+  // The copy issued in every step, by role B: block cur.b while the stream lasts, afterwards a copy
+  // of no rows (zeros arrive; the buffer is one that no later step reads for anything that counts).
+  // Every step thus issues the same four loads and waits with the same count, with no branch around
   // either: the compiler's own bookkeeping of copies in flight follows that, whereas with a
   // condition evaluated at both places it assumed older copies pending and put a wait for
   // everything in front of some steps' first operand reads, i.e. right behind the copy just issued.
+  int voff2[2] = {0, 0};
+  if constexpr (ROLE == 1) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int r2 = (2 * g + i) * (64 / (D / 8)) + lane / (D / 8);
+      voff2[i] = r2 * rs + (((lane % (D / 8)) ^ swz<D>(r2)) << 4);
+    }
+  }
   auto copy_step = [&](char* buf, bool live) {
     const int valid = live ? cur.valid : 0;
-    block_copy_async<D>(buf, cur.q, rs, valid, wave, voff);
-    block_copy_async<D>(buf + QB, cur.g, rs, valid, wave, voff);
+    block_copy_async_half<D>(buf, cur.q, rs, valid, g, voff2);
+    block_copy_async_half<D>(buf + QB, cur.g, rs, valid, g, voff2);
     if (live) cur.next(a, it, st, h);
   };
   auto block_pos = [&](int b) { return tile_ref(it, st, b >> 1).pos + (b & 1) * BR; };
@@ -322,7 +344,7 @@ __device__ __forceinline__ void pair_body(const AttnArgs& a, const Item& it, int
 
     auto step = [&](int t, auto tag) {
       constexpr int S = decltype(tag)::value;  // t mod 6; S & 1 is the parity of t
-      copy_step(ring((S + AHEAD_COPY) % NSLOT), t + AHEAD_COPY < NBLK);
+      if constexpr (ROLE == 1) copy_step(ring((S + AHEAD_COPY) % NSLOT), t + AHEAD_COPY < NBLK);
       if constexpr (ROLE == 0) {
         if (t <= NBLK + 1) {  // (nothing left to contract in the last step)
           // block t-1: masked when the diagonal touches it or when it lies beyond the stream
@@ -342,7 +364,7 @@ __device__ __forceinline__ void pair_body(const AttnArgs& a, const Item& it, int
                          sd[(S + 1) & 1], pk[(S + 1) & 1], pk[S & 1], acc, S & 1 ? xa1 : xa0);
       }
       // block t+1 must have landed; the copies of the later blocks may stay in flight
-      tile_copy_wait<2 * (AHEAD_COPY - 1)>();
+      if constexpr (ROLE == 1) tile_copy_wait<4 * (AHEAD_COPY - 1)>();
       tile_barrier();
     };
     for (int t = 0; t < nsteps; t += NSLOT) {
