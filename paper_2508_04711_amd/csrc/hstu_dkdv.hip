@@ -98,16 +98,16 @@ __device__ __forceinline__ void dkdv_step(const Init& init, const char* qn, cons
         for (int j = 0; j < EPG; ++j) st_t[j] = 1.0f + st_t[j];
 #pragma unroll
         for (int j = 0; j < EPG; ++j) st_g[j] = __builtin_amdgcn_rcpf(st_t[j]);
-      } else if (ph == 2) {  // p' = s * sg, 1 - sg
+      } else if (ph == 2) {  // p' = s * sg, p' * (1 - sg) as p' - p' * sg
 #pragma unroll
         for (int j = 0; j < EPG; ++j) p[e0 + j] = s_in[e0 + j] * st_g[j];
 #pragma unroll
-        for (int j = 0; j < EPG; ++j) st_t[j] = 1.0f - st_g[j];
-      } else {               // ds' = dp * (sg + alpha * p' * (1 - sg))
+        for (int j = 0; j < EPG; ++j) st_t[j] = __builtin_fmaf(-p[e0 + j], st_g[j], p[e0 + j]);
+      } else {               // ds' = dp * (sg + alpha * p' * (1 - sg)): two fused multiply-adds after p'
 #pragma unroll
-        for (int j = 0; j < EPG; ++j) st_t[j] = alpha * p[e0 + j] * st_t[j];
+        for (int j = 0; j < EPG; ++j) st_t[j] = __builtin_fmaf(alpha, st_t[j], st_g[j]);
 #pragma unroll
-        for (int j = 0; j < EPG; ++j) ds[e0 + j] = d_in[e0 + j] * (st_g[j] + st_t[j]);
+        for (int j = 0; j < EPG; ++j) ds[e0 + j] = d_in[e0 + j] * st_t[j];
       }
     } else {
 #pragma unroll

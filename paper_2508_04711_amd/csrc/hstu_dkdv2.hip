@@ -153,16 +153,14 @@ __device__ __forceinline__ void role_a_step(const char* qn, const char* gp, cons
       for (int j = 0; j < 8; ++j) st_t[j] = 1.0f + st_t[j];
 #pragma unroll
       for (int j = 0; j < 8; ++j) st_g[j] = __builtin_amdgcn_rcpf(st_t[j]);
-    } else if (ph == 2) {  // p' = s * sg, 1 - sg
+    } else if (ph == 2) {  // p' = s * sg, p' * (1 - sg) as p' - p' * sg
 #pragma unroll
       for (int j = 0; j < 8; ++j) p[j] = s_in[e0 + j] * st_g[j];
 #pragma unroll
-      for (int j = 0; j < 8; ++j) st_t[j] = 1.0f - st_g[j];
-    } else {               // silu' = sg + alpha * p' * (1 - sg)
+      for (int j = 0; j < 8; ++j) st_t[j] = __builtin_fmaf(-p[j], st_g[j], p[j]);
+    } else {               // silu' = sg + alpha * p' * (1 - sg): two fused multiply-adds after p'
 #pragma unroll
-      for (int j = 0; j < 8; ++j) st_t[j] = alpha * p[j] * st_t[j];
-#pragma unroll
-      for (int j = 0; j < 8; ++j) st_g[j] = st_g[j] + st_t[j];
+      for (int j = 0; j < 8; ++j) st_g[j] = __builtin_fmaf(alpha, st_t[j], st_g[j]);
       if (mask) {
         asm volatile("" ::: "memory");  // not speculable: keeps the selects off the unmasked path
         const auto vis = vis_of();

@@ -705,7 +705,7 @@ __device__ __forceinline__ BiasCtx bias_setup(const AttnArgs& a, float* wtab, co
 __device__ __forceinline__ void bwd_elem(float s, float dp, float c1, float alpha, float& p, float& ds) {
   const float sg = sigmoid_scaled(s, c1);
   p = s * sg;
-  ds = dp * (sg + alpha * p * (1.0f - sg));
+  ds = dp * __builtin_fmaf(alpha, __builtin_fmaf(-p, sg, p), sg);
 }
 
 // CAP > 0: at most that many workgroups (for kernels that walk over the (item, head) pairs).
