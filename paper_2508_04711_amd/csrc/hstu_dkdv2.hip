@@ -130,10 +130,50 @@ __device__ __forceinline__ void role_a_step(const char* qn, const char* gp, cons
     tp[m] = cag.read(gp, m & 1, m >> 1);
   }
   fence();
-  // The arithmetic of eight elements per group of four slots, one stage per slot, so that no
-  // instruction consumes its predecessor's result; a group's results leave the registers (silu'
-  // to the exchange buffer, p' packed) as soon as they are complete.
-  float p[8], st_t[8], st_g[8];
+  // The arithmetic of eight elements per group, one stage per slot, so that no instruction consumes
+  // its predecessor's result; a group's results leave the registers (silu' to the exchange buffer,
+  // p' packed) as soon as they are complete.  The first group takes slots 0..3, the second slots
+  // 3..6: the last slot has no stage, so the wave's exchange writes are under way while its last
+  // matrix instructions issue, and the wait for them that ends the step finds them done.
+  float p[2][8], st_t[2][8], st_g[2][8];
+  auto stage = [&](auto gtag, int ph) {
+    constexpr int G = decltype(gtag)::value, e0 = G * 8;
+    if (ph == 0) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) st_t[G][j] = s_in[e0 + j] * c1;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) st_t[G][j] = __builtin_amdgcn_exp2f(st_t[G][j]);
+    } else if (ph == 1) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) st_t[G][j] = 1.0f + st_t[G][j];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) st_g[G][j] = __builtin_amdgcn_rcpf(st_t[G][j]);
+    } else if (ph == 2) {  // p' = s * sg, p' * (1 - sg) as p' - p' * sg
+#pragma unroll
+      for (int j = 0; j < 8; ++j) p[G][j] = s_in[e0 + j] * st_g[G][j];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) st_t[G][j] = __builtin_fmaf(-p[G][j], st_g[G][j], p[G][j]);
+    } else {               // silu' = sg + alpha * p' * (1 - sg): two fused multiply-adds after p'
+#pragma unroll
+      for (int j = 0; j < 8; ++j) st_g[G][j] = __builtin_fmaf(alpha, st_t[G][j], st_g[G][j]);
+      if (mask) {
+        asm volatile("" ::: "memory");  // not speculable: keeps the selects off the unmasked path
+        const auto vis = vis_of();
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const bool on = vis(e0 + j);
+          p[G][j] = on ? p[G][j] : 0.f;
+          st_g[G][j] = on ? st_g[G][j] : 0.f;
+        }
+      }
+#pragma unroll
+      for (int q4 = 0; q4 < 2; ++q4) {
+        const f32x4 vf = {st_g[G][4 * q4], st_g[G][4 * q4 + 1], st_g[G][4 * q4 + 2], st_g[G][4 * q4 + 3]};
+        *HSTU_LDS(f32x4, xw + (e0 / 4 + q4) * XG) = vf;
+      }
+      p_cur[G] = pack8(p[G]);
+    }
+  };
 #pragma unroll
   for (int m = 0; m < NS; ++m) {
     s_out = mfma(op[m], kreg[m], s_out);
@@ -142,42 +182,8 @@ __device__ __forceinline__ void role_a_step(const char* qn, const char* gp, cons
       op[m + AHEAD] = raq.read(qn, 0, m + AHEAD);
       tp[m + AHEAD] = cag.read(gp, (m + AHEAD) & 1, (m + AHEAD) >> 1);
     }
-    const int e0 = (m / 4) * 8, ph = m % 4;
-    if (ph == 0) {
-#pragma unroll
-      for (int j = 0; j < 8; ++j) st_t[j] = s_in[e0 + j] * c1;
-#pragma unroll
-      for (int j = 0; j < 8; ++j) st_t[j] = __builtin_amdgcn_exp2f(st_t[j]);
-    } else if (ph == 1) {
-#pragma unroll
-      for (int j = 0; j < 8; ++j) st_t[j] = 1.0f + st_t[j];
-#pragma unroll
-      for (int j = 0; j < 8; ++j) st_g[j] = __builtin_amdgcn_rcpf(st_t[j]);
-    } else if (ph == 2) {  // p' = s * sg, p' * (1 - sg) as p' - p' * sg
-#pragma unroll
-      for (int j = 0; j < 8; ++j) p[j] = s_in[e0 + j] * st_g[j];
-#pragma unroll
-      for (int j = 0; j < 8; ++j) st_t[j] = __builtin_fmaf(-p[j], st_g[j], p[j]);
-    } else {               // silu' = sg + alpha * p' * (1 - sg): two fused multiply-adds after p'
-#pragma unroll
-      for (int j = 0; j < 8; ++j) st_g[j] = __builtin_fmaf(alpha, st_t[j], st_g[j]);
-      if (mask) {
-        asm volatile("" ::: "memory");  // not speculable: keeps the selects off the unmasked path
-        const auto vis = vis_of();
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          const bool on = vis(e0 + j);
-          p[j] = on ? p[j] : 0.f;
-          st_g[j] = on ? st_g[j] : 0.f;
-        }
-      }
-#pragma unroll
-      for (int q4 = 0; q4 < 2; ++q4) {
-        const f32x4 vf = {st_g[4 * q4], st_g[4 * q4 + 1], st_g[4 * q4 + 2], st_g[4 * q4 + 3]};
-        *HSTU_LDS(f32x4, xw + (e0 / 4 + q4) * XG) = vf;
-      }
-      p_cur[m / 4] = pack8(p);
-    }
+    if (m < 4) stage(std::integral_constant<int, 0>{}, m);
+    if (m >= 3 && m < 7) stage(std::integral_constant<int, 1>{}, m - 3);
     fence();
   }
 }
