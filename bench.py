@@ -309,7 +309,7 @@ def main() -> int:
     dom_ms = avg_ms[dom]
     achieved = alg[dom] / n_launch / (dom_ms * 1e-3) / 1e12
     # (the dk/dv pass of the long-sequence workloads at d = 128 is the kernel with two waves per 32 keys)
-    pair = (w.d_qk == 128 and w.d_v == 128 and not (args.flags & lib.HSTU_FLAG_DKDV_ONE_WAVE) and not with_bias
+    pair = (w.d_qk == 128 and w.d_v == 128 and not (args.flags & lib.HSTU_FLAG_DKDV_ONE_WAVE)
             and args.workload not in ("short", "mid", "cfg2"))
     kernel_name = {"fwd": "hstu_fwd_bf16", "dkdv": "hstu_dkdv_pair_bf16" if pair else "hstu_dkdv_bf16",
                    "dq": "hstu_dq_bf16"}[dom]

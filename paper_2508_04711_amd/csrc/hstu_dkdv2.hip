@@ -51,6 +51,7 @@ struct BlockCursor {
   const __bf16* g;
   int valid;  // visible rows from the block's first row on (<= 0: none)
   int b;      // block index
+  int row;    // the block's first row in the streamed tensors (the bias variant copies its records)
   __device__ __forceinline__ void seek(const AttnArgs& a, const Item& it, const Stream& st, int h, int blk) {
     const TileRef t = tile_ref(it, st, blk >> 1);
     const int o = (blk & 1) * BR;
@@ -59,13 +60,14 @@ struct BlockCursor {
     g = (const __bf16*)a.d_o + off;
     valid = t.valid - o;
     b = blk;
+    row = t.row + o;
   }
   __device__ __forceinline__ void next(const AttnArgs& a, const Item& it, const Stream& st, int h) {
     if (b + 1 == 2 * st.n[0]) {
       seek(a, it, st, h, b + 1);
     } else {
       const int64_t step = (int64_t)BR * a.num_heads * D;
-      q += step; g += step; valid -= BR; ++b;
+      q += step; g += step; valid -= BR; ++b; row += BR;
     }
   }
 };
@@ -99,6 +101,15 @@ __device__ __forceinline__ void block_copy_async_half(char* buf, const __bf16* b
   __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, HSTU_LDS(void, buf + (2 * w + 1) * 1024), 16, voff2[1], 0, 0, 0);
 }
 
+// Asynchronous copy of the timestamp records of one block into a 1 KB buffer (one wave-wide load:
+// 32 records of 16 bytes; the lanes beyond them and rows >= valid arrive as zeros).
+__device__ __forceinline__ void rec_block_copy_async(char* buf, const TsRecord* rec, int valid, int lane) {
+  const int rows = valid < 0 ? 0 : (valid < BR ? valid : BR);
+  const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      (void*)rec, 0, __builtin_amdgcn_readfirstlane(rows * (int)sizeof(TsRecord)), 0x00020000);
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, HSTU_LDS(void, buf), 16, lane * 16, 0, 0, 0);
+}
+
 __device__ __forceinline__ void lds_writes_done() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
 
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
@@ -110,8 +121,8 @@ constexpr int XK = 4 * XG;     // floats per 32 keys
 
 // Role A, one step: scores of the block at qn into s_out, SiLU of s_in (p' packed into p_cur,
 // silu' written to xw), dV^T += dO^T P with the block at gp and p_prev.
-template <int D, class Vis>
-__device__ __forceinline__ void role_a_step(const char* qn, const char* gp, const RowAddr<D>& raq,
+template <int D, class Init, class Vis>
+__device__ __forceinline__ void role_a_step(const Init& init, const char* qn, const char* gp, const RowAddr<D>& raq,
                                             const ColAddr<D>& cag, const bf16x8 (&kreg)[D / 16],
                                             const f32x16& s_in, f32x16& s_out,
                                             const bf16x8 (&p_prev)[2], bf16x8 (&p_cur)[2],
@@ -122,8 +133,7 @@ __device__ __forceinline__ void role_a_step(const char* qn, const char* gp, cons
   static_assert(NS == 8, "eight slots per step: two groups of four stages");
   bf16x8 op[NS], tp[NS];
   auto fence = [] { __builtin_amdgcn_sched_barrier(0); };
-#pragma unroll
-  for (int r = 0; r < 16; ++r) s_out[r] = 0.f;
+  init(s_out);  // zeros, or the block's bias
 #pragma unroll
   for (int m = 0; m < AHEAD; ++m) {
     op[m] = raq.read(qn, 0, m);
@@ -230,13 +240,17 @@ __device__ __forceinline__ void role_b_step(const char* gn, const char* qp, cons
 }
 
 // The whole item for one role (ROLE 0: A, 1: B).
-template <int D, int ROLE>
+template <int D, int ROLE, bool BIAS>
 __device__ __forceinline__ void pair_body(const AttnArgs& a, const Item& it, int h, char* ring0,
                                           char* ring1, char* ring2, char* ring3, char* ring4,
-                                          char* ring5, float* xbuf0, float* xbuf1) {
+                                          char* ring5, float* xbuf0, float* xbuf1, char* rec0, char* rec1,
+                                          char* rec2, char* rec3, char* rec4, char* rec5, float* wtab) {
   constexpr int QB = BR * D * 2;
   auto ring = [&](int b) {
     return b == 0 ? ring0 : (b == 1 ? ring1 : (b == 2 ? ring2 : (b == 3 ? ring3 : (b == 4 ? ring4 : ring5))));
+  };
+  auto recb = [&](int b) {  // the records of the block in ring buffer b (bias variant)
+    return b == 0 ? rec0 : (b == 1 ? rec1 : (b == 2 ? rec2 : (b == 3 ? rec3 : (b == 4 ? rec4 : rec5))));
   };
   const int H = a.num_heads;
   const int tid = threadIdx.x, lane = tid & 63, n = lane & 31, hh = lane >> 5;
@@ -252,9 +266,10 @@ __device__ __forceinline__ void pair_body(const AttnArgs& a, const Item& it, int
   const int crow = wave * (64 / (D / 8)) + lane / (D / 8);
   const int voff = crow * rs + (((lane % (D / 8)) ^ swz<D>(crow)) << 4);
   BlockCursor<D> cur;
-  auto copy_next = [&](char* buf) {  // copies block cur.b, then moves on
+  auto copy_next = [&](char* buf, char* rbuf) {  // copies block cur.b, then moves on
     block_copy_async<D>(buf, cur.q, rs, cur.valid, wave, voff);
     block_copy_async<D>(buf + QB, cur.g, rs, cur.valid, wave, voff);
+    if (BIAS && wave == 0) rec_block_copy_async(rbuf, a.ts_rec + cur.row, cur.valid, lane);
     cur.next(a, it, st, h);
   };
   // The copy issued in every step, by role B: block cur.b while the stream lasts, afterwards a copy
@@ -271,10 +286,13 @@ __device__ __forceinline__ void pair_body(const AttnArgs& a, const Item& it, int
       voff2[i] = r2 * rs + (((lane % (D / 8)) ^ swz<D>(r2)) << 4);
     }
   }
-  auto copy_step = [&](char* buf, bool live) {
+  // (With the bias every wave of role B also issues the load of the block's records: the same
+  // kilobyte four times, so that all four keep the same count of loads in flight.)
+  auto copy_step = [&](char* buf, char* rbuf, bool live) {
     const int valid = live ? cur.valid : 0;
     block_copy_async_half<D>(buf, cur.q, rs, valid, g, voff2);
     block_copy_async_half<D>(buf + QB, cur.g, rs, valid, g, voff2);
+    if constexpr (BIAS) rec_block_copy_async(rbuf, a.ts_rec + (live ? cur.row : 0), valid, lane);
     if (live) cur.next(a, it, st, h);
   };
   auto block_pos = [&](int b) { return tile_ref(it, st, b >> 1).pos + (b & 1) * BR; };
@@ -296,9 +314,12 @@ __device__ __forceinline__ void pair_body(const AttnArgs& a, const Item& it, int
   }
   if (NBLK > 0) {
     cur.seek(a, it, st, h, 0);
-    copy_next(ring0);
-    copy_next(ring1);  // (NBLK is even)
+    copy_next(ring0, rec0);
+    copy_next(ring1, rec1);  // (NBLK is even)
   }
+  // The bias enters the scores only, i.e. role A's product (the table's gradient is the dq pass's).
+  BiasCtx bias = {};
+  if constexpr (BIAS) bias = bias_setup<PW * 64>(a, wtab, it, orow, tid, hh);  // (all waves: has a barrier)
 
   const float c1 = -a.alpha * 1.4426950408889634f;
   const int k_lo = it.pos0 + g * 32, k_hi = k_lo + 31;
@@ -345,11 +366,19 @@ __device__ __forceinline__ void pair_body(const AttnArgs& a, const Item& it, int
     float* xa0 = xbuf0 + g * XK + lane * 4;
     float* xa1 = xbuf1 + g * XK + lane * 4;
     const int nsteps = NBLK + 3;
+    BlockTable tab = {};
+    if constexpr (BIAS && ROLE == 0) {
+      tab.fill(bias, 0, NBLK, it, st, lane);
+      tab.fill(bias, 64, NBLK, it, st, lane);
+    }
 
     auto step = [&](int t, auto tag) {
       constexpr int S = decltype(tag)::value;  // t mod 6; S & 1 is the parity of t
-      if constexpr (ROLE == 1) copy_step(ring((S + AHEAD_COPY) % NSLOT), t + AHEAD_COPY < NBLK);
+      if constexpr (ROLE == 1)
+        copy_step(ring((S + AHEAD_COPY) % NSLOT), recb((S + AHEAD_COPY) % NSLOT), t + AHEAD_COPY < NBLK);
       if constexpr (ROLE == 0) {
+        if constexpr (BIAS)  // the stream enters one set of the block table: refill the other
+          if (t > 0 && (t & 63) == 0) tab.fill(bias, t + 64, NBLK, it, st, lane);
         if (t <= NBLK + 1) {  // (nothing left to contract in the last step)
           // block t-1: masked when the diagonal touches it or when it lies beyond the stream
           const int b = t - 1;
@@ -358,7 +387,8 @@ __device__ __forceinline__ void pair_body(const AttnArgs& a, const Item& it, int
             const int rel = b >= NBLK ? (1 << 20) : k_lo + n - block_pos(b < 0 ? 0 : b);
             return VisAfter{rel, hh};
           };
-          role_a_step<D>(ring(S), ring((S + 4) % NSLOT) + QB, ra, ca, oreg, sd[(S + 1) & 1], sd[S & 1],
+          const ScoreInit<BIAS> init = {&bias, recb(S), 0, BIAS ? tab.get(t) : BlockBias{}};
+          role_a_step<D>(init, ring(S), ring((S + 4) % NSLOT) + QB, ra, ca, oreg, sd[(S + 1) & 1], sd[S & 1],
                          pk[S & 1], pk[(S + 1) & 1], acc, (S + 1) & 1 ? xa1 : xa0, c1, a.alpha, mask, vis_of);
           lds_writes_done();
         }
@@ -368,7 +398,7 @@ __device__ __forceinline__ void pair_body(const AttnArgs& a, const Item& it, int
                          sd[(S + 1) & 1], pk[(S + 1) & 1], pk[S & 1], acc, S & 1 ? xa1 : xa0);
       }
       // block t+1 must have landed; the copies of the later blocks may stay in flight
-      if constexpr (ROLE == 1) tile_copy_wait<4 * (AHEAD_COPY - 1)>();
+      if constexpr (ROLE == 1) tile_copy_wait<(BIAS ? 5 : 4) * (AHEAD_COPY - 1)>();
       tile_barrier();
     };
     for (int t = 0; t < nsteps; t += NSLOT) {
@@ -389,7 +419,7 @@ __device__ __forceinline__ void pair_body(const AttnArgs& a, const Item& it, int
                          a.alpha * a.inv_n, hh, a.accumulate, a.out_f32);
 }
 
-template <int D>
+template <int D, bool BIAS>
 __global__ void __launch_bounds__(PW * 64) hstu_dkdv_pair_bf16(AttnArgs a) {
   constexpr int QB = BR * D * 2;
   // One array per ring buffer (the Q block, then the dO block), so that the compiler can see that
@@ -402,29 +432,42 @@ __global__ void __launch_bounds__(PW * 64) hstu_dkdv_pair_bf16(AttnArgs a) {
   __shared__ __attribute__((aligned(1024))) char ring5[2 * QB];
   __shared__ __attribute__((aligned(1024))) float xbuf0[4 * XK];  // silu' of blocks of even index
   __shared__ __attribute__((aligned(1024))) float xbuf1[4 * XK];  // ... of odd index
+  // bias variant: the timestamp records of the blocks in the ring buffers, and the table
+  __shared__ __attribute__((aligned(1024))) char rec0[BIAS ? 1024 : 16];
+  __shared__ __attribute__((aligned(1024))) char rec1[BIAS ? 1024 : 16];
+  __shared__ __attribute__((aligned(1024))) char rec2[BIAS ? 1024 : 16];
+  __shared__ __attribute__((aligned(1024))) char rec3[BIAS ? 1024 : 16];
+  __shared__ __attribute__((aligned(1024))) char rec4[BIAS ? 1024 : 16];
+  __shared__ __attribute__((aligned(1024))) char rec5[BIAS ? 1024 : 16];
+  __shared__ float wtab[BIAS ? MAX_TS_BUCKETS : 1];
 
   const Unit un = unit_of(a, blockIdx.x);
   Item it;
   if (!un.on || !fetch_item<false>(a.plan, un.slot, it)) return;
   const int role = __builtin_amdgcn_readfirstlane(threadIdx.x >> 8);
-  if (role == 0) pair_body<D, 0>(a, it, un.h, ring0, ring1, ring2, ring3, ring4, ring5, xbuf0, xbuf1);
-  else pair_body<D, 1>(a, it, un.h, ring0, ring1, ring2, ring3, ring4, ring5, xbuf0, xbuf1);
+  if (role == 0)
+    pair_body<D, 0, BIAS>(a, it, un.h, ring0, ring1, ring2, ring3, ring4, ring5, xbuf0, xbuf1, rec0, rec1, rec2,
+                          rec3, rec4, rec5, wtab);
+  else
+    pair_body<D, 1, BIAS>(a, it, un.h, ring0, ring1, ring2, ring3, ring4, ring5, xbuf0, xbuf1, rec0, rec1, rec2,
+                          rec3, rec4, rec5, wtab);
 }
 
 }  // namespace
 
-// The pair kernel serves plain per-sequence schedules (no bias, no packed tiles, no walking
-// workgroups) of the head dimensions that do not fit two workgroups per CU.
+// The pair kernel serves per-sequence schedules, with or without the timestamp bias (no packed
+// tiles, no walking workgroups), of the head dimensions that do not fit two workgroups per CU.
 bool dkdv_pair_supported(const AttnArgs& a, int d_qk, int d_v) {
-  return d_qk == 128 && d_v == 128 && !a.row_seq && !a.ts_rec && !a.large_batch && !a.walk_chunks &&
-         a.waves == 4;
+  if (a.ts_rec && (a.nb < 1 || a.nb > MAX_TS_BUCKETS || !a.ts_w || !a.ts_rec_own)) return false;
+  return d_qk == 128 && d_v == 128 && !a.row_seq && !a.large_batch && !a.walk_chunks && a.waves == 4;
 }
 
 hipError_t launch_dkdv_pair_bf16(const AttnArgs& a, int d_qk, int d_v, hipStream_t stream) {
   if (!dkdv_pair_supported(a, d_qk, d_v)) return hipErrorInvalidValue;
   const int64_t units = a.xcd_parts <= 1 ? (int64_t)a.max_items * a.num_heads
                                          : 8 * (((int64_t)a.max_items + a.xcd_parts - 1) / a.xcd_parts);
-  hipLaunchKernelGGL((hstu_dkdv_pair_bf16<128>), dim3((unsigned)units), dim3(PW * 64), 0, stream, a);
+  if (a.ts_rec) hipLaunchKernelGGL((hstu_dkdv_pair_bf16<128, true>), dim3((unsigned)units), dim3(PW * 64), 0, stream, a);
+  else hipLaunchKernelGGL((hstu_dkdv_pair_bf16<128, false>), dim3((unsigned)units), dim3(PW * 64), 0, stream, a);
   return hipGetLastError();
 }
 
