@@ -69,6 +69,15 @@ def test_bias_matches_oracle(kind, d):
     _run(w, kind, nb=40, f=2, causal=True, seed=d)
 
 
+@pytest.mark.parametrize("kind", ["events", "shuffled"])
+def test_bias_one_wave_dkdv_kernel(kind, monkeypatch):
+    """d = 128 with per-sequence tiles runs the dk/dv kernel with two waves per 32 keys (above); the
+    one-wave kernel, which packed tiles and large batches run with the bias, is selected by its flag."""
+    set_flags(monkeypatch, add="DKDV_ONE_WAVE")
+    w = workloads.custom("bias_one_wave", LENGTHS, 2, 128, 128, 700, dtype="bf16", seed=31)
+    _run(w, kind, nb=40, f=2, causal=True, seed=7)
+
+
 @pytest.mark.parametrize("nb,f", [(1, 0), (7, 0), (33, 1), (512, 4), (300, 8)])
 def test_bias_bucket_shapes(nb, f):
     w = workloads.custom("bias_buckets", [300, 257, 90], 2, 64, 64, 300, dtype="bf16", seed=5)

@@ -364,3 +364,30 @@ def test_wide_forward_tiles(name, lengths, H, dqk, dv, causal, monkeypatch):
                                       out_dtype=torch.float32)
     scale = narrow.abs().max().item()
     assert (wide - narrow).abs().max().item() <= 1e-5 * scale   # same sums, another order
+
+
+@pytest.mark.parametrize("causal", [True, False])
+def test_both_dkdv_kernels_at_d128(causal, monkeypatch):
+    """Per-sequence schedules at d = 128 run the dk/dv kernel with two waves per 32 keys; the kernel
+    with one wave (which large batches, packed tiles and the other head dimensions run) is selected
+    here by its flag: it meets the oracle too, and the two agree to the order of fp32 additions
+    (same products, same roundings of P and dS, same order of blocks)."""
+    w = workloads.custom("dkdv_forms", [700, 255, 256, 257, 1, 0, 513, 90], 2, 128, 128, max_len=700,
+                         dtype="bf16", seed=23)
+    print("dkdv forms", causal, flush=True)
+    lib = _lib()
+    vals = _dev(workloads.values(w))
+    off = torch.from_numpy(w.seq_offsets()).cuda()
+
+    def bwd():
+        return lib.hstu_jagged_attn_bwd(vals["q"], vals["k"], vals["v"], vals["d_o"], off, w.max_len, w.alpha,
+                                        causal, out_dtype=torch.float32)
+    _run_full(w, causal=causal)
+    two = bwd()
+    set_flags(monkeypatch, add="DKDV_ONE_WAVE")
+    _run_full(w, causal=causal)
+    one = bwd()
+    torch.cuda.synchronize()
+    for name, a, b in zip(("dq", "dk", "dv"), two, one):
+        scale = a.abs().max().item()
+        assert (a - b).abs().max().item() <= 1e-4 * scale, name
