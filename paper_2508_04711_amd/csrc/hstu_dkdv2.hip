@@ -29,11 +29,16 @@ namespace {
 // buffers.  Step t:
 //   A: scores of block t | SiLU of block t-1 (writes silu' of t-1) | dV contraction of block t-2
 //   B: dP of block t-1   | dS of block t-2 (reads silu' of t-2)    | dK contraction of block t-3
-//   all waves: the copy of block t+2 is issued at the start; block t+1 has landed at the end.
+//   B: the copy of block t+2 is issued at the start; block t+1 has landed at the end.
 // One workgroup barrier per step orders the hand-over (the exchange buffers alternate by parity)
 // and the reuse of ring buffers.  Steps run from 0 to blocks + 2; the blocks before block 0 are
 // zeros (their ring buffers are cleared at the start) and blocks at or beyond the end are treated
 // as wholly masked, so one step body serves the whole item.
+// Role A is the longer role (the SiLU arithmetic is its alone) and the two meet at the barrier,
+// so the step's time is A's: inside the loop A issues no copies, keeps no cursor and waits for no
+// memory (B's waves do), and its last exchange write leaves a slot before the step ends.
+// With the timestamp bias (BIAS) role A writes the block's bias into its score accumulator before
+// the block's first product (see bias_block); the table's gradient belongs to the dq pass.
 // =============================================================================================
 
 constexpr int BR = 32;     // streamed rows per block
