@@ -8,7 +8,11 @@ reorder back, ranks one after the other on the one GPU).
 Inputs are resident in HBM before the timed region starts.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg5|cfg3|cfg2|cfg4|cfg4_ring|cfg5_bias|short|mid]
-                    [--flags N] [--probes]
+                    [--flags N] [--probes] [--no-other-workloads]
+
+A run of the default workload also measures cfg3 and cfg4 (same steps, no CPU leg) and reports them
+under `other_workloads`, so that one line carries the fractions of all three long-sequence
+configurations; `value` is the default workload's alone.
 
 Beside the nominal peaks the line carries what the machine sustains on matrix instructions alone
 (`roofline.measured_peak`, measured in the same run by the library's matrix-instruction loop), and
@@ -134,7 +138,7 @@ def _cpu_baseline(w: workloads.Workload, prefix_rows: int):
     }
 
 
-def main() -> int:
+def _parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
@@ -144,14 +148,20 @@ def main() -> int:
     ap.add_argument("--flags", type=int, default=0, help="hstu_flags passed with every call (A/B runs)")
     ap.add_argument("--probes", action="store_true", help="also print the measurement kernels' line")
     ap.add_argument("--cpu-prefix-rows", type=int, default=0, help="rows per sequence in the CPU sample")
-    args = ap.parse_args()
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="default workload only: leave out the short runs of cfg3 and cfg4 reported beside it")
+    return ap.parse_args()
+
+
+def measure(args):
+    """One workload: the JSON line's dictionary, and what the probes line needs."""
     if args.gpus != 1:
         print("bench.py measures one GPU only: this build has no multi-GPU path (run with --gpus 1)",
               file=sys.stderr)
-        return 2
+        return None
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)
-        return 2
+        return None
 
     import paper_2508_04711_amd as lib
     lib.load_library()  # fail loudly if the HIP library is not built
@@ -376,6 +386,31 @@ def main() -> int:
             if w.backward:
                 outs.update({"dq": dq, "dk": dk, "dv": dv})
             out["cpu_baseline"]["timed_outputs_check"] = _check_timed_outputs(w, vals_cpu, off_np, outs)
+    return out, measured, lib, dev
+
+
+def main() -> int:
+    args = _parse_args()
+    res = measure(args)
+    if res is None:
+        return 2
+    out, measured, lib, dev = res
+    if args.workload == "cfg5" and not args.no_other_workloads:
+        # The other long-sequence configurations in the same run, so that one line carries all three
+        # fractions: the same steps and warm-up, no CPU leg.  (`value` above is cfg5's alone.)
+        others = {}
+        for name in ("cfg3", "cfg4"):
+            a2 = argparse.Namespace(**vars(args))
+            a2.workload, a2.no_cpu_baseline = name, True
+            o2 = measure(a2)[0]
+            r2 = o2["roofline"]
+            others[o2["config"]["workload"]] = {
+                "value": o2["value"], "unit": o2["unit"], "ms_per_step": o2["ms_per_step"],
+                "frac_of_bf16_mfma_peak": o2["frac_of_bf16_mfma_peak"],
+                "frac_of_measured_mfma_peak": o2["frac_of_measured_mfma_peak"],
+                "roofline": {k: r2[k] for k in ("kernel", "achieved", "frac", "frac_of_measured_peak",
+                                                "avg_launch_ms", "launches_per_step") if k in r2}}
+        out["other_workloads"] = others
     print(json.dumps(out))
     if args.probes:
         print(json.dumps({"probes": {"mfma_loop_tflops": measured, "dq_atomic_gbs": _dq_atomic_rate(lib, dev)}}))
