@@ -391,3 +391,13 @@ def test_both_dkdv_kernels_at_d128(causal, monkeypatch):
     for name, a, b in zip(("dq", "dk", "dv"), two, one):
         scale = a.abs().max().item()
         assert (a - b).abs().max().item() <= 1e-4 * scale, name
+
+
+@pytest.mark.parametrize("d", [64, 128])
+def test_saturated_scores(d):
+    """Inputs eight times the usual size: alpha * q.k has a standard deviation of 64, so the sigmoid
+    saturates both ways and the exponential inside it overflows for a part of the pairs (x < -88):
+    those pairs must come out as exact zeros of P and SiLU', not as NaN, in every kernel."""
+    w = workloads.custom("saturated", [300, 129, 64, 1], 2, d, d, max_len=300, dtype="bf16", scale=8.0, seed=29)
+    print("saturated", d, flush=True)
+    _run_full(w, causal=True)
