@@ -288,10 +288,12 @@ def test_heavy_tiles_cut_along_the_keys(causal, monkeypatch):
         assert (a - b).abs().max().item() <= 1e-5 * b.abs().max().item()
 
 
-def test_accumulate_adds_to_existing_outputs():
-    # accumulate = 1 adds to what the output buffers hold (fp32 and bf16 outputs)
+@pytest.mark.parametrize("d", [64, 128])
+def test_accumulate_adds_to_existing_outputs(d):
+    # accumulate = 1 adds to what the output buffers hold (fp32 and bf16 outputs; d = 128 runs the
+    # two-wave dk/dv kernel's epilogue)
     lib = _lib()
-    w = workloads.custom("acc", [90, 140], 2, 64, 64, 140, dtype="bf16", seed=8)
+    w = workloads.custom("acc", [90, 140], 2, d, d, 140, dtype="bf16", seed=8)
     d = _dev(workloads.values(w))
     off = torch.from_numpy(w.seq_offsets()).cuda()
     T = w.total_rows
